@@ -1,0 +1,152 @@
+"""Benchmark of the shard-parallel training hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload: K=8 MLPs of 16 x Linear(4096,4096)+GeLU and Linear(4096,1000), bf16 working weights with
+fp32 master/Adam state, batch 512, 4 shards per model, shard-parallel schedule.  A step is one
+forward + backward + Adam update of all 8 models on one batch.  Inputs are synthetic and already
+resident in HBM when the timed region starts.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+
+
+def _set_steps(w, n):
+    w.steps = w.n_batches = n
+    return w
+
+
+def cpu_baseline(w, budget_s=30.0):
+    """Times the oracle as it stands on a bounded sample: whole model-steps of model 0."""
+    import numpy as np
+    from hydra_workloads import make_data
+    from oracle import model as OM
+    from oracle import optim as OO
+    from oracle import train as OT
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    ws = _set_steps(w, 2)
+    data = make_data(ws)
+    arch, hp = w.archs[0], w.hparams[0]
+    params = OM.init_params(arch, w.init_seed, 0)
+    st = OO.new_state(params)
+    t0 = time.perf_counter()
+    done = 0
+    while done < 2 and (done == 0 or time.perf_counter() - t0 < budget_s / 2):
+        _, grads = OM.loss_and_grads(arch, params, OT.batch_at(data, done + 1))
+        for j, g in enumerate(grads):
+            OO.update_tensor(hp, done + 1, params[j], g, st["m"][j], st["v"][j])
+        done += 1
+    dt = time.perf_counter() - t0
+    return dict(value=done * w.batch / dt, unit="samples/s", cores=int(cores), kind="oracle",
+                sample=f"model 0 of {w.K}, {done} step(s) of batch {w.batch} (fp64 arithmetic, one model at a time); "
+                       f"{dt:.1f} s of CPU work")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--sequential-steps", type=int, default=3,
+                    help="steps of the one-shard-at-a-time model-parallel schedule timed beside (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from hydra_workloads import make_data, workload
+    from paper_2107_06469_amd import hydra as H
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device", file=sys.stderr)
+        sys.exit(1)
+
+    w = workload(args.workload)
+    ctx = H.hydra_create(n_streams=4)
+    H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+    for k in range(w.K):
+        H.hydra_shard(ctx, k, w.boundaries[k])
+
+    def run(n_steps, policy, profile):
+        d = make_data(_set_steps(w, n_steps))
+        H.hydra_set_data(ctx, d["inputs"], d["target_pos"], d["targets"])       # copies to HBM, untimed
+        H.hydra_profile_enable(ctx, profile)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        st = H.hydra_train_epoch(ctx, policy)                                   # drains the device at both ends
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, st
+
+    if args.warmup > 0:
+        run(args.warmup, H.SCHED_SHARD_PARALLEL, False)
+    H.hydra_profile_read(ctx, reset=True)
+    dt, st = run(args.steps, H.SCHED_SHARD_PARALLEL, not args.no_profile)
+    prof = H.hydra_profile_read(ctx, reset=True)
+    samples = w.K * w.batch * args.steps
+    losses = [float(H.hydra_read_loss(ctx, k)[-1]) for k in range(w.K)]
+
+    out = {
+        "metric": "aggregate training samples/sec across K models (1 GPU)",
+        "value": samples / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.archs[0]["dtype"] == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.workload}] {w.name}: K={w.K} models, batch {w.batch}, "
+                               f"{len(w.boundaries[0]) + 1} shards/model, shard-parallel schedule, 4 streams",
+                   "launches_per_step": st["launches"] / args.steps, "final_loss_model0": losses[0]},
+    }
+
+    # roofline of the dominant kernel class (largest share of kernel time in the timed region)
+    if prof:
+        name = max(prof, key=lambda k: prof[k]["total_ms"])
+        p = prof[name]
+        avg_ms = p["total_ms"] / p["launches"]
+        if p["flops"] > 0:
+            peak = PEAK_BF16_TFLOPS if out["dtype"] == "bf16" else PEAK_F32_TFLOPS
+            ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
+            out["roofline"] = {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                               "frac": ach / peak, "traffic": None, "avg_launch_ms": avg_ms, "launches": p["launches"]}
+        else:
+            ach = p["bytes"] / p["launches"] / (avg_ms * 1e-3) / 1e9
+            out["roofline"] = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": avg_ms,
+                               "launches": p["launches"]}
+        tot = sum(v["total_ms"] for v in prof.values())
+        out["kernel_time_ms_per_step"] = {k: v["total_ms"] / args.steps for k, v in prof.items()}
+        gemm_ms = sum(v["total_ms"] for k, v in prof.items() if k.startswith("gemm"))
+        gemm_fl = sum(v["flops"] for k, v in prof.items() if k.startswith("gemm"))
+        if gemm_ms > 0:
+            out["mfma_util_gemm_time_weighted"] = gemm_fl / (gemm_ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
+            out["mfma_util_whole_epoch"] = gemm_fl / dt / (PEAK_BF16_TFLOPS * 1e12)
+        out["kernel_time_over_wall"] = tot * 1e-3 / dt
+
+    if args.sequential_steps > 0:
+        dts, _ = run(args.sequential_steps, H.SCHED_SEQUENTIAL, False)
+        out["model_parallel_baseline"] = {"value": w.K * w.batch * args.sequential_steps / dts, "unit": "samples/s",
+                                          "schedule": "one shard task at a time, one stream, ungrouped launches",
+                                          "steps": args.sequential_steps}
+    H.hydra_destroy(ctx)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(workload(args.workload))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,82 @@
+/*
+ * hydra_ops.h -- C entry points of the individual device operations the trainer is built from.
+ *
+ * They exist so that every kernel can be checked and timed on its own.  All data pointers are
+ * DEVICE pointers owned by the caller; the pointer tables themselves (X, W, ...) are HOST arrays of
+ * G entries.  `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work and return;
+ * they neither allocate nor synchronise.  Return value: 0 on success, otherwise a hydra_status
+ * (HYDRA_ERR_INVALID_ARG for shapes/alignments the kernel does not accept, HYDRA_ERR_DEVICE for a
+ * launch failure); hydra_ops_last_error() gives the text.
+ *
+ * The operations are the ones a forward pass, a backward pass and a gradient update of a shard
+ * consist of (paper, Introduction, "Motivation": features flow layer to layer forward, gradients
+ * backward; Approach, "Desiderata": gradient updates must be exactly those of unsharded training),
+ * written for G same-shaped problems of different models at once (Approach: shards of different
+ * models are independent units of parallel work).
+ */
+#ifndef HYDRA_OPS_H
+#define HYDRA_OPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { HYDRA_OPS_F32 = 0, HYDRA_OPS_BF16 = 1 };                  /* operand dtype                    */
+enum { HYDRA_EPI_NONE = 0, HYDRA_EPI_RELU = 1, HYDRA_EPI_GELU = 2 };
+
+/* out_g[M,N] = epilogue( sum_k X_g(m,k) * W_g(n,k) ), fp32 accumulation.
+ *   epilogue: v = acc + bias[n] (if bias); pre[m,n] = v (if pre);
+ *             v = gate ? v * act'(gate[m,n]) : act(v);  v += resid[m,n] (if resid); out[m,n] = v.
+ * x_kmajor = 1: X_g stored [M, ldx], k contiguous; 0: stored [K, ldx], m contiguous.
+ * w_kmajor = 1: W_g stored [N, ldw], k contiguous; 0: stored [K, ldw], n contiguous.
+ * Forward Linear: X = input, W = weight[out,in], both k-major.  Input gradient: X = dY (k-major),
+ * W = weight (k is its slow index).  Weight gradient: X = dY, W = input, both with k slow.
+ * Leading dimensions count elements; ldx, ldw multiples of 16 bytes and >= the contiguous extent
+ * rounded up to 16 bytes; ldo, ldg, ldr multiples of 8 and >= N.  bias is fp32 [N].  out is fp32
+ * when out_f32, else the operand dtype; pre, gate, resid have the operand dtype.  Optional tables
+ * may be NULL.  tile: 0 = automatic, 1 = 256x256, 2 = 128x128, 3 = 32x128 workgroup tiles. */
+typedef struct {
+  int dtype, M, N, K, x_kmajor, w_kmajor, ldx, ldw, ldo, ldg, ldr, act, out_f32, tile, G;
+  const void* const* X;
+  const void* const* W;
+  const float* const* bias;
+  void* const* out;
+  void* const* pre;
+  const void* const* gate;
+  const void* const* resid;
+} hydra_gemm_desc;
+int hydra_op_gemm(const hydra_gemm_desc* d, void* stream);
+
+/* out_g[n] = sum_{m<M} src_g[m,n]; src has the operand dtype and leading dimension ld, out is fp32. */
+int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out, void* stream);
+
+/* Softmax cross-entropy over fp32 logits [M, ldz] with C classes and int32 labels [M] (shared by the
+ * group): rowloss_g[m] = logsumexp(z_m) - z_m[y_m]; dz_g[m,c] = (softmax(z_m)[c] - [c==y_m]) * inv_n
+ * in the operand dtype with leading dimension lddz (columns [C,lddz) are zeroed);
+ * loss_g[0] = inv_n * sum_m rowloss_g[m]. */
+int hydra_op_softmax_ce(int dtype, int M, int C, int ldz, int lddz, float inv_n, int G, const float* const* logits,
+                        const int32_t* labels, void* const* dz, float* const* rowloss, float* const* loss, void* stream);
+
+/* Optimizer step over flat fp32 blocks of n elements (n % 4 == 0).  opt 0 = SGD (m, v ignored),
+ * 1 = Adam with bias-correction factors bc1 = 1/(1-b1^t), bc2 = 1/(1-b2^t) given per problem.
+ * w16 (optional) receives the bf16 rounding of the updated parameters.  hp: G rows of
+ * {lr, b1, b2, eps, bc1, bc2} in double (host); they are rounded to fp32 once, as is 1-b. */
+int hydra_op_optim(int opt, size_t n, int G, float* const* p, const float* const* g, float* const* m, float* const* v,
+                   void* const* w16, const double* hp, void* stream);
+
+/* dst[i] = u_i * 2a - a with u_i the 24-bit uniform of the counter generator (SplitMix64 keyed by
+ * (seed, stream_id)); the values a model's tensor `stream_id = (model << 20) | tensor` is initialised with. */
+int hydra_op_init_uniform(float* dst, size_t n, uint64_t seed, uint64_t stream_id, float a, void* stream);
+
+/* dst[i] = bf16(src[i]) (round to nearest even), i < n. */
+int hydra_op_cast_bf16(const float* src, void* dst, size_t n, void* stream);
+
+const char* hydra_ops_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYDRA_OPS_H */

@@ -1,0 +1,117 @@
+// Small memory-bound kernels: seeded initialisation, fills, casts, batch staging, column sums.
+#include "kernels.h"
+
+namespace hydra {
+namespace {
+
+__device__ __forceinline__ bf16_t f2bf(float v) {
+  __bf16 h = (__bf16)v;  // round to nearest even
+  return __builtin_bit_cast(bf16_t, h);
+}
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// SplitMix64 (Steele, Lea, Flood 2014): output n of the generator started at `key` is the
+// finaliser applied to key + (n+1)*golden.  24 high bits -> u in [0,1); value = u*2a - a, one rounding.
+__global__ void init_uniform_kernel(float* dst, size_t n, uint64_t key, float a) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    uint64_t z = key + (i + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    float u = (float)(uint32_t)(z >> 40) * 5.9604644775390625e-08f;  // exact: 24 bits * 2^-24
+    dst[i] = __fmaf_rn(u, 2.0f * a, -a);
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t* dst, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = v;
+}
+
+__global__ void cast_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = f2bf(src[i]);
+}
+
+__global__ void stage_rows_kernel(const float* __restrict__ src, void* __restrict__ dst, int rows, int cols, int ld,
+                                  int to_bf16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t n = (size_t)rows * cols, stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    size_t r = i / cols, c = i % cols;
+    float v = src[i];
+    if (to_bf16) static_cast<bf16_t*>(dst)[r * ld + c] = f2bf(v);
+    else static_cast<float*>(dst)[r * ld + c] = v;
+  }
+}
+
+// Column sums.  A block owns 64 columns; its 16 row lanes each add every 16th row in ascending
+// order, then the 16 partial sums are added in lane order.  The order is fixed by (M, column) only.
+template <typename T>
+__global__ __launch_bounds__(1024) void colsum_kernel(const ColsumArgs a) {
+  __shared__ float part[16][64];
+  const int g = blockIdx.y, col = blockIdx.x * 64 + (threadIdx.x & 63), rl = threadIdx.x >> 6;
+  const T* src = static_cast<const T*>(a.src[g]);
+  float s = 0.f;
+  if (col < a.N) {
+    for (int m = rl; m < a.M; m += 16) {
+      T v = src[(size_t)m * a.ld + col];
+      s += sizeof(T) == 4 ? *reinterpret_cast<const float*>(&v) : bf2f(*reinterpret_cast<const bf16_t*>(&v));
+    }
+  }
+  part[rl][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (rl == 0 && col < a.N) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += part[i][threadIdx.x];
+    a.out[g][col] = t;
+  }
+}
+
+inline int blocks_for(size_t n, int threads, int cap = 4096) {
+  size_t b = (n + threads - 1) / threads;
+  return (int)(b < 1 ? 1 : (b > (size_t)cap ? cap : b));
+}
+
+}  // namespace
+
+hipError_t launch_init_uniform(float* dst, size_t n, uint64_t key, float a, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(init_uniform_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, dst, n, key, a);
+  return hipGetLastError();
+}
+hipError_t launch_fill_u32(uint32_t* dst, size_t n, uint32_t v, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, dst, n, v);
+  return hipGetLastError();
+}
+hipError_t launch_fill_f32(float* dst, size_t n, float v, hipStream_t s) {
+  uint32_t bits;
+  __builtin_memcpy(&bits, &v, 4);
+  return launch_fill_u32(reinterpret_cast<uint32_t*>(dst), n, bits, s);
+}
+hipError_t launch_cast_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, s, src, dst, n);
+  return hipGetLastError();
+}
+hipError_t launch_stage_rows(const float* src, void* dst, int rows, int cols, int ld, int to_bf16, hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || ld < cols) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stage_rows_kernel, dim3(blocks_for((size_t)rows * cols, 256)), dim3(256), 0, s, src, dst, rows,
+                     cols, ld, to_bf16);
+  return hipGetLastError();
+}
+hipError_t launch_colsum(const ColsumArgs& a, hipStream_t s) {
+  if (a.G < 1 || a.G > MAXG || a.M < 1 || a.N < 1 || a.ld < a.N) return hipErrorInvalidValue;
+  dim3 grid((a.N + 63) / 64, a.G);
+  if (a.dtype == GEMM_F32) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(1024), 0, s, a);
+  else hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(1024), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace hydra

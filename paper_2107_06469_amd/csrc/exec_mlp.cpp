@@ -1,0 +1,196 @@
+// Shard executor for MLP models: forward, backward and update of layer units [u0,u1) for a launch
+// group of same-shaped shards of different models (paper, Introduction, "Motivation": features are
+// sent layer to layer in the forward pass, gradients in the backward pass).
+//
+// unit l < L:  z_l = x_l W_l^T + b_l,  h_l = act(z_l),  x_{l+1} = h_l          (x_0 = the batch)
+// unit L:      logits = x_L W_out^T + b_out, softmax cross-entropy
+// backward of unit l given dz_l:  dW_l = dz_l^T x_l;  db_l = column sums of dz_l;
+//                                 dz_{l-1} = (dz_l W_l) * act'(z_{l-1})         (l > 0)
+#include <cmath>
+
+#include "hydra_internal.h"
+
+namespace hydra {
+
+static int rup8(int v) { return (v + 7) / 8 * 8; }
+
+static const Tensor& W_of(const Model& m, int u) { return m.tensors[2 * u]; }
+static const Tensor& b_of(const Model& m, int u) { return m.tensors[2 * u + 1]; }
+
+// pointer to tensor `t` inside the shard's state block `base` (same offsets for p, g and w16)
+template <typename T>
+static T* at(T* base, const Shard& sh, const Tensor& t) { return base + (t.off - sh.off); }
+
+static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
+  const Model& m0 = c->models[b.members[0].first];
+  const Shard& sh0 = m0.shards[b.members[0].second];
+  const hydra_arch& a = m0.arch;
+  const bool bf = a.dtype == HYDRA_DTYPE_BF16;
+  const size_t es = bf ? 2 : 4;
+  const int L = a.n_layers, G = (int)b.members.size();
+  const int ldd = rup8(a.d_model), ldv = rup8(a.n_out);
+  for (int u = sh0.u0; u < sh0.u1; ++u) {
+    GemmArgs g{};
+    g.dtype = bf ? GEMM_BF16 : GEMM_F32;
+    g.M = c->B;
+    g.N = u < L ? a.d_model : a.n_out;
+    g.K = u == 0 ? a.d_in : a.d_model;
+    g.x_kmajor = g.w_kmajor = 1;
+    g.ldx = u == 0 ? c->ld_in : ldd;
+    g.ldw = W_of(m0, u).cols;
+    g.G = G;
+    g.ldo = u < L ? ldd : ldv;
+    g.act = u < L ? (a.act == HYDRA_ACT_RELU ? EPI_ACT_RELU : EPI_ACT_GELU) : EPI_ACT_NONE;
+    g.out_f32 = u < L ? 0 : 1;
+    for (int i = 0; i < G; ++i) {
+      const Model& m = c->models[b.members[i].first];
+      const Shard& sh = m.shards[b.members[i].second];
+      g.X[i] = u == 0 ? static_cast<const char*>(c->x_staged) + (size_t)batch * c->B * c->ld_in * es : m.mlp.h[u - 1];
+      g.W[i] = bf ? (const void*)at(sh.w16, sh, W_of(m, u)) : (const void*)at(sh.p, sh, W_of(m, u));
+      g.bias[i] = at(sh.p, sh, b_of(m, u));
+      if (u < L) {
+        g.out[i] = m.mlp.h[u];
+        g.pre[i] = m.mlp.z[u];
+      } else {
+        g.out[i] = m.mlp.logits;
+      }
+    }
+    HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, s, 2.0 * g.M * g.N * g.K * G, 0.0, launch_gemm(g, s));
+    if (u == L) {
+      SoftmaxCeArgs ce{};
+      ce.dtype = g.dtype;
+      ce.M = c->B;
+      ce.C = a.n_out;
+      ce.ldz = ce.lddz = ldv;
+      ce.G = G;
+      ce.inv_n = 1.0f / (float)c->B;
+      ce.labels = c->targets + (size_t)batch * c->B;
+      for (int i = 0; i < G; ++i) {
+        const Model& m = c->models[b.members[i].first];
+        ce.logits[i] = m.mlp.logits;
+        ce.dz[i] = m.mlp.dlogits;
+        ce.rowloss[i] = m.mlp.rowloss;
+        ce.loss_out[i] = m.loss_dev + step;
+      }
+      ++c->launches;  // the row kernel and the reduction are two launches
+      HYDRA_LAUNCH(c, HYDRA_K_SOFTMAX_CE, s, 0.0, (double)G * ce.M * ce.C * (4 + 4 + (bf ? 2 : 4)), launch_softmax_ce(ce, s));
+    }
+  }
+  return HYDRA_OK;
+}
+
+static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, hipStream_t s) {
+  const Model& m0 = c->models[b.members[0].first];
+  const Shard& sh0 = m0.shards[b.members[0].second];
+  const hydra_arch& a = m0.arch;
+  const bool bf = a.dtype == HYDRA_DTYPE_BF16;
+  const size_t es = bf ? 2 : 4;
+  const int L = a.n_layers, G = (int)b.members.size();
+  const int ldd = rup8(a.d_model), ldv = rup8(a.n_out);
+  const int act = a.act == HYDRA_ACT_RELU ? EPI_ACT_RELU : EPI_ACT_GELU;
+  for (int u = sh0.u1 - 1; u >= sh0.u0; --u) {
+    const int N = u < L ? a.d_model : a.n_out;     // width of dz_u
+    const int Kin = u == 0 ? a.d_in : a.d_model;   // width of x_u
+    const int lddz = u < L ? ldd : ldv;
+    // weight gradient: dW[N, Kin] = sum_m dz[m, N] x[m, Kin]
+    GemmArgs w{};
+    w.dtype = bf ? GEMM_BF16 : GEMM_F32;
+    w.M = N;
+    w.N = Kin;
+    w.K = c->B;
+    w.x_kmajor = w.w_kmajor = 0;
+    w.ldx = lddz;
+    w.ldw = u == 0 ? c->ld_in : ldd;
+    w.G = G;
+    w.ldo = W_of(m0, u).cols;
+    w.act = EPI_ACT_NONE;
+    w.out_f32 = 1;
+    ColsumArgs cs{};
+    cs.dtype = w.dtype;
+    cs.M = c->B;
+    cs.N = N;
+    cs.ld = lddz;
+    cs.G = G;
+    for (int i = 0; i < G; ++i) {
+      const Model& m = c->models[b.members[i].first];
+      const Shard& sh = m.shards[b.members[i].second];
+      const void* dz = u < L ? m.mlp.dz[u] : m.mlp.dlogits;
+      w.X[i] = dz;
+      w.W[i] = u == 0 ? static_cast<const char*>(c->x_staged) + (size_t)batch * c->B * c->ld_in * es : m.mlp.h[u - 1];
+      w.out[i] = at(sh.g, sh, W_of(m, u));
+      cs.src[i] = dz;
+      cs.out[i] = at(sh.g, sh, b_of(m, u));
+    }
+    HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, s, 2.0 * w.M * w.N * w.K * G, 0.0, launch_gemm(w, s));
+    HYDRA_LAUNCH(c, HYDRA_K_COLSUM, s, 0.0, (double)G * cs.M * cs.N * es, launch_colsum(cs, s));
+    if (u == 0) continue;
+    // input gradient through the previous activation: dz_{u-1}[B, Kin] = (dz_u W_u) * act'(z_{u-1})
+    GemmArgs d{};
+    d.dtype = w.dtype;
+    d.M = c->B;
+    d.N = Kin;
+    d.K = N;
+    d.x_kmajor = 1;
+    d.w_kmajor = 0;
+    d.ldx = lddz;
+    d.ldw = W_of(m0, u).cols;
+    d.G = G;
+    d.ldo = d.ldg = ldd;
+    d.act = act;
+    for (int i = 0; i < G; ++i) {
+      const Model& m = c->models[b.members[i].first];
+      const Shard& sh = m.shards[b.members[i].second];
+      d.X[i] = u < L ? m.mlp.dz[u] : m.mlp.dlogits;
+      d.W[i] = bf ? (const void*)at(sh.w16, sh, W_of(m, u)) : (const void*)at(sh.p, sh, W_of(m, u));
+      d.out[i] = m.mlp.dz[u - 1];
+      d.gate[i] = m.mlp.z[u - 1];
+    }
+    HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, 2.0 * d.M * d.N * d.K * G, 0.0, launch_gemm(d, s));
+  }
+  return HYDRA_OK;
+}
+
+hydra_status fill_optim(hydra_ctx* c, const Bucket& b, int step, OptimArgs& o) {
+  o = OptimArgs{};
+  o.G = (int)b.members.size();
+  const Model& m0 = c->models[b.members[0].first];
+  o.opt = m0.hp.opt == HYDRA_OPT_ADAM ? 1 : 0;
+  o.n = m0.shards[b.members[0].second].n;
+  for (int i = 0; i < o.G; ++i) {
+    const Model& m = c->models[b.members[i].first];
+    const Shard& sh = m.shards[b.members[i].second];
+    if ((m.hp.opt == HYDRA_OPT_ADAM) != (o.opt == 1) || sh.n != o.n)
+      return c->fail(HYDRA_ERR_BAD_STATE, "launch group mixes optimizers or shard sizes");
+    const long t = m.t + step + 1;
+    const double lr = m.hp.warmup_steps > 0 ? m.hp.lr * std::min(1.0, (double)t / m.hp.warmup_steps) : m.hp.lr;
+    o.p[i] = sh.p;
+    o.g[i] = sh.g;
+    o.m[i] = sh.m;
+    o.v[i] = sh.v;
+    o.w16[i] = sh.w16;
+    o.lr[i] = (float)lr;
+    o.b1[i] = (float)m.hp.beta1;
+    o.b2[i] = (float)m.hp.beta2;
+    o.c1[i] = (float)(1.0 - m.hp.beta1);
+    o.c2[i] = (float)(1.0 - m.hp.beta2);
+    o.eps[i] = (float)m.hp.eps;
+    o.bc1[i] = (float)(1.0 / (1.0 - std::pow(m.hp.beta1, (double)t)));
+    o.bc2[i] = (float)(1.0 / (1.0 - std::pow(m.hp.beta2, (double)t)));
+  }
+  return HYDRA_OK;
+}
+
+hydra_status mlp_run(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
+  if (b.ph == HYDRA_PHASE_F) return mlp_forward(c, b, batch, step, s);
+  if (b.ph == HYDRA_PHASE_B) return mlp_backward(c, b, batch, s);
+  OptimArgs o;
+  hydra_status st = fill_optim(c, b, step, o);
+  if (st != HYDRA_OK) return st;
+  // algorithmic traffic per parameter: SGD reads p,g and writes p (12 B); Adam reads p,g,m,v and writes
+  // p,m,v (28 B); the bf16 working copy adds 2 B
+  const double per = (o.opt == 1 ? 28.0 : 12.0) + (o.w16[0] ? 2.0 : 0.0);
+  HYDRA_LAUNCH(c, HYDRA_K_OPTIM, s, 0.0, per * (double)o.n * o.G, launch_optim(o, s));
+  return HYDRA_OK;
+}
+
+}  // namespace hydra

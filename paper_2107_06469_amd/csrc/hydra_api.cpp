@@ -1,0 +1,361 @@
+// The C boundary declared in include/hydra.h: argument checking, call-order checking and copies
+// between caller memory and the device.  No exception leaves these functions.
+#include <cstring>
+#include <new>
+
+#include "hydra_internal.h"
+
+using namespace hydra;
+
+static std::string g_create_error;
+
+#define HYDRA_TRY try {
+#define HYDRA_CATCH(c)                                                          \
+  }                                                                             \
+  catch (const std::bad_alloc&) { return (c)->fail(HYDRA_ERR_OOM_HOST, "host allocation failed"); } \
+  catch (const std::exception& e) { return (c)->fail(HYDRA_ERR_DEVICE, "internal error: %s", e.what()); }
+
+extern "C" {
+
+hydra_status hydra_create(const hydra_options* opts, hydra_ctx** out) {
+  if (!out) {
+    g_create_error = "hydra_create: out is NULL";
+    return HYDRA_ERR_INVALID_ARG;
+  }
+  hydra_ctx* c = nullptr;
+  try {
+    c = new hydra_ctx();
+  } catch (...) {
+    g_create_error = "hydra_create: host allocation failed";
+    return HYDRA_ERR_OOM_HOST;
+  }
+  if (opts) c->opt = *opts;
+  c->dry = c->opt.dry_run != 0;
+  if (c->opt.n_streams < 0 || (c->opt.n_streams > 0 && !c->opt.streams && !c->dry) ||
+      ((c->opt.dev_alloc == nullptr) != (c->opt.dev_free == nullptr))) {
+    g_create_error = "hydra_create: inconsistent options (streams / allocator callbacks)";
+    delete c;
+    return HYDRA_ERR_INVALID_ARG;
+  }
+  if (!c->dry) {
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+      g_create_error = "hydra_create: no HIP device is available (use dry_run for planning without a device)";
+      delete c;
+      return HYDRA_ERR_DEVICE;
+    }
+    hipError_t e = gemm_init();
+    if (e != hipSuccess) {
+      g_create_error = std::string("hydra_create: kernel set-up failed: ") + hipGetErrorString(e);
+      delete c;
+      return HYDRA_ERR_DEVICE;
+    }
+    if (c->opt.n_streams > 0) {
+      for (int i = 0; i < c->opt.n_streams; ++i) c->streams.push_back(static_cast<hipStream_t>(c->opt.streams[i]));
+    } else {
+      c->own_streams = true;
+      for (int i = 0; i < 4; ++i) {
+        hipStream_t s;
+        if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) {
+          g_create_error = "hydra_create: stream creation failed";
+          delete c;
+          return HYDRA_ERR_DEVICE;
+        }
+        c->streams.push_back(s);
+      }
+    }
+  }
+  *out = c;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_destroy(hydra_ctx* c) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  if (!c->dry) {
+    for (hipStream_t s : c->streams) (void)hipStreamSynchronize(s);
+    for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
+    ctx_free_all(c);
+    if (c->own_streams)
+      for (hipStream_t s : c->streams) (void)hipStreamDestroy(s);
+  }
+  delete c;
+  return HYDRA_OK;
+}
+
+const char* hydra_last_error(const hydra_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+static hydra_status check_arch(hydra_ctx* c, const hydra_arch& a, int i) {
+  if (a.kind < 0 || a.kind > 2) return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: unknown kind %d", i, a.kind);
+  if (a.dtype != HYDRA_DTYPE_F32 && a.dtype != HYDRA_DTYPE_BF16) return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: unknown dtype", i);
+  if (a.n_layers < (a.kind == HYDRA_KIND_MLP ? 0 : 1) || a.d_model < 1 || a.n_out < 1)
+    return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: n_layers, d_model and n_out must be positive", i);
+  if (a.d_model % 8) return c->fail(HYDRA_ERR_UNSUPPORTED, "arch %d: d_model must be a multiple of 8", i);
+  if (a.kind == HYDRA_KIND_MLP) {
+    if (a.d_in < 1 || a.d_in % 8) return c->fail(HYDRA_ERR_UNSUPPORTED, "arch %d: d_in must be a positive multiple of 8", i);
+    if (a.act != HYDRA_ACT_RELU && a.act != HYDRA_ACT_GELU) return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: unknown activation", i);
+  } else {
+    if (a.n_heads < 1 || a.d_model % a.n_heads) return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: n_heads must divide d_model", i);
+    if (a.d_ffn < 1 || a.d_ffn % 8) return c->fail(HYDRA_ERR_UNSUPPORTED, "arch %d: d_ffn must be a positive multiple of 8", i);
+    if (a.max_seq < 1) return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: max_seq must be positive", i);
+    if ((a.kind == HYDRA_KIND_DECODER) != (a.causal != 0))
+      return c->fail(HYDRA_ERR_INVALID_ARG, "arch %d: decoders are causal, encoders are not", i);
+  }
+  return HYDRA_OK;
+}
+
+hydra_status hydra_define_models(hydra_ctx* c, int K, const hydra_arch* archs, int n_archs, const hydra_hparams* grid,
+                                 uint64_t seed) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state != ST_CREATED) return c->fail(HYDRA_ERR_BAD_STATE, "models are already defined");
+  if (K < 1 || !archs || !grid || (n_archs != 1 && n_archs != K))
+    return c->fail(HYDRA_ERR_INVALID_ARG, "need K >= 1, archs with 1 or K entries and a grid with K entries");
+  for (int i = 0; i < n_archs; ++i) {
+    hydra_status st = check_arch(c, archs[i], i);
+    if (st != HYDRA_OK) return st;
+    if (archs[i].kind != archs[0].kind || archs[i].dtype != archs[0].dtype)
+      return c->fail(HYDRA_ERR_UNSUPPORTED, "all models of a context must share kind and dtype");
+  }
+  for (int k = 0; k < K; ++k) {
+    const hydra_hparams& h = grid[k];
+    if (h.opt != HYDRA_OPT_SGD && h.opt != HYDRA_OPT_ADAM) return c->fail(HYDRA_ERR_INVALID_ARG, "grid %d: unknown optimizer", k);
+    if (!(h.lr >= 0.0) || h.warmup_steps < 0) return c->fail(HYDRA_ERR_INVALID_ARG, "grid %d: lr and warmup must be >= 0", k);
+    if (h.opt == HYDRA_OPT_ADAM && !(h.beta1 >= 0 && h.beta1 < 1 && h.beta2 >= 0 && h.beta2 < 1 && h.eps >= 0))
+      return c->fail(HYDRA_ERR_INVALID_ARG, "grid %d: Adam needs 0 <= beta < 1 and eps >= 0", k);
+  }
+  c->K = K;
+  c->seed = seed;
+  c->models.assign(K, Model());
+  for (int k = 0; k < K; ++k) {
+    Model& m = c->models[k];
+    m.arch = archs[n_archs == 1 ? 0 : k];
+    m.hp = grid[k];
+    hydra_status st = build_tensors(c, m);
+    if (st == HYDRA_OK) st = cut_model(c, m, nullptr, 0);
+    if (st != HYDRA_OK) {
+      c->models.clear();
+      return st;
+    }
+  }
+  hydra_status st = alloc_models(c);
+  if (st != HYDRA_OK) {
+    ctx_free_all(c);
+    c->models.clear();
+    return st;
+  }
+  for (Model& m : c->models)
+    for (Shard& sh : m.shards) {  // re-point after allocation
+      sh.p = m.p ? m.p + sh.off : nullptr;
+      sh.m = m.m ? m.m + sh.off : nullptr;
+      sh.v = m.v ? m.v + sh.off : nullptr;
+      sh.g = m.g ? m.g + sh.off : nullptr;
+      sh.w16 = m.w16 ? m.w16 + sh.off : nullptr;
+    }
+  c->state = ST_DEFINED;
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_shard(hydra_ctx* c, int model, const int32_t* cuts, int n_cuts) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "define models before sharding them");
+  if (model < -1 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  if (n_cuts < 0 || (n_cuts > 0 && !cuts)) return c->fail(HYDRA_ERR_INVALID_ARG, "n_cuts < 0 or cuts is NULL");
+  // validate every affected model before changing any
+  for (int k = 0; k < c->K; ++k) {
+    if (model != -1 && model != k) continue;
+    Model tmp = c->models[k];
+    hydra_status st = cut_model(c, tmp, cuts, n_cuts);
+    if (st != HYDRA_OK) return st;
+  }
+  for (int k = 0; k < c->K; ++k)
+    if (model == -1 || model == k) cut_model(c, c->models[k], cuts, n_cuts);
+  if (c->state < ST_SHARDED) c->state = ST_SHARDED;
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_set_data(hydra_ctx* c, const void* inputs, const int32_t* tgt_pos, const int32_t* targets, int n_batches,
+                            int B, int S_or_d, int P) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_SHARDED) return c->fail(HYDRA_ERR_BAD_STATE, "shard the models before setting data");
+  if (!inputs || !targets || n_batches < 1 || B < 1) return c->fail(HYDRA_ERR_INVALID_ARG, "inputs/targets NULL or empty");
+  const hydra_arch& a = c->models[0].arch;
+  if (c->state == ST_DATA) {  // replacing the data set: batch geometry must stay (activations are sized by it)
+    if (B != c->B || (a.kind != HYDRA_KIND_MLP && (S_or_d != c->S || P != c->P)))
+      return c->fail(HYDRA_ERR_INVALID_ARG, "new data must keep the batch size (and sequence / target counts)");
+    for (hipStream_t st : c->streams) HYDRA_HIP(c, hipStreamSynchronize(st));
+    ctx_free(c, c->x_staged, c->x_bytes);
+    ctx_free(c, c->ids, c->ids_bytes);
+    ctx_free(c, c->tgt_pos, c->tp_bytes);
+    ctx_free(c, c->targets, c->tg_bytes);
+    c->x_staged = nullptr;
+    c->ids = c->tgt_pos = c->targets = nullptr;
+  }
+  c->n_batches = n_batches;
+  c->B = B;
+  hipStream_t s = c->dry ? nullptr : c->streams[0];
+  if (a.kind == HYDRA_KIND_MLP) {
+    if (S_or_d != a.d_in || P != 0 || tgt_pos) return c->fail(HYDRA_ERR_INVALID_ARG, "MLP data: S_or_d must equal d_in, P = 0, target_pos NULL");
+    const size_t rows = (size_t)n_batches * B;
+    for (size_t i = 0; i < rows; ++i)
+      if (targets[i] < 0 || targets[i] >= a.n_out) return c->fail(HYDRA_ERR_INVALID_ARG, "target %zu out of range", i);
+    const bool bf = a.dtype == HYDRA_DTYPE_BF16;
+    c->ld_in = a.d_in;
+    c->x_bytes = rows * c->ld_in * (bf ? 2 : 4);
+    c->tg_bytes = rows * 4;
+    c->x_staged = ctx_alloc(c, c->x_bytes);
+    c->targets = static_cast<int32_t*>(ctx_alloc(c, c->tg_bytes));
+    if (!c->dry) {
+      if (!c->x_staged || !c->targets) return c->fail(HYDRA_ERR_OOM_DEVICE, "device allocation for the data failed");
+      float* tmp = static_cast<float*>(ctx_alloc(c, rows * a.d_in * 4));
+      if (!tmp) return c->fail(HYDRA_ERR_OOM_DEVICE, "device allocation for the data failed");
+      HYDRA_HIP(c, hipMemcpyAsync(tmp, inputs, rows * a.d_in * 4, hipMemcpyHostToDevice, s));
+      HYDRA_HIP(c, hipMemcpyAsync(c->targets, targets, rows * 4, hipMemcpyHostToDevice, s));
+      HYDRA_HIP(c, launch_stage_rows(tmp, c->x_staged, (int)rows, a.d_in, c->ld_in, bf ? 1 : 0, s));
+      HYDRA_HIP(c, hipStreamSynchronize(s));
+      ctx_free(c, tmp, rows * a.d_in * 4);
+    }
+  } else {
+    return c->fail(HYDRA_ERR_UNSUPPORTED, "Transformer models are not implemented yet");
+  }
+  hydra_status st = alloc_activations(c);
+  if (st != HYDRA_OK) return st;
+  c->state = ST_DATA;
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_train_epoch(hydra_ctx* c, const hydra_schedule* sch, hydra_epoch_stats* stats) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state != ST_DATA) return c->fail(HYDRA_ERR_BAD_STATE, "set the data before training");
+  if (!sch) return c->fail(HYDRA_ERR_INVALID_ARG, "schedule is NULL");
+  std::vector<Bucket> plan;
+  hydra_status st = build_plan(c, sch, plan);
+  if (st != HYDRA_OK) return st;
+  hydra_epoch_stats local{};
+  st = run_epoch(c, plan, &local);
+  if (st != HYDRA_OK) return st;
+  for (Model& m : c->models) m.t += c->n_batches;
+  if (stats) *stats = local;
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+static hydra_status copy_out(hydra_ctx* c, int model, int tensor, float* dst, size_t cap, size_t* n_written, bool grads) {
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  Model& m = c->models[model];
+  const int nt = (int)m.tensors.size();
+  if (tensor < -1 || tensor >= nt) return c->fail(HYDRA_ERR_INVALID_ARG, "tensor %d does not exist", tensor);
+  size_t need = 0;
+  for (int j = 0; j < nt; ++j)
+    if (tensor == -1 || tensor == j) need += m.tensors[j].n;
+  if (!n_written) return c->fail(HYDRA_ERR_INVALID_ARG, "n_written is NULL");
+  if (cap < need || !dst) {
+    *n_written = need;
+    return c->fail(HYDRA_ERR_BUFFER_TOO_SMALL, "need room for %zu floats, got %zu", need, cap);
+  }
+  if (c->dry) return c->fail(HYDRA_ERR_BAD_STATE, "a dry-run context holds no values");
+  for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  const float* src = grads ? m.g : m.p;
+  size_t o = 0;
+  for (int j = 0; j < nt; ++j) {
+    if (tensor != -1 && tensor != j) continue;
+    HYDRA_HIP(c, hipMemcpy(dst + o, src + m.tensors[j].off, m.tensors[j].n * 4, hipMemcpyDeviceToHost));
+    o += m.tensors[j].n;
+  }
+  *n_written = need;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_read_params(hydra_ctx* c, int model, int tensor, float* dst, size_t cap, size_t* n_written) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  return copy_out(c, model, tensor, dst, cap, n_written, false);
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_read_grads(hydra_ctx* c, int model, int tensor, float* dst, size_t cap, size_t* n_written) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  return copy_out(c, model, tensor, dst, cap, n_written, true);
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_write_params(hydra_ctx* c, int model, int tensor, const float* src, size_t n) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  Model& m = c->models[model];
+  const int nt = (int)m.tensors.size();
+  if (tensor < -1 || tensor >= nt || !src) return c->fail(HYDRA_ERR_INVALID_ARG, "tensor %d does not exist or src is NULL", tensor);
+  size_t need = 0;
+  for (int j = 0; j < nt; ++j)
+    if (tensor == -1 || tensor == j) need += m.tensors[j].n;
+  if (n != need) return c->fail(HYDRA_ERR_INVALID_ARG, "expected %zu floats, got %zu", need, n);
+  if (c->dry) return HYDRA_OK;
+  for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  size_t o = 0;
+  for (int j = 0; j < nt; ++j) {
+    if (tensor != -1 && tensor != j) continue;
+    const Tensor& t = m.tensors[j];
+    HYDRA_HIP(c, hipMemcpy(m.p + t.off, src + o, t.n * 4, hipMemcpyHostToDevice));
+    if (m.w16) HYDRA_HIP(c, launch_cast_bf16(m.p + t.off, m.w16 + t.off, t.n, c->streams[0]));
+    o += t.n;
+  }
+  HYDRA_HIP(c, hipStreamSynchronize(c->streams[0]));
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_read_loss(hydra_ctx* c, int model, float* dst, size_t cap, size_t* n_written) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  if (!n_written) return c->fail(HYDRA_ERR_INVALID_ARG, "n_written is NULL");
+  const std::vector<float>& l = c->models[model].losses;
+  if (cap < l.size() || (!dst && !l.empty())) {
+    *n_written = l.size();
+    return c->fail(HYDRA_ERR_BUFFER_TOO_SMALL, "need room for %zu floats, got %zu", l.size(), cap);
+  }
+  if (!l.empty()) memcpy(dst, l.data(), l.size() * 4);
+  *n_written = l.size();
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_tensor_count(hydra_ctx* c, int model, int* n_tensors) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K || !n_tensors) return c->fail(HYDRA_ERR_INVALID_ARG, "bad model or NULL output");
+  *n_tensors = (int)c->models[model].tensors.size();
+  return HYDRA_OK;
+}
+
+hydra_status hydra_tensor_shape(hydra_ctx* c, int model, int tensor, int* rows, int* cols) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K || !rows || !cols) return c->fail(HYDRA_ERR_INVALID_ARG, "bad model or NULL output");
+  const Model& m = c->models[model];
+  if (tensor < 0 || tensor >= (int)m.tensors.size()) return c->fail(HYDRA_ERR_INVALID_ARG, "tensor %d does not exist", tensor);
+  *rows = m.tensors[tensor].rows;
+  *cols = m.tensors[tensor].cols;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_shard_count(hydra_ctx* c, int model, int* n_shards) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K || !n_shards) return c->fail(HYDRA_ERR_INVALID_ARG, "bad model or NULL output");
+  *n_shards = (int)c->models[model].shards.size();
+  return HYDRA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,171 @@
+// Host-side structures of the shard-parallel trainer (not part of the C boundary).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <map>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "../../include/hydra.h"
+#include "kernels.h"
+
+namespace hydra {
+
+enum { INIT_ZERO = 0, INIT_ONE = 1, INIT_UNIFORM = 2 };
+
+struct Tensor {
+  std::string name;
+  int rows = 0, cols = 0;  // vectors: rows = 1
+  size_t n = 0;            // rows * cols
+  int init = INIT_ZERO;
+  float a = 0.f;           // bound of the uniform init
+  int unit = 0;            // layer unit that owns it
+  size_t off = 0;          // element offset inside the model's parameter block (64-element aligned)
+};
+
+// A shard: layer units [u0, u1) of one model (paper, Introduction: a contiguous piece of the model)
+// with the parameters, gradients and optimizer state of those units.  Tensors of a shard are a
+// contiguous range of the model's canonical order, so its state is one contiguous block.
+struct Shard {
+  int u0 = 0, u1 = 0;
+  int t0 = 0, t1 = 0;      // tensor range [t0, t1)
+  size_t off = 0, n = 0;   // element range inside the model block (n is a multiple of 64)
+  uint64_t sig = 0;        // shape signature: shards with equal signatures can share a grouped launch
+  // device pointers of the shard's state (null while spilled)
+  float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
+  bf16_t* w16 = nullptr;
+};
+
+struct MlpActs {                // per model, allocated by set_data
+  std::vector<void*> z, h, dz;  // per hidden unit: pre-activation, activation, gradient w.r.t. z  [B, ldd]
+  float* logits = nullptr;      // [B, ldv] fp32
+  void* dlogits = nullptr;      // [B, ldv] operand dtype
+  float* rowloss = nullptr;     // [B]
+};
+
+struct Model {
+  hydra_arch arch{};
+  hydra_hparams hp{};
+  std::vector<Tensor> tensors;
+  size_t n_block = 0;           // padded elements of the whole parameter block
+  std::vector<Shard> shards;
+  int n_units = 0;
+  // whole-model state blocks (resident mode): shards point into these
+  float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
+  bf16_t* w16 = nullptr;
+  MlpActs mlp;
+  float* loss_dev = nullptr;    // one float per step of the current epoch
+  int loss_cap = 0;
+  std::vector<float> losses;    // all steps so far (host)
+  long t = 0;                   // optimizer steps taken
+};
+
+struct Task {
+  int k, s, ph;
+  bool operator<(const Task& o) const { return k != o.k ? k < o.k : (s != o.s ? s < o.s : ph < o.ph); }
+  bool operator==(const Task& o) const { return k == o.k && s == o.s && ph == o.ph; }
+};
+
+// A launch group: same phase, same shard signature, different models.
+struct Bucket {
+  int ph = 0;
+  std::vector<std::pair<int, int>> members;  // (model, shard)
+  int stream = 0;
+};
+
+enum State { ST_CREATED = 0, ST_DEFINED = 1, ST_SHARDED = 2, ST_DATA = 3 };
+
+}  // namespace hydra
+
+struct hydra_ctx {
+  hydra_options opt{};
+  bool dry = false;
+  int state = hydra::ST_CREATED;
+  std::string err;
+  int K = 0;
+  uint64_t seed = 0;
+  std::vector<hydra::Model> models;
+  // data (device)
+  int n_batches = 0, B = 0, S = 0, P = 0, ld_in = 0;
+  size_t x_bytes = 0, ids_bytes = 0, tp_bytes = 0, tg_bytes = 0;
+  void* x_staged = nullptr;      // MLP: [n_batches, B, ld_in] operand dtype
+  int32_t* ids = nullptr;        // Transformer: [n_batches, B, S]
+  int32_t* tgt_pos = nullptr;    // [n_batches, B, P]
+  int32_t* targets = nullptr;    // [n_batches, B] or [n_batches, B, P]
+  bool acts_ready = false;
+  // streams / events
+  std::vector<hipStream_t> streams;
+  bool own_streams = false;
+  std::vector<hipEvent_t> events;
+  // allocations
+  std::vector<void*> dev_allocs;
+  size_t dev_bytes = 0, peak_dev_bytes = 0;
+  // accounting of the running epoch
+  uint64_t launches = 0, grouped_tasks = 0;
+  // optional per-launch timing (hydra_profile_enable): event pairs on the launching stream
+  bool profiling = false;
+  struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_pool;
+  size_t prof_used = 0;
+  struct ProfSum { uint64_t launches = 0; double ms = 0, flops = 0, bytes = 0; };
+  ProfSum prof_sum[HYDRA_K_COUNT];
+
+  hydra_status fail(hydra_status st, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    err = buf;
+    return st;
+  }
+};
+
+namespace hydra {
+
+// models.cpp
+hydra_status build_tensors(hydra_ctx* c, Model& m);
+hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts);
+hydra_status alloc_models(hydra_ctx* c);
+hydra_status alloc_activations(hydra_ctx* c);
+void* ctx_alloc(hydra_ctx* c, size_t bytes);  // nullptr on failure (or in dry-run, where only bytes are counted)
+void ctx_free(hydra_ctx* c, void* p, size_t bytes);
+void ctx_free_all(hydra_ctx* c);
+
+// scheduler.cpp
+hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan);
+hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoch_stats* stats);
+
+// exec_mlp.cpp
+hydra_status mlp_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch, hipStream_t s);
+
+#define HYDRA_HIP(c, expr)                                                                              \
+  do {                                                                                                  \
+    hipError_t e_ = (expr);                                                                             \
+    if (e_ != hipSuccess) return (c)->fail(HYDRA_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// profile.cpp: event pair around one launch when profiling is on
+hipError_t prof_begin(hydra_ctx* c, hipStream_t s, hipEvent_t* a);
+hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double flops, double bytes);
+hydra_status prof_collect(hydra_ctx* c);  // after the streams have drained
+
+// a kernel launch of class `cls` on stream `s` doing `flops` / moving `bytes` of algorithmic work:
+// counted always, executed unless the context is a dry run, timed when profiling is on
+#define HYDRA_LAUNCH(c, cls, s, flops, bytes, expr)                                                     \
+  do {                                                                                                  \
+    ++(c)->launches;                                                                                    \
+    if (!(c)->dry) {                                                                                    \
+      hipEvent_t pa_ = nullptr;                                                                         \
+      hipError_t e_ = (c)->profiling ? prof_begin(c, s, &pa_) : hipSuccess;                             \
+      if (e_ == hipSuccess) e_ = (expr);                                                                \
+      if (e_ == hipSuccess && (c)->profiling) e_ = prof_end(c, s, pa_, cls, flops, bytes);              \
+      if (e_ != hipSuccess) return (c)->fail(HYDRA_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+    }                                                                                                   \
+  } while (0)
+
+}  // namespace hydra

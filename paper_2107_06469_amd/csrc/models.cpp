@@ -1,0 +1,242 @@
+// Model registry: canonical tensor lists, shard cutting, device state and seeded initialisation.
+#include <cmath>
+#include <cstring>
+
+#include "hydra_internal.h"
+
+namespace hydra {
+
+static size_t rup(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static void add_tensor(Model& m, const std::string& name, int rows, int cols, int init, float a, int unit) {
+  Tensor t;
+  t.name = name;
+  t.rows = rows;
+  t.cols = cols;
+  t.n = (size_t)rows * cols;
+  t.init = init;
+  t.a = a;
+  t.unit = unit;
+  t.off = m.n_block;
+  m.n_block += rup(t.n, 64);
+  m.tensors.push_back(t);
+}
+
+hydra_status build_tensors(hydra_ctx* c, Model& m) {
+  const hydra_arch& a = m.arch;
+  m.tensors.clear();
+  m.n_block = 0;
+  if (a.kind == HYDRA_KIND_MLP) {
+    int prev = a.d_in;
+    for (int l = 0; l < a.n_layers; ++l) {
+      add_tensor(m, "W" + std::to_string(l), a.d_model, prev, INIT_UNIFORM, (float)std::sqrt(6.0 / prev), l);
+      add_tensor(m, "b" + std::to_string(l), 1, a.d_model, INIT_ZERO, 0.f, l);
+      prev = a.d_model;
+    }
+    add_tensor(m, "Wout", a.n_out, prev, INIT_UNIFORM, (float)std::sqrt(6.0 / prev), a.n_layers);
+    add_tensor(m, "bout", 1, a.n_out, INIT_ZERO, 0.f, a.n_layers);
+    m.n_units = a.n_layers + 1;
+    return HYDRA_OK;
+  }
+  const int d = a.d_model, F = a.d_ffn, V = a.n_out, S = a.max_seq, L = a.n_layers;
+  const float s02 = (float)(0.02 * std::sqrt(3.0));
+  add_tensor(m, "tok_emb", V, d, INIT_UNIFORM, s02, 0);
+  add_tensor(m, "pos_emb", S, d, INIT_UNIFORM, s02, 0);
+  for (int l = 0; l < L; ++l) {
+    std::string p = "L" + std::to_string(l) + ".";
+    add_tensor(m, p + "ln1.g", 1, d, INIT_ONE, 0.f, l);
+    add_tensor(m, p + "ln1.b", 1, d, INIT_ZERO, 0.f, l);
+    add_tensor(m, p + "Wqkv", 3 * d, d, INIT_UNIFORM, s02, l);
+    add_tensor(m, p + "bqkv", 1, 3 * d, INIT_ZERO, 0.f, l);
+    add_tensor(m, p + "Wo", d, d, INIT_UNIFORM, s02, l);
+    add_tensor(m, p + "bo", 1, d, INIT_ZERO, 0.f, l);
+    add_tensor(m, p + "ln2.g", 1, d, INIT_ONE, 0.f, l);
+    add_tensor(m, p + "ln2.b", 1, d, INIT_ZERO, 0.f, l);
+    add_tensor(m, p + "W1", F, d, INIT_UNIFORM, s02, l);
+    add_tensor(m, p + "b1", 1, F, INIT_ZERO, 0.f, l);
+    if (a.ffn_gated) {
+      add_tensor(m, p + "Wg", F, d, INIT_UNIFORM, s02, l);
+      add_tensor(m, p + "bg", 1, F, INIT_ZERO, 0.f, l);
+    }
+    add_tensor(m, p + "W2", d, F, INIT_UNIFORM, s02, l);
+    add_tensor(m, p + "b2", 1, d, INIT_ZERO, 0.f, l);
+  }
+  add_tensor(m, "lnf.g", 1, d, INIT_ONE, 0.f, L - 1);
+  add_tensor(m, "lnf.b", 1, d, INIT_ZERO, 0.f, L - 1);
+  add_tensor(m, "Whead", V, d, INIT_UNIFORM, s02, L - 1);
+  add_tensor(m, "bhead", 1, V, INIT_ZERO, 0.f, L - 1);
+  m.n_units = L;
+  (void)c;
+  return HYDRA_OK;
+}
+
+static uint64_t mix_sig(uint64_t h, uint64_t v) {
+  h ^= v + 0x9E3779B97F4A7C15ull + (h << 6) + (h >> 2);
+  return h;
+}
+
+static void point_shard(Model& m, Shard& sh) {
+  sh.p = m.p ? m.p + sh.off : nullptr;
+  sh.m = m.m ? m.m + sh.off : nullptr;
+  sh.v = m.v ? m.v + sh.off : nullptr;
+  sh.g = m.g ? m.g + sh.off : nullptr;
+  sh.w16 = m.w16 ? m.w16 + sh.off : nullptr;
+}
+
+hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts) {
+  const int U = m.n_units;
+  std::vector<int> b{0};
+  for (int i = 0; i < n_cuts; ++i) {
+    if (cuts[i] <= b.back() || cuts[i] >= U)
+      return c->fail(HYDRA_ERR_INVALID_ARG, "cut %d (= %d) must be strictly increasing and inside (0, %d)", i, cuts[i], U);
+    b.push_back(cuts[i]);
+  }
+  b.push_back(U);
+  m.shards.clear();
+  const int nt = (int)m.tensors.size();
+  for (size_t s = 0; s + 1 < b.size(); ++s) {
+    Shard sh;
+    sh.u0 = b[s];
+    sh.u1 = b[s + 1];
+    // tensors of units [u0,u1) form a contiguous range of the canonical order
+    sh.t0 = nt;
+    sh.t1 = 0;
+    for (int j = 0; j < nt; ++j)
+      if (m.tensors[j].unit >= sh.u0 && m.tensors[j].unit < sh.u1) {
+        if (j < sh.t0) sh.t0 = j;
+        if (j + 1 > sh.t1) sh.t1 = j + 1;
+      }
+    sh.off = m.tensors[sh.t0].off;
+    sh.n = (sh.t1 < nt ? m.tensors[sh.t1].off : m.n_block) - sh.off;
+    const hydra_arch& a = m.arch;
+    uint64_t h = 0x1234;
+    for (uint64_t v : {(uint64_t)a.kind, (uint64_t)a.dtype, (uint64_t)a.d_model, (uint64_t)a.n_heads, (uint64_t)a.d_ffn,
+                       (uint64_t)a.n_out, (uint64_t)a.ffn_gated, (uint64_t)a.causal, (uint64_t)a.act, (uint64_t)a.max_seq,
+                       (uint64_t)(sh.u1 - sh.u0), (uint64_t)(sh.u0 == 0), (uint64_t)(sh.u1 == U),
+                       (uint64_t)(sh.u0 == 0 ? a.d_in : 0)})
+      h = mix_sig(h, v);
+    sh.sig = h;
+    point_shard(m, sh);
+    m.shards.push_back(sh);
+  }
+  return HYDRA_OK;
+}
+
+void* ctx_alloc(hydra_ctx* c, size_t bytes) {
+  bytes = rup(bytes ? bytes : 1, 256);
+  c->dev_bytes += bytes;
+  if (c->dev_bytes > c->peak_dev_bytes) c->peak_dev_bytes = c->dev_bytes;
+  if (c->dry) return nullptr;
+  void* p = nullptr;
+  if (c->opt.dev_alloc) p = c->opt.dev_alloc(bytes, c->opt.user);
+  else if (hipMalloc(&p, bytes) != hipSuccess) p = nullptr;
+  if (p) c->dev_allocs.push_back(p);
+  return p;
+}
+
+void ctx_free(hydra_ctx* c, void* p, size_t bytes) {
+  if (!p) {
+    if (c->dry) c->dev_bytes -= rup(bytes ? bytes : 1, 256);
+    return;
+  }
+  for (size_t i = 0; i < c->dev_allocs.size(); ++i)
+    if (c->dev_allocs[i] == p) {
+      c->dev_allocs.erase(c->dev_allocs.begin() + i);
+      if (c->opt.dev_free) c->opt.dev_free(p, c->opt.user);
+      else if (!c->opt.dev_alloc) (void)hipFree(p);
+      c->dev_bytes -= rup(bytes ? bytes : 1, 256);
+      return;
+    }
+}
+
+void ctx_free_all(hydra_ctx* c) {
+  for (void* p : c->dev_allocs) {
+    if (c->opt.dev_free) c->opt.dev_free(p, c->opt.user);
+    else if (!c->opt.dev_alloc) (void)hipFree(p);
+  }
+  c->dev_allocs.clear();
+  c->dev_bytes = 0;
+}
+
+// SplitMix64 (Steele, Lea, Flood 2014): n-th output from state s
+static uint64_t splitmix_at(uint64_t s, uint64_t n) {
+  uint64_t z = s + (n + 1) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+#define ALLOC_OR_FAIL(c, ptr, type, bytes)                                                       \
+  do {                                                                                           \
+    ptr = static_cast<type>(ctx_alloc(c, bytes));                                                \
+    if (!ptr && !(c)->dry) return (c)->fail(HYDRA_ERR_OOM_DEVICE, "device allocation of %zu bytes failed", (size_t)(bytes)); \
+  } while (0)
+
+hydra_status alloc_models(hydra_ctx* c) {
+  hipStream_t s = c->dry ? nullptr : c->streams[0];
+  for (int k = 0; k < c->K; ++k) {
+    Model& m = c->models[k];
+    const size_t n = m.n_block;
+    ALLOC_OR_FAIL(c, m.p, float*, n * 4);
+    ALLOC_OR_FAIL(c, m.g, float*, n * 4);
+    if (m.hp.opt == HYDRA_OPT_ADAM) {
+      ALLOC_OR_FAIL(c, m.m, float*, n * 4);
+      ALLOC_OR_FAIL(c, m.v, float*, n * 4);
+    }
+    if (m.arch.dtype == HYDRA_DTYPE_BF16) ALLOC_OR_FAIL(c, m.w16, bf16_t*, n * 2);
+    if (c->dry) continue;
+    HYDRA_HIP(c, launch_fill_f32(m.p, n, 0.f, s));
+    HYDRA_HIP(c, launch_fill_f32(m.g, n, 0.f, s));
+    if (m.m) HYDRA_HIP(c, launch_fill_f32(m.m, n, 0.f, s));
+    if (m.v) HYDRA_HIP(c, launch_fill_f32(m.v, n, 0.f, s));
+    for (size_t j = 0; j < m.tensors.size(); ++j) {
+      const Tensor& t = m.tensors[j];
+      if (t.init == INIT_ONE) HYDRA_HIP(c, launch_fill_f32(m.p + t.off, t.n, 1.f, s));
+      else if (t.init == INIT_UNIFORM) {
+        const uint64_t stream_id = ((uint64_t)k << 20) | (uint64_t)j;
+        const uint64_t key = splitmix_at(splitmix_at(c->seed, 0) ^ stream_id, 0);
+        HYDRA_HIP(c, launch_init_uniform(m.p + t.off, t.n, key, t.a, s));
+      }
+    }
+    if (m.w16) HYDRA_HIP(c, launch_cast_bf16(m.p, m.w16, n, s));
+  }
+  if (!c->dry) HYDRA_HIP(c, hipStreamSynchronize(s));
+  return HYDRA_OK;
+}
+
+hydra_status alloc_activations(hydra_ctx* c) {
+  for (int k = 0; k < c->K; ++k) {  // the loss buffer holds one float per step of an epoch
+    Model& m = c->models[k];
+    if (m.loss_cap >= c->n_batches) continue;
+    if (m.loss_cap) ctx_free(c, m.loss_dev, (size_t)m.loss_cap * 4);
+    ALLOC_OR_FAIL(c, m.loss_dev, float*, (size_t)c->n_batches * 4);
+    m.loss_cap = c->n_batches;
+  }
+  if (c->acts_ready) return HYDRA_OK;
+  for (int k = 0; k < c->K; ++k) {
+    Model& m = c->models[k];
+    const hydra_arch& a = m.arch;
+    const size_t es = a.dtype == HYDRA_DTYPE_BF16 ? 2 : 4;
+    if (a.kind == HYDRA_KIND_MLP) {
+      const size_t ldd = rup(a.d_model, 8), ldv = rup(a.n_out, 8);
+      MlpActs& t = m.mlp;
+      t.z.assign(a.n_layers, nullptr);
+      t.h.assign(a.n_layers, nullptr);
+      t.dz.assign(a.n_layers, nullptr);
+      for (int l = 0; l < a.n_layers; ++l) {
+        ALLOC_OR_FAIL(c, t.z[l], void*, (size_t)c->B * ldd * es);
+        ALLOC_OR_FAIL(c, t.h[l], void*, (size_t)c->B * ldd * es);
+        ALLOC_OR_FAIL(c, t.dz[l], void*, (size_t)c->B * ldd * es);
+      }
+      ALLOC_OR_FAIL(c, t.logits, float*, (size_t)c->B * ldv * 4);
+      ALLOC_OR_FAIL(c, t.dlogits, void*, (size_t)c->B * ldv * es);
+      ALLOC_OR_FAIL(c, t.rowloss, float*, (size_t)c->B * 4);
+    } else {
+      return c->fail(HYDRA_ERR_UNSUPPORTED, "Transformer models are not implemented yet");
+    }
+  }
+  c->acts_ready = true;
+  return HYDRA_OK;
+}
+
+}  // namespace hydra

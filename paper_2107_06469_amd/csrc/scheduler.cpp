@@ -1,0 +1,202 @@
+// Shard scheduler: turns a scheduling policy into an ordered list of launch groups for one step
+// and replays it for every step of an epoch on the context's streams.
+//
+// Tasks are F(k,s), B(k,s), U(k,s): forward, backward and update of shard s of model k.  Within a
+// step F(k,s) needs F(k,s-1); B(k,s) needs B(k,s+1), or F(k,S-1) for the last shard; U(k,s) needs
+// B(k,s).  Across steps F(k,s) needs the previous U(k,s).  Models never depend on each other, which
+// is what lets a shard of one model run while another model's next shard waits on its dependency
+// (paper, Introduction, "Model Selection Integration").  The order of a model's own tasks, and
+// hence every value it computes, is the same under every policy.
+#include <algorithm>
+#include <chrono>
+#include <set>
+
+#include "hydra_internal.h"
+
+namespace hydra {
+
+static std::vector<Task> preds_of(const hydra_ctx* c, const Task& t) {
+  const int S = (int)c->models[t.k].shards.size();
+  std::vector<Task> p;
+  if (t.ph == HYDRA_PHASE_F) {
+    if (t.s > 0) p.push_back({t.k, t.s - 1, HYDRA_PHASE_F});
+  } else if (t.ph == HYDRA_PHASE_B) {
+    if (t.s < S - 1) p.push_back({t.k, t.s + 1, HYDRA_PHASE_B});
+    else p.push_back({t.k, t.s, HYDRA_PHASE_F});
+  } else {
+    p.push_back({t.k, t.s, HYDRA_PHASE_B});
+  }
+  return p;
+}
+
+static const char* ph_name(int ph) { return ph == 0 ? "F" : (ph == 1 ? "B" : "U"); }
+
+hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan) {
+  plan.clear();
+  const int K = c->K;
+  const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
+  size_t total = 0;
+  for (int k = 0; k < K; ++k) total += 3 * c->models[k].shards.size();
+
+  if (sch->policy == HYDRA_SCHED_SEQUENTIAL) {
+    for (int k = 0; k < K; ++k) {
+      const int S = (int)c->models[k].shards.size();
+      for (int s = 0; s < S; ++s) plan.push_back({HYDRA_PHASE_F, {{k, s}}, 0});
+      for (int s = S - 1; s >= 0; --s) {
+        plan.push_back({HYDRA_PHASE_B, {{k, s}}, 0});
+        plan.push_back({HYDRA_PHASE_U, {{k, s}}, 0});
+      }
+    }
+    return HYDRA_OK;
+  }
+
+  if (sch->policy == HYDRA_SCHED_EXPLICIT) {
+    if (!sch->tasks || sch->n_tasks <= 0) return c->fail(HYDRA_ERR_INVALID_ARG, "explicit schedule without tasks");
+    std::set<Task> done;
+    for (int i = 0; i < sch->n_tasks; ++i) {
+      Task t{sch->tasks[3 * i], sch->tasks[3 * i + 1], sch->tasks[3 * i + 2]};
+      if (t.k < 0 || t.k >= K || t.s < 0 || t.s >= (int)c->models[t.k].shards.size() || t.ph < 0 || t.ph > 2)
+        return c->fail(HYDRA_ERR_BAD_SCHEDULE, "task %d = (%d,%d,%d) does not exist", i, t.k, t.s, t.ph);
+      if (done.count(t))
+        return c->fail(HYDRA_ERR_BAD_SCHEDULE, "task %d: %s(%d,%d) listed twice", i, ph_name(t.ph), t.k, t.s);
+      for (const Task& p : preds_of(c, t))
+        if (!done.count(p))
+          return c->fail(HYDRA_ERR_BAD_SCHEDULE, "task %d: %s(%d,%d) is scheduled before %s(%d,%d)", i, ph_name(t.ph), t.k,
+                         t.s, ph_name(p.ph), p.k, p.s);
+      done.insert(t);
+      // neighbours in the list with the same phase and shape share a launch group
+      const uint64_t sig = c->models[t.k].shards[t.s].sig;
+      bool joined = false;
+      if (!plan.empty() && plan.back().ph == t.ph && (int)plan.back().members.size() < MAXG) {
+        const auto& mb = plan.back().members;
+        bool same = c->models[mb[0].first].shards[mb[0].second].sig == sig;
+        for (const auto& q : mb) same = same && q.first != t.k;
+        if (same) {
+          plan.back().members.push_back({t.k, t.s});
+          joined = true;
+        }
+      }
+      if (!joined) plan.push_back({t.ph, {{t.k, t.s}}, 0});
+    }
+    if (done.size() != total)
+      return c->fail(HYDRA_ERR_BAD_SCHEDULE, "schedule lists %zu of the %zu (model, shard, phase) tasks", done.size(), total);
+    return HYDRA_OK;
+  }
+
+  if (sch->policy != HYDRA_SCHED_SHARD_PARALLEL) return c->fail(HYDRA_ERR_INVALID_ARG, "unknown policy %d", sch->policy);
+
+  // wavefronts of ready tasks; inside a wavefront tasks are bucketed by (phase, signature)
+  const int nc = ns >= 2 ? std::max(1, ns / 2) : 1;  // streams [0,nc): F and B; [nc,ns): U
+  const int nu = ns - nc;
+  int next_u = 0;
+  std::set<Task> issued;
+  while (issued.size() < total) {
+    std::vector<Task> ready;
+    for (int k = 0; k < K; ++k)
+      for (int s = 0; s < (int)c->models[k].shards.size(); ++s)
+        for (int ph = 0; ph < 3; ++ph) {
+          Task t{k, s, ph};
+          if (issued.count(t)) continue;
+          bool ok = true;
+          for (const Task& p : preds_of(c, t)) ok = ok && issued.count(p);
+          if (ok) ready.push_back(t);
+        }
+    // deterministic bucket order: backward first (it is on the critical path), then forward, then update
+    auto rank = [](int ph) { return ph == HYDRA_PHASE_B ? 0 : (ph == HYDRA_PHASE_F ? 1 : 2); };
+    std::map<std::pair<int, uint64_t>, std::vector<Task>> groups;
+    std::vector<std::pair<int, uint64_t>> order;
+    for (const Task& t : ready) {
+      auto key = std::make_pair(rank(t.ph), c->models[t.k].shards[t.s].sig);
+      if (!groups.count(key)) order.push_back(key);
+      groups[key].push_back(t);
+    }
+    std::stable_sort(order.begin(), order.end(), [](const auto& x, const auto& y) { return x.first < y.first; });
+    int next_c = 0;
+    for (const auto& key : order) {
+      const std::vector<Task>& ts = groups[key];
+      for (size_t i = 0; i < ts.size(); i += MAXG) {
+        Bucket b;
+        b.ph = ts[i].ph;
+        for (size_t j = i; j < std::min(ts.size(), i + (size_t)MAXG); ++j) b.members.push_back({ts[j].k, ts[j].s});
+        if (b.ph == HYDRA_PHASE_U && nu > 0) b.stream = nc + (next_u++ % nu);
+        else b.stream = next_c++ % nc;
+        plan.push_back(b);
+      }
+    }
+    for (const Task& t : ready) issued.insert(t);
+  }
+  return HYDRA_OK;
+}
+
+hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoch_stats* stats) {
+  const size_t nb = plan.size();
+  c->launches = 0;
+  c->grouped_tasks = 0;
+  if (!c->dry) {
+    while (c->events.size() < 2 * nb) {
+      hipEvent_t e;
+      HYDRA_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      c->events.push_back(e);
+    }
+    for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  }
+  struct Done { hipEvent_t ev; int stream; };
+  std::map<Task, Done> last;  // most recent completion event of every task
+  const auto t0 = std::chrono::steady_clock::now();
+  for (int step = 0; step < c->n_batches; ++step) {
+    for (size_t i = 0; i < nb; ++i) {
+      const Bucket& b = plan[i];
+      if (b.members.size() > 1) c->grouped_tasks += b.members.size();
+      if (c->dry) {
+        hydra_status st = mlp_run(c, b, step, step, nullptr);
+        if (st != HYDRA_OK) return st;
+        continue;
+      }
+      hipStream_t s = c->streams[b.stream];
+      std::vector<hipEvent_t> waited;
+      for (const auto& mem : b.members) {
+        Task t{mem.first, mem.second, b.ph};
+        std::vector<Task> deps = preds_of(c, t);
+        if (b.ph == HYDRA_PHASE_F) deps.push_back({t.k, t.s, HYDRA_PHASE_U});  // previous step's update
+        for (const Task& d : deps) {
+          auto it = last.find(d);
+          if (it == last.end() || it->second.stream == b.stream) continue;
+          if (std::find(waited.begin(), waited.end(), it->second.ev) != waited.end()) continue;
+          HYDRA_HIP(c, hipStreamWaitEvent(s, it->second.ev, 0));
+          waited.push_back(it->second.ev);
+        }
+      }
+      hydra_status st = mlp_run(c, b, step, step, s);
+      if (st != HYDRA_OK) return st;
+      hipEvent_t ev = c->events[(step & 1) * nb + i];
+      HYDRA_HIP(c, hipEventRecord(ev, s));
+      for (const auto& mem : b.members) last[{mem.first, mem.second, b.ph}] = {ev, b.stream};
+    }
+  }
+  if (!c->dry)
+    for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  const auto t1 = std::chrono::steady_clock::now();
+  if (!c->dry && c->profiling) {
+    hydra_status ps = prof_collect(c);
+    if (ps != HYDRA_OK) return ps;
+  }
+  // losses of this epoch
+  for (int k = 0; k < c->K; ++k) {
+    Model& m = c->models[k];
+    std::vector<float> l(c->n_batches, 0.f);
+    if (!c->dry) HYDRA_HIP(c, hipMemcpy(l.data(), m.loss_dev, l.size() * 4, hipMemcpyDeviceToHost));
+    m.losses.insert(m.losses.end(), l.begin(), l.end());
+  }
+  if (stats) {
+    stats->wall_ms = std::chrono::duration<double, std::milli>(t1 - t0).count();
+    stats->h2d_bytes = stats->d2h_bytes = 0;
+    stats->launches = c->launches;
+    stats->grouped_tasks = c->grouped_tasks;
+    stats->peak_dev_bytes = c->peak_dev_bytes;
+    stats->peak_host_bytes = 0;
+    stats->steps = c->n_batches;
+  }
+  return HYDRA_OK;
+}
+
+}  // namespace hydra

@@ -1,0 +1,303 @@
+"""ctypes binding of include/hydra.h: argument marshalling only.
+
+Every function has the name of the C entry point it calls.  PyTorch is used for
+plumbing only: device memory (through the allocator callbacks of
+hydra_options) and HIP streams.  Nothing here computes any part of training,
+and there is no fallback: if libhydra.so is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhydra.so")
+
+STATUS = {0: "HYDRA_OK", 1: "HYDRA_ERR_INVALID_ARG", 2: "HYDRA_ERR_BAD_STATE", 3: "HYDRA_ERR_BAD_SCHEDULE",
+          4: "HYDRA_ERR_OOM_DEVICE", 5: "HYDRA_ERR_OOM_HOST", 6: "HYDRA_ERR_DEVICE", 7: "HYDRA_ERR_UNSUPPORTED",
+          8: "HYDRA_ERR_BUFFER_TOO_SMALL"}
+SCHED_SEQUENTIAL, SCHED_SHARD_PARALLEL, SCHED_EXPLICIT = 0, 1, 2
+PHASE_F, PHASE_B, PHASE_U = 0, 1, 2
+
+
+class HydraError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+_ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+_FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
+class hydra_options(C.Structure):
+    _fields_ = [("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("user", C.c_void_p),
+                ("streams", C.POINTER(C.c_void_p)), ("n_streams", C.c_int),
+                ("device_budget_bytes", C.c_size_t), ("host_budget_bytes", C.c_size_t), ("dry_run", C.c_int)]
+
+
+class hydra_arch(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("kind", "n_layers", "d_in", "d_model", "n_heads", "d_ffn", "n_out", "max_seq",
+                                       "act", "ffn_gated", "causal", "dtype")]
+
+
+class hydra_hparams(C.Structure):
+    _fields_ = [("opt", C.c_int), ("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("eps", C.c_double), ("warmup_steps", C.c_int)]
+
+
+class hydra_schedule(C.Structure):
+    _fields_ = [("policy", C.c_int), ("tasks", C.POINTER(C.c_int32)), ("n_tasks", C.c_int)]
+
+
+class hydra_epoch_stats(C.Structure):
+    _fields_ = [("wall_ms", C.c_double), ("h2d_bytes", C.c_uint64), ("d2h_bytes", C.c_uint64),
+                ("launches", C.c_uint64), ("grouped_tasks", C.c_uint64), ("peak_dev_bytes", C.c_uint64),
+                ("peak_host_bytes", C.c_uint64), ("steps", C.c_int32)]
+
+
+class hydra_kernel_profile(C.Structure):
+    _fields_ = [("launches", C.c_uint64), ("total_ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+KERNEL_CLASSES = ["gemm_fwd", "gemm_dgrad", "gemm_wgrad", "optim", "softmax_ce", "colsum", "layernorm", "attention",
+                  "embed", "elementwise"]
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libhydra.so (built by paper_2107_06469_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2107_06469_amd.build` first")
+        L = C.CDLL(LIB_PATH)
+        vp, i32p, fp, szp = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_size_t)
+        L.hydra_create.argtypes = [C.POINTER(hydra_options), C.POINTER(vp)]
+        L.hydra_destroy.argtypes = [vp]
+        L.hydra_define_models.argtypes = [vp, C.c_int, C.POINTER(hydra_arch), C.c_int, C.POINTER(hydra_hparams), C.c_uint64]
+        L.hydra_shard.argtypes = [vp, C.c_int, i32p, C.c_int]
+        L.hydra_set_data.argtypes = [vp, vp, i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int]
+        L.hydra_train_epoch.argtypes = [vp, C.POINTER(hydra_schedule), C.POINTER(hydra_epoch_stats)]
+        for f in (L.hydra_read_params, L.hydra_read_grads):
+            f.argtypes = [vp, C.c_int, C.c_int, fp, C.c_size_t, szp]
+        L.hydra_read_loss.argtypes = [vp, C.c_int, fp, C.c_size_t, szp]
+        L.hydra_write_params.argtypes = [vp, C.c_int, C.c_int, fp, C.c_size_t]
+        L.hydra_tensor_count.argtypes = [vp, C.c_int, C.POINTER(C.c_int)]
+        L.hydra_tensor_shape.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+        L.hydra_shard_count.argtypes = [vp, C.c_int, C.POINTER(C.c_int)]
+        L.hydra_profile_enable.argtypes = [vp, C.c_int]
+        L.hydra_profile_read.argtypes = [vp, C.c_int, C.c_int, C.POINTER(hydra_kernel_profile)]
+        L.hydra_last_error.argtypes = [vp]
+        L.hydra_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(ctx, st: int):
+    if st != 0:
+        raise HydraError(st, lib().hydra_last_error(ctx).decode())
+
+
+def _i32(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a: Optional[np.ndarray], ty):
+    return None if a is None else a.ctypes.data_as(ty)
+
+
+class Context:
+    """Holds a hydra_ctx* plus the Python objects that must outlive it (callbacks, streams, memory)."""
+
+    def __init__(self, handle, keep):
+        self.handle = handle
+        self._keep = keep
+
+
+def hydra_create(n_streams: int = 4, dry_run: bool = False, use_torch: bool = True,
+                 device_budget_bytes: int = 0, host_budget_bytes: int = 0) -> Context:
+    """use_torch: device memory comes from torch's allocator and streams are torch.cuda.Stream objects."""
+    opts = hydra_options()
+    opts.dry_run = 1 if dry_run else 0
+    opts.device_budget_bytes = device_budget_bytes
+    opts.host_budget_bytes = host_budget_bytes
+    keep: Dict = {}
+    if dry_run:
+        opts.n_streams = n_streams
+    elif use_torch:
+        import torch
+        torch.cuda.init()
+        blocks: Dict[int, "torch.Tensor"] = {}
+
+        def _alloc(nbytes, _user):
+            try:
+                t = torch.empty(int(nbytes), dtype=torch.uint8, device="cuda:0")
+            except Exception:  # out of memory: report NULL, the library returns HYDRA_ERR_OOM_DEVICE
+                return None
+            blocks[t.data_ptr()] = t
+            return t.data_ptr()
+
+        def _free(ptr, _user):
+            blocks.pop(ptr, None)
+        streams = [torch.cuda.Stream(device="cuda:0") for _ in range(n_streams)]
+        arr = (C.c_void_p * n_streams)(*[s.cuda_stream for s in streams])
+        a_cb, f_cb = _ALLOC_FN(_alloc), _FREE_FN(_free)
+        opts.dev_alloc, opts.dev_free = a_cb, f_cb
+        opts.streams, opts.n_streams = C.cast(arr, C.POINTER(C.c_void_p)), n_streams
+        keep.update(blocks=blocks, streams=streams, arr=arr, cbs=(a_cb, f_cb))
+    h = C.c_void_p()
+    st = lib().hydra_create(C.byref(opts), C.byref(h))
+    if st != 0:
+        raise HydraError(st, lib().hydra_last_error(None).decode())
+    return Context(h, keep)
+
+
+def hydra_destroy(ctx: Context):
+    if ctx.handle:
+        lib().hydra_destroy(ctx.handle)
+        ctx.handle = None
+        ctx._keep.clear()
+
+
+def hydra_define_models(ctx: Context, archs: Sequence[Dict], grid: Sequence[Dict], seed: int):
+    K = len(grid)
+    same = all(a == archs[0] for a in archs)
+    arr_a = (hydra_arch * (1 if same else len(archs)))()
+    for i in range(len(arr_a)):
+        for n, _ in hydra_arch._fields_:
+            setattr(arr_a[i], n, int(archs[i][n]))
+    arr_h = (hydra_hparams * K)()
+    for i, h in enumerate(grid):
+        arr_h[i].opt, arr_h[i].lr, arr_h[i].beta1 = int(h["opt"]), float(h["lr"]), float(h["beta1"])
+        arr_h[i].beta2, arr_h[i].eps, arr_h[i].warmup_steps = float(h["beta2"]), float(h["eps"]), int(h["warmup_steps"])
+    _check(ctx.handle, lib().hydra_define_models(ctx.handle, K, arr_a, len(arr_a), arr_h, C.c_uint64(seed)))
+
+
+def hydra_shard(ctx: Context, model: int, cuts: Sequence[int]):
+    a = _i32(list(cuts))
+    _check(ctx.handle, lib().hydra_shard(ctx.handle, model, _ptr(a, C.POINTER(C.c_int32)), len(cuts)))
+
+
+def hydra_set_data(ctx: Context, inputs: np.ndarray, target_pos: Optional[np.ndarray], targets: np.ndarray):
+    """inputs: fp32 [n_batches,B,d_in] or int32 [n_batches,B,S]; targets int32 [n_batches,B(,P)]."""
+    inputs = np.ascontiguousarray(inputs)
+    tp, tg = _i32(target_pos), _i32(targets)
+    nb, B, last = inputs.shape
+    P = 0 if tp is None else tp.shape[2]
+    _check(ctx.handle, lib().hydra_set_data(ctx.handle, inputs.ctypes.data_as(C.c_void_p), _ptr(tp, C.POINTER(C.c_int32)),
+                                            _ptr(tg, C.POINTER(C.c_int32)), nb, B, last, P))
+
+
+def hydra_train_epoch(ctx: Context, policy: int = SCHED_SHARD_PARALLEL, tasks=None) -> Dict:
+    sch = hydra_schedule()
+    sch.policy = policy
+    t = None
+    if tasks is not None:
+        t = _i32(np.asarray(tasks).reshape(-1, 3))
+        sch.tasks, sch.n_tasks = t.ctypes.data_as(C.POINTER(C.c_int32)), t.shape[0]
+    st = hydra_epoch_stats()
+    _check(ctx.handle, lib().hydra_train_epoch(ctx.handle, C.byref(sch), C.byref(st)))
+    return {n: getattr(st, n) for n, _ in hydra_epoch_stats._fields_}
+
+
+def _read(fn, ctx: Context, model: int, tensor: int) -> np.ndarray:
+    n = C.c_size_t(0)
+    st = fn(ctx.handle, model, tensor, None, 0, C.byref(n))
+    if st not in (0, 8):
+        _check(ctx.handle, st)
+    out = np.empty(n.value, dtype=np.float32)
+    if n.value:
+        _check(ctx.handle, fn(ctx.handle, model, tensor, out.ctypes.data_as(C.POINTER(C.c_float)), n.value, C.byref(n)))
+    return out
+
+
+def hydra_tensor_shapes(ctx: Context, model: int) -> List[tuple]:
+    n = C.c_int(0)
+    _check(ctx.handle, lib().hydra_tensor_count(ctx.handle, model, C.byref(n)))
+    shapes = []
+    for j in range(n.value):
+        r, c = C.c_int(0), C.c_int(0)
+        _check(ctx.handle, lib().hydra_tensor_shape(ctx.handle, model, j, C.byref(r), C.byref(c)))
+        shapes.append((r.value, c.value))
+    return shapes
+
+
+def hydra_shard_count(ctx: Context, model: int) -> int:
+    n = C.c_int(0)
+    _check(ctx.handle, lib().hydra_shard_count(ctx.handle, model, C.byref(n)))
+    return n.value
+
+
+def _split(flat: np.ndarray, shapes) -> List[np.ndarray]:
+    out, o = [], 0
+    for r, c in shapes:
+        out.append(flat[o:o + r * c].reshape((r, c) if r > 1 else (c,)))
+        o += r * c
+    return out
+
+
+def hydra_read_params(ctx: Context, model: int, tensor: int = -1):
+    """tensor = -1: list of arrays in canonical order (vectors 1-D, matrices [out,in]); else one flat array."""
+    flat = _read(lib().hydra_read_params, ctx, model, tensor)
+    return _split(flat, hydra_tensor_shapes(ctx, model)) if tensor == -1 else flat
+
+
+def hydra_read_grads(ctx: Context, model: int, tensor: int = -1):
+    flat = _read(lib().hydra_read_grads, ctx, model, tensor)
+    return _split(flat, hydra_tensor_shapes(ctx, model)) if tensor == -1 else flat
+
+
+def hydra_read_loss(ctx: Context, model: int) -> np.ndarray:
+    n = C.c_size_t(0)
+    st = lib().hydra_read_loss(ctx.handle, model, None, 0, C.byref(n))
+    if st not in (0, 8):
+        _check(ctx.handle, st)
+    out = np.empty(n.value, dtype=np.float32)
+    if n.value:
+        _check(ctx.handle, lib().hydra_read_loss(ctx.handle, model, out.ctypes.data_as(C.POINTER(C.c_float)), n.value, C.byref(n)))
+    return out
+
+
+def hydra_write_params(ctx: Context, model: int, tensor: int, values):
+    if tensor == -1 and isinstance(values, (list, tuple)):
+        values = np.concatenate([np.asarray(v, dtype=np.float32).reshape(-1) for v in values])
+    v = np.ascontiguousarray(values, dtype=np.float32).reshape(-1)
+    _check(ctx.handle, lib().hydra_write_params(ctx.handle, model, tensor, v.ctypes.data_as(C.POINTER(C.c_float)), v.size))
+
+
+def hydra_profile_enable(ctx: Context, on: bool = True):
+    _check(ctx.handle, lib().hydra_profile_enable(ctx.handle, 1 if on else 0))
+
+
+def hydra_profile_read(ctx: Context, reset: bool = True) -> Dict[str, Dict]:
+    """Per kernel class: launches, total_ms, flops, bytes of the profiled epochs."""
+    out = {}
+    for i, name in enumerate(KERNEL_CLASSES):
+        kp = hydra_kernel_profile()
+        _check(ctx.handle, lib().hydra_profile_read(ctx.handle, i, 1 if reset else 0, C.byref(kp)))
+        if kp.launches:
+            out[name] = dict(launches=int(kp.launches), total_ms=kp.total_ms, flops=kp.flops, bytes=kp.bytes)
+    return out
+
+
+def train_workload(w, data, policy: int = SCHED_SHARD_PARALLEL, n_streams: int = 4, epochs: int = 1, tasks=None,
+                   cuts=None):
+    """Convenience used by tests and the benchmark: runs a hydra_workloads.Workload through the
+    boundary and returns ({model: (losses, params)}, [stats per epoch])."""
+    ctx = hydra_create(n_streams=n_streams)
+    try:
+        hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            hydra_shard(ctx, k, (cuts if cuts is not None else w.boundaries)[k])
+        hydra_set_data(ctx, data["inputs"], data["target_pos"], data["targets"])
+        stats = [hydra_train_epoch(ctx, policy, tasks) for _ in range(epochs)]
+        out = {k: (hydra_read_loss(ctx, k), hydra_read_params(ctx, k)) for k in range(w.K)}
+        return out, stats
+    finally:
+        hydra_destroy(ctx)

@@ -1,0 +1,90 @@
+"""ctypes binding of include/hydra_ops.h (argument marshalling only).
+
+Arguments are torch CUDA tensors (device memory is PyTorch's job here); every
+function enqueues the named C entry point on torch's current stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Optional, Sequence
+
+from .hydra import HydraError, lib
+
+F32, BF16 = 0, 1
+EPI_NONE, EPI_RELU, EPI_GELU = 0, 1, 2
+
+
+class hydra_gemm_desc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("dtype", "M", "N", "K", "x_kmajor", "w_kmajor", "ldx", "ldw", "ldo", "ldg", "ldr",
+                                       "act", "out_f32", "tile", "G")] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("X", "W", "bias", "out", "pre", "gate", "resid")]
+
+
+_ready = False
+
+
+def _L():
+    global _ready
+    L = lib()
+    if not _ready:
+        vp, pp = C.c_void_p, C.POINTER(C.c_void_p)
+        L.hydra_op_gemm.argtypes = [C.POINTER(hydra_gemm_desc), vp]
+        L.hydra_op_colsum.argtypes = [C.c_int] * 5 + [pp, pp, vp]
+        L.hydra_op_softmax_ce.argtypes = [C.c_int] * 5 + [C.c_float, C.c_int, pp, vp, pp, pp, pp, vp]
+        L.hydra_op_optim.argtypes = [C.c_int, C.c_size_t, C.c_int, pp, pp, pp, pp, pp, C.POINTER(C.c_double), vp]
+        L.hydra_op_init_uniform.argtypes = [vp, C.c_size_t, C.c_uint64, C.c_uint64, C.c_float, vp]
+        L.hydra_op_cast_bf16.argtypes = [vp, vp, C.c_size_t, vp]
+        L.hydra_ops_last_error.restype = C.c_char_p
+        _ready = True
+    return L
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _tab(ts: Optional[Sequence]):
+    if ts is None:
+        return None
+    return (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+
+
+def _check(st: int):
+    if st != 0:
+        raise HydraError(st, _L().hydra_ops_last_error().decode())
+
+
+def hydra_op_gemm(dtype, M, N, K, X, W, out, *, x_kmajor, w_kmajor, ldx, ldw, ldo, bias=None, pre=None, gate=None,
+                  resid=None, ldg=0, ldr=0, act=EPI_NONE, out_f32=False, tile=0):
+    d = hydra_gemm_desc()
+    d.dtype, d.M, d.N, d.K, d.x_kmajor, d.w_kmajor = dtype, M, N, K, int(x_kmajor), int(w_kmajor)
+    d.ldx, d.ldw, d.ldo, d.ldg, d.ldr, d.act, d.out_f32, d.tile, d.G = ldx, ldw, ldo, ldg, ldr, act, int(out_f32), tile, len(X)
+    tabs = [_tab(t) for t in (X, W, bias, out, pre, gate, resid)]
+    for name, t in zip(("X", "W", "bias", "out", "pre", "gate", "resid"), tabs):
+        if t is not None:
+            setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
+    _check(_L().hydra_op_gemm(C.byref(d), _stream()))
+
+
+def hydra_op_colsum(dtype, M, N, ld, src, out):
+    _check(_L().hydra_op_colsum(dtype, M, N, ld, len(src), _tab(src), _tab(out), _stream()))
+
+
+def hydra_op_softmax_ce(dtype, M, Cn, ldz, lddz, inv_n, logits, labels, dz, rowloss, loss):
+    _check(_L().hydra_op_softmax_ce(dtype, M, Cn, ldz, lddz, inv_n, len(logits), _tab(logits), C.c_void_p(labels.data_ptr()),
+                                    _tab(dz), _tab(rowloss), _tab(loss), _stream()))
+
+
+def hydra_op_optim(opt, n, p, g, m, v, w16, hp_rows):
+    """hp_rows: per problem (lr, b1, b2, eps, bc1, bc2)."""
+    flat = (C.c_double * (6 * len(p)))(*[float(x) for row in hp_rows for x in row])
+    _check(_L().hydra_op_optim(opt, n, len(p), _tab(p), _tab(g), _tab(m), _tab(v), _tab(w16), flat, _stream()))
+
+
+def hydra_op_init_uniform(dst, n, seed, stream_id, a):
+    _check(_L().hydra_op_init_uniform(C.c_void_p(dst.data_ptr()), n, C.c_uint64(seed), C.c_uint64(stream_id), a, _stream()))
+
+
+def hydra_op_cast_bf16(src, dst, n):
+    _check(_L().hydra_op_cast_bf16(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), n, _stream()))

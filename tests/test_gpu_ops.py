@@ -1,0 +1,282 @@
+"""Parity of the individual HIP operations with the oracle's layer functions (GPU only).
+
+Inputs are seeded; bf16 operands are rounded to bf16 once on the host and the oracle gets exactly
+those values in fp64, so the only differences are fp32 accumulation order and output rounding.
+Tolerance for a dot product of length K accumulated in fp32: |err| <= 2*K*2^-24 * sum|x||w| (the
+standard forward bound), plus 2^-8 relative when the output is rounded to bf16.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import layers as OL
+from oracle import rng as ORNG
+
+pytestmark = pytest.mark.gpu
+
+EPS32 = 2.0 ** -24
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "GPU tests need a HIP device"
+    return t
+
+
+@pytest.fixture(scope="module")
+def ops():
+    from paper_2107_06469_amd import ops as o
+    return o
+
+
+def _ld(n, e=8):
+    return (n + e - 1) // e * e
+
+
+def _dev(torch, a, dtype, ld=None):
+    """host fp array [r,c] -> device tensor [r,ld] of dtype (zero padded); returns (tensor, values as fp64)."""
+    r, c = a.shape
+    ld = ld or _ld(c)
+    t = torch.zeros((r, ld), dtype=torch.float32)
+    t[:, :c] = torch.from_numpy(a.astype(np.float32))
+    t = t.to(torch.bfloat16 if dtype == 1 else torch.float32)
+    vals = t[:, :c].to(torch.float64).numpy().copy()
+    return t.cuda(), vals
+
+
+def _check(got, want, bound, out_bf16, what):
+    tol = bound + (2.0 ** -8) * np.abs(want) * (1.0 if out_bf16 else 0.0) + 1e-30
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} off, worst {np.abs(got - want).max()} vs tol {tol[bad].min()}"
+
+
+SHAPES = [  # (M, N, K)
+    (32, 256, 256), (96, 72, 320), (130, 200, 136), (512, 1000, 520), (257, 130, 72), (40, 10, 256),
+]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("layout", ["fwd", "dgrad", "wgrad"])
+def test_gemm_layouts_tiles_and_ragged_shapes(torch, ops, dtype, tile, layout):
+    r = np.random.default_rng(100 * dtype + 10 * tile + len(layout))
+    G = 3
+    for (M, N, K) in SHAPES:
+        Xs, Ws, outs, wants, bounds = [], [], [], [], []
+        for g in range(G):
+            x = r.normal(size=(M, K))
+            w = r.normal(size=(N, K)) / math.sqrt(K)
+            if layout == "fwd":      # out[M,N] = x w^T, both k-major
+                xd, xv = _dev(torch, x, dtype)
+                wd, wv = _dev(torch, w, dtype)
+                kw = dict(x_kmajor=1, w_kmajor=1, ldx=xd.shape[1], ldw=wd.shape[1])
+            elif layout == "dgrad":  # out[M,N] = x(m,k) * wt[k,n]: second operand stored [K,N]
+                xd, xv = _dev(torch, x, dtype)
+                wd, wtv = _dev(torch, w.T.copy(), dtype)
+                wv = wtv.T
+                kw = dict(x_kmajor=1, w_kmajor=0, ldx=xd.shape[1], ldw=wd.shape[1])
+            else:                    # out[M,N] = xt[k,m]^T wt[k,n]: both stored with k slow
+                xd, xtv = _dev(torch, x.T.copy(), dtype)
+                wd, wtv = _dev(torch, w.T.copy(), dtype)
+                xv, wv = xtv.T, wtv.T
+                kw = dict(x_kmajor=0, w_kmajor=0, ldx=xd.shape[1], ldw=wd.shape[1])
+            Xs.append(xd)
+            Ws.append(wd)
+            outs.append(torch.full((M, _ld(N)), 7.0, dtype=torch.float32, device="cuda"))
+            wants.append(OL.linear_fwd(xv, wv, np.zeros(N)))
+            bounds.append(2 * K * EPS32 * (np.abs(xv) @ np.abs(wv).T))
+        ops.hydra_op_gemm(dtype, M, N, K, Xs, Ws, outs, ldo=_ld(N), out_f32=True, tile=tile, **kw)
+        torch.cuda.synchronize()
+        for g in range(G):
+            o = outs[g].cpu().numpy().astype(np.float64)
+            _check(o[:, :N], wants[g], bounds[g], False, f"{layout} dtype={dtype} tile={tile} {(M, N, K)} g={g}")
+            assert np.all(o[:, N:] == 7.0), "columns beyond N were written"
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("act", [1, 2])
+def test_gemm_forward_epilogue_bias_activation_preactivation(torch, ops, dtype, act):
+    r = np.random.default_rng(7 + dtype + act)
+    M, N, K, G = 96, 200, 136, 2
+    tdt = torch.bfloat16 if dtype else torch.float32
+    Xs, Ws, Bs, outs, pres, want_h, want_z, bounds = [], [], [], [], [], [], [], []
+    for g in range(G):
+        xd, xv = _dev(torch, r.normal(size=(M, K)), dtype)
+        wd, wv = _dev(torch, r.normal(size=(N, K)) / math.sqrt(K), dtype)
+        b = r.normal(size=N).astype(np.float32)
+        Xs.append(xd), Ws.append(wd), Bs.append(torch.from_numpy(b).cuda())
+        outs.append(torch.zeros((M, _ld(N)), dtype=tdt, device="cuda"))
+        pres.append(torch.zeros((M, _ld(N)), dtype=tdt, device="cuda"))
+        z = OL.linear_fwd(xv, wv, b.astype(np.float64))
+        want_z.append(z)
+        want_h.append(OL.relu(z) if act == 1 else OL.gelu(z))
+        bounds.append(2 * K * EPS32 * (np.abs(xv) @ np.abs(wv).T) + 1e-6)
+    ops.hydra_op_gemm(dtype, M, N, K, Xs, Ws, outs, x_kmajor=1, w_kmajor=1, ldx=Xs[0].shape[1], ldw=Ws[0].shape[1],
+                      ldo=_ld(N), bias=Bs, pre=pres, act=act)
+    torch.cuda.synchronize()
+    for g in range(G):
+        _check(pres[g][:, :N].double().cpu().numpy(), want_z[g], bounds[g], dtype == 1, "pre-activation")
+        # the activation is applied to the fp32 value before rounding; allow one more bf16 ulp of the input side
+        _check(outs[g][:, :N].double().cpu().numpy(), want_h[g], 1.2 * bounds[g] + 1e-6, dtype == 1, "activation")
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("act", [1, 2])
+def test_gemm_dgrad_epilogue_gate_and_residual(torch, ops, dtype, act):
+    r = np.random.default_rng(17 + dtype + act)
+    M, N, K, G = 72, 136, 200, 2
+    tdt = torch.bfloat16 if dtype else torch.float32
+    Xs, Ws, gates, resids, outs, wants, bounds = [], [], [], [], [], [], []
+    for g in range(G):
+        xd, xv = _dev(torch, r.normal(size=(M, K)), dtype)
+        wd, wtv = _dev(torch, (r.normal(size=(N, K)) / math.sqrt(K)).T.copy(), dtype)
+        zd, zv = _dev(torch, r.normal(size=(M, N)) + 0.3, dtype)
+        rd, rv = _dev(torch, r.normal(size=(M, N)), dtype)
+        Xs.append(xd), Ws.append(wd), gates.append(zd), resids.append(rd)
+        outs.append(torch.zeros((M, _ld(N)), dtype=tdt, device="cuda"))
+        grad = OL.relu_grad(zv) if act == 1 else OL.gelu_grad(zv)
+        wants.append((xv @ wtv) * grad + rv)
+        bounds.append(2 * K * EPS32 * (np.abs(xv) @ np.abs(wtv)) * np.abs(grad) + 2e-6)
+    ops.hydra_op_gemm(dtype, M, N, K, Xs, Ws, outs, x_kmajor=1, w_kmajor=0, ldx=Xs[0].shape[1], ldw=Ws[0].shape[1],
+                      ldo=_ld(N), gate=gates, ldg=_ld(N), resid=resids, ldr=_ld(N), act=act)
+    torch.cuda.synchronize()
+    for g in range(G):
+        _check(outs[g][:, :N].double().cpu().numpy(), wants[g], bounds[g], dtype == 1, "dgrad epilogue")
+
+
+def test_gemm_result_is_independent_of_tile_and_group(torch, ops):
+    """Bitwise: the same problem alone, inside a group, and with every tile shape gives the same bits."""
+    r = np.random.default_rng(5)
+    M, N, K = 160, 264, 328
+    xd, _ = _dev(torch, r.normal(size=(M, K)), 1)
+    wd, _ = _dev(torch, r.normal(size=(N, K)), 1)
+    other_x, _ = _dev(torch, r.normal(size=(M, K)), 1)
+    other_w, _ = _dev(torch, r.normal(size=(N, K)), 1)
+    ref = None
+    for tile in (1, 2, 3):
+        for group in ([(xd, wd)], [(other_x, other_w), (xd, wd), (other_x, wd)]):
+            outs = [torch.zeros((M, _ld(N)), dtype=torch.float32, device="cuda") for _ in group]
+            ops.hydra_op_gemm(1, M, N, K, [g[0] for g in group], [g[1] for g in group], outs, x_kmajor=1, w_kmajor=1,
+                              ldx=xd.shape[1], ldw=wd.shape[1], ldo=_ld(N), out_f32=True, tile=tile)
+            torch.cuda.synchronize()
+            mine = outs[[i for i, g in enumerate(group) if g[0] is xd and g[1] is wd][0]].cpu().numpy()
+            if ref is None:
+                ref = mine
+            assert np.array_equal(ref, mine), f"tile {tile}, group of {len(group)}"
+
+
+def test_gemm_rejects_bad_arguments(torch, ops):
+    from paper_2107_06469_amd.hydra import HydraError
+    x = torch.zeros((8, 16), dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros((8, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(HydraError):   # ldx not a multiple of 8 elements
+        ops.hydra_op_gemm(1, 8, 8, 12, [x], [x], [o], x_kmajor=1, w_kmajor=1, ldx=12, ldw=16, ldo=8, out_f32=True)
+    with pytest.raises(HydraError):   # ldo smaller than N
+        ops.hydra_op_gemm(1, 8, 16, 16, [x], [x], [o], x_kmajor=1, w_kmajor=1, ldx=16, ldw=16, ldo=8, out_f32=True)
+    with pytest.raises(HydraError):   # group too large
+        ops.hydra_op_gemm(1, 8, 8, 16, [x] * 17, [x] * 17, [o] * 17, x_kmajor=1, w_kmajor=1, ldx=16, ldw=16, ldo=8,
+                          out_f32=True)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_colsum(torch, ops, dtype):
+    r = np.random.default_rng(3)
+    for (M, N) in [(32, 10), (512, 1000), (97, 130)]:
+        srcs, outs, wants = [], [], []
+        for g in range(2):
+            d, v = _dev(torch, r.normal(size=(M, N)), dtype)
+            srcs.append(d), wants.append(v.sum(axis=0))
+            outs.append(torch.zeros(N, dtype=torch.float32, device="cuda"))
+        ops.hydra_op_colsum(dtype, M, N, srcs[0].shape[1], srcs, outs)
+        torch.cuda.synchronize()
+        for g in range(2):
+            assert np.allclose(outs[g].cpu().numpy(), wants[g], rtol=0, atol=2 * M * EPS32 * 4)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("shape", [(32, 10), (64, 1000), (24, 30522)])
+def test_softmax_cross_entropy(torch, ops, dtype, shape):
+    M, Cn = shape
+    r = np.random.default_rng(Cn)
+    ldz = _ld(Cn)
+    y = r.integers(0, Cn, size=M).astype(np.int32)
+    yd = torch.from_numpy(y).cuda()
+    logits, dzs, rls, ls, wants = [], [], [], [], []
+    for g in range(2):
+        z = (r.normal(size=(M, Cn)) * 3).astype(np.float32)
+        zd = torch.zeros((M, ldz), dtype=torch.float32)
+        zd[:, :Cn] = torch.from_numpy(z)
+        logits.append(zd.cuda())
+        dzs.append(torch.full((M, ldz), 5.0, dtype=torch.bfloat16 if dtype else torch.float32, device="cuda"))
+        rls.append(torch.zeros(M, dtype=torch.float32, device="cuda"))
+        ls.append(torch.zeros(1, dtype=torch.float32, device="cuda"))
+        wants.append(OL.softmax_ce(z.astype(np.float64), y))
+    ops.hydra_op_softmax_ce(dtype, M, Cn, ldz, ldz, 1.0 / M, logits, yd, dzs, rls, ls)
+    torch.cuda.synchronize()
+    for g in range(2):
+        loss, dz = wants[g]
+        assert float(ls[g].item()) == pytest.approx(loss, rel=5e-6)
+        got = dzs[g].double().cpu().numpy()
+        tol = 4e-7 / M + (2.0 ** -8 if dtype else 5e-6) * np.abs(dz)
+        assert np.all(np.abs(got[:, :Cn] - dz) <= tol)
+        assert np.all(got[:, Cn:] == 0.0)
+
+
+@pytest.mark.parametrize("opt", [0, 1])
+@pytest.mark.parametrize("w16", [False, True])
+def test_optimizer_step_matches_oracle(torch, ops, opt, w16):
+    from oracle import optim as OO
+    r = np.random.default_rng(11 + opt)
+    n, G = 4096 + 64, 3
+    P, Gr, Ms, Vs, W16, hp_rows, want = [], [], [], [], [], [], []
+    for g in range(G):
+        p = r.normal(size=n).astype(np.float32)
+        gr = (r.normal(size=n) * 0.1).astype(np.float32)
+        gr[::7] = 0.0
+        m = (r.normal(size=n) * 0.05).astype(np.float32)
+        v = (r.random(size=n) * 0.01).astype(np.float32)
+        t = 3 + g
+        hp = dict(opt=opt, lr=1e-3 * (g + 1), beta1=0.9, beta2=0.999, eps=1e-8, warmup_steps=0)
+        P.append(torch.from_numpy(p).cuda()), Gr.append(torch.from_numpy(gr).cuda())
+        Ms.append(torch.from_numpy(m).cuda()), Vs.append(torch.from_numpy(v).cuda())
+        W16.append(torch.zeros(n, dtype=torch.bfloat16, device="cuda"))
+        hp_rows.append((hp["lr"], 0.9, 0.999, 1e-8, 1 / (1 - 0.9 ** t), 1 / (1 - 0.999 ** t)))
+        pw, mw, vw = p.copy(), m.copy(), v.copy()
+        OO.update_tensor(hp, t, pw, gr.astype(np.float64), mw, vw)
+        want.append((pw, mw, vw))
+    ops.hydra_op_optim(opt, n, P, Gr, Ms, Vs, W16 if w16 else None, hp_rows)
+    torch.cuda.synchronize()
+    for g in range(G):
+        pw, mw, vw = want[g]
+        assert np.allclose(P[g].cpu().numpy(), pw, rtol=3e-6, atol=1e-7)
+        if opt == 1:
+            assert np.allclose(Ms[g].cpu().numpy(), mw, rtol=1e-6, atol=2e-8)   # fp32 rounding of a two-term sum
+            assert np.allclose(Vs[g].cpu().numpy(), vw, rtol=1e-6, atol=1e-10)
+        if w16:
+            assert torch.equal(W16[g], P[g].to(torch.bfloat16))
+
+
+def test_seeded_initialisation_is_bit_identical_to_the_oracle(torch, ops):
+    for (seed, model, tensor, n, a) in [(42, 0, 0, 65536, math.sqrt(6 / 256)), (42, 7, 33, 1000, 0.02 * math.sqrt(3)),
+                                        (2 ** 40 + 5, 15, 2, 4097, 1.0)]:
+        d = torch.zeros(n, dtype=torch.float32, device="cuda")
+        ops.hydra_op_init_uniform(d, n, seed, ORNG.tensor_stream(model, tensor), float(np.float32(a)))
+        torch.cuda.synchronize()
+        want = ORNG.uniform_sym(seed, ORNG.tensor_stream(model, tensor), n, np.float32(a))
+        assert np.array_equal(d.cpu().numpy(), want)
+
+
+def test_bf16_cast_rounds_to_nearest_even(torch, ops):
+    r = np.random.default_rng(1)
+    x = r.normal(size=5000).astype(np.float32)
+    x[:4] = np.array([1.00390625, 1.01171875, -1.00390625, 3.0e38], dtype=np.float32)   # ties and a large value
+    s = torch.from_numpy(x).cuda()
+    d = torch.zeros(5000, dtype=torch.bfloat16, device="cuda")
+    ops.hydra_op_cast_bf16(s, d, 5000)
+    torch.cuda.synchronize()
+    # reference rounding done with integer arithmetic on the host
+    bits = x.view(np.uint32).astype(np.uint64)
+    rounded = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16).astype(np.uint16)
+    assert np.array_equal(d.view(torch.int16).cpu().numpy().view(np.uint16), rounded)

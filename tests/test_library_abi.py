@@ -1,0 +1,152 @@
+"""The C boundary without a GPU: the library loads, exports every declared symbol, and its host
+logic (argument checks, call order, shard cutting, schedule validation, planning) behaves."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from hydra_workloads import make_data, scaled_workload, workload
+from paper_2107_06469_amd import hydra as H
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = set()
+    for f in os.listdir(os.path.join(ROOT, "include")):
+        if f.endswith(".h"):
+            src = open(os.path.join(ROOT, "include", f)).read()
+            src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+            names |= set(re.findall(r"\b(hydra_\w+)\s*\(", src))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = H.lib()
+    names = _declared()
+    assert {"hydra_define_models", "hydra_shard", "hydra_train_epoch", "hydra_read_params", "hydra_read_loss"} <= names
+    for n in sorted(names):
+        assert hasattr(L, n), f"libhydra.so does not export {n}"
+
+
+def _dry(w, data=None):
+    ctx = H.hydra_create(n_streams=4, dry_run=True)
+    H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+    for k in range(w.K):
+        H.hydra_shard(ctx, k, w.boundaries[k])
+    if data is not None:
+        H.hydra_set_data(ctx, data["inputs"], data["target_pos"], data["targets"])
+    return ctx
+
+
+def test_call_order_is_enforced():
+    w = workload(0)
+    d = make_data(w)
+    ctx = H.hydra_create(dry_run=True)
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_shard(ctx, 0, [2])
+    assert e.value.status == 2
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_train_epoch(ctx)
+    assert e.value.status == 2
+    H.hydra_define_models(ctx, w.archs, w.hparams, 1)
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_define_models(ctx, w.archs, w.hparams, 1)
+    assert e.value.status == 2
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_set_data(ctx, d["inputs"], None, d["targets"])
+    assert e.value.status == 2
+    H.hydra_shard(ctx, -1, [2])
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_train_epoch(ctx)
+    assert e.value.status == 2
+    H.hydra_set_data(ctx, d["inputs"], None, d["targets"])
+    assert H.hydra_train_epoch(ctx)["steps"] == 10
+    H.hydra_destroy(ctx)
+
+
+def test_argument_checks():
+    w = workload(0)
+    ctx = H.hydra_create(dry_run=True)
+    bad = dict(w.archs[0], d_model=250)
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_define_models(ctx, [bad] * 4, w.hparams, 1)
+    assert e.value.status == 7
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_define_models(ctx, w.archs, [dict(h, lr=-1.0) for h in w.hparams], 1)
+    assert e.value.status == 1
+    H.hydra_define_models(ctx, w.archs, w.hparams, 1)
+    for cuts in ([0], [5], [3, 3], [3, 2], [1, 2, 3, 4, 5]):
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_shard(ctx, 0, cuts)
+        assert e.value.status == 1
+    H.hydra_shard(ctx, 0, [1, 2, 3, 4])
+    assert H.hydra_shard_count(ctx, 0) == 5 and H.hydra_shard_count(ctx, 1) == 1
+    with pytest.raises(H.HydraError):
+        H.hydra_shard(ctx, 9, [1])
+    d = make_data(w)
+    y = d["targets"].copy()
+    y[0, 0] = 10
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_set_data(ctx, d["inputs"], None, y)
+    assert e.value.status == 1
+    H.hydra_destroy(ctx)
+
+
+def test_tensor_shapes_follow_the_canonical_order():
+    w = workload(0)
+    ctx = _dry(w)
+    assert H.hydra_tensor_shapes(ctx, 3) == [(256, 256), (1, 256)] * 4 + [(10, 256), (1, 10)]
+    H.hydra_destroy(ctx)
+
+
+def test_explicit_schedules_are_validated_before_anything_runs():
+    w = workload(0)
+    ctx = _dry(w, make_data(w))
+    F, B, U = H.PHASE_F, H.PHASE_B, H.PHASE_U
+    one = [(0, 0, F), (0, 1, F), (0, 1, B), (0, 0, B), (0, 0, U), (0, 1, U)]
+    full = [(k, s, p) for k in range(4) for (_, s, p) in one]
+    assert H.hydra_train_epoch(ctx, H.SCHED_EXPLICIT, full)["steps"] == 10
+    bad = [
+        [(0, 1, F)] + full,                                             # F before its predecessor
+        [t for t in full if t != (2, 0, U)],                            # a task is missing
+        full + [(1, 1, U)],                                             # listed twice
+        [(0, 0, F), (0, 1, F), (0, 0, B)] + full[3:],                   # B(0,0) before B(0,1)
+        [(0, 0, F), (0, 1, F), (0, 1, U)] + full[2:],                   # U before B
+        [(7, 0, F)] + full,                                             # no such model
+    ]
+    for tasks in bad:
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_train_epoch(ctx, H.SCHED_EXPLICIT, tasks)
+        assert e.value.status == 3, tasks[:3]
+    H.hydra_destroy(ctx)
+
+
+def test_shard_parallel_plan_groups_models_and_sequential_does_not():
+    w = workload(1)
+    d = make_data(scaled_workload(1, d=4096, n_out=1000, batch=8, steps=2))     # shapes only matter in a dry run
+    ctx = H.hydra_create(n_streams=4, dry_run=True)
+    H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+    H.hydra_shard(ctx, -1, w.boundaries[0])
+    H.hydra_set_data(ctx, d["inputs"], None, d["targets"])
+    seq = H.hydra_train_epoch(ctx, H.SCHED_SEQUENTIAL)
+    par = H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL)
+    assert seq["grouped_tasks"] == 0
+    assert par["grouped_tasks"] == 2 * 8 * 4 * 3                                 # every task of both steps
+    assert seq["launches"] == 8 * par["launches"]
+    # 8 models x (4 fp32 state blocks + 1 bf16 copy) of 272.6 M parameters
+    assert par["peak_dev_bytes"] > 8 * 272_000_000 * 18
+    H.hydra_destroy(ctx)
+
+
+def test_read_buffers_report_required_size():
+    import ctypes as C
+    w = workload(0)
+    ctx = _dry(w)
+    n = C.c_size_t(0)
+    st = H.lib().hydra_read_params(ctx.handle, 0, -1, None, 0, C.byref(n))
+    assert st == 8 and n.value == 4 * (256 * 256 + 256) + 2560 + 10
+    st = H.lib().hydra_read_params(ctx.handle, 0, 8, None, 0, C.byref(n))
+    assert st == 8 and n.value == 2560
+    H.hydra_destroy(ctx)
