@@ -74,6 +74,38 @@ int hydra_op_init_uniform(float* dst, size_t n, uint64_t seed, uint64_t stream_i
 /* dst[i] = bf16(src[i]) (round to nearest even), i < n. */
 int hydra_op_cast_bf16(const float* src, void* dst, size_t n, void* stream);
 
+/* LayerNorm over rows of width d (d % 8 == 0, d <= 4096, ld % 8 == 0): per row mu = mean, var = biased
+ * variance, y = (x-mu)/sqrt(var+eps)*gamma + beta.  x, y have the operand dtype; gamma, beta, mean, rstd fp32. */
+int hydra_op_layernorm_fwd(int dtype, int rows, int d, int ld, float eps, int G, const void* const* x, void* const* y,
+                           const float* const* gamma, const float* const* beta, float* const* mean,
+                           float* const* rstd, void* stream);
+/* Adjoint: dx = rstd*(g - mean(g) - xhat*mean(g*xhat)) + add, g = dy*gamma (add optional: NULL table);
+ * dgamma = sum_rows dy*xhat; dbeta = sum_rows dy.  part_g: scratch of hydra_op_layernorm_part_floats(rows, d) floats. */
+int hydra_op_layernorm_bwd(int dtype, int rows, int d, int ld, int G, const void* const* x, const void* const* dy,
+                           const void* const* add, void* const* dx, const float* const* gamma,
+                           const float* const* mean, const float* const* rstd, float* const* part,
+                           float* const* dgamma, float* const* dbeta, void* stream);
+size_t hydra_op_layernorm_part_floats(int rows, int d);
+
+/* Attention, bf16, head width DH in {64,128}.  qkv_g [B*S, ld_qkv]: q of head h at columns [h*DH,(h+1)*DH),
+ * k at H*DH + the same, v at 2*H*DH + the same.  o_g [B*S, ld_o].  P = softmax(q k^T * scale (+ causal mask)),
+ * o = P v, lse_g [B*H*S] = log-sum-exp of the scaled scores. */
+int hydra_op_attention_fwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
+                           const void* const* qkv, void* const* o, float* const* lse, void* stream);
+/* Adjoint given dout_g [B*S, ld_o] (gradient w.r.t. o): dqkv_g in the layout of qkv; delta_g [B*H*S] scratch. */
+int hydra_op_attention_bwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
+                           const void* const* qkv, const void* const* o, const void* const* dout,
+                           const float* const* lse, float* const* delta, void* const* dqkv, void* stream);
+
+/* x_g[t,:] = tok_g[ids[t],:] + pos_g[t mod S,:]; ids int32 [tokens] shared by the group; tables in the operand dtype. */
+int hydra_op_embed_fwd(int dtype, int tokens, int S, int d, int ld, int G, const int32_t* ids, const void* const* tok,
+                       const void* const* pos, void* const* x, void* stream);
+/* dtok_g[v,:] = sum of dx_g[t,:] over tokens with id v, listed by the CSR (row_ptr [V+1], positions [B*S], both
+ * int32 device arrays); dpos_g[s,:] = sum_b dx_g[b*S+s,:] for s < S, zero for S <= s < S_table.  Outputs fp32. */
+int hydra_op_embed_bwd(int dtype, int V, int S, int S_table, int B, int d, int ld, int G, const int32_t* row_ptr,
+                       const int32_t* positions, const void* const* dx, float* const* dtok, float* const* dpos,
+                       void* stream);
+
 const char* hydra_ops_last_error(void);
 
 #ifdef __cplusplus

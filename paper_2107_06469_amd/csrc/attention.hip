@@ -1,0 +1,424 @@
+// Scaled dot-product attention for bf16 activations, forward and backward, block-wise so the S x S
+// score matrix never reaches HBM.
+//   forward:   P = softmax(q k^T * scale [+ causal mask]),  o = P v,  lse = log sum exp (saved)
+//   backward:  delta_i = sum_c do[i,c] o[i,c];  P recomputed from lse;
+//              dv = P^T do;  dP = do v^T;  dS = P * (dP - delta);  dq = scale * dS k;  dk = scale * dS^T q
+// Memory layout: qkv is [B*S, ld] with q of head h at columns [h*DH, h*DH+DH), k at d + ..., v at 2d + ...
+// (d = H*DH); o/do are [B*S, ld_o] with head h at columns [h*DH, ...); dqkv has the layout of qkv.
+//
+// Matrix-core mapping (v_mfma_f32_32x32x16_bf16, 64-wide wavefronts).  A 32x32 accumulator gives lane l
+// column l%32 and rows 8q+4(l/32)+e (q,e = 0..3).  Every product is arranged so that the accumulator of
+// the first contraction is already in the lane layout the second contraction needs as its B operand
+// (k index = accumulator row), i.e. probabilities never go through LDS:
+//   forward and dq:  S^T[j,i] = K Q^T  (lane = query i, rows = keys j)  ->  O^T[c,i] += Vt[c,j] P^T[j,i]
+//   dk/dv:           S[i,j]   = Q K^T  (lane = key j, rows = queries i) ->  dV^T[c,j] += dOt[c,i] P[i,j]
+// The A operand of the second contraction walks the tile along its slow index, so those tiles (V, K, Q,
+// dO) are also kept transposed in LDS (transposed in registers while loading), with an XOR swizzle of the
+// 8-byte chunk index against bank conflicts.  Softmax statistics of a query live in the two lanes l and
+// l^32 and are combined with one cross-lane exchange.  A wavefront owns 32 queries (or 32 keys) and loops
+// over tiles of 64 keys (queries) shared through LDS by the four wavefronts of the workgroup.  All sums run
+// in a fixed order; dq and dk/dv are separate kernels so that no atomics are needed.
+#include "kernels.h"
+
+namespace hydra {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+constexpr float NEG_BIG = -1.0e30f;
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  __bf16 x = (__bf16)a, y = (__bf16)b;
+  return (uint32_t)__builtin_bit_cast(uint16_t, x) | ((uint32_t)__builtin_bit_cast(uint16_t, y) << 16);
+}
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ f32x16 mfma(const uint4& a, const uint4& b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// ---- LDS tiles of 64 rows x DH columns ---------------------------------------------------------------
+// "row-major" tile: uint4 chunk (row, kc) at row*NCH + (kc ^ (row & (NCH-1))), NCH = DH/8.
+// "transposed" tile: 8-byte chunk (c, q8) (c = column of the source, q8 = source row / 4) at
+//  c*16 + (q8 ^ (c & 15)) in units of 8 bytes.
+template <int DH>
+__device__ __forceinline__ void load_rows(uint4* tile, const bf16_t* src, int ld, int row0, int nrows, int tid) {
+  constexpr int NCH = DH / 8;
+#pragma unroll
+  for (int i = 0; i < 64 * NCH / 256; ++i) {
+    const int c = tid + 256 * i, row = c / NCH, kc = c % NCH;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * ld + 8 * kc);
+    tile[row * NCH + (kc ^ (row & (NCH - 1)))] = v;
+  }
+}
+
+template <int DH>
+__device__ __forceinline__ void load_transposed(uint2* tile, const bf16_t* src, int ld, int row0, int nrows, int tid) {
+  constexpr int NCH = DH / 8;
+  if (tid < 8 * NCH) {
+    const int cb = tid % NCH, jb = tid / NCH;
+    uint32_t in[8][4];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      const int row = row0 + 8 * jb + r;
+      if (row < nrows) v = *reinterpret_cast<const uint4*>(src + (size_t)row * ld + 8 * cb);
+      in[r][0] = v.x; in[r][1] = v.y; in[r][2] = v.z; in[r][3] = v.w;
+    }
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      uint32_t o[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t lo = (in[2 * q][m >> 1] >> (16 * (m & 1))) & 0xffffu;
+        const uint32_t hi = (in[2 * q + 1][m >> 1] >> (16 * (m & 1))) & 0xffffu;
+        o[q] = lo | (hi << 16);
+      }
+      const int c = 8 * cb + m;
+      tile[c * 16 + ((2 * jb) ^ (c & 15))] = make_uint2(o[0], o[1]);
+      tile[c * 16 + ((2 * jb + 1) ^ (c & 15))] = make_uint2(o[2], o[3]);
+    }
+  }
+}
+
+// A operand (8 values along the slow index) for accumulator rows of sub-tile `sub`, MFMA half x:
+// source rows sub*32 + 16x + 4g + {0..3} and + 8
+__device__ __forceinline__ uint4 read_transposed(const uint2* tile, int c, int sub, int x, int g) {
+  const int q8 = sub * 8 + 4 * x + g;
+  const uint2 a = tile[c * 16 + (q8 ^ (c & 15))];
+  const uint2 b = tile[c * 16 + ((q8 + 2) ^ (c & 15))];
+  return make_uint4(a.x, a.y, b.x, b.y);
+}
+
+template <int DH>
+__device__ __forceinline__ uint4 read_rows(const uint4* tile, int row, int kc) {
+  constexpr int NCH = DH / 8;
+  return tile[row * NCH + (kc ^ (row & (NCH - 1)))];
+}
+
+__device__ __forceinline__ uint4 pack_half(const f32x16& p, int x) {
+  return make_uint4(pack2(p[8 * x], p[8 * x + 1]), pack2(p[8 * x + 2], p[8 * x + 3]), pack2(p[8 * x + 4], p[8 * x + 5]),
+                    pack2(p[8 * x + 6], p[8 * x + 7]));
+}
+
+// ---- forward ---------------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const AttnArgs a) {
+  constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
+  extern __shared__ uint4 lds[];
+  uint4* tK = lds;                                        // [64][NCH]
+  uint2* tVt = reinterpret_cast<uint2*>(lds + 64 * NCH);  // [DH][16]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
+  const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int d = a.H * DH;
+  const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
+  const int iq = blockIdx.x * 128 + wave * 32 + li;  // this lane's query
+  uint4 qf[NK];
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    qf[kk] = make_uint4(0, 0, 0, 0);
+    if (iq < a.S) qf[kk] = *reinterpret_cast<const uint4*>(base + (size_t)iq * a.ld_qkv + 16 * kk + 8 * g);
+  }
+  f32x16 oacc[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
+  float m_run = NEG_BIG, l_run = 0.f;
+  const float sc = a.scale * LOG2E;
+  const int q_hi = min(a.S, blockIdx.x * 128 + 128) - 1;          // last query of the workgroup
+  const int n_tiles = a.causal ? (q_hi / 64 + 1) : (a.S + 63) / 64;
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * 64;
+    __syncthreads();
+    load_rows<DH>(tK, base + d, a.ld_qkv, j0, a.S, tid);
+    load_transposed<DH>(tVt, base + 2 * d, a.ld_qkv, j0, a.S, tid);
+    __syncthreads();
+    f32x16 s[2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) s[sub] = mfma(read_rows<DH>(tK, sub * 32 + li, 2 * kk + g), qf[kk], s[sub]);
+    }
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        float v = s[sub][r] * sc;
+        if (j >= a.S || (a.causal && j > iq)) v = NEG_BIG;
+        s[sub][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = exp2f(m_run - m_new);
+    float rs = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[sub][r] - m_new);
+        s[sub][r] = p;
+        rs += p;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    l_run = l_run * alpha + rs;
+    m_run = m_new;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const uint4 pf = pack_half(s[sub], x);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) oacc[c] = mfma(read_transposed(tVt, c * 32 + li, sub, x, g), pf, oacc[c]);
+      }
+  }
+  if (iq < a.S) {
+    const float inv = 1.f / l_run;
+    bf16_t* o = a.o[gi] + ((size_t)b * a.S + iq) * a.ld_o + h * DH;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = c * 32 + 8 * q + 4 * g;
+        *reinterpret_cast<uint2*>(o + col) = make_uint2(pack2(oacc[c][4 * q] * inv, oacc[c][4 * q + 1] * inv),
+                                                        pack2(oacc[c][4 * q + 2] * inv, oacc[c][4 * q + 3] * inv));
+      }
+    if (g == 0) a.lse[gi][(size_t)bh * a.S + iq] = (m_run + log2f(l_run)) * LN2;
+  }
+}
+
+// ---- backward, dq (also writes delta) ------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnBwdArgs a) {
+  constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
+  extern __shared__ uint4 lds[];
+  uint4* tK = lds;                                            // [64][NCH]
+  uint4* tV = lds + 64 * NCH;                                 // [64][NCH]
+  uint2* tKt = reinterpret_cast<uint2*>(lds + 2 * 64 * NCH);  // [DH][16]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
+  const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int d = a.H * DH;
+  const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
+  const int iq = blockIdx.x * 128 + wave * 32 + li;
+  uint4 qf[NK], dof[NK];
+  float delta = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    qf[kk] = dof[kk] = make_uint4(0, 0, 0, 0);
+    if (iq < a.S) {
+      qf[kk] = *reinterpret_cast<const uint4*>(base + (size_t)iq * a.ld_qkv + 16 * kk + 8 * g);
+      const size_t off = ((size_t)b * a.S + iq) * a.ld_o + h * DH + 16 * kk + 8 * g;
+      dof[kk] = *reinterpret_cast<const uint4*>(a.dout[gi] + off);
+      const uint4 of = *reinterpret_cast<const uint4*>(a.o[gi] + off);
+      const uint32_t dw[4] = {dof[kk].x, dof[kk].y, dof[kk].z, dof[kk].w}, ow[4] = {of.x, of.y, of.z, of.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) delta += bf_lo(dw[e]) * bf_lo(ow[e]) + bf_hi(dw[e]) * bf_hi(ow[e]);
+    }
+  }
+  delta += __shfl_xor(delta, 32, 64);
+  const float lse2 = iq < a.S ? a.lse[gi][(size_t)bh * a.S + iq] * LOG2E : 0.f;
+  if (iq < a.S && g == 0) a.delta[gi][(size_t)bh * a.S + iq] = delta;
+  f32x16 acc[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+  const float sc = a.scale * LOG2E;
+  const int q_hi = min(a.S, blockIdx.x * 128 + 128) - 1;
+  const int n_tiles = a.causal ? (q_hi / 64 + 1) : (a.S + 63) / 64;
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = t * 64;
+    __syncthreads();
+    load_rows<DH>(tK, base + d, a.ld_qkv, j0, a.S, tid);
+    load_rows<DH>(tV, base + 2 * d, a.ld_qkv, j0, a.S, tid);
+    load_transposed<DH>(tKt, base + d, a.ld_qkv, j0, a.S, tid);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+        s = mfma(read_rows<DH>(tK, sub * 32 + li, 2 * kk + g), qf[kk], s);
+        dp = mfma(read_rows<DH>(tV, sub * 32 + li, 2 * kk + g), dof[kk], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        float p = exp2f(s[r] * sc - lse2);
+        if (j >= a.S || (a.causal && j > iq)) p = 0.f;
+        s[r] = p * (dp[r] - delta);
+      }
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const uint4 df = pack_half(s, x);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[c] = mfma(read_transposed(tKt, c * 32 + li, sub, x, g), df, acc[c]);
+      }
+    }
+  }
+  if (iq < a.S) {
+    bf16_t* o = a.dqkv[gi] + ((size_t)b * a.S + iq) * a.ld_qkv + h * DH;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = c * 32 + 8 * q + 4 * g;
+        *reinterpret_cast<uint2*>(o + col) =
+            make_uint2(pack2(acc[c][4 * q] * a.scale, acc[c][4 * q + 1] * a.scale),
+                       pack2(acc[c][4 * q + 2] * a.scale, acc[c][4 * q + 3] * a.scale));
+      }
+  }
+}
+
+// ---- backward, dk and dv -----------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const AttnBwdArgs a) {
+  constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
+  extern __shared__ uint4 lds[];
+  uint4* tQ = lds;                                              // [64][NCH]
+  uint4* tdO = lds + 64 * NCH;                                  // [64][NCH]
+  uint2* tQt = reinterpret_cast<uint2*>(lds + 2 * 64 * NCH);    // [DH][16]
+  uint2* tdOt = tQt + DH * 16;                                  // [DH][16]
+  float* st = reinterpret_cast<float*>(tdOt + DH * 16);         // [2][64]: lse*log2e, delta
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
+  const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int d = a.H * DH;
+  const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
+  const bf16_t* dobase = a.dout[gi] + (size_t)b * a.S * a.ld_o + h * DH;
+  const int jk = blockIdx.x * 128 + wave * 32 + li;  // this lane's key
+  uint4 kf[NK], vf[NK];
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    kf[kk] = vf[kk] = make_uint4(0, 0, 0, 0);
+    if (jk < a.S) {
+      kf[kk] = *reinterpret_cast<const uint4*>(base + d + (size_t)jk * a.ld_qkv + 16 * kk + 8 * g);
+      vf[kk] = *reinterpret_cast<const uint4*>(base + 2 * d + (size_t)jk * a.ld_qkv + 16 * kk + 8 * g);
+    }
+  }
+  f32x16 dk[NC], dv[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[c][r] = dv[c][r] = 0.f;
+  const float sc = a.scale * LOG2E;
+  const int t0 = a.causal ? (blockIdx.x * 128) / 64 : 0;  // queries before the workgroup's first key see none of its keys
+  const int n_tiles = (a.S + 63) / 64;
+  for (int t = t0; t < n_tiles; ++t) {
+    const int i0 = t * 64;
+    __syncthreads();
+    load_rows<DH>(tQ, base, a.ld_qkv, i0, a.S, tid);
+    load_rows<DH>(tdO, dobase, a.ld_o, i0, a.S, tid);
+    load_transposed<DH>(tQt, base, a.ld_qkv, i0, a.S, tid);
+    load_transposed<DH>(tdOt, dobase, a.ld_o, i0, a.S, tid);
+    if (tid < 128) {
+      const int i = i0 + (tid & 63);
+      float v = 0.f;
+      if (i < a.S) v = tid < 64 ? a.lse[gi][(size_t)bh * a.S + i] * LOG2E : a.delta[gi][(size_t)bh * a.S + i];
+      st[tid] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+        s = mfma(read_rows<DH>(tQ, sub * 32 + li, 2 * kk + g), kf[kk], s);
+        dp = mfma(read_rows<DH>(tdO, sub * 32 + li, 2 * kk + g), vf[kk], dp);
+      }
+      f32x16 ds;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int il = sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3), i = i0 + il;
+        float p = exp2f(s[r] * sc - st[il]);
+        if (i >= a.S || (a.causal && jk > i)) p = 0.f;
+        s[r] = p;
+        ds[r] = p * (dp[r] - st[64 + il]);
+      }
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const uint4 pf = pack_half(s, x), df = pack_half(ds, x);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          dv[c] = mfma(read_transposed(tdOt, c * 32 + li, sub, x, g), pf, dv[c]);
+          dk[c] = mfma(read_transposed(tQt, c * 32 + li, sub, x, g), df, dk[c]);
+        }
+      }
+    }
+  }
+  if (jk < a.S) {
+    bf16_t* ok = a.dqkv[gi] + ((size_t)b * a.S + jk) * a.ld_qkv + d + h * DH;
+    bf16_t* ov = ok + d;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = c * 32 + 8 * q + 4 * g;
+        *reinterpret_cast<uint2*>(ok + col) =
+            make_uint2(pack2(dk[c][4 * q] * a.scale, dk[c][4 * q + 1] * a.scale),
+                       pack2(dk[c][4 * q + 2] * a.scale, dk[c][4 * q + 3] * a.scale));
+        *reinterpret_cast<uint2*>(ov + col) = make_uint2(pack2(dv[c][4 * q], dv[c][4 * q + 1]),
+                                                         pack2(dv[c][4 * q + 2], dv[c][4 * q + 3]));
+      }
+  }
+}
+
+template <int DH> constexpr size_t fwd_lds() { return (size_t)64 * (DH / 8) * 16 + (size_t)DH * 16 * 8; }
+template <int DH> constexpr size_t dq_lds() { return (size_t)2 * 64 * (DH / 8) * 16 + (size_t)DH * 16 * 8; }
+template <int DH> constexpr size_t dkv_lds() { return (size_t)2 * 64 * (DH / 8) * 16 + (size_t)2 * DH * 16 * 8 + 128 * 4; }
+
+bool attn_ok(int B, int S, int H, int DH, int ld_qkv, int ld_o, int G) {
+  return G >= 1 && G <= MAXG && B >= 1 && S >= 1 && H >= 1 && (DH == 64 || DH == 128) && ld_qkv >= 3 * H * DH &&
+         !(ld_qkv & 7) && ld_o >= H * DH && !(ld_o & 7);
+}
+
+}  // namespace
+
+hipError_t attn_init() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkv_kernel<128>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)dkv_lds<128>());
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<128>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)dq_lds<128>());
+}
+
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
+  if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
+  dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
+  if (a.DH == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), fwd_lds<64>(), s, a);
+  else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), fwd_lds<128>(), s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd(const AttnBwdArgs& a, hipStream_t s) {
+  if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
+  dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
+  if (a.DH == 64) {
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), dq_lds<64>(), s, a);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, grid, dim3(256), dkv_lds<64>(), s, a);
+  } else {
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(256), dq_lds<128>(), s, a);
+    hipLaunchKernelGGL(attn_bwd_dkv_kernel<128>, grid, dim3(256), dkv_lds<128>(), s, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace hydra

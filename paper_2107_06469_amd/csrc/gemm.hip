@@ -315,6 +315,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
   T* pre = static_cast<T*>(a.pre[g]);
   const T* gate = static_cast<const T*>(a.gate[g]);
   const T* resid = static_cast<const T*>(a.resid[g]);
+  const T* mul = static_cast<const T*>(a.mul[g]);
   const int act = a.act;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
@@ -349,6 +350,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] = act_fwd(v[e], act);
         }
+        if (mul) {
+          float z[8];
+          load8<T>(mul + (size_t)m * a.ldo + n, z);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= z[e];
+        }
         if (resid) {
           float z[8];
           load8<T>(resid + (size_t)m * a.ldr + n, z);
@@ -366,6 +373,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
             if (pre) pre[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
             if (gate) t *= act_grad(Elem<T>::to_f(gate[(size_t)m * a.ldg + n + e]), act);
             else t = act_fwd(t, act);
+            if (mul) t *= Elem<T>::to_f(mul[(size_t)m * a.ldo + n + e]);
             if (resid) t += Elem<T>::to_f(resid[(size_t)m * a.ldr + n + e]);
             if (a.out_f32) static_cast<float*>(a.out[g])[(size_t)m * a.ldo + n + e] = t;
             else static_cast<T*>(a.out[g])[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
@@ -435,6 +443,13 @@ hipError_t gemm_init() {
   return Cfg<float, 1, 4, 1, 1>::attr();
 }
 
+hipError_t kernels_init() {
+  hipError_t e;
+  if ((e = gemm_init()) != hipSuccess) return e;
+  if ((e = ln_init()) != hipSuccess) return e;
+  return attn_init();
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   const int E = a.dtype == GEMM_F32 ? 4 : 8;
   auto rup = [&](int v) { return (v + E - 1) / E * E; };
@@ -447,9 +462,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   for (int g = 0; g < a.G; ++g) {
     if (!a.X[g] || !a.W[g] || !a.out[g]) return hipErrorInvalidValue;
     if (((uintptr_t)a.X[g] | (uintptr_t)a.W[g] | (uintptr_t)a.out[g] | (uintptr_t)a.bias[g] | (uintptr_t)a.pre[g] |
-         (uintptr_t)a.gate[g] | (uintptr_t)a.resid[g]) & 15)
+         (uintptr_t)a.gate[g] | (uintptr_t)a.resid[g] | (uintptr_t)a.mul[g]) & 15)
       return hipErrorInvalidValue;
     if ((a.bias[g] == nullptr) != (a.bias[0] == nullptr) || (a.pre[g] == nullptr) != (a.pre[0] == nullptr) ||
+        (a.mul[g] == nullptr) != (a.mul[0] == nullptr) ||
         (a.gate[g] == nullptr) != (a.gate[0] == nullptr) || (a.resid[g] == nullptr) != (a.resid[0] == nullptr))
       return hipErrorInvalidValue;
   }

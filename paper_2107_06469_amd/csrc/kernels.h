@@ -21,7 +21,8 @@ enum { GEMM_F32 = 0, GEMM_BF16 = 1 };
 
 // C[M,N] = sum_k X(m,k) * W(n,k) followed by the epilogue
 //   v = acc (+ bias[n]);  pre[m,n] = v (optional);
-//   v = gate ? v * act'(gate[m,n]) : act(v);  v += resid[m,n] (optional);  out[m,n] = v.
+//   v = gate ? v * act'(gate[m,n]) : act(v);  v *= mul[m,n] (optional);  v += resid[m,n] (optional);
+//   out[m,n] = v.
 // x_kmajor: X stored [M, ldx] with k contiguous, else stored [K, ldx] with m contiguous.
 // w_kmajor: W stored [N, ldw] with k contiguous, else stored [K, ldw] with n contiguous.
 // Leading dimensions are in elements and must be multiples of 16 bytes worth of elements, and at
@@ -39,6 +40,7 @@ struct GemmArgs {
   void* pre[MAXG];          // nullable, [M, ldo], operand dtype
   const void* gate[MAXG];   // nullable, [M, ldg], operand dtype
   const void* resid[MAXG];  // nullable, [M, ldr], operand dtype
+  const void* mul[MAXG];    // nullable, [M, ldo], operand dtype: v *= mul[m,n] after the activation
   int ldo, ldg, ldr;
   int act;
   int out_f32;
@@ -103,5 +105,98 @@ struct OptimArgs {
   float lr[MAXG], b1[MAXG], b2[MAXG], c1[MAXG], c2[MAXG], eps[MAXG], bc1[MAXG], bc2[MAXG];  // c = 1 - b, rounded from double
 };
 hipError_t launch_optim(const OptimArgs& a, hipStream_t s);
+
+// ---- LayerNorm (layernorm.hip) --------------------------------------------------------------------------
+// y = (x-mean)*rstd*gamma + beta over rows of width d (d % 8 == 0, d <= 4096); mean/rstd fp32 per row.
+struct LnArgs {
+  int dtype, rows, d, ld, G;
+  float eps;
+  const void* x[MAXG];
+  void* y[MAXG];
+  const float* gamma[MAXG];
+  const float* beta[MAXG];
+  float* mean[MAXG];
+  float* rstd[MAXG];
+};
+hipError_t launch_ln_fwd(const LnArgs& a, hipStream_t s);
+// dx = rstd*(g - mean(g) - xhat*mean(g*xhat)) + add (add optional), g = dy*gamma;
+// dgamma = sum_rows dy*xhat, dbeta = sum_rows dy.  part: scratch of ln_bwd_blocks(rows)*2*d floats.
+struct LnBwdArgs {
+  int dtype, rows, d, ld, G;
+  const void* x[MAXG];
+  const void* dy[MAXG];
+  const void* add[MAXG];
+  void* dx[MAXG];
+  const float* gamma[MAXG];
+  const float* mean[MAXG];
+  const float* rstd[MAXG];
+  float* part[MAXG];
+  float* dgamma[MAXG];
+  float* dbeta[MAXG];
+};
+int ln_bwd_blocks(int rows);
+hipError_t launch_ln_bwd(const LnBwdArgs& a, hipStream_t s);
+hipError_t ln_init();
+
+// ---- embedding, row gather/scatter, gated feed-forward pieces (embedding.hip) -------------------------------
+struct EmbedArgs {
+  int dtype, tokens, S, d, ld, G;
+  const int32_t* ids;  // [tokens], shared by the group
+  const void* tok[MAXG];
+  const void* pos[MAXG];
+  void* x[MAXG];
+};
+hipError_t launch_embed_fwd(const EmbedArgs& a, hipStream_t s);
+struct EmbedBwdArgs {
+  int dtype, V, S, S_table, B, d, ld, G;
+  const int32_t* row_ptr;    // [V+1] CSR over token ids of this batch
+  const int32_t* positions;  // [B*S] token indices grouped by id, ascending inside a group
+  const void* dx[MAXG];
+  float* dtok[MAXG];  // [V, d]
+  float* dpos[MAXG];  // [S_table, d]
+};
+hipError_t launch_embed_bwd(const EmbedBwdArgs& a, hipStream_t s);
+struct RowsArgs {
+  int dtype, n, d, ld_src, ld_dst, G;
+  const int32_t* rows;  // [n], shared by the group
+  const void* src[MAXG];
+  void* dst[MAXG];
+};
+hipError_t launch_gather_rows(const RowsArgs& a, hipStream_t s);   // dst[r] = src[rows[r]]
+hipError_t launch_scatter_rows(const RowsArgs& a, hipStream_t s);  // dst[rows[r]] = src[r]
+struct GatedBwdArgs {
+  int dtype, rows, ld, G;
+  const void* dh[MAXG];
+  const void* z1[MAXG];
+  const void* zg[MAXG];
+  void* dz1[MAXG];
+  void* dzg[MAXG];
+};
+hipError_t launch_gated_bwd(const GatedBwdArgs& a, hipStream_t s);
+
+// ---- attention (attention.hip), bf16 only, head width 64 or 128 ------------------------------------------
+struct AttnArgs {
+  int B, S, H, DH, ld_qkv, ld_o, causal, G;
+  float scale;
+  const bf16_t* qkv[MAXG];
+  bf16_t* o[MAXG];
+  float* lse[MAXG];  // [B*H*S]
+};
+hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
+struct AttnBwdArgs {
+  int B, S, H, DH, ld_qkv, ld_o, causal, G;
+  float scale;
+  const bf16_t* qkv[MAXG];
+  const bf16_t* o[MAXG];
+  const bf16_t* dout[MAXG];
+  const float* lse[MAXG];
+  float* delta[MAXG];  // [B*H*S] scratch, written by the dq kernel and read by the dk/dv kernel
+  bf16_t* dqkv[MAXG];
+};
+hipError_t launch_attn_bwd(const AttnBwdArgs& a, hipStream_t s);
+hipError_t attn_init();
+
+// all per-process kernel set-up (LDS limits); call once before the first launch
+hipError_t kernels_init();
 
 }  // namespace hydra

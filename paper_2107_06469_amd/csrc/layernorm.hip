@@ -1,0 +1,267 @@
+// LayerNorm forward and backward over rows of width d (bf16 or fp32 rows, fp32 statistics).
+//   forward:  mu = mean(x), var = mean((x-mu)^2) (biased), rstd = 1/sqrt(var+eps),
+//             y = (x-mu)*rstd*gamma + beta; mu and rstd are saved per row.
+//   backward: g = dy*gamma; dx = rstd*(g - mean(g) - xhat*mean(g*xhat)) (+ add);
+//             dgamma = sum_rows dy*xhat; dbeta = sum_rows dy.
+// One wavefront owns a row: each lane keeps its 16-byte chunks of the row in registers, statistics are
+// butterfly reductions over the 64 lanes (fixed order).  The column sums of the backward pass are
+// accumulated per workgroup over a fixed range of rows, written as partial sums, and added over
+// workgroups in index order by a second kernel: no atomics, so results do not depend on timing.
+#include "kernels.h"
+
+namespace hydra {
+namespace {
+
+// MAXC = 8-element chunks a lane may own: d <= 8*64*MAXC (2 -> 1024, 4 -> 2048, 8 -> 4096)
+constexpr int LN_ROWS_PER_WG = 64;  // rows per workgroup in the backward pass (4 waves x 16 rows)
+
+__device__ __forceinline__ bf16_t f2bf(float v) {
+  __bf16 h = (__bf16)v;
+  return __builtin_bit_cast(bf16_t, h);
+}
+
+template <typename T>
+__device__ __forceinline__ void ld8(const T* p, float (&v)[8]);
+template <>
+__device__ __forceinline__ void ld8<float>(const float* p, float (&v)[8]) {
+  float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void ld8<bf16_t>(const bf16_t* p, float (&v)[8]) {
+  uint4 a = *reinterpret_cast<const uint4*>(p);
+  uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+template <typename T>
+__device__ __forceinline__ void st8(T* p, const float (&v)[8]);
+template <>
+__device__ __forceinline__ void st8<float>(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+template <>
+__device__ __forceinline__ void st8<bf16_t>(bf16_t* p, const float (&v)[8]) {
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+  *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T, int LN_MAXC>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const LnArgs a) {
+  const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= a.rows) return;
+  const T* x = static_cast<const T*>(a.x[g]) + (size_t)row * a.ld;
+  T* y = static_cast<T*>(a.y[g]) + (size_t)row * a.ld;
+  const int nch = a.d >> 3;
+  float v[LN_MAXC][8];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      ld8<T>(x + 8 * c, v[i]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += v[i][e];
+    }
+  }
+  const float mu = wave_sum(s) / (float)a.d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float t = v[i][e] - mu;
+        q += t * t;
+      }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)a.d + a.eps);
+  const float* gamma = a.gamma[g];
+  const float* beta = a.beta[g];
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+      float ga[8], be[8], o[8];
+      ld8<float>(gamma + 8 * c, ga);
+      ld8<float>(beta + 8 * c, be);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (v[i][e] - mu) * rstd * ga[e] + be[e];
+      st8<T>(y + 8 * c, o);
+    }
+  }
+  if (lane == 0) {
+    a.mean[g][row] = mu;
+    a.rstd[g][row] = rstd;
+  }
+}
+
+// dx and per-workgroup partial column sums.  Workgroup b owns rows [b*64, b*64+64); wave w takes rows
+// b*64 + w, +4, +8, ...; partial sums go to part[g][b][2][d].
+template <typename T, int LN_MAXC>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const LnBwdArgs a) {
+  extern __shared__ float red[];  // [4][2][d]
+  const int g = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nch = a.d >> 3;
+  const float* gamma = a.gamma[g];
+  float ga[LN_MAXC][8], sg[LN_MAXC][8], sb[LN_MAXC][8];
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + 64 * i;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sg[i][e] = sb[i][e] = ga[i][e] = 0.f;
+    if (c < nch) ld8<float>(gamma + 8 * c, ga[i]);
+  }
+  const int row0 = blockIdx.x * LN_ROWS_PER_WG;
+  for (int r = wave; r < LN_ROWS_PER_WG; r += 4) {
+    const int row = row0 + r;
+    if (row >= a.rows) break;
+    const T* x = static_cast<const T*>(a.x[g]) + (size_t)row * a.ld;
+    const T* dy = static_cast<const T*>(a.dy[g]) + (size_t)row * a.ld;
+    const float mu = a.mean[g][row], rstd = a.rstd[g][row];
+    float xh[LN_MAXC][8], gg[LN_MAXC][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        float xv[8], dv[8];
+        ld8<T>(x + 8 * c, xv);
+        ld8<T>(dy + 8 * c, dv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          xh[i][e] = (xv[e] - mu) * rstd;
+          gg[i][e] = dv[e] * ga[i][e];
+          s1 += gg[i][e];
+          s2 += gg[i][e] * xh[i][e];
+          sg[i][e] += dv[e] * xh[i][e];
+          sb[i][e] += dv[e];
+        }
+      }
+    }
+    const float c1 = wave_sum(s1) / (float)a.d, c2 = wave_sum(s2) / (float)a.d;
+    T* dx = static_cast<T*>(a.dx[g]) + (size_t)row * a.ld;
+    const T* add = a.add[g] ? static_cast<const T*>(a.add[g]) + (size_t)row * a.ld : nullptr;
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = rstd * (gg[i][e] - c1 - xh[i][e] * c2);
+        if (add) {
+          float av[8];
+          ld8<T>(add + 8 * c, av);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += av[e];
+        }
+        st8<T>(dx + 8 * c, o);
+      }
+    }
+  }
+  // the four waves' partial sums are added in wave order
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + 64 * i;
+    if (c < nch) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        red[(wave * 2 + 0) * a.d + 8 * c + e] = sg[i][e];
+        red[(wave * 2 + 1) * a.d + 8 * c + e] = sb[i][e];
+      }
+    }
+  }
+  __syncthreads();
+  float* part = a.part[g] + (size_t)blockIdx.x * 2 * a.d;
+  for (int j = threadIdx.x; j < 2 * a.d; j += 256) {
+    const int which = j / a.d, col = j % a.d;
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) t += red[(w * 2 + which) * a.d + col];
+    part[which * a.d + col] = t;
+  }
+}
+
+// dgamma[col] = sum_b part[b][0][col], dbeta[col] = sum_b part[b][1][col], b ascending
+__global__ __launch_bounds__(256) void ln_reduce_kernel(const LnBwdArgs a, int nblocks) {
+  const int g = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= 2 * a.d) return;
+  const float* part = a.part[g];
+  float t = 0.f;
+  for (int b = 0; b < nblocks; ++b) t += part[(size_t)b * 2 * a.d + j];
+  if (j < a.d) a.dgamma[g][j] = t;
+  else a.dbeta[g][j - a.d] = t;
+}
+
+}  // namespace
+
+int ln_bwd_blocks(int rows) { return (rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG; }
+
+static bool ln_shape_ok(int G, int rows, int d, int ld) {
+  return G >= 1 && G <= MAXG && rows >= 1 && d >= 8 && !(d & 7) && d <= 4096 && ld >= d && !(ld & 7);
+}
+
+template <typename T, int C>
+static hipError_t ln_fwd_run(const LnArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((ln_fwd_kernel<T, C>), dim3((a.rows + 3) / 4, a.G), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+template <typename T>
+static hipError_t ln_fwd_pick(const LnArgs& a, hipStream_t s) {
+  if (a.d <= 1024) return ln_fwd_run<T, 2>(a, s);
+  if (a.d <= 2048) return ln_fwd_run<T, 4>(a, s);
+  return ln_fwd_run<T, 8>(a, s);
+}
+
+hipError_t launch_ln_fwd(const LnArgs& a, hipStream_t s) {
+  if (!ln_shape_ok(a.G, a.rows, a.d, a.ld)) return hipErrorInvalidValue;
+  return a.dtype == GEMM_F32 ? ln_fwd_pick<float>(a, s) : ln_fwd_pick<bf16_t>(a, s);
+}
+
+template <typename T, int C>
+static hipError_t ln_bwd_run(const LnBwdArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)4 * 2 * a.d * sizeof(float);
+  hipLaunchKernelGGL((ln_bwd_kernel<T, C>), dim3(ln_bwd_blocks(a.rows), a.G), dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+template <typename T>
+static hipError_t ln_bwd_pick(const LnBwdArgs& a, hipStream_t s) {
+  if (a.d <= 1024) return ln_bwd_run<T, 2>(a, s);
+  if (a.d <= 2048) return ln_bwd_run<T, 4>(a, s);
+  return ln_bwd_run<T, 8>(a, s);
+}
+
+hipError_t launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
+  if (!ln_shape_ok(a.G, a.rows, a.d, a.ld)) return hipErrorInvalidValue;
+  hipError_t e = a.dtype == GEMM_F32 ? ln_bwd_pick<float>(a, s) : ln_bwd_pick<bf16_t>(a, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(ln_reduce_kernel, dim3((2 * a.d + 255) / 256, a.G), dim3(256), 0, s, a, ln_bwd_blocks(a.rows));
+  return hipGetLastError();
+}
+
+// the widest rows need 128 KB of LDS for the cross-wave column sums
+hipError_t ln_init() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_kernel<float, 8>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2 * 4096 * 4);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&ln_bwd_kernel<bf16_t, 8>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2 * 4096 * 4);
+}
+
+}  // namespace hydra

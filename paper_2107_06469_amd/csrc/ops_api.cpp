@@ -23,6 +23,11 @@ static int bad(const char* what) {
   return HYDRA_ERR_INVALID_ARG;
 }
 
+static int ensure_init() {
+  std::call_once(g_gemm_once, [] { g_gemm_init = kernels_init(); });
+  return g_gemm_init == hipSuccess ? 0 : done(g_gemm_init, "kernel set-up");
+}
+
 // splitmix64, n-th output from state s (twin of the device generator's keying step)
 static uint64_t sm_at(uint64_t s, uint64_t n) {
   uint64_t z = s + (n + 1) * 0x9E3779B97F4A7C15ull;
@@ -37,8 +42,7 @@ const char* hydra_ops_last_error(void) { return g_ops_err.c_str(); }
 
 int hydra_op_gemm(const hydra_gemm_desc* d, void* stream) {
   if (!d || !d->X || !d->W || !d->out || d->G < 1 || d->G > MAXG) return bad("hydra_op_gemm: NULL table or G out of range");
-  std::call_once(g_gemm_once, [] { g_gemm_init = gemm_init(); });
-  if (g_gemm_init != hipSuccess) return done(g_gemm_init, "hydra_op_gemm: kernel set-up");
+  if (int st = ensure_init()) return st;
   GemmArgs a{};
   a.dtype = d->dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
   a.M = d->M; a.N = d->N; a.K = d->K;
@@ -110,6 +114,86 @@ int hydra_op_init_uniform(float* dst, size_t n, uint64_t seed, uint64_t stream_i
   if (!dst) return bad("hydra_op_init_uniform: dst is NULL");
   const uint64_t key = sm_at(sm_at(seed, 0) ^ stream_id, 0);
   return done(launch_init_uniform(dst, n, key, a, static_cast<hipStream_t>(stream)), "hydra_op_init_uniform");
+}
+
+int hydra_op_layernorm_fwd(int dtype, int rows, int d, int ld, float eps, int G, const void* const* x, void* const* y,
+                           const float* const* gamma, const float* const* beta, float* const* mean,
+                           float* const* rstd, void* stream) {
+  if (!x || !y || !gamma || !beta || !mean || !rstd || G < 1 || G > MAXG) return bad("hydra_op_layernorm_fwd: NULL table or G out of range");
+  LnArgs a{};
+  a.dtype = dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
+  a.rows = rows; a.d = d; a.ld = ld; a.G = G; a.eps = eps;
+  for (int g = 0; g < G; ++g) {
+    a.x[g] = x[g]; a.y[g] = y[g]; a.gamma[g] = gamma[g]; a.beta[g] = beta[g]; a.mean[g] = mean[g]; a.rstd[g] = rstd[g];
+  }
+  return done(launch_ln_fwd(a, static_cast<hipStream_t>(stream)), "hydra_op_layernorm_fwd");
+}
+
+size_t hydra_op_layernorm_part_floats(int rows, int d) { return (size_t)ln_bwd_blocks(rows) * 2 * d; }
+
+int hydra_op_layernorm_bwd(int dtype, int rows, int d, int ld, int G, const void* const* x, const void* const* dy,
+                           const void* const* add, void* const* dx, const float* const* gamma,
+                           const float* const* mean, const float* const* rstd, float* const* part,
+                           float* const* dgamma, float* const* dbeta, void* stream) {
+  if (!x || !dy || !dx || !gamma || !mean || !rstd || !part || !dgamma || !dbeta || G < 1 || G > MAXG)
+    return bad("hydra_op_layernorm_bwd: NULL table or G out of range");
+  if (int st = ensure_init()) return st;
+  LnBwdArgs a{};
+  a.dtype = dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
+  a.rows = rows; a.d = d; a.ld = ld; a.G = G;
+  for (int g = 0; g < G; ++g) {
+    a.x[g] = x[g]; a.dy[g] = dy[g]; a.add[g] = add ? add[g] : nullptr; a.dx[g] = dx[g]; a.gamma[g] = gamma[g];
+    a.mean[g] = mean[g]; a.rstd[g] = rstd[g]; a.part[g] = part[g]; a.dgamma[g] = dgamma[g]; a.dbeta[g] = dbeta[g];
+  }
+  return done(launch_ln_bwd(a, static_cast<hipStream_t>(stream)), "hydra_op_layernorm_bwd");
+}
+
+int hydra_op_attention_fwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
+                           const void* const* qkv, void* const* o, float* const* lse, void* stream) {
+  if (!qkv || !o || !lse || G < 1 || G > MAXG) return bad("hydra_op_attention_fwd: NULL table or G out of range");
+  if (int st = ensure_init()) return st;
+  AttnArgs a{};
+  a.B = B; a.S = S; a.H = H; a.DH = DH; a.ld_qkv = ld_qkv; a.ld_o = ld_o; a.causal = causal; a.G = G; a.scale = scale;
+  for (int g = 0; g < G; ++g) {
+    a.qkv[g] = static_cast<const bf16_t*>(qkv[g]); a.o[g] = static_cast<bf16_t*>(o[g]); a.lse[g] = lse[g];
+  }
+  return done(launch_attn_fwd(a, static_cast<hipStream_t>(stream)), "hydra_op_attention_fwd");
+}
+
+int hydra_op_attention_bwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
+                           const void* const* qkv, const void* const* o, const void* const* dout,
+                           const float* const* lse, float* const* delta, void* const* dqkv, void* stream) {
+  if (!qkv || !o || !dout || !lse || !delta || !dqkv || G < 1 || G > MAXG) return bad("hydra_op_attention_bwd: NULL table or G out of range");
+  if (int st = ensure_init()) return st;
+  AttnBwdArgs a{};
+  a.B = B; a.S = S; a.H = H; a.DH = DH; a.ld_qkv = ld_qkv; a.ld_o = ld_o; a.causal = causal; a.G = G; a.scale = scale;
+  for (int g = 0; g < G; ++g) {
+    a.qkv[g] = static_cast<const bf16_t*>(qkv[g]); a.o[g] = static_cast<const bf16_t*>(o[g]);
+    a.dout[g] = static_cast<const bf16_t*>(dout[g]); a.lse[g] = lse[g]; a.delta[g] = delta[g];
+    a.dqkv[g] = static_cast<bf16_t*>(dqkv[g]);
+  }
+  return done(launch_attn_bwd(a, static_cast<hipStream_t>(stream)), "hydra_op_attention_bwd");
+}
+
+int hydra_op_embed_fwd(int dtype, int tokens, int S, int d, int ld, int G, const int32_t* ids, const void* const* tok,
+                       const void* const* pos, void* const* x, void* stream) {
+  if (!ids || !tok || !pos || !x || G < 1 || G > MAXG) return bad("hydra_op_embed_fwd: NULL table or G out of range");
+  EmbedArgs a{};
+  a.dtype = dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
+  a.tokens = tokens; a.S = S; a.d = d; a.ld = ld; a.G = G; a.ids = ids;
+  for (int g = 0; g < G; ++g) { a.tok[g] = tok[g]; a.pos[g] = pos[g]; a.x[g] = x[g]; }
+  return done(launch_embed_fwd(a, static_cast<hipStream_t>(stream)), "hydra_op_embed_fwd");
+}
+
+int hydra_op_embed_bwd(int dtype, int V, int S, int S_table, int B, int d, int ld, int G, const int32_t* row_ptr,
+                       const int32_t* positions, const void* const* dx, float* const* dtok, float* const* dpos,
+                       void* stream) {
+  if (!row_ptr || !positions || !dx || !dtok || !dpos || G < 1 || G > MAXG) return bad("hydra_op_embed_bwd: NULL table or G out of range");
+  EmbedBwdArgs a{};
+  a.dtype = dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
+  a.V = V; a.S = S; a.S_table = S_table; a.B = B; a.d = d; a.ld = ld; a.G = G; a.row_ptr = row_ptr; a.positions = positions;
+  for (int g = 0; g < G; ++g) { a.dx[g] = dx[g]; a.dtok[g] = dtok[g]; a.dpos[g] = dpos[g]; }
+  return done(launch_embed_bwd(a, static_cast<hipStream_t>(stream)), "hydra_op_embed_bwd");
 }
 
 int hydra_op_cast_bf16(const float* src, void* dst, size_t n, void* stream) {

@@ -34,6 +34,14 @@ def _L():
         L.hydra_op_optim.argtypes = [C.c_int, C.c_size_t, C.c_int, pp, pp, pp, pp, pp, C.POINTER(C.c_double), vp]
         L.hydra_op_init_uniform.argtypes = [vp, C.c_size_t, C.c_uint64, C.c_uint64, C.c_float, vp]
         L.hydra_op_cast_bf16.argtypes = [vp, vp, C.c_size_t, vp]
+        L.hydra_op_layernorm_fwd.argtypes = [C.c_int] * 4 + [C.c_float, C.c_int] + [pp] * 6 + [vp]
+        L.hydra_op_layernorm_bwd.argtypes = [C.c_int] * 5 + [pp] * 10 + [vp]
+        L.hydra_op_layernorm_part_floats.argtypes = [C.c_int, C.c_int]
+        L.hydra_op_layernorm_part_floats.restype = C.c_size_t
+        L.hydra_op_attention_fwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int, pp, pp, pp, vp]
+        L.hydra_op_attention_bwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int] + [pp] * 6 + [vp]
+        L.hydra_op_embed_fwd.argtypes = [C.c_int] * 6 + [vp, pp, pp, pp, vp]
+        L.hydra_op_embed_bwd.argtypes = [C.c_int] * 8 + [vp, vp, pp, pp, pp, vp]
         L.hydra_ops_last_error.restype = C.c_char_p
         _ready = True
     return L
@@ -88,3 +96,37 @@ def hydra_op_init_uniform(dst, n, seed, stream_id, a):
 
 def hydra_op_cast_bf16(src, dst, n):
     _check(_L().hydra_op_cast_bf16(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), n, _stream()))
+
+
+def hydra_op_layernorm_fwd(dtype, rows, d, ld, eps, x, y, gamma, beta, mean, rstd):
+    _check(_L().hydra_op_layernorm_fwd(dtype, rows, d, ld, eps, len(x), _tab(x), _tab(y), _tab(gamma), _tab(beta),
+                                       _tab(mean), _tab(rstd), _stream()))
+
+
+def hydra_op_layernorm_part_floats(rows, d) -> int:
+    return int(_L().hydra_op_layernorm_part_floats(rows, d))
+
+
+def hydra_op_layernorm_bwd(dtype, rows, d, ld, x, dy, add, dx, gamma, mean, rstd, part, dgamma, dbeta):
+    _check(_L().hydra_op_layernorm_bwd(dtype, rows, d, ld, len(x), _tab(x), _tab(dy), _tab(add), _tab(dx), _tab(gamma),
+                                       _tab(mean), _tab(rstd), _tab(part), _tab(dgamma), _tab(dbeta), _stream()))
+
+
+def hydra_op_attention_fwd(B, S, H, DH, ld_qkv, ld_o, causal, scale, qkv, o, lse):
+    _check(_L().hydra_op_attention_fwd(B, S, H, DH, ld_qkv, ld_o, int(causal), scale, len(qkv), _tab(qkv), _tab(o),
+                                       _tab(lse), _stream()))
+
+
+def hydra_op_attention_bwd(B, S, H, DH, ld_qkv, ld_o, causal, scale, qkv, o, dout, lse, delta, dqkv):
+    _check(_L().hydra_op_attention_bwd(B, S, H, DH, ld_qkv, ld_o, int(causal), scale, len(qkv), _tab(qkv), _tab(o),
+                                       _tab(dout), _tab(lse), _tab(delta), _tab(dqkv), _stream()))
+
+
+def hydra_op_embed_fwd(dtype, tokens, S, d, ld, ids, tok, pos, x):
+    _check(_L().hydra_op_embed_fwd(dtype, tokens, S, d, ld, len(x), C.c_void_p(ids.data_ptr()), _tab(tok), _tab(pos),
+                                   _tab(x), _stream()))
+
+
+def hydra_op_embed_bwd(dtype, V, S, S_table, B, d, ld, row_ptr, positions, dx, dtok, dpos):
+    _check(_L().hydra_op_embed_bwd(dtype, V, S, S_table, B, d, ld, len(dx), C.c_void_p(row_ptr.data_ptr()),
+                                   C.c_void_p(positions.data_ptr()), _tab(dx), _tab(dtok), _tab(dpos), _stream()))
