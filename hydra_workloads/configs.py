@@ -136,10 +136,10 @@ def scaled_workload(i: int, **kw) -> Workload:
     if i in (2, 3, 4):
         K = kw.get("K", 3)
         S = kw.get("seq", 48)
-        d, H = kw.get("d", 64), kw.get("heads", 4)
+        d, H = kw.get("d", 128), kw.get("heads", 2)      # head width 64, as in the full-size workloads
         kind = KIND_DECODER if i == 4 else KIND_ENCODER
         depths = kw.get("depths", [4] * K if i != 3 else [2, 4, 6][:K])
-        archs = [transformer_arch(kind, L, d, H, kw.get("d_ffn", 4 * d if i != 4 else 172), kw.get("vocab", 301), S,
+        archs = [transformer_arch(kind, L, d, H, kw.get("d_ffn", 4 * d if i != 4 else 344), kw.get("vocab", 301), S,
                                   1 if i == 4 else 0, kw.get("dtype", DTYPE_BF16)) for L in depths]
         hps = [hparams(OPT_ADAM, 1e-3 * (k + 1), kw.get("warmup", 0) * (k % 2)) for k in range(K)]
         per = kw.get("layers_per_shard", 2)

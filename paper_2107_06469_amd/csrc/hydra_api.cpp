@@ -1,7 +1,9 @@
 // The C boundary declared in include/hydra.h: argument checking, call-order checking and copies
 // between caller memory and the device.  No exception leaves these functions.
+#include <algorithm>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "hydra_internal.h"
 
@@ -192,8 +194,10 @@ hydra_status hydra_set_data(hydra_ctx* c, const void* inputs, const int32_t* tgt
     ctx_free(c, c->ids, c->ids_bytes);
     ctx_free(c, c->tgt_pos, c->tp_bytes);
     ctx_free(c, c->targets, c->tg_bytes);
+    ctx_free(c, c->csr_ptr, c->csr_ptr_bytes);
+    ctx_free(c, c->csr_pos, c->csr_pos_bytes);
     c->x_staged = nullptr;
-    c->ids = c->tgt_pos = c->targets = nullptr;
+    c->ids = c->tgt_pos = c->targets = c->csr_ptr = c->csr_pos = nullptr;
   }
   c->n_batches = n_batches;
   c->B = B;
@@ -220,7 +224,59 @@ hydra_status hydra_set_data(hydra_ctx* c, const void* inputs, const int32_t* tgt
       ctx_free(c, tmp, rows * a.d_in * 4);
     }
   } else {
-    return c->fail(HYDRA_ERR_UNSUPPORTED, "Transformer models are not implemented yet");
+    const int S = S_or_d, V = a.n_out;
+    if (!tgt_pos || P < 1 || S < 1) return c->fail(HYDRA_ERR_INVALID_ARG, "Transformer data needs target_pos, P >= 1 and S >= 1");
+    for (const Model& m : c->models) {
+      if (S > m.arch.max_seq) return c->fail(HYDRA_ERR_INVALID_ARG, "S = %d exceeds max_seq = %d", S, m.arch.max_seq);
+      if (m.arch.dtype != HYDRA_DTYPE_BF16) return c->fail(HYDRA_ERR_UNSUPPORTED, "Transformer models run in bf16 only");
+      const int dh = m.arch.d_model / m.arch.n_heads;
+      if (dh != 64 && dh != 128) return c->fail(HYDRA_ERR_UNSUPPORTED, "head width %d: the attention kernels take 64 or 128", dh);
+    }
+    if (P > S) return c->fail(HYDRA_ERR_INVALID_ARG, "P = %d target positions exceed S = %d", P, S);
+    const int32_t* ids = static_cast<const int32_t*>(inputs);
+    const size_t Tk = (size_t)B * S, NT = (size_t)B * P;
+    std::vector<int32_t> rows((size_t)n_batches * NT), ptr((size_t)n_batches * (V + 1)), pos((size_t)n_batches * Tk);
+    for (int nb = 0; nb < n_batches; ++nb) {
+      const int32_t* id = ids + (size_t)nb * Tk;
+      int32_t* rp = ptr.data() + (size_t)nb * (V + 1);
+      std::fill(rp, rp + V + 1, 0);
+      for (size_t t = 0; t < Tk; ++t) {
+        if (id[t] < 0 || id[t] >= V) return c->fail(HYDRA_ERR_INVALID_ARG, "token id %d at batch %d is outside [0,%d)", id[t], nb, V);
+        ++rp[id[t] + 1];
+      }
+      for (int v = 0; v < V; ++v) rp[v + 1] += rp[v];
+      std::vector<int32_t> fill(rp, rp + V);
+      int32_t* ps = pos.data() + (size_t)nb * Tk;
+      for (size_t t = 0; t < Tk; ++t) ps[fill[id[t]]++] = (int32_t)t;   // ascending token index inside every id
+      for (int b = 0; b < B; ++b)
+        for (int p = 0; p < P; ++p) {
+          const size_t i = ((size_t)nb * B + b) * P + p;
+          if (tgt_pos[i] < 0 || tgt_pos[i] >= S || (p > 0 && tgt_pos[i] <= tgt_pos[i - 1]))
+            return c->fail(HYDRA_ERR_INVALID_ARG, "target positions of sequence %d in batch %d must be ascending and inside [0,%d)", b, nb, S);
+          if (targets[i] < 0 || targets[i] >= V) return c->fail(HYDRA_ERR_INVALID_ARG, "target %zu out of range", i);
+          rows[i] = b * S + tgt_pos[i];
+        }
+    }
+    c->S = S;
+    c->P = P;
+    c->ids_bytes = (size_t)n_batches * Tk * 4;
+    c->tp_bytes = c->tg_bytes = (size_t)n_batches * NT * 4;
+    c->csr_ptr_bytes = ptr.size() * 4;
+    c->csr_pos_bytes = pos.size() * 4;
+    c->ids = static_cast<int32_t*>(ctx_alloc(c, c->ids_bytes));
+    c->tgt_pos = static_cast<int32_t*>(ctx_alloc(c, c->tp_bytes));
+    c->targets = static_cast<int32_t*>(ctx_alloc(c, c->tg_bytes));
+    c->csr_ptr = static_cast<int32_t*>(ctx_alloc(c, c->csr_ptr_bytes));
+    c->csr_pos = static_cast<int32_t*>(ctx_alloc(c, c->csr_pos_bytes));
+    if (!c->dry) {
+      if (!c->ids || !c->tgt_pos || !c->targets || !c->csr_ptr || !c->csr_pos)
+        return c->fail(HYDRA_ERR_OOM_DEVICE, "device allocation for the data failed");
+      HYDRA_HIP(c, hipMemcpy(c->ids, ids, c->ids_bytes, hipMemcpyHostToDevice));
+      HYDRA_HIP(c, hipMemcpy(c->tgt_pos, rows.data(), c->tp_bytes, hipMemcpyHostToDevice));
+      HYDRA_HIP(c, hipMemcpy(c->targets, targets, c->tg_bytes, hipMemcpyHostToDevice));
+      HYDRA_HIP(c, hipMemcpy(c->csr_ptr, ptr.data(), c->csr_ptr_bytes, hipMemcpyHostToDevice));
+      HYDRA_HIP(c, hipMemcpy(c->csr_pos, pos.data(), c->csr_pos_bytes, hipMemcpyHostToDevice));
+    }
   }
   hydra_status st = alloc_activations(c);
   if (st != HYDRA_OK) return st;

@@ -46,6 +46,25 @@ struct MlpActs {                // per model, allocated by set_data
   float* rowloss = nullptr;     // [B]
 };
 
+// Transformer activations of one model (bf16), allocated by set_data.  Tk = B*S tokens, NT = B*P targets.
+struct TrBlockActs {
+  void *a = nullptr, *qkv = nullptr, *o = nullptr, *x1 = nullptr, *f = nullptr;  // [Tk,d], [Tk,3d], [Tk,d] x3
+  void *z1 = nullptr, *zg = nullptr, *hmid = nullptr;                            // [Tk,F]
+  float *mu1 = nullptr, *rs1 = nullptr, *mu2 = nullptr, *rs2 = nullptr;          // [Tk]
+  float* lse = nullptr;                                                          // [B*H*S]
+};
+struct TrActs {
+  std::vector<void*> x;    // [L+1]: x[l] = input of block l, x[L] = output of the last block; [Tk,d]
+  std::vector<void*> dx;   // [L+1]: gradient w.r.t. x[l]
+  std::vector<TrBlockActs> blk;
+  void *xf = nullptr, *xt = nullptr, *dlogits = nullptr, *dxt = nullptr, *dxf = nullptr;
+  float *logits = nullptr, *rowloss = nullptr, *muf = nullptr, *rsf = nullptr;
+  // backward scratch shared by the blocks of the model
+  void *dhm = nullptr, *dz1 = nullptr, *dzg = nullptr, *df = nullptr, *dx1 = nullptr, *dob = nullptr,
+       *dqkv = nullptr, *da = nullptr;
+  float *delta = nullptr, *lnpart = nullptr;
+};
+
 struct Model {
   hydra_arch arch{};
   hydra_hparams hp{};
@@ -57,6 +76,7 @@ struct Model {
   float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
   bf16_t* w16 = nullptr;
   MlpActs mlp;
+  TrActs tr;
   float* loss_dev = nullptr;    // one float per step of the current epoch
   int loss_cap = 0;
   std::vector<float> losses;    // all steps so far (host)
@@ -93,7 +113,10 @@ struct hydra_ctx {
   size_t x_bytes = 0, ids_bytes = 0, tp_bytes = 0, tg_bytes = 0;
   void* x_staged = nullptr;      // MLP: [n_batches, B, ld_in] operand dtype
   int32_t* ids = nullptr;        // Transformer: [n_batches, B, S]
-  int32_t* tgt_pos = nullptr;    // [n_batches, B, P]
+  int32_t* tgt_pos = nullptr;    // Transformer: [n_batches, B*P] row index (b*S + position) of every target
+  int32_t* csr_ptr = nullptr;    // Transformer: [n_batches, V+1] CSR over token ids of each batch
+  int32_t* csr_pos = nullptr;    // Transformer: [n_batches, B*S] token indices grouped by id
+  size_t csr_ptr_bytes = 0, csr_pos_bytes = 0;
   int32_t* targets = nullptr;    // [n_batches, B] or [n_batches, B, P]
   bool acts_ready = false;
   // streams / events
@@ -140,8 +163,13 @@ void ctx_free_all(hydra_ctx* c);
 hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan);
 hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoch_stats* stats);
 
-// exec_mlp.cpp
+// exec_mlp.cpp / exec_transformer.cpp: run one launch group (forward, backward or update of its shards)
 hydra_status mlp_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch, hipStream_t s);
+hydra_status tr_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch, hipStream_t s);
+hydra_status fill_optim(hydra_ctx* c, const Bucket& b, int step, OptimArgs& o);
+inline hydra_status run_bucket(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
+  return c->models[0].arch.kind == HYDRA_KIND_MLP ? mlp_run(c, b, batch, step, s) : tr_run(c, b, batch, step, s);
+}
 
 #define HYDRA_HIP(c, expr)                                                                              \
   do {                                                                                                  \

@@ -232,7 +232,53 @@ hydra_status alloc_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, t.dlogits, void*, (size_t)c->B * ldv * es);
       ALLOC_OR_FAIL(c, t.rowloss, float*, (size_t)c->B * 4);
     } else {
-      return c->fail(HYDRA_ERR_UNSUPPORTED, "Transformer models are not implemented yet");
+      const size_t Tk = (size_t)c->B * c->S, NT = (size_t)c->B * c->P, d = a.d_model, F = a.d_ffn;
+      const size_t ldv = rup(a.n_out, 8), bhs = (size_t)c->B * a.n_heads * c->S;
+      TrActs& t = m.tr;
+      t.x.assign(a.n_layers + 1, nullptr);
+      t.dx.assign(a.n_layers + 1, nullptr);
+      t.blk.assign(a.n_layers, TrBlockActs());
+      for (int l = 0; l <= a.n_layers; ++l) {
+        ALLOC_OR_FAIL(c, t.x[l], void*, Tk * d * 2);
+        ALLOC_OR_FAIL(c, t.dx[l], void*, Tk * d * 2);
+      }
+      for (int l = 0; l < a.n_layers; ++l) {
+        TrBlockActs& b = t.blk[l];
+        ALLOC_OR_FAIL(c, b.a, void*, Tk * d * 2);
+        ALLOC_OR_FAIL(c, b.qkv, void*, Tk * 3 * d * 2);
+        ALLOC_OR_FAIL(c, b.o, void*, Tk * d * 2);
+        ALLOC_OR_FAIL(c, b.x1, void*, Tk * d * 2);
+        ALLOC_OR_FAIL(c, b.f, void*, Tk * d * 2);
+        ALLOC_OR_FAIL(c, b.z1, void*, Tk * F * 2);
+        if (a.ffn_gated) ALLOC_OR_FAIL(c, b.zg, void*, Tk * F * 2);
+        ALLOC_OR_FAIL(c, b.hmid, void*, Tk * F * 2);
+        ALLOC_OR_FAIL(c, b.mu1, float*, Tk * 4);
+        ALLOC_OR_FAIL(c, b.rs1, float*, Tk * 4);
+        ALLOC_OR_FAIL(c, b.mu2, float*, Tk * 4);
+        ALLOC_OR_FAIL(c, b.rs2, float*, Tk * 4);
+        ALLOC_OR_FAIL(c, b.lse, float*, bhs * 4);
+      }
+      ALLOC_OR_FAIL(c, t.xf, void*, Tk * d * 2);
+      ALLOC_OR_FAIL(c, t.dxf, void*, Tk * d * 2);
+      ALLOC_OR_FAIL(c, t.xt, void*, NT * d * 2);
+      ALLOC_OR_FAIL(c, t.dxt, void*, NT * d * 2);
+      ALLOC_OR_FAIL(c, t.logits, float*, NT * ldv * 4);
+      ALLOC_OR_FAIL(c, t.dlogits, void*, NT * ldv * 2);
+      ALLOC_OR_FAIL(c, t.rowloss, float*, NT * 4);
+      ALLOC_OR_FAIL(c, t.muf, float*, Tk * 4);
+      ALLOC_OR_FAIL(c, t.rsf, float*, Tk * 4);
+      if (a.ffn_gated) {
+        ALLOC_OR_FAIL(c, t.dhm, void*, Tk * F * 2);
+        ALLOC_OR_FAIL(c, t.dzg, void*, Tk * F * 2);
+      }
+      ALLOC_OR_FAIL(c, t.dz1, void*, Tk * F * 2);
+      ALLOC_OR_FAIL(c, t.df, void*, Tk * d * 2);
+      ALLOC_OR_FAIL(c, t.dx1, void*, Tk * d * 2);
+      ALLOC_OR_FAIL(c, t.dob, void*, Tk * d * 2);
+      ALLOC_OR_FAIL(c, t.dqkv, void*, Tk * 3 * d * 2);
+      ALLOC_OR_FAIL(c, t.da, void*, Tk * d * 2);
+      ALLOC_OR_FAIL(c, t.delta, float*, bhs * 4);
+      ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)Tk) * 2 * d * 4);
     }
   }
   c->acts_ready = true;

@@ -148,7 +148,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
       const Bucket& b = plan[i];
       if (b.members.size() > 1) c->grouped_tasks += b.members.size();
       if (c->dry) {
-        hydra_status st = mlp_run(c, b, step, step, nullptr);
+        hydra_status st = run_bucket(c, b, step, step, nullptr);
         if (st != HYDRA_OK) return st;
         continue;
       }
@@ -166,7 +166,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
           waited.push_back(it->second.ev);
         }
       }
-      hydra_status st = mlp_run(c, b, step, step, s);
+      hydra_status st = run_bucket(c, b, step, step, s);
       if (st != HYDRA_OK) return st;
       hipEvent_t ev = c->events[(step & 1) * nb + i];
       HYDRA_HIP(c, hipEventRecord(ev, s));

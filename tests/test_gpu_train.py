@@ -47,10 +47,13 @@ def _assert_fp32_parity(got, ref, names, rel=1e-5, outlier_frac=0.0, outlier_cap
     for nm, a, b in zip(names, gp, rp):
         b = b.astype(np.float64)
         scale = max(float(np.abs(b).max()), 1e-2)
-        r2 = _rel_l2(a, b) if np.linalg.norm(b) > 1e-2 else float(np.linalg.norm(a - b)) / 1e-2
+        small = np.linalg.norm(b) <= 1e-2   # tensors that start at zero and have barely moved: absolute floor
+        r2 = float(np.linalg.norm(a - b)) / 1e-2 if small else _rel_l2(a, b)
         d = np.abs(a - b) / scale
         n_out = int((d > rel).sum())
-        if r2 > rel or n_out > outlier_frac * d.size or float(d.max()) > max(rel, outlier_cap):
+        # a permitted outlier element in such a small tensor dominates its norm: bound it by the cap instead
+        r2_max = max(rel, outlier_cap) if (small and outlier_frac > 0) else rel
+        if r2 > r2_max or n_out > max(outlier_frac * d.size, 1 if outlier_frac > 0 else 0) or float(d.max()) > max(rel, outlier_cap):
             bad.append(f"{nm}: rel-L2 {r2:.2e} max-abs/scale {float(d.max()):.2e} outliers {n_out}/{d.size}")
     assert not bad, "; ".join(bad)
 

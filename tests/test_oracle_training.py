@@ -84,6 +84,19 @@ def test_unused_embedding_rows_get_zero_gradient():
         assert (np.abs(grads[0][v]).max() > 0) == (v in used)
 
 
+@pytest.mark.parametrize("kind", [C.KIND_ENCODER, C.KIND_DECODER])
+def test_key_bias_gradient_is_zero(kind):
+    # adding a constant to every key shifts all scores of a query equally: softmax, hence the loss, cannot see it
+    arch = _tiny_tr(kind, 0)
+    r = np.random.default_rng(3)
+    params = [r.normal(size=s) * 0.5 for _, s, _ in M.tensor_specs(arch)]
+    _, grads = M.loss_and_grads(arch, params, _tiny_batch(arch))
+    d = arch["d_model"]
+    for l in range(arch["n_layers"]):
+        g = grads[2 + 12 * l + 3]
+        assert np.abs(g[d:2 * d]).max() < 1e-15 and np.abs(g[:d]).max() > 1e-4 and np.abs(g[2 * d:]).max() > 1e-4
+
+
 def test_tiny_encoder_forward_matches_scalar_loops():
     """Brute-force scalar forward of one pre-LN block + head (index-by-index, Python floats)."""
     arch = C.transformer_arch(C.KIND_ENCODER, 1, 4, 2, 6, 5, 3, 0, C.DTYPE_F32)
