@@ -50,8 +50,11 @@ typedef struct {
 } hydra_gemm_desc;
 int hydra_op_gemm(const hydra_gemm_desc* d, void* stream);
 
-/* out_g[n] = sum_{m<M} src_g[m,n]; src has the operand dtype and leading dimension ld, out is fp32. */
-int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out, void* stream);
+/* out_g[n] = sum_{m<M} src_g[m,n]; src has the operand dtype and leading dimension ld, out is fp32.
+ * part_g: scratch of hydra_op_colsum_part_floats(M, N) floats (0 for M <= 256: the table may then be NULL). */
+int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out,
+                    float* const* part, void* stream);
+size_t hydra_op_colsum_part_floats(int M, int N);
 
 /* Softmax cross-entropy over fp32 logits [M, ldz] with C classes and int32 labels [M] (shared by the
  * group): rowloss_g[m] = logsumexp(z_m) - z_m[y_m]; dz_g[m,c] = (softmax(z_m)[c] - [c==y_m]) * inv_n

@@ -49,16 +49,21 @@ __global__ void stage_rows_kernel(const float* __restrict__ src, void* __restric
   }
 }
 
-// Column sums.  A block owns 64 columns; its 16 row lanes each add every 16th row in ascending
-// order, then the 16 partial sums are added in lane order.  The order is fixed by (M, column) only.
+// Column sums in two fixed-order stages.  Stage 1: a block owns 64 columns and a chunk of 256 rows;
+// its 16 row lanes each add every 16th row of the chunk in ascending order, then the 16 partial sums
+// are added in lane order.  Stage 2 (only when there is more than one chunk) adds the chunk sums in
+// chunk order.  The order depends on (M, column) only, never on timing or on the group.
+constexpr int COLSUM_CHUNK = 256;
+
 template <typename T>
-__global__ __launch_bounds__(1024) void colsum_kernel(const ColsumArgs a) {
+__global__ __launch_bounds__(1024) void colsum_kernel(const ColsumArgs a, int nch) {
   __shared__ float part[16][64];
-  const int g = blockIdx.y, col = blockIdx.x * 64 + (threadIdx.x & 63), rl = threadIdx.x >> 6;
+  const int g = blockIdx.z, ch = blockIdx.y, col = blockIdx.x * 64 + (threadIdx.x & 63), rl = threadIdx.x >> 6;
   const T* src = static_cast<const T*>(a.src[g]);
+  const int m_end = min(a.M, (ch + 1) * COLSUM_CHUNK);
   float s = 0.f;
   if (col < a.N) {
-    for (int m = rl; m < a.M; m += 16) {
+    for (int m = ch * COLSUM_CHUNK + rl; m < m_end; m += 16) {
       T v = src[(size_t)m * a.ld + col];
       s += sizeof(T) == 4 ? *reinterpret_cast<const float*>(&v) : bf2f(*reinterpret_cast<const bf16_t*>(&v));
     }
@@ -69,8 +74,17 @@ __global__ __launch_bounds__(1024) void colsum_kernel(const ColsumArgs a) {
     float t = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) t += part[i][threadIdx.x];
-    a.out[g][col] = t;
+    if (nch == 1) a.out[g][col] = t;
+    else a.part[g][(size_t)ch * a.N + col] = t;
   }
+}
+
+__global__ __launch_bounds__(256) void colsum_reduce_kernel(const ColsumArgs a, int nch) {
+  const int g = blockIdx.y, col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= a.N) return;
+  float t = 0.f;
+  for (int ch = 0; ch < nch; ++ch) t += a.part[g][(size_t)ch * a.N + col];
+  a.out[g][col] = t;
 }
 
 inline int blocks_for(size_t n, int threads, int cap = 4096) {
@@ -106,11 +120,23 @@ hipError_t launch_stage_rows(const float* src, void* dst, int rows, int cols, in
                      cols, ld, to_bf16);
   return hipGetLastError();
 }
+size_t colsum_part_floats(int M, int N) {
+  const int nch = (M + COLSUM_CHUNK - 1) / COLSUM_CHUNK;
+  return nch > 1 ? (size_t)nch * N : 0;
+}
+
 hipError_t launch_colsum(const ColsumArgs& a, hipStream_t s) {
   if (a.G < 1 || a.G > MAXG || a.M < 1 || a.N < 1 || a.ld < a.N) return hipErrorInvalidValue;
-  dim3 grid((a.N + 63) / 64, a.G);
-  if (a.dtype == GEMM_F32) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(1024), 0, s, a);
-  else hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(1024), 0, s, a);
+  const int nch = (a.M + COLSUM_CHUNK - 1) / COLSUM_CHUNK;
+  if (nch > 1)
+    for (int g = 0; g < a.G; ++g)
+      if (!a.part[g]) return hipErrorInvalidValue;
+  dim3 grid((a.N + 63) / 64, nch, a.G);
+  if (a.dtype == GEMM_F32) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(1024), 0, s, a, nch);
+  else hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(1024), 0, s, a, nch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || nch == 1) return e;
+  hipLaunchKernelGGL(colsum_reduce_kernel, dim3((a.N + 255) / 256, a.G), dim3(256), 0, s, a, nch);
   return hipGetLastError();
 }
 

@@ -90,8 +90,11 @@ __global__ __launch_bounds__(256) void gated_bwd_kernel(const GatedBwdArgs a) {
   const size_t n = (size_t)a.rows * a.ld, stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
     const float d = to_f<T>(dh[i]), u = to_f<T>(z1[i]), z = to_f<T>(zg[i]);
-    const float cdf = 0.5f * (1.f + erff(z * 0.70710678118654752f));
-    const float pdf = expf(-0.5f * z * z) * 0.39894228040143268f;
+    // normal CDF/density as in the GEMM epilogue (Abramowitz & Stegun 7.1.26 for erf)
+    const float xa = fabsf(z) * 0.70710678118654752f, tt = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * xa), ee = __expf(-xa * xa);
+    const float er = 1.0f - tt * (0.254829592f + tt * (-0.284496736f + tt * (1.421413741f + tt * (-1.453152027f + tt * 1.061405429f)))) * ee;
+    const float cdf = 0.5f * (1.0f + (z < 0.f ? -er : er));
+    const float pdf = ee * 0.39894228040143268f;
     dz1[i] = from_f<T>(d * z * cdf);
     dzg[i] = from_f<T>(d * u * (cdf + z * pdf));
   }

@@ -120,6 +120,7 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, hipSt
       w.out[i] = at(sh.g, sh, W_of(m, u));
       cs.src[i] = dz;
       cs.out[i] = at(sh.g, sh, b_of(m, u));
+      cs.part[i] = m.colpart;
     }
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, s, 2.0 * w.M * w.N * w.K * G, 0.0, launch_gemm(w, s));
     HYDRA_LAUNCH(c, HYDRA_K_COLSUM, s, 0.0, (double)G * cs.M * cs.N * es, launch_colsum(cs, s));

@@ -206,7 +206,7 @@ static hydra_status wgrad(Ctx& x, int rows, int n_out, int k_in, int ld_dy, int 
   w.ldo = k_in; w.out_f32 = 1; w.G = x.G;
   ColsumArgs cs{};
   cs.dtype = GEMM_BF16; cs.M = rows; cs.N = n_out; cs.ld = ld_dy; cs.G = x.G;
-  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = dW[i]; cs.src[i] = dy[i]; cs.out[i] = db[i]; }
+  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = dW[i]; cs.src[i] = dy[i]; cs.out[i] = db[i]; cs.part[i] = x.model(i).colpart; }
   HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, x.s, 2.0 * w.M * w.N * w.K * x.G, 0.0, launch_gemm(w, x.s));
   HYDRA_LAUNCH(c, HYDRA_K_COLSUM, x.s, 0.0, (double)x.G * rows * n_out * 2, launch_colsum(cs, x.s));
   return HYDRA_OK;

@@ -70,16 +70,46 @@ __device__ __forceinline__ uint4 mask_tail(uint4 v, int valid) {
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Normal CDF and density for GeLU.  erf by the rational approximation of Abramowitz & Stegun 7.1.26
+// (|error| <= 1.5e-7, below fp32 rounding of the surrounding arithmetic): a dozen VALU operations per
+// element instead of a library erf, which matters because the epilogue applies it to every output.
+__device__ __forceinline__ void normal_cdf_pdf(float z, float& cdf, float& pdf) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
+  const float e = __expf(-x * x);  // = exp(-z^2/2)
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float erf_abs = 1.0f - poly * e;
+  cdf = 0.5f * (1.0f + (z < 0.f ? -erf_abs : erf_abs));
+  pdf = e * 0.39894228040143268f;
+}
 __device__ __forceinline__ float act_fwd(float v, int act) {
   if (act == EPI_ACT_RELU) return v > 0.f ? v : 0.f;
-  if (act == EPI_ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
+  if (act == EPI_ACT_GELU) {
+    float cdf, pdf;
+    normal_cdf_pdf(v, cdf, pdf);
+    return v * cdf;
+  }
   return v;
 }
 __device__ __forceinline__ float act_grad(float z, int act) {
   if (act == EPI_ACT_RELU) return z > 0.f ? 1.f : 0.f;
-  if (act == EPI_ACT_GELU)
-    return 0.5f * (1.f + erff(z * 0.70710678118654752f)) + z * expf(-0.5f * z * z) * 0.39894228040143268f;
+  if (act == EPI_ACT_GELU) {
+    float cdf, pdf;
+    normal_cdf_pdf(z, cdf, pdf);
+    return cdf + z * pdf;
+  }
   return 1.f;
+}
+
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
+// Buffer descriptor covering bytes [first, total) of a matrix (empty when first >= total).  Reads beyond
+// it return zero, which is what pads ragged tiles.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* base, long first, long total) {
+  long rem = total - first;
+  rem = rem < 0 ? 0 : (rem > 0x7fffffffL ? 0x7fffffffL : rem);
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(base)) + (rem > 0 ? first : 0), 0,
+                                           (int)rem, 0x00020000);
 }
 
 // ---- global -> register loaders ---------------------------------------------------------------------
@@ -91,18 +121,22 @@ struct LoaderK {
   static constexpr int E = Elem<T>::E;
   static constexpr int NCH = ROWS * 8 / NT;
   static_assert(ROWS * 8 % NT == 0 && NCH >= 1, "tile too small for the workgroup");
+  static constexpr int N_LOAD = NCH, N_STORE = NCH;  // global loads / LDS writes per thread and tile
   uint4 r[NCH];
+  // Buffer loads: the descriptor starts at the tile's first element and ends with the matrix, so rows
+  // past the matrix read as zero without a guard; a chunk past the end of k is sent out of range.
   __device__ __forceinline__ void load(const T* base, int ld, int row0, int nrows, int k0, int K, int tid) {
+    const long first = ((long)row0 * ld + k0) * (long)sizeof(T);
+    const __amdgpu_buffer_rsrc_t rs = tile_rsrc(base, first, (long)nrows * ld * (long)sizeof(T));
+    const int kc = tid & 7, gk = k0 + kc * E;
+    const unsigned voff = ((unsigned)(tid >> 3) * (unsigned)ld + (unsigned)(kc * E)) * (unsigned)sizeof(T);
+    const unsigned step = (unsigned)(NT / 8) * (unsigned)ld * (unsigned)sizeof(T);
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      int c = tid + NT * i, row = c >> 3, kc = c & 7;
-      int gr = row0 + row, gk = k0 + kc * E;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (gr < nrows && gk < K) {
-        v = *reinterpret_cast<const uint4*>(base + (size_t)gr * ld + gk);
-        if (gk + E > K) v = mask_tail<T>(v, K - gk);
-      }
-      r[i] = v;
+      const unsigned off = gk < K ? voff + step * i : 0xfffffff0u;
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+      r[i] = make_uint4(v.x, v.y, v.z, v.w);
+      if (gk < K && gk + E > K) r[i] = mask_tail<T>(r[i], K - gk);
     }
   }
   __device__ __forceinline__ void store(uint4* tile, int tid) const {
@@ -120,51 +154,64 @@ struct LoaderK {
 template <typename T, int ROWS, int NT>
 struct LoaderT {
   static constexpr int E = Elem<T>::E;
-  static constexpr int NB = (ROWS / E) * 8;
-  static constexpr int NBT = (NB + NT - 1) / NT;
-  uint4 r[NBT][E];
+  static constexpr int NB = (ROWS / E) * 8;                     // E x E blocks in the tile
+  static constexpr int SPLIT = (2 * NB <= NT) ? 2 : 1;          // threads sharing a block (halves of its k rows)
+  static constexpr int KR = E / SPLIT;                          // k rows per thread
+  static constexpr int NU = NB * SPLIT;                         // work units
+  static constexpr int NBT = (NU + NT - 1) / NT;
+  static constexpr int N_LOAD = NBT * KR, N_STORE = NBT * E;
+  static constexpr int OW = KR * (int)sizeof(T) / 4;            // dwords written per output row (4, 2 or 1)
+  uint4 r[NBT][KR];
+  // Buffer loads: the descriptor starts at element (k0, row0) and ends after k row K-1, so k rows past K
+  // read as zero without a guard.  Tile rows past the matrix read whatever follows (padding or the next
+  // k row); they only feed outputs that are never stored.
   __device__ __forceinline__ void load(const T* base, int ld, int row0, int nrows, int k0, int K, int tid) {
+    const long first = ((long)k0 * ld + row0) * (long)sizeof(T);
+    const __amdgpu_buffer_rsrc_t rs = tile_rsrc(base, first, (long)K * ld * (long)sizeof(T));
+    (void)nrows;
 #pragma unroll
     for (int i = 0; i < NBT; ++i) {
-      int b = tid + NT * i;
-      int mb = b % (ROWS / E), kb = b / (ROWS / E);
-      int gr = row0 + mb * E;
+      const int u = tid + NT * i, b = u % NB, half = u / NB;
+      const int mb = b % (ROWS / E), kb = b / (ROWS / E);
+      const unsigned voff = ((unsigned)(kb * E + half * KR) * (unsigned)ld + (unsigned)(mb * E)) * (unsigned)sizeof(T);
 #pragma unroll
-      for (int j = 0; j < E; ++j) {
-        int gk = k0 + kb * E + j;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (b < NB && gr < nrows && gk < K) v = *reinterpret_cast<const uint4*>(base + (size_t)gk * ld + gr);
-        r[i][j] = v;
+      for (int j = 0; j < KR; ++j) {
+        const unsigned off = u < NU ? voff + (unsigned)j * (unsigned)ld * (unsigned)sizeof(T) : 0xfffffff0u;
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+        r[i][j] = make_uint4(v.x, v.y, v.z, v.w);
       }
     }
   }
   __device__ __forceinline__ void store(uint4* tile, int tid) const {
 #pragma unroll
     for (int i = 0; i < NBT; ++i) {
-      int b = tid + NT * i;
-      if (b >= NB) continue;
-      int mb = b % (ROWS / E), kb = b / (ROWS / E);
-      uint32_t in[E][4];
+      const int u = tid + NT * i, b = u % NB, half = u / NB;
+      if (u >= NU) continue;
+      const int mb = b % (ROWS / E), kb = b / (ROWS / E);
+      uint32_t in[KR][4];
 #pragma unroll
-      for (int j = 0; j < E; ++j) {
+      for (int j = 0; j < KR; ++j) {
         in[j][0] = r[i][j].x; in[j][1] = r[i][j].y; in[j][2] = r[i][j].z; in[j][3] = r[i][j].w;
       }
 #pragma unroll
       for (int m = 0; m < E; ++m) {
-        uint32_t o[4];
+        uint32_t o[OW];
         if (sizeof(T) == 4) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) o[q] = in[q][m];
+          for (int q = 0; q < OW; ++q) o[q] = in[q][m];
         } else {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
+          for (int q = 0; q < OW; ++q) {
             uint32_t lo = (in[2 * q][m >> 1] >> (16 * (m & 1))) & 0xffffu;
             uint32_t hi = (in[2 * q + 1][m >> 1] >> (16 * (m & 1))) & 0xffffu;
             o[q] = lo | (hi << 16);
           }
         }
-        int row = mb * E + m;
-        tile[row * 8 + (kb ^ swz(row))] = make_uint4(o[0], o[1], o[2], o[3]);
+        const int row = mb * E + m;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(tile + row * 8 + (kb ^ swz(row))) + half * OW;
+        if (OW == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1 % OW], o[2 % OW], o[3 % OW]);
+        else if (OW == 2) *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1 % OW]);
+        else *dst = o[0];
       }
     }
   }
@@ -225,7 +272,29 @@ __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&v)[8]) {
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-template <typename T, int WM, int WN, int FM, int FN, bool X_KMAJ, bool W_KMAJ>
+// Scheduling hint for one MFMA step: spread NR LDS reads and NMEM memory operations (mask MEMMASK:
+// 0x200 = LDS write, 0x020 = global read) evenly between the step's NM MFMAs.
+template <int NM, int NR, int NMEM, int MEMMASK>
+__device__ __forceinline__ void sched_interleave() {
+  constexpr int want = NR > NMEM ? NR : NMEM;
+  constexpr int groups = want < NM ? want : NM;
+  if constexpr (groups > 0) {
+    constexpr int per = NM / groups;
+    constexpr int rd = (NR + groups - 1) / groups, mem = (NMEM + groups - 1) / groups;
+#pragma unroll
+    for (int i = 0; i < groups; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, per, 0);
+      if constexpr (rd > 0) __builtin_amdgcn_sched_group_barrier(0x100, rd, 0);
+      if constexpr (mem > 0) __builtin_amdgcn_sched_group_barrier(MEMMASK, mem, 0);
+    }
+    if constexpr (NM - per * groups > 0) __builtin_amdgcn_sched_group_barrier(0x008, NM - per * groups, 0);
+  }
+}
+
+// PF (W operand) and PFX <= PF (X operand) = k-tiles kept in flight in registers (1 or 2 register sets).  With one wave per SIMD
+// (4-wave workgroups) fragments are double buffered so LDS latency hides behind the previous step's MFMAs;
+// with two waves per SIMD the other wave's MFMAs hide it and the registers are saved.
+template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF, bool X_KMAJ, bool W_KMAJ>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
   constexpr int E = Elem<T>::E;
   constexpr int BK = 8 * E;
@@ -249,8 +318,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
   const T* X = static_cast<const T*>(a.X[g]);
   const T* W = static_cast<const T*>(a.W[g]);
 
-  typename LoaderSel<T, BM, NT, X_KMAJ>::type lx;
-  typename LoaderSel<T, BN, NT, W_KMAJ>::type lw;
+  typedef typename LoaderSel<T, BM, NT, X_KMAJ>::type LX;
+  typedef typename LoaderSel<T, BN, NT, W_KMAJ>::type LW;
+  LX lx[PFX];
+  LW lw[PF];
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -260,46 +331,72 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // ---- main loop ---------------------------------------------------------------------------------------
+  // Software pipeline over k-tiles.  While the MFMAs of k-tile t run out of LDS buffer t&1, the register
+  // set holding k-tile t+1 is written to the other buffer (first half of the tile's MFMAs) and the global
+  // loads of k-tile t+1+PF are issued into that set (second half): with PF = 2 a load has a whole k-tile
+  // of MFMAs to arrive.  Inside a k-tile the fragments of MFMA step s+1 are read from LDS while step s
+  // computes.  Loads past the end of K return zeros, so the pipeline needs no tail handling.
   const int nk = (a.K + BK - 1) / BK;
-  lx.load(X, a.ldx, m0, a.M, 0, a.K, tid);
-  lw.load(W, a.ldw, n0, a.N, 0, a.K, tid);
-  lx.store(lds, tid);
-  lw.store(lds + BM * 8, tid);
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  lx[0].load(X, a.ldx, m0, a.M, 0, a.K, tid);
+  lw[0].load(W, a.ldw, n0, a.N, 0, a.K, tid);
+  lx[0].store(lds, tid);
+  lw[0].store(lds + BM * 8, tid);
+#pragma unroll
+  for (int p = 0; p < PFX; ++p) lx[p].load(X, a.ldx, m0, a.M, (1 + p) * BK, a.K, tid);
+#pragma unroll
+  for (int p = 0; p < PF; ++p) lw[p].load(W, a.ldw, n0, a.N, (1 + p) * BK, a.K, tid);
   __syncthreads();
 
-  const int lrow = lane & 31, lgrp = lane >> 5;
-  for (int kt = 0; kt < nk; ++kt) {
-    const uint4* tx = lds + (kt & 1) * STAGE;
+  constexpr bool FDB = WM * WN <= 4;  // fragment double buffering
+  constexpr int NFB = FDB ? 2 : 1;
+  uint4 xf[NFB][FM], wf[NFB][FN];
+  auto read_frags = [&](const uint4* tx, int s, uint4(&xo)[FM], uint4(&wo)[FN]) {
     const uint4* tw = tx + BM * 8;
-    if (kt + 1 < nk) {
-      lx.load(X, a.ldx, m0, a.M, (kt + 1) * BK, a.K, tid);
-      lw.load(W, a.ldw, n0, a.N, (kt + 1) * BK, a.K, tid);
+    const int kc = 2 * s + lgrp;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const int row = (wm * FM + i) * 32 + lrow;
+      xo[i] = tx[row * 8 + (kc ^ swz(row))];
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int kc = 2 * s + lgrp;
-      uint4 xf[FM], wf[FN];
+    for (int j = 0; j < FN; ++j) {
+      const int row = (wn * FN + j) * 32 + lrow;
+      wo[j] = tw[row * 8 + (kc ^ swz(row))];
+    }
+  };
+  constexpr int NM = FM * FN * (sizeof(T) == 4 ? 4 : 1);  // MFMA instructions per step
+  if (FDB) read_frags(lds, 0, xf[0], wf[0]);
+  for (int kt = 0; kt < nk; kt += PF) {
 #pragma unroll
-      for (int i = 0; i < FM; ++i) {
-        int row = (wm * FM + i) * 32 + lrow;
-        xf[i] = tx[row * 8 + (kc ^ swz(row))];
+    for (int u = 0; u < PF; ++u) {
+      const int t = kt + u;
+      if (t < nk) {  // uniform over the workgroup
+        const uint4* tx = lds + (t & 1) * STAGE;
+        uint4* nx = lds + ((t + 1) & 1) * STAGE;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          if (FDB && s < 3) read_frags(tx, s + 1, xf[(s + 1) & 1], wf[(s + 1) & 1]);
+          if (!FDB) read_frags(tx, s, xf[0], wf[0]);
+          if (s == 0) lx[u % PFX].store(nx, tid);
+          if (s == 1) lw[u].store(nx + BM * 8, tid);
+          if (s == 2) lx[u % PFX].load(X, a.ldx, m0, a.M, (t + 1 + PFX) * BK, a.K, tid);
+          if (s == 3) lw[u].load(W, a.ldw, n0, a.N, (t + 1 + PF) * BK, a.K, tid);
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) mma<T>(acc[i][j], wf[FDB ? (s & 1) : 0][j], xf[FDB ? (s & 1) : 0][i]);
+          // interleave the step's LDS reads and memory operations between its MFMAs
+          if (s == 0) sched_interleave<NM, FM + FN, LX::N_STORE, 0x200>();
+          if (s == 1) sched_interleave<NM, FM + FN, LW::N_STORE, 0x200>();
+          if (s == 2) sched_interleave<NM, FM + FN, LX::N_LOAD, 0x020>();
+          if (s == 3) sched_interleave<NM, FDB ? 0 : FM + FN, LW::N_LOAD, 0x020>();
+        }
+        __syncthreads();
+        if (FDB && t + 1 < nk) read_frags(nx, 0, xf[0], wf[0]);
       }
-#pragma unroll
-      for (int j = 0; j < FN; ++j) {
-        int row = (wn * FN + j) * 32 + lrow;
-        wf[j] = tw[row * 8 + (kc ^ swz(row))];
-      }
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) mma<T>(acc[i][j], wf[j], xf[i]);
     }
-    if (kt + 1 < nk) {
-      uint4* nx = lds + ((kt + 1) & 1) * STAGE;
-      lx.store(nx, tid);
-      lw.store(nx + BM * 8, tid);
-    }
-    __syncthreads();
   }
 
   // ---- epilogue -----------------------------------------------------------------------------------
@@ -385,7 +482,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
   }
 }
 
-template <typename T, int WM, int WN, int FM, int FN>
+template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF>
 struct Cfg {
   static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NT = WM * WN * 64;
   static constexpr size_t LDS = 2 * (size_t)(BM + BN) * 8 * 16;
@@ -393,7 +490,7 @@ struct Cfg {
   static hipError_t run1(const GemmArgs& a, hipStream_t s) {
     int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
     int grid = ((tiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_kernel<T, WM, WN, FM, FN, XK, WK>), dim3(grid), dim3(NT), LDS, s, a);
+    hipLaunchKernelGGL((gemm_kernel<T, WM, WN, FM, FN, PFX, PF, XK, WK>), dim3(grid), dim3(NT), LDS, s, a);
     return hipGetLastError();
   }
   static hipError_t run(const GemmArgs& a, hipStream_t s) {
@@ -402,7 +499,7 @@ struct Cfg {
   }
   template <bool XK, bool WK>
   static hipError_t attr1() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, FM, FN, XK, WK>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, FM, FN, PFX, PF, XK, WK>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   }
   static hipError_t attr() {
@@ -414,11 +511,14 @@ struct Cfg {
   }
 };
 
+template <typename T> struct Tiles {
+  typedef Cfg<T, 2, 2, 4, 4, 1, 1> Big;    // 256 x 256, one k-tile in flight in registers (register-bound)
+  typedef Cfg<T, 2, 2, 2, 2, 2, 2> Mid;    // 128 x 128, two k-tiles in flight, two workgroups per CU
+  typedef Cfg<T, 1, 4, 1, 1, 1, 1> Small;  // 32 x 128
+};
+
 template <typename T>
 hipError_t dispatch(const GemmArgs& a, hipStream_t s) {
-  typedef Cfg<T, 2, 2, 4, 4> Big;   // 256 x 256
-  typedef Cfg<T, 2, 2, 2, 2> Mid;   // 128 x 128
-  typedef Cfg<T, 1, 4, 1, 1> Small; // 32 x 128
   int tile = a.tile;
   if (tile == 0) {
     auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * a.G; };
@@ -426,21 +526,27 @@ hipError_t dispatch(const GemmArgs& a, hipStream_t s) {
     else if (a.M >= 96 && tiles(128, 128) >= 64) tile = 2;
     else tile = 3;
   }
-  if (tile == 1) return Big::run(a, s);
-  if (tile == 2) return Mid::run(a, s);
-  return Small::run(a, s);
+  switch (tile) {
+    case 1: return Tiles<T>::Big::run(a, s);
+    case 2: return Tiles<T>::Mid::run(a, s);
+    case 3: return Tiles<T>::Small::run(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <typename T>
+hipError_t init_tiles() {
+  hipError_t e;
+  if ((e = Tiles<T>::Big::attr()) != hipSuccess) return e;
+  if ((e = Tiles<T>::Mid::attr()) != hipSuccess) return e;
+  return Tiles<T>::Small::attr();
 }
 
 }  // namespace
 
 hipError_t gemm_init() {
-  hipError_t e;
-  if ((e = Cfg<bf16_t, 2, 2, 4, 4>::attr()) != hipSuccess) return e;
-  if ((e = Cfg<bf16_t, 2, 2, 2, 2>::attr()) != hipSuccess) return e;
-  if ((e = Cfg<bf16_t, 1, 4, 1, 1>::attr()) != hipSuccess) return e;
-  if ((e = Cfg<float, 2, 2, 4, 4>::attr()) != hipSuccess) return e;
-  if ((e = Cfg<float, 2, 2, 2, 2>::attr()) != hipSuccess) return e;
-  return Cfg<float, 1, 4, 1, 1>::attr();
+  hipError_t e = init_tiles<bf16_t>();
+  return e != hipSuccess ? e : init_tiles<float>();
 }
 
 hipError_t kernels_init() {

@@ -77,6 +77,7 @@ struct Model {
   bf16_t* w16 = nullptr;
   MlpActs mlp;
   TrActs tr;
+  float* colpart = nullptr;     // scratch of the column-sum kernel
   float* loss_dev = nullptr;    // one float per step of the current epoch
   int loss_cap = 0;
   std::vector<float> losses;    // all steps so far (host)

@@ -67,11 +67,14 @@ hipError_t launch_cast_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t
 hipError_t launch_stage_rows(const float* src, void* dst, int rows, int cols, int ld, int to_bf16, hipStream_t s);
 
 // Column sums: out_g[n] = sum_m src_g[m,n] for m < M (fp32 accumulation in a fixed order).
+// part: scratch of colsum_part_floats(M, N) floats per problem (none needed for M <= 256).
 struct ColsumArgs {
   int dtype, M, N, ld, G;
   const void* src[MAXG];
   float* out[MAXG];
+  float* part[MAXG];
 };
+size_t colsum_part_floats(int M, int N);
 hipError_t launch_colsum(const ColsumArgs& a, hipStream_t s);
 
 // Softmax cross-entropy over rows of fp32 logits [M, ldz] with C classes:

@@ -61,7 +61,10 @@ int hydra_op_gemm(const hydra_gemm_desc* d, void* stream) {
   return done(launch_gemm(a, static_cast<hipStream_t>(stream)), "hydra_op_gemm");
 }
 
-int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out, void* stream) {
+size_t hydra_op_colsum_part_floats(int M, int N) { return colsum_part_floats(M, N); }
+
+int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out,
+                    float* const* part, void* stream) {
   if (!src || !out || G < 1 || G > MAXG) return bad("hydra_op_colsum: NULL table or G out of range");
   ColsumArgs a{};
   a.dtype = dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
@@ -70,6 +73,7 @@ int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* s
     if (!src[g] || !out[g]) return bad("hydra_op_colsum: NULL entry");
     a.src[g] = src[g];
     a.out[g] = out[g];
+    a.part[g] = part ? part[g] : nullptr;
   }
   return done(launch_colsum(a, static_cast<hipStream_t>(stream)), "hydra_op_colsum");
 }

@@ -29,7 +29,9 @@ def _L():
     if not _ready:
         vp, pp = C.c_void_p, C.POINTER(C.c_void_p)
         L.hydra_op_gemm.argtypes = [C.POINTER(hydra_gemm_desc), vp]
-        L.hydra_op_colsum.argtypes = [C.c_int] * 5 + [pp, pp, vp]
+        L.hydra_op_colsum.argtypes = [C.c_int] * 5 + [pp, pp, pp, vp]
+        L.hydra_op_colsum_part_floats.argtypes = [C.c_int, C.c_int]
+        L.hydra_op_colsum_part_floats.restype = C.c_size_t
         L.hydra_op_softmax_ce.argtypes = [C.c_int] * 5 + [C.c_float, C.c_int, pp, vp, pp, pp, pp, vp]
         L.hydra_op_optim.argtypes = [C.c_int, C.c_size_t, C.c_int, pp, pp, pp, pp, pp, C.POINTER(C.c_double), vp]
         L.hydra_op_init_uniform.argtypes = [vp, C.c_size_t, C.c_uint64, C.c_uint64, C.c_float, vp]
@@ -75,8 +77,12 @@ def hydra_op_gemm(dtype, M, N, K, X, W, out, *, x_kmajor, w_kmajor, ldx, ldw, ld
     _check(_L().hydra_op_gemm(C.byref(d), _stream()))
 
 
-def hydra_op_colsum(dtype, M, N, ld, src, out):
-    _check(_L().hydra_op_colsum(dtype, M, N, ld, len(src), _tab(src), _tab(out), _stream()))
+def hydra_op_colsum_part_floats(M, N) -> int:
+    return int(_L().hydra_op_colsum_part_floats(M, N))
+
+
+def hydra_op_colsum(dtype, M, N, ld, src, out, part=None):
+    _check(_L().hydra_op_colsum(dtype, M, N, ld, len(src), _tab(src), _tab(out), _tab(part), _stream()))
 
 
 def hydra_op_softmax_ce(dtype, M, Cn, ldz, lddz, inv_n, logits, labels, dz, rowloss, loss):

@@ -183,13 +183,14 @@ def test_gemm_rejects_bad_arguments(torch, ops):
 @pytest.mark.parametrize("dtype", [0, 1])
 def test_colsum(torch, ops, dtype):
     r = np.random.default_rng(3)
-    for (M, N) in [(32, 10), (512, 1000), (97, 130)]:
-        srcs, outs, wants = [], [], []
+    for (M, N) in [(32, 10), (512, 1000), (97, 130), (2000, 72)]:
+        srcs, outs, wants, parts = [], [], [], []
         for g in range(2):
             d, v = _dev(torch, r.normal(size=(M, N)), dtype)
             srcs.append(d), wants.append(v.sum(axis=0))
             outs.append(torch.zeros(N, dtype=torch.float32, device="cuda"))
-        ops.hydra_op_colsum(dtype, M, N, srcs[0].shape[1], srcs, outs)
+            parts.append(torch.zeros(max(1, ops.hydra_op_colsum_part_floats(M, N)), dtype=torch.float32, device="cuda"))
+        ops.hydra_op_colsum(dtype, M, N, srcs[0].shape[1], srcs, outs, parts)
         torch.cuda.synchronize()
         for g in range(2):
             assert np.allclose(outs[g].cpu().numpy(), wants[g], rtol=0, atol=2 * M * EPS32 * 4)
