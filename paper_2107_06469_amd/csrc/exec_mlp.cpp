@@ -47,7 +47,7 @@ static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int st
       const Shard& sh = m.shards[b.members[i].second];
       g.X[i] = u == 0 ? static_cast<const char*>(c->x_staged) + (size_t)batch * c->B * c->ld_in * es : m.mlp.h[u - 1];
       g.W[i] = bf ? (const void*)at(sh.w16, sh, W_of(m, u)) : (const void*)at(sh.p, sh, W_of(m, u));
-      g.bias[i] = at(sh.p, sh, b_of(m, u));
+      g.bias[i] = c->spill ? m.pv + m.voff[2 * u + 1] : at(sh.p, sh, b_of(m, u));
       if (u < L) {
         g.out[i] = m.mlp.h[u];
         g.pre[i] = m.mlp.z[u];

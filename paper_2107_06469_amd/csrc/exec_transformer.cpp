@@ -66,16 +66,12 @@ struct Ctx {
   const Shard& shard(int i) const { return model(i).shards[b.members[i].second]; }
   // pointers into the shard's state blocks for tensor j of member i
   const bf16_t* w16(int i, int j) const { return shard(i).w16 + (model(i).tensors[j].off - shard(i).off); }
-  const float* p32(int i, int j) const { return shard(i).p + (model(i).tensors[j].off - shard(i).off); }
+  // fp32 vector tensors (biases, LayerNorm gains): the resident copy when the state is spilled
+  const float* p32(int i, int j) const {
+    if (c->spill) return model(i).pv + model(i).voff[j];
+    return shard(i).p + (model(i).tensors[j].off - shard(i).off);
+  }
   float* g32(int i, int j) const { return shard(i).g + (model(i).tensors[j].off - shard(i).off); }
-};
-
-typedef const void* (*PtrFn)(const Ctx&, int member, int l);
-
-// y[M,N] = x[M,K] W[N,K]^T + bias with optional epilogue pieces; W, bias are tensors (wj, bj evaluated per member)
-struct Lin {
-  int cls = HYDRA_K_GEMM_FWD;
-  int M = 0, N = 0, K = 0, ldx = 0, ldo = 0, ldr = 0, act = EPI_ACT_NONE, out_f32 = 0;
 };
 
 }  // namespace

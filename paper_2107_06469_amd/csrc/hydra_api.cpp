@@ -77,6 +77,7 @@ hydra_status hydra_destroy(hydra_ctx* c) {
     for (hipStream_t s : c->streams) (void)hipStreamSynchronize(s);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
+    spill_release_all(c);
     ctx_free_all(c);
     if (c->own_streams)
       for (hipStream_t s : c->streams) (void)hipStreamDestroy(s);
@@ -140,8 +141,10 @@ hydra_status hydra_define_models(hydra_ctx* c, int K, const hydra_arch* archs, i
       return st;
     }
   }
-  hydra_status st = alloc_models(c);
+  c->spill = c->opt.device_budget_bytes > 0 && resident_state_bytes(c) > c->opt.device_budget_bytes;
+  hydra_status st = c->spill ? spill_alloc_models(c) : alloc_models(c);
   if (st != HYDRA_OK) {
+    if (!c->dry) spill_release_all(c);
     ctx_free_all(c);
     c->models.clear();
     return st;
@@ -291,7 +294,12 @@ hydra_status hydra_train_epoch(hydra_ctx* c, const hydra_schedule* sch, hydra_ep
   if (c->state != ST_DATA) return c->fail(HYDRA_ERR_BAD_STATE, "set the data before training");
   if (!sch) return c->fail(HYDRA_ERR_INVALID_ARG, "schedule is NULL");
   std::vector<Bucket> plan;
-  hydra_status st = build_plan(c, sch, plan);
+  hydra_status st = HYDRA_OK;
+  if (c->spill) {
+    if ((st = spill_prepare(c)) != HYDRA_OK) return st;
+    c->sync_spill = sch->policy == HYDRA_SCHED_SEQUENTIAL;
+  }
+  st = build_plan(c, sch, plan);
   if (st != HYDRA_OK) return st;
   hydra_epoch_stats local{};
   st = run_epoch(c, plan, &local);
@@ -318,6 +326,18 @@ static hydra_status copy_out(hydra_ctx* c, int model, int tensor, float* dst, si
   }
   if (c->dry) return c->fail(HYDRA_ERR_BAD_STATE, "a dry-run context holds no values");
   for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  if (c->spill && grads) return c->fail(HYDRA_ERR_UNSUPPORTED, "gradients are transient while state is spilled to host memory");
+  if (c->spill) {
+    if (c->copy_out) HYDRA_HIP(c, hipStreamSynchronize(c->copy_out));
+    size_t o2 = 0;
+    for (int j = 0; j < nt; ++j) {
+      if (tensor != -1 && tensor != j) continue;
+      memcpy(dst + o2, m.host_p + m.tensors[j].off, m.tensors[j].n * 4);
+      o2 += m.tensors[j].n;
+    }
+    *n_written = need;
+    return HYDRA_OK;
+  }
   const float* src = grads ? m.g : m.p;
   size_t o = 0;
   for (int j = 0; j < nt; ++j) {
@@ -361,6 +381,18 @@ hydra_status hydra_write_params(hydra_ctx* c, int model, int tensor, const float
   for (int j = 0; j < nt; ++j) {
     if (tensor != -1 && tensor != j) continue;
     const Tensor& t = m.tensors[j];
+    if (c->spill) {
+      memcpy(m.host_p + t.off, src + o, t.n * 4);
+      float* tmp = static_cast<float*>(ctx_alloc(c, t.n * 4));
+      if (!tmp) return c->fail(HYDRA_ERR_OOM_DEVICE, "device allocation failed");
+      HYDRA_HIP(c, hipMemcpy(tmp, src + o, t.n * 4, hipMemcpyHostToDevice));
+      HYDRA_HIP(c, launch_cast_bf16(tmp, m.w16 + t.off, t.n, c->streams[0]));
+      if (m.voff[j] >= 0) HYDRA_HIP(c, hipMemcpyAsync(m.pv + m.voff[j], tmp, t.n * 4, hipMemcpyDeviceToDevice, c->streams[0]));
+      HYDRA_HIP(c, hipStreamSynchronize(c->streams[0]));
+      ctx_free(c, tmp, t.n * 4);
+      o += t.n;
+      continue;
+    }
     HYDRA_HIP(c, hipMemcpy(m.p + t.off, src + o, t.n * 4, hipMemcpyHostToDevice));
     if (m.w16) HYDRA_HIP(c, launch_cast_bf16(m.p + t.off, m.w16 + t.off, t.n, c->streams[0]));
     o += t.n;

@@ -37,6 +37,9 @@ struct Shard {
   // device pointers of the shard's state (null while spilled)
   float *p = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
   bf16_t* w16 = nullptr;
+  // spill mode: slot held between the shard's backward and the end of its update, and the events that order it
+  int slot = -1;
+  hipEvent_t loaded_ev = nullptr, updated_ev = nullptr;
 };
 
 struct MlpActs {                // per model, allocated by set_data
@@ -78,6 +81,12 @@ struct Model {
   MlpActs mlp;
   TrActs tr;
   float* colpart = nullptr;     // scratch of the column-sum kernel
+  // spill mode: resident fp32 copy of the vector tensors (offset per tensor, -1 for matrices) and the pinned
+  // host home of master weights and Adam moments
+  float* pv = nullptr;
+  std::vector<long> voff;
+  size_t n_vec = 0;
+  float *host_p = nullptr, *host_m = nullptr, *host_v = nullptr;
   float* loss_dev = nullptr;    // one float per step of the current epoch
   int loss_cap = 0;
   std::vector<float> losses;    // all steps so far (host)
@@ -127,8 +136,17 @@ struct hydra_ctx {
   // allocations
   std::vector<void*> dev_allocs;
   size_t dev_bytes = 0, peak_dev_bytes = 0;
+  // spill mode (state does not fit device_budget_bytes)
+  bool spill = false, sync_spill = false;
+  struct Slot { float* base = nullptr; hipEvent_t free_ev = nullptr; bool used = false, held = false; };
+  std::vector<Slot> slots;
+  size_t slot_elems = 0, next_slot = 0;
+  size_t state_bytes = 0;  // resident parameter bytes (working weights, vectors) counted against the budget
+  hipStream_t copy_in = nullptr, copy_out = nullptr;
+  std::vector<void*> host_allocs;
+  size_t host_bytes = 0, peak_host_bytes = 0;
   // accounting of the running epoch
-  uint64_t launches = 0, grouped_tasks = 0;
+  uint64_t launches = 0, grouped_tasks = 0, h2d_bytes = 0, d2h_bytes = 0;
   // optional per-launch timing (hydra_profile_enable): event pairs on the launching stream
   bool profiling = false;
   struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
@@ -159,6 +177,17 @@ hydra_status alloc_activations(hydra_ctx* c);
 void* ctx_alloc(hydra_ctx* c, size_t bytes);  // nullptr on failure (or in dry-run, where only bytes are counted)
 void ctx_free(hydra_ctx* c, void* p, size_t bytes);
 void ctx_free_all(hydra_ctx* c);
+
+// spill.cpp
+size_t resident_state_bytes(const hydra_ctx* c);
+hydra_status spill_alloc_models(hydra_ctx* c);
+hydra_status spill_prepare(hydra_ctx* c);
+int spill_max_group(const hydra_ctx* c);
+hydra_status spill_acquire(hydra_ctx* c, int k, int s, hipStream_t compute, bool synchronous);
+hydra_status spill_before_update(hydra_ctx* c, int k, int s, hipStream_t compute);
+hydra_status spill_after_update(hydra_ctx* c, int k, int s, hipStream_t compute, bool synchronous);
+void spill_release_all(hydra_ctx* c);
+uint64_t tensor_key(uint64_t seed, int model, int tensor);  // models.cpp: key of the init stream of a tensor
 
 // scheduler.cpp
 hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan);

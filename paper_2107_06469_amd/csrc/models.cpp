@@ -93,6 +93,10 @@ hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts) 
     b.push_back(cuts[i]);
   }
   b.push_back(U);
+  for (Shard& old : m.shards) {
+    if (old.loaded_ev) (void)hipEventDestroy(old.loaded_ev);
+    if (old.updated_ev) (void)hipEventDestroy(old.updated_ev);
+  }
   m.shards.clear();
   const int nt = (int)m.tensors.size();
   for (size_t s = 0; s + 1 < b.size(); ++s) {
@@ -167,6 +171,11 @@ static uint64_t splitmix_at(uint64_t s, uint64_t n) {
   return z ^ (z >> 31);
 }
 
+uint64_t tensor_key(uint64_t seed, int model, int tensor) {
+  const uint64_t stream_id = ((uint64_t)model << 20) | (uint64_t)tensor;
+  return splitmix_at(splitmix_at(seed, 0) ^ stream_id, 0);
+}
+
 #define ALLOC_OR_FAIL(c, ptr, type, bytes)                                                       \
   do {                                                                                           \
     ptr = static_cast<type>(ctx_alloc(c, bytes));                                                \
@@ -194,9 +203,7 @@ hydra_status alloc_models(hydra_ctx* c) {
       const Tensor& t = m.tensors[j];
       if (t.init == INIT_ONE) HYDRA_HIP(c, launch_fill_f32(m.p + t.off, t.n, 1.f, s));
       else if (t.init == INIT_UNIFORM) {
-        const uint64_t stream_id = ((uint64_t)k << 20) | (uint64_t)j;
-        const uint64_t key = splitmix_at(splitmix_at(c->seed, 0) ^ stream_id, 0);
-        HYDRA_HIP(c, launch_init_uniform(m.p + t.off, t.n, key, t.a, s));
+        HYDRA_HIP(c, launch_init_uniform(m.p + t.off, t.n, tensor_key(c->seed, k, (int)j), t.a, s));
       }
     }
     if (m.w16) HYDRA_HIP(c, launch_cast_bf16(m.p, m.w16, n, s));

@@ -34,6 +34,7 @@ static const char* ph_name(int ph) { return ph == 0 ? "F" : (ph == 1 ? "B" : "U"
 hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan) {
   plan.clear();
   const int K = c->K;
+  const int maxg = c->spill ? std::min(MAXG, spill_max_group(c)) : MAXG;  // a group holds one slot per member
   const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
   size_t total = 0;
   for (int k = 0; k < K; ++k) total += 3 * c->models[k].shards.size();
@@ -67,7 +68,7 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
       // neighbours in the list with the same phase and shape share a launch group
       const uint64_t sig = c->models[t.k].shards[t.s].sig;
       bool joined = false;
-      if (!plan.empty() && plan.back().ph == t.ph && (int)plan.back().members.size() < MAXG) {
+      if (!plan.empty() && plan.back().ph == t.ph && (int)plan.back().members.size() < maxg) {
         const auto& mb = plan.back().members;
         bool same = c->models[mb[0].first].shards[mb[0].second].sig == sig;
         for (const auto& q : mb) same = same && q.first != t.k;
@@ -91,7 +92,7 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
   int next_u = 0;
   std::set<Task> issued;
   while (issued.size() < total) {
-    std::vector<Task> ready;
+    std::vector<Task> ready, also_issued;
     for (int k = 0; k < K; ++k)
       for (int s = 0; s < (int)c->models[k].shards.size(); ++s)
         for (int ph = 0; ph < 3; ++ph) {
@@ -114,16 +115,25 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
     int next_c = 0;
     for (const auto& key : order) {
       const std::vector<Task>& ts = groups[key];
-      for (size_t i = 0; i < ts.size(); i += MAXG) {
+      for (size_t i = 0; i < ts.size(); i += maxg) {
         Bucket b;
         b.ph = ts[i].ph;
-        for (size_t j = i; j < std::min(ts.size(), i + (size_t)MAXG); ++j) b.members.push_back({ts[j].k, ts[j].s});
+        for (size_t j = i; j < std::min(ts.size(), i + (size_t)maxg); ++j) b.members.push_back({ts[j].k, ts[j].s});
         if (b.ph == HYDRA_PHASE_U && nu > 0) b.stream = nc + (next_u++ % nu);
         else b.stream = next_c++ % nc;
         plan.push_back(b);
+        if (c->spill && b.ph == HYDRA_PHASE_B) {
+          // a backward holds a state slot until its update has run: schedule the update right behind it
+          Bucket u = b;
+          u.ph = HYDRA_PHASE_U;
+          u.stream = nu > 0 ? nc + (next_u++ % nu) : b.stream;
+          plan.push_back(u);
+          for (const auto& mem : u.members) also_issued.push_back({mem.first, mem.second, HYDRA_PHASE_U});
+        }
       }
     }
     for (const Task& t : ready) issued.insert(t);
+    for (const Task& t : also_issued) issued.insert(t);
   }
   return HYDRA_OK;
 }
@@ -132,6 +142,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
   const size_t nb = plan.size();
   c->launches = 0;
   c->grouped_tasks = 0;
+  c->h2d_bytes = c->d2h_bytes = 0;
   if (!c->dry) {
     while (c->events.size() < 2 * nb) {
       hipEvent_t e;
@@ -148,8 +159,15 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
       const Bucket& b = plan[i];
       if (b.members.size() > 1) c->grouped_tasks += b.members.size();
       if (c->dry) {
-        hydra_status st = run_bucket(c, b, step, step, nullptr);
+        hydra_status st = HYDRA_OK;
+        if (c->spill && b.ph == HYDRA_PHASE_B)
+          for (const auto& mem : b.members)
+            if ((st = spill_acquire(c, mem.first, mem.second, nullptr, true)) != HYDRA_OK) return st;
+        st = run_bucket(c, b, step, step, nullptr);
         if (st != HYDRA_OK) return st;
+        if (c->spill && b.ph == HYDRA_PHASE_U)
+          for (const auto& mem : b.members)
+            if ((st = spill_after_update(c, mem.first, mem.second, nullptr, true)) != HYDRA_OK) return st;
         continue;
       }
       hipStream_t s = c->streams[b.stream];
@@ -166,15 +184,28 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
           waited.push_back(it->second.ev);
         }
       }
-      hydra_status st = run_bucket(c, b, step, step, s);
+      hydra_status st = HYDRA_OK;
+      if (c->spill && b.ph == HYDRA_PHASE_B)
+        for (const auto& mem : b.members)
+          if ((st = spill_acquire(c, mem.first, mem.second, s, c->sync_spill)) != HYDRA_OK) return st;
+      if (c->spill && b.ph == HYDRA_PHASE_U)
+        for (const auto& mem : b.members)
+          if ((st = spill_before_update(c, mem.first, mem.second, s)) != HYDRA_OK) return st;
+      st = run_bucket(c, b, step, step, s);
       if (st != HYDRA_OK) return st;
+      if (c->spill && b.ph == HYDRA_PHASE_U)
+        for (const auto& mem : b.members)
+          if ((st = spill_after_update(c, mem.first, mem.second, s, c->sync_spill)) != HYDRA_OK) return st;
       hipEvent_t ev = c->events[(step & 1) * nb + i];
       HYDRA_HIP(c, hipEventRecord(ev, s));
       for (const auto& mem : b.members) last[{mem.first, mem.second, b.ph}] = {ev, b.stream};
     }
   }
-  if (!c->dry)
+  if (!c->dry) {
     for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+    if (c->copy_in) HYDRA_HIP(c, hipStreamSynchronize(c->copy_in));
+    if (c->copy_out) HYDRA_HIP(c, hipStreamSynchronize(c->copy_out));
+  }
   const auto t1 = std::chrono::steady_clock::now();
   if (!c->dry && c->profiling) {
     hydra_status ps = prof_collect(c);
@@ -189,11 +220,12 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
   }
   if (stats) {
     stats->wall_ms = std::chrono::duration<double, std::milli>(t1 - t0).count();
-    stats->h2d_bytes = stats->d2h_bytes = 0;
+    stats->h2d_bytes = c->h2d_bytes;
+    stats->d2h_bytes = c->d2h_bytes;
     stats->launches = c->launches;
     stats->grouped_tasks = c->grouped_tasks;
     stats->peak_dev_bytes = c->peak_dev_bytes;
-    stats->peak_host_bytes = 0;
+    stats->peak_host_bytes = c->peak_host_bytes;
     stats->steps = c->n_batches;
   }
   return HYDRA_OK;

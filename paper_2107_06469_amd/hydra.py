@@ -287,10 +287,10 @@ def hydra_profile_read(ctx: Context, reset: bool = True) -> Dict[str, Dict]:
 
 
 def train_workload(w, data, policy: int = SCHED_SHARD_PARALLEL, n_streams: int = 4, epochs: int = 1, tasks=None,
-                   cuts=None):
+                   cuts=None, device_budget_bytes: int = 0):
     """Convenience used by tests and the benchmark: runs a hydra_workloads.Workload through the
     boundary and returns ({model: (losses, params)}, [stats per epoch])."""
-    ctx = hydra_create(n_streams=n_streams)
+    ctx = hydra_create(n_streams=n_streams, device_budget_bytes=device_budget_bytes)
     try:
         hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
         for k in range(w.K):
