@@ -82,6 +82,11 @@ typedef struct {
   size_t host_budget_bytes;    /* 0 = unlimited.  Upper bound on pinned host bytes used for spill    */
   int dry_run;                 /* 1: plan only.  No device is touched; define/shard/set_data record
                                   shapes, train_epoch validates the schedule and fills the stats     */
+  int keep_grads;              /* 0: the update of a weight matrix runs inside the kernel that produces
+                                  its gradient and that gradient is never stored (hydra_read_grads
+                                  is then refused); 1: every gradient is stored and the update task
+                                  applies all of them.  Both give the same parameters bit for bit.
+                                  Spilled state always keeps gradients                               */
 } hydra_options;
 
 typedef struct {
@@ -178,7 +183,9 @@ hydra_status hydra_shard_count(hydra_ctx* ctx, int model, int* n_shards);
  * reset = 1.  Disabled by default. */
 enum { HYDRA_K_GEMM_FWD = 0, HYDRA_K_GEMM_DGRAD = 1, HYDRA_K_GEMM_WGRAD = 2, HYDRA_K_OPTIM = 3,
        HYDRA_K_SOFTMAX_CE = 4, HYDRA_K_COLSUM = 5, HYDRA_K_LAYERNORM = 6, HYDRA_K_ATTENTION = 7,
-       HYDRA_K_EMBED = 8, HYDRA_K_ELEMENTWISE = 9, HYDRA_K_COUNT = 10 };
+       HYDRA_K_EMBED = 8, HYDRA_K_ELEMENTWISE = 9,
+       HYDRA_K_WGRAD_UPDATE = 10, /* weight-gradient GEMM with the parameter update in its epilogue */
+       HYDRA_K_COUNT = 11 };
 typedef struct {
   uint64_t launches;
   double total_ms;   /* sum of event-pair times                                                     */

@@ -70,6 +70,16 @@ int hydra_op_softmax_ce(int dtype, int M, int C, int ldz, int lddz, float inv_n,
 int hydra_op_optim(int opt, size_t n, int G, float* const* p, const float* const* g, float* const* m, float* const* v,
                    void* const* w16, const double* hp, void* stream);
 
+/* Weight gradient with the optimizer step in its epilogue (paper, Approach, "Desiderata": the update
+ * is the one a separate optimizer pass would apply, bit for bit).  d describes the gradient GEMM
+ * dW_g[M,N] = sum_k X_g(m,k) W_g(n,k) with x_kmajor = w_kmajor = 0, out_f32 = 1, no bias/pre/gate/resid
+ * and act = HYDRA_EPI_NONE; element [m,n] of the gradient updates p_g[m*ldo + n] (and m_g, v_g, w16_g
+ * at the same index) as hydra_op_optim would.  d->out may be NULL (the gradient is then never
+ * stored) or a table of fp32 [M, ldo] buffers that also receive it.  p, m, v 32-byte aligned, w16 16-byte;
+ * hp as for hydra_op_optim.  Errors: HYDRA_ERR_INVALID_ARG for shapes or tables the kernel cannot take. */
+int hydra_op_gemm_update(const hydra_gemm_desc* d, int opt, float* const* p, float* const* m, float* const* v,
+                         void* const* w16, const double* hp, void* stream);
+
 /* dst[i] = u_i * 2a - a with u_i the 24-bit uniform of the counter generator (SplitMix64 keyed by
  * (seed, stream_id)); the values a model's tensor `stream_id = (model << 20) | tensor` is initialised with. */
 int hydra_op_init_uniform(float* dst, size_t n, uint64_t seed, uint64_t stream_id, float a, void* stream);

@@ -79,7 +79,7 @@ static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int st
   return HYDRA_OK;
 }
 
-static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, hipStream_t s) {
+static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   const Model& m0 = c->models[b.members[0].first];
   const Shard& sh0 = m0.shards[b.members[0].second];
   const hydra_arch& a = m0.arch;
@@ -92,6 +92,31 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, hipSt
     const int N = u < L ? a.d_model : a.n_out;     // width of dz_u
     const int Kin = u == 0 ? a.d_in : a.d_model;   // width of x_u
     const int lddz = u < L ? ldd : ldv;
+    // input gradient through the previous activation, before the weights of this unit change:
+    // dz_{u-1}[B, Kin] = (dz_u W_u) * act'(z_{u-1})
+    if (u > 0) {
+      GemmArgs d{};
+      d.dtype = bf ? GEMM_BF16 : GEMM_F32;
+      d.M = c->B;
+      d.N = Kin;
+      d.K = N;
+      d.x_kmajor = 1;
+      d.w_kmajor = 0;
+      d.ldx = lddz;
+      d.ldw = W_of(m0, u).cols;
+      d.G = G;
+      d.ldo = d.ldg = ldd;
+      d.act = act;
+      for (int i = 0; i < G; ++i) {
+        const Model& m = c->models[b.members[i].first];
+        const Shard& sh = m.shards[b.members[i].second];
+        d.X[i] = u < L ? m.mlp.dz[u] : m.mlp.dlogits;
+        d.W[i] = bf ? (const void*)at(sh.w16, sh, W_of(m, u)) : (const void*)at(sh.p, sh, W_of(m, u));
+        d.out[i] = m.mlp.dz[u - 1];
+        d.gate[i] = m.mlp.z[u - 1];
+      }
+      HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, 2.0 * d.M * d.N * d.K * G, 0.0, launch_gemm(d, s));
+    }
     // weight gradient: dW[N, Kin] = sum_m dz[m, N] x[m, Kin]
     GemmArgs w{};
     w.dtype = bf ? GEMM_BF16 : GEMM_F32;
@@ -122,33 +147,43 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, hipSt
       cs.out[i] = at(sh.g, sh, b_of(m, u));
       cs.part[i] = m.colpart;
     }
-    HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, s, 2.0 * w.M * w.N * w.K * G, 0.0, launch_gemm(w, s));
-    HYDRA_LAUNCH(c, HYDRA_K_COLSUM, s, 0.0, (double)G * cs.M * cs.N * es, launch_colsum(cs, s));
-    if (u == 0) continue;
-    // input gradient through the previous activation: dz_{u-1}[B, Kin] = (dz_u W_u) * act'(z_{u-1})
-    GemmArgs d{};
-    d.dtype = w.dtype;
-    d.M = c->B;
-    d.N = Kin;
-    d.K = N;
-    d.x_kmajor = 1;
-    d.w_kmajor = 0;
-    d.ldx = lddz;
-    d.ldw = W_of(m0, u).cols;
-    d.G = G;
-    d.ldo = d.ldg = ldd;
-    d.act = act;
-    for (int i = 0; i < G; ++i) {
-      const Model& m = c->models[b.members[i].first];
-      const Shard& sh = m.shards[b.members[i].second];
-      d.X[i] = u < L ? m.mlp.dz[u] : m.mlp.dlogits;
-      d.W[i] = bf ? (const void*)at(sh.w16, sh, W_of(m, u)) : (const void*)at(sh.p, sh, W_of(m, u));
-      d.out[i] = m.mlp.dz[u - 1];
-      d.gate[i] = m.mlp.z[u - 1];
+    if (c->fuse) {
+      // the update of W_u runs in the epilogue of its gradient GEMM; the gradient is never stored
+      GemmUpdate up{};
+      up.opt = m0.hp.opt == HYDRA_OPT_ADAM ? 1 : 0;
+      for (int i = 0; i < G; ++i) {
+        const Model& m = c->models[b.members[i].first];
+        const Shard& sh = m.shards[b.members[i].second];
+        w.out[i] = nullptr;
+        up.p[i] = at(sh.p, sh, W_of(m, u));
+        up.m[i] = sh.m ? at(sh.m, sh, W_of(m, u)) : nullptr;
+        up.v[i] = sh.v ? at(sh.v, sh, W_of(m, u)) : nullptr;
+        up.w16[i] = sh.w16 ? at(sh.w16, sh, W_of(m, u)) : nullptr;
+        up.hp[i] = step_hparams(m, step);
+      }
+      HYDRA_LAUNCH(c, HYDRA_K_WGRAD_UPDATE, s, 2.0 * w.M * w.N * w.K * G,
+                   fused_update_bytes(up.opt, bf) * w.M * w.N * G, launch_gemm_update(w, up, s));
+    } else {
+      HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, s, 2.0 * w.M * w.N * w.K * G, 0.0, launch_gemm(w, s));
     }
-    HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, 2.0 * d.M * d.N * d.K * G, 0.0, launch_gemm(d, s));
+    HYDRA_LAUNCH(c, HYDRA_K_COLSUM, s, 0.0, (double)G * cs.M * cs.N * es, launch_colsum(cs, s));
   }
   return HYDRA_OK;
+}
+
+OptimHp step_hparams(const Model& m, int step) {
+  const long t = m.t + step + 1;
+  const double lr = m.hp.warmup_steps > 0 ? m.hp.lr * std::min(1.0, (double)t / m.hp.warmup_steps) : m.hp.lr;
+  OptimHp h;
+  h.lr = (float)lr;
+  h.b1 = (float)m.hp.beta1;
+  h.b2 = (float)m.hp.beta2;
+  h.c1 = (float)(1.0 - m.hp.beta1);
+  h.c2 = (float)(1.0 - m.hp.beta2);
+  h.eps = (float)m.hp.eps;
+  h.bc1 = (float)(1.0 / (1.0 - std::pow(m.hp.beta1, (double)t)));
+  h.bc2 = (float)(1.0 / (1.0 - std::pow(m.hp.beta2, (double)t)));
+  return h;
 }
 
 hydra_status fill_optim(hydra_ctx* c, const Bucket& b, int step, OptimArgs& o) {
@@ -162,36 +197,39 @@ hydra_status fill_optim(hydra_ctx* c, const Bucket& b, int step, OptimArgs& o) {
     const Shard& sh = m.shards[b.members[i].second];
     if ((m.hp.opt == HYDRA_OPT_ADAM) != (o.opt == 1) || sh.n != o.n)
       return c->fail(HYDRA_ERR_BAD_STATE, "launch group mixes optimizers or shard sizes");
-    const long t = m.t + step + 1;
-    const double lr = m.hp.warmup_steps > 0 ? m.hp.lr * std::min(1.0, (double)t / m.hp.warmup_steps) : m.hp.lr;
     o.p[i] = sh.p;
     o.g[i] = sh.g;
     o.m[i] = sh.m;
     o.v[i] = sh.v;
     o.w16[i] = sh.w16;
-    o.lr[i] = (float)lr;
-    o.b1[i] = (float)m.hp.beta1;
-    o.b2[i] = (float)m.hp.beta2;
-    o.c1[i] = (float)(1.0 - m.hp.beta1);
-    o.c2[i] = (float)(1.0 - m.hp.beta2);
-    o.eps[i] = (float)m.hp.eps;
-    o.bc1[i] = (float)(1.0 / (1.0 - std::pow(m.hp.beta1, (double)t)));
-    o.bc2[i] = (float)(1.0 / (1.0 - std::pow(m.hp.beta2, (double)t)));
+    o.hp[i] = step_hparams(m, step);
   }
+  return HYDRA_OK;
+}
+
+hydra_status run_update(hydra_ctx* c, const Bucket& b, int step, hipStream_t s) {
+  OptimArgs o;
+  hydra_status st = fill_optim(c, b, step, o);
+  if (st != HYDRA_OK) return st;
+  size_t n = o.n;
+  if (c->fuse) {
+    const Shard& sh0 = c->models[b.members[0].first].shards[b.members[0].second];
+    if (!sh0.n_tail_chunks) return HYDRA_OK;  // every tensor of the shard was updated by its gradient GEMM
+    o.chunks = sh0.tail_chunks;
+    o.n_chunks = sh0.n_tail_chunks;
+    n = sh0.n_tail;
+  }
+  // algorithmic traffic per parameter: SGD reads p,g and writes p (12 B); Adam reads p,g,m,v and writes
+  // p,m,v (28 B); the bf16 working copy adds 2 B
+  const double per = (o.opt == 1 ? 28.0 : 12.0) + (o.w16[0] ? 2.0 : 0.0);
+  HYDRA_LAUNCH(c, HYDRA_K_OPTIM, s, 0.0, per * (double)n * o.G, launch_optim(o, s));
   return HYDRA_OK;
 }
 
 hydra_status mlp_run(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   if (b.ph == HYDRA_PHASE_F) return mlp_forward(c, b, batch, step, s);
-  if (b.ph == HYDRA_PHASE_B) return mlp_backward(c, b, batch, s);
-  OptimArgs o;
-  hydra_status st = fill_optim(c, b, step, o);
-  if (st != HYDRA_OK) return st;
-  // algorithmic traffic per parameter: SGD reads p,g and writes p (12 B); Adam reads p,g,m,v and writes
-  // p,m,v (28 B); the bf16 working copy adds 2 B
-  const double per = (o.opt == 1 ? 28.0 : 12.0) + (o.w16[0] ? 2.0 : 0.0);
-  HYDRA_LAUNCH(c, HYDRA_K_OPTIM, s, 0.0, per * (double)o.n * o.G, launch_optim(o, s));
-  return HYDRA_OK;
+  if (b.ph == HYDRA_PHASE_B) return mlp_backward(c, b, batch, step, s);
+  return run_update(c, b, step, s);
 }
 
 }  // namespace hydra

@@ -193,17 +193,36 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
   return HYDRA_OK;
 }
 
-// weight gradient dW[N_out, K_in] = dy[rows, N_out]^T x_in[rows, K_in] plus bias gradient = column sums of dy
-static hydra_status wgrad(Ctx& x, int rows, int n_out, int k_in, int ld_dy, int ld_x, const void* const* dy,
-                          const void* const* xin, float* const* dW, float* const* db) {
+// weight gradient dW[N_out, K_in] = dy[rows, N_out]^T x_in[rows, K_in] of tensor jw[i] of member i, plus the
+// bias gradient = column sums of dy.  In fused-update mode the GEMM's epilogue applies the update of
+// the weight, so every reader of the old weight (the matching dgrad) must have been issued before.
+static hydra_status wgrad(Ctx& x, int step, int rows, int n_out, int k_in, int ld_dy, int ld_x, const void* const* dy,
+                          const void* const* xin, const int* jw, float* const* db) {
   hydra_ctx* c = x.c;
   GemmArgs w{};
   w.dtype = GEMM_BF16; w.M = n_out; w.N = k_in; w.K = rows; w.x_kmajor = w.w_kmajor = 0; w.ldx = ld_dy; w.ldw = ld_x;
   w.ldo = k_in; w.out_f32 = 1; w.G = x.G;
   ColsumArgs cs{};
   cs.dtype = GEMM_BF16; cs.M = rows; cs.N = n_out; cs.ld = ld_dy; cs.G = x.G;
-  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = dW[i]; cs.src[i] = dy[i]; cs.out[i] = db[i]; cs.part[i] = x.model(i).colpart; }
-  HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, x.s, 2.0 * w.M * w.N * w.K * x.G, 0.0, launch_gemm(w, x.s));
+  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = x.g32(i, jw[i]); cs.src[i] = dy[i]; cs.out[i] = db[i]; cs.part[i] = x.model(i).colpart; }
+  if (c->fuse) {
+    GemmUpdate up{};
+    up.opt = x.model(0).hp.opt == HYDRA_OPT_ADAM ? 1 : 0;
+    FOR_G {
+      const Shard& sh = x.shard(i);
+      const size_t o = x.model(i).tensors[jw[i]].off - sh.off;
+      w.out[i] = nullptr;
+      up.p[i] = sh.p + o;
+      up.m[i] = sh.m ? sh.m + o : nullptr;
+      up.v[i] = sh.v ? sh.v + o : nullptr;
+      up.w16[i] = sh.w16 + o;
+      up.hp[i] = step_hparams(x.model(i), step);
+    }
+    HYDRA_LAUNCH(c, HYDRA_K_WGRAD_UPDATE, x.s, 2.0 * w.M * w.N * w.K * x.G,
+                 fused_update_bytes(up.opt, true) * w.M * w.N * x.G, launch_gemm_update(w, up, x.s));
+  } else {
+    HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, x.s, 2.0 * w.M * w.N * w.K * x.G, 0.0, launch_gemm(w, x.s));
+  }
   HYDRA_LAUNCH(c, HYDRA_K_COLSUM, x.s, 0.0, (double)x.G * rows * n_out * 2, launch_colsum(cs, x.s));
   return HYDRA_OK;
 }
@@ -230,7 +249,7 @@ static hydra_status dgrad(Ctx& x, int rows, int n_out, int k_in, int ld_dy, cons
     if (st_ != HYDRA_OK) return st_;   \
   } while (0)
 
-static hydra_status tr_backward(Ctx& x, int batch) {
+static hydra_status tr_backward(Ctx& x, int batch, int step) {
   hydra_ctx* c = x.c;
   const int n_units = x.shard(0).u1 - x.shard(0).u0;
   const int Tk = x.Tk, d = x.d, F = x.F, G = x.G;
@@ -240,7 +259,7 @@ static hydra_status tr_backward(Ctx& x, int batch) {
   const void* pc[MAXG];
   const void* pd[MAXG];
   void* po[MAXG];
-  float* pw[MAXG];
+  int jw[MAXG];
   float* pbias[MAXG];
   if (last) {
     const int NT = x.NT, V = x.V;
@@ -248,11 +267,11 @@ static hydra_status tr_backward(Ctx& x, int batch) {
     FOR_G {
       const Model& m = x.model(i);
       Idx ix(m.arch);
-      pa[i] = m.tr.dlogits; pb[i] = m.tr.xt; pw[i] = x.g32(i, ix.whead()); pbias[i] = x.g32(i, ix.bhead());
+      pa[i] = m.tr.dlogits; pb[i] = m.tr.xt; jw[i] = ix.whead(); pbias[i] = x.g32(i, ix.bhead());
       pc[i] = x.w16(i, ix.whead()); po[i] = m.tr.dxt;
     }
-    TRY(wgrad(x, NT, V, d, x.ldv, d, pa, pb, pw, pbias));
     TRY(dgrad(x, NT, V, d, x.ldv, pa, pc, po, nullptr, nullptr));
+    TRY(wgrad(x, step, NT, V, d, x.ldv, d, pa, pb, jw, pbias));
     // scatter the target rows into a zero [Tk, d] gradient of the final LayerNorm's output
     FOR_G HYDRA_LAUNCH(c, HYDRA_K_ELEMENTWISE, x.s, 0.0, (double)Tk * d * 2,
                        launch_fill_u32(static_cast<uint32_t*>(x.model(i).tr.dxf), (size_t)Tk * d / 2, 0u, x.s));
@@ -279,12 +298,12 @@ static hydra_status tr_backward(Ctx& x, int batch) {
     auto T = [&](int i) -> const TrActs& { return x.model(i).tr; };
     // FFN2: dW2 = dx2^T hmid, db2; dh = dx2 W2 (gated by GeLU'(z1) when the block is not gated)
     FOR_G {
-      pa[i] = T(i).dx[L(i) + 1]; pb[i] = A(i).hmid; pw[i] = x.g32(i, x.ix.w2(L(i))); pbias[i] = x.g32(i, x.ix.b2(L(i)));
+      pa[i] = T(i).dx[L(i) + 1]; pb[i] = A(i).hmid; jw[i] = x.ix.w2(L(i)); pbias[i] = x.g32(i, x.ix.b2(L(i)));
       pc[i] = x.w16(i, x.ix.w2(L(i))); pd[i] = A(i).z1;
       po[i] = x.a.ffn_gated ? T(i).dhm : T(i).dz1;
     }
-    TRY(wgrad(x, Tk, d, F, d, F, pa, pb, pw, pbias));
     TRY(dgrad(x, Tk, d, F, d, pa, pc, po, x.a.ffn_gated ? nullptr : pd, nullptr));
+    TRY(wgrad(x, step, Tk, d, F, d, F, pa, pb, jw, pbias));
     if (x.a.ffn_gated) {
       GatedBwdArgs gb{};
       gb.dtype = GEMM_BF16; gb.rows = Tk; gb.ld = F; gb.G = G;
@@ -293,18 +312,18 @@ static hydra_status tr_backward(Ctx& x, int batch) {
     }
     // FFN1: dW1 = dz1^T f, db1; df = dz1 W1 (+ dzg Wg)
     FOR_G {
-      pa[i] = T(i).dz1; pb[i] = A(i).f; pw[i] = x.g32(i, x.ix.w1(L(i))); pbias[i] = x.g32(i, x.ix.b1(L(i)));
+      pa[i] = T(i).dz1; pb[i] = A(i).f; jw[i] = x.ix.w1(L(i)); pbias[i] = x.g32(i, x.ix.b1(L(i)));
       pc[i] = x.w16(i, x.ix.w1(L(i))); po[i] = T(i).df;
     }
-    TRY(wgrad(x, Tk, F, d, F, d, pa, pb, pw, pbias));
     TRY(dgrad(x, Tk, F, d, F, pa, pc, po, nullptr, nullptr));
+    TRY(wgrad(x, step, Tk, F, d, F, d, pa, pb, jw, pbias));
     if (x.a.ffn_gated) {
       FOR_G {
-        pa[i] = T(i).dzg; pw[i] = x.g32(i, x.ix.wg(L(i))); pbias[i] = x.g32(i, x.ix.bg(L(i)));
+        pa[i] = T(i).dzg; jw[i] = x.ix.wg(L(i)); pbias[i] = x.g32(i, x.ix.bg(L(i)));
         pc[i] = x.w16(i, x.ix.wg(L(i))); pd[i] = T(i).df;
       }
-      TRY(wgrad(x, Tk, F, d, F, d, pa, pb, pw, pbias));
       TRY(dgrad(x, Tk, F, d, F, pa, pc, po, nullptr, pd));  // df += dzg Wg (read and written by the same lane)
+      TRY(wgrad(x, step, Tk, F, d, F, d, pa, pb, jw, pbias));
     }
     // LN2: dx1 = LN2'(df) + dx2
     LnBwdArgs lb{};
@@ -318,11 +337,11 @@ static hydra_status tr_backward(Ctx& x, int batch) {
     HYDRA_LAUNCH(c, HYDRA_K_LAYERNORM, x.s, 0.0, (double)G * Tk * d * 8, launch_ln_bwd(lb, x.s));
     // Wo: dWo = dx1^T o, dbo; do = dx1 Wo
     FOR_G {
-      pa[i] = T(i).dx1; pb[i] = A(i).o; pw[i] = x.g32(i, x.ix.wo(L(i))); pbias[i] = x.g32(i, x.ix.bo(L(i)));
+      pa[i] = T(i).dx1; pb[i] = A(i).o; jw[i] = x.ix.wo(L(i)); pbias[i] = x.g32(i, x.ix.bo(L(i)));
       pc[i] = x.w16(i, x.ix.wo(L(i))); po[i] = T(i).dob;
     }
-    TRY(wgrad(x, Tk, d, d, d, d, pa, pb, pw, pbias));
     TRY(dgrad(x, Tk, d, d, d, pa, pc, po, nullptr, nullptr));
+    TRY(wgrad(x, step, Tk, d, d, d, d, pa, pb, jw, pbias));
     // attention backward
     AttnBwdArgs ab{};
     ab.B = c->B; ab.S = c->S; ab.H = x.H; ab.DH = x.DH; ab.ld_qkv = 3 * d; ab.ld_o = d; ab.causal = x.a.causal; ab.G = G;
@@ -337,11 +356,11 @@ static hydra_status tr_backward(Ctx& x, int batch) {
     HYDRA_LAUNCH(c, HYDRA_K_ATTENTION, x.s, att_fl, 0.0, launch_attn_bwd(ab, x.s));
     // Wqkv: dWqkv = dqkv^T a, dbqkv; da = dqkv Wqkv
     FOR_G {
-      pa[i] = T(i).dqkv; pb[i] = A(i).a; pw[i] = x.g32(i, x.ix.wqkv(L(i))); pbias[i] = x.g32(i, x.ix.bqkv(L(i)));
+      pa[i] = T(i).dqkv; pb[i] = A(i).a; jw[i] = x.ix.wqkv(L(i)); pbias[i] = x.g32(i, x.ix.bqkv(L(i)));
       pc[i] = x.w16(i, x.ix.wqkv(L(i))); po[i] = T(i).da;
     }
-    TRY(wgrad(x, Tk, 3 * d, d, 3 * d, d, pa, pb, pw, pbias));
     TRY(dgrad(x, Tk, 3 * d, d, 3 * d, pa, pc, po, nullptr, nullptr));
+    TRY(wgrad(x, step, Tk, 3 * d, d, 3 * d, d, pa, pb, jw, pbias));
     // LN1: dx = LN1'(da) + dx1
     FOR_G {
       lb.x[i] = T(i).x[L(i)]; lb.dy[i] = T(i).da; lb.add[i] = T(i).dx1; lb.dx[i] = T(i).dx[L(i)];
@@ -367,13 +386,8 @@ static hydra_status tr_backward(Ctx& x, int batch) {
 hydra_status tr_run(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   Ctx x(c, b, s);
   if (b.ph == HYDRA_PHASE_F) return tr_forward(x, batch, step);
-  if (b.ph == HYDRA_PHASE_B) return tr_backward(x, batch);
-  OptimArgs o;
-  hydra_status st = fill_optim(c, b, step, o);
-  if (st != HYDRA_OK) return st;
-  const double per = (o.opt == 1 ? 28.0 : 12.0) + (o.w16[0] ? 2.0 : 0.0);
-  HYDRA_LAUNCH(c, HYDRA_K_OPTIM, s, 0.0, per * (double)o.n * o.G, launch_optim(o, s));
-  return HYDRA_OK;
+  if (b.ph == HYDRA_PHASE_B) return tr_backward(x, batch, step);
+  return run_update(c, b, step, s);
 }
 
 }  // namespace hydra

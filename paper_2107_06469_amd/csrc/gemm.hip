@@ -23,6 +23,7 @@
 //    so each XCD gets a contiguous run of tiles (m fastest) and the M-tiles that share a W tile hit
 //    the same L2.
 #include "kernels.h"
+#include "optim_math.h"
 
 namespace hydra {
 
@@ -294,8 +295,14 @@ __device__ __forceinline__ void sched_interleave() {
 // PF (W operand) and PFX <= PF (X operand) = k-tiles kept in flight in registers (1 or 2 register sets).  With one wave per SIMD
 // (4-wave workgroups) fragments are double buffered so LDS latency hides behind the previous step's MFMAs;
 // with two waves per SIMD the other wave's MFMAs hide it and the registers are saved.
-template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF, bool X_KMAJ, bool W_KMAJ>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
+struct NoUpdate {};
+template <bool UPD> struct UpdSel { typedef NoUpdate type; };
+template <> struct UpdSel<true> { typedef GemmUpdate type; };
+
+// UPD: the accumulators are weight gradients and the epilogue applies the parameter update to the
+// elements it holds instead of (or besides) storing them.
+template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF, bool X_KMAJ, bool W_KMAJ, bool UPD>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, const typename UpdSel<UPD>::type upd) {
   constexpr int E = Elem<T>::E;
   constexpr int BK = 8 * E;
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
@@ -430,7 +437,30 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a) {
       float v[8];
       load8<float>(&patch[r * SP + c], v);
       const int cnt = a.N - n;  // >= 8: full vector
-      if (cnt >= 8) {
+      if constexpr (UPD) {
+        const size_t idx = (size_t)m * a.ldo + n;
+        const OptimHp h = upd.hp[g];
+        float* up = upd.p[g] + idx;
+        float* ug = a.out[g] ? static_cast<float*>(a.out[g]) + idx : nullptr;
+        bf16_t* uw = upd.w16[g] ? upd.w16[g] + idx : nullptr;
+        // N is a multiple of 8 here (checked by the launcher): every lane holds a full vector
+        float pe[8], me[8], ve[8];
+        load8<float>(up, pe);
+        if (upd.opt == 1) {
+          load8<float>(upd.m[g] + idx, me);
+          load8<float>(upd.v[g] + idx, ve);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
+          store8<float>(upd.m[g] + idx, me);
+          store8<float>(upd.v[g] + idx, ve);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
+        }
+        store8<float>(up, pe);
+        if (uw) store8<bf16_t>(uw, pe);
+        if (ug) store8<float>(ug, v);
+      } else if (cnt >= 8) {
         if (bias) {
           float b[8];
           load8<float>(bias + n, b);
@@ -490,7 +520,13 @@ struct Cfg {
   static hipError_t run1(const GemmArgs& a, hipStream_t s) {
     int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
     int grid = ((tiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_kernel<T, WM, WN, FM, FN, PFX, PF, XK, WK>), dim3(grid), dim3(NT), LDS, s, a);
+    hipLaunchKernelGGL((gemm_kernel<T, WM, WN, FM, FN, PFX, PF, XK, WK, false>), dim3(grid), dim3(NT), LDS, s, a, NoUpdate());
+    return hipGetLastError();
+  }
+  static hipError_t run_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
+    int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
+    int grid = ((tiles + 7) / 8) * 8;
+    hipLaunchKernelGGL((gemm_kernel<T, WM, WN, FM, FN, PFX, PF, false, false, true>), dim3(grid), dim3(NT), LDS, s, a, u);
     return hipGetLastError();
   }
   static hipError_t run(const GemmArgs& a, hipStream_t s) {
@@ -499,11 +535,14 @@ struct Cfg {
   }
   template <bool XK, bool WK>
   static hipError_t attr1() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, FM, FN, PFX, PF, XK, WK>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, FM, FN, PFX, PF, XK, WK, false>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   }
   static hipError_t attr() {
     hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<T, WM, WN, FM, FN, PFX, PF, false, false, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS)) != hipSuccess)
+      return e;
     if ((e = attr1<true, true>()) != hipSuccess) return e;
     if ((e = attr1<true, false>()) != hipSuccess) return e;
     if ((e = attr1<false, true>()) != hipSuccess) return e;
@@ -517,15 +556,27 @@ template <typename T> struct Tiles {
   typedef Cfg<T, 1, 4, 1, 1, 1, 1> Small;  // 32 x 128
 };
 
+int choose_tile(const GemmArgs& a) {
+  if (a.tile) return a.tile;
+  auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * a.G; };
+  if (a.M >= 192 && tiles(256, 256) >= 192) return 1;
+  if (a.M >= 96 && tiles(128, 128) >= 64) return 2;
+  return 3;
+}
+
+template <typename T>
+hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
+  switch (choose_tile(a)) {
+    case 1: return Tiles<T>::Big::run_update(a, u, s);
+    case 2: return Tiles<T>::Mid::run_update(a, u, s);
+    case 3: return Tiles<T>::Small::run_update(a, u, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 template <typename T>
 hipError_t dispatch(const GemmArgs& a, hipStream_t s) {
-  int tile = a.tile;
-  if (tile == 0) {
-    auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * a.G; };
-    if (a.M >= 192 && tiles(256, 256) >= 192) tile = 1;
-    else if (a.M >= 96 && tiles(128, 128) >= 64) tile = 2;
-    else tile = 3;
-  }
+  const int tile = choose_tile(a);
   switch (tile) {
     case 1: return Tiles<T>::Big::run(a, s);
     case 2: return Tiles<T>::Mid::run(a, s);
@@ -556,7 +607,7 @@ hipError_t kernels_init() {
   return attn_init();
 }
 
-hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
+static hipError_t check_gemm(const GemmArgs& a, bool need_out) {
   const int E = a.dtype == GEMM_F32 ? 4 : 8;
   auto rup = [&](int v) { return (v + E - 1) / E * E; };
   if (a.G < 1 || a.G > MAXG || a.M < 1 || a.N < 1 || a.K < 1) return hipErrorInvalidValue;
@@ -566,7 +617,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   // the epilogue moves 8 consecutive outputs as 16/32-byte vectors
   if (a.ldo % 8 || (a.gate[0] && a.ldg % 8) || (a.resid[0] && a.ldr % 8)) return hipErrorInvalidValue;
   for (int g = 0; g < a.G; ++g) {
-    if (!a.X[g] || !a.W[g] || !a.out[g]) return hipErrorInvalidValue;
+    if (!a.X[g] || !a.W[g] || (need_out && !a.out[g])) return hipErrorInvalidValue;
     if (((uintptr_t)a.X[g] | (uintptr_t)a.W[g] | (uintptr_t)a.out[g] | (uintptr_t)a.bias[g] | (uintptr_t)a.pre[g] |
          (uintptr_t)a.gate[g] | (uintptr_t)a.resid[g] | (uintptr_t)a.mul[g]) & 15)
       return hipErrorInvalidValue;
@@ -577,7 +628,30 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   }
   if (a.gate[0] && a.ldg < a.N) return hipErrorInvalidValue;
   if (a.resid[0] && a.ldr < a.N) return hipErrorInvalidValue;
+  return hipSuccess;
+}
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
+  hipError_t e = check_gemm(a, true);
+  if (e != hipSuccess) return e;
   return a.dtype == GEMM_F32 ? dispatch<float>(a, s) : dispatch<bf16_t>(a, s);
+}
+
+hipError_t launch_gemm_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
+  hipError_t e = check_gemm(a, false);
+  if (e != hipSuccess) return e;
+  if (a.x_kmajor || a.w_kmajor || !a.out_f32 || a.act != EPI_ACT_NONE) return hipErrorInvalidValue;
+  if (a.bias[0] || a.pre[0] || a.gate[0] || a.resid[0] || a.mul[0]) return hipErrorInvalidValue;
+  if (u.opt != 0 && u.opt != 1 || a.N % 8) return hipErrorInvalidValue;
+  for (int g = 0; g < a.G; ++g) {
+    if (!u.p[g] || (u.opt == 1 && (!u.m[g] || !u.v[g]))) return hipErrorInvalidValue;
+    if ((u.w16[g] == nullptr) != (u.w16[0] == nullptr) || (a.out[g] == nullptr) != (a.out[0] == nullptr))
+      return hipErrorInvalidValue;
+    if (((uintptr_t)u.p[g] | (uintptr_t)u.m[g] | (uintptr_t)u.v[g]) & 31 || ((uintptr_t)u.w16[g] & 15) ||
+        ((uintptr_t)a.out[g] & 31))
+      return hipErrorInvalidValue;
+  }
+  return a.dtype == GEMM_F32 ? dispatch_update<float>(a, u, s) : dispatch_update<bf16_t>(a, u, s);
 }
 
 }  // namespace hydra

@@ -142,6 +142,7 @@ hydra_status hydra_define_models(hydra_ctx* c, int K, const hydra_arch* archs, i
     }
   }
   c->spill = c->opt.device_budget_bytes > 0 && resident_state_bytes(c) > c->opt.device_budget_bytes;
+  c->fuse = !c->spill && !c->opt.keep_grads;
   hydra_status st = c->spill ? spill_alloc_models(c) : alloc_models(c);
   if (st != HYDRA_OK) {
     if (!c->dry) spill_release_all(c);
@@ -299,6 +300,7 @@ hydra_status hydra_train_epoch(hydra_ctx* c, const hydra_schedule* sch, hydra_ep
     if ((st = spill_prepare(c)) != HYDRA_OK) return st;
     c->sync_spill = sch->policy == HYDRA_SCHED_SEQUENTIAL;
   }
+  if (c->fuse && (st = build_update_chunks(c)) != HYDRA_OK) return st;
   st = build_plan(c, sch, plan);
   if (st != HYDRA_OK) return st;
   hydra_epoch_stats local{};
@@ -327,6 +329,8 @@ static hydra_status copy_out(hydra_ctx* c, int model, int tensor, float* dst, si
   if (c->dry) return c->fail(HYDRA_ERR_BAD_STATE, "a dry-run context holds no values");
   for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
   if (c->spill && grads) return c->fail(HYDRA_ERR_UNSUPPORTED, "gradients are transient while state is spilled to host memory");
+  if (c->fuse && grads)
+    return c->fail(HYDRA_ERR_UNSUPPORTED, "weight gradients are not stored when updates run inside the gradient kernels; create the context with keep_grads = 1");
   if (c->spill) {
     if (c->copy_out) HYDRA_HIP(c, hipStreamSynchronize(c->copy_out));
     size_t o2 = 0;

@@ -24,6 +24,7 @@ struct Tensor {
   float a = 0.f;           // bound of the uniform init
   int unit = 0;            // layer unit that owns it
   size_t off = 0;          // element offset inside the model's parameter block (64-element aligned)
+  bool fused = false;      // a matrix whose gradient one GEMM produces: its update can run in that GEMM's epilogue
 };
 
 // A shard: layer units [u0, u1) of one model (paper, Introduction: a contiguous piece of the model)
@@ -40,6 +41,11 @@ struct Shard {
   // spill mode: slot held between the shard's backward and the end of its update, and the events that order it
   int slot = -1;
   hipEvent_t loaded_ev = nullptr, updated_ev = nullptr;
+  // fused-update mode: the pieces of the block that the update task still owns (tensors that are not `fused`),
+  // as a device table of (first 16-byte vector, vectors <= 256) pairs relative to the shard's block
+  uint2* tail_chunks = nullptr;
+  int n_tail_chunks = 0;
+  size_t n_tail = 0;  // elements covered by the table
 };
 
 struct MlpActs {                // per model, allocated by set_data
@@ -137,6 +143,8 @@ struct hydra_ctx {
   std::vector<void*> dev_allocs;
   size_t dev_bytes = 0, peak_dev_bytes = 0;
   // spill mode (state does not fit device_budget_bytes)
+  // weight updates run in the epilogue of the weight-gradient GEMM (resident state, gradients not kept)
+  bool fuse = false;
   bool spill = false, sync_spill = false;
   struct Slot { float* base = nullptr; hipEvent_t free_ev = nullptr; bool used = false, held = false; };
   std::vector<Slot> slots;
@@ -174,6 +182,7 @@ hydra_status build_tensors(hydra_ctx* c, Model& m);
 hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts);
 hydra_status alloc_models(hydra_ctx* c);
 hydra_status alloc_activations(hydra_ctx* c);
+hydra_status build_update_chunks(hydra_ctx* c);  // fused-update mode: the per-shard tables of what the update task owns
 void* ctx_alloc(hydra_ctx* c, size_t bytes);  // nullptr on failure (or in dry-run, where only bytes are counted)
 void ctx_free(hydra_ctx* c, void* p, size_t bytes);
 void ctx_free_all(hydra_ctx* c);
@@ -197,6 +206,9 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
 hydra_status mlp_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch, hipStream_t s);
 hydra_status tr_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch, hipStream_t s);
 hydra_status fill_optim(hydra_ctx* c, const Bucket& b, int step, OptimArgs& o);
+OptimHp step_hparams(const Model& m, int step_in_epoch);  // fp32 hyper-parameters of optimizer step m.t + step_in_epoch + 1
+// runs the update task of a launch group: the whole block, or only what the fused epilogues leave
+hydra_status run_update(hydra_ctx* c, const Bucket& b, int step, hipStream_t s);
 inline hydra_status run_bucket(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   return c->models[0].arch.kind == HYDRA_KIND_MLP ? mlp_run(c, b, batch, step, s) : tr_run(c, b, batch, step, s);
 }
@@ -206,6 +218,10 @@ inline hydra_status run_bucket(hydra_ctx* c, const Bucket& b, int batch, int ste
     hipError_t e_ = (expr);                                                                             \
     if (e_ != hipSuccess) return (c)->fail(HYDRA_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
+
+// algorithmic HBM bytes per parameter of an update applied in a gradient GEMM's epilogue: the state is read and
+// written once (p, and m, v for Adam), the working copy written, the gradient never stored
+inline double fused_update_bytes(int opt, bool bf16) { return (opt == 1 ? 24.0 : 8.0) + (bf16 ? 2.0 : 0.0); }
 
 // profile.cpp: event pair around one launch when profiling is on
 hipError_t prof_begin(hydra_ctx* c, hipStream_t s, hipEvent_t* a);

@@ -94,9 +94,14 @@ hipError_t launch_softmax_ce(const SoftmaxCeArgs& a, hipStream_t s);
 
 // Optimizer over flat fp32 blocks of n elements (n multiple of 4).
 //   SGD:  p -= lr * g
-//   Adam: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; p -= lr * (m*bc1) / (sqrt(v*bc2) + eps)
-// with bc1 = 1/(1-b1^t), bc2 = 1/(1-b2^t) precomputed by the host.  When w16 is non-null the bf16
-// working copy is refreshed: w16 = bf16(p).
+//   Adam: m = b1 m + c1 g; v = b2 v + c2 g^2; p -= lr * (m*bc1) / (sqrt(v*bc2) + eps)
+// with c = 1 - b and bc1 = 1/(1-b1^t), bc2 = 1/(1-b2^t) rounded from double by the host.  When w16 is
+// non-null the bf16 working copy is refreshed: w16 = bf16(p).
+// With chunks non-null only the listed pieces of the block are updated: chunk i covers elements
+// [4*chunks[i].x, 4*(chunks[i].x + chunks[i].y)) with chunks[i].y <= 256 (a device array shared by the group).
+struct OptimHp {
+  float lr, b1, b2, c1, c2, eps, bc1, bc2;
+};
 struct OptimArgs {
   int opt, G;
   size_t n;
@@ -105,9 +110,25 @@ struct OptimArgs {
   float* m[MAXG];
   float* v[MAXG];
   bf16_t* w16[MAXG];
-  float lr[MAXG], b1[MAXG], b2[MAXG], c1[MAXG], c2[MAXG], eps[MAXG], bc1[MAXG], bc2[MAXG];  // c = 1 - b, rounded from double
+  OptimHp hp[MAXG];
+  const uint2* chunks;
+  int n_chunks;
 };
 hipError_t launch_optim(const OptimArgs& a, hipStream_t s);
+
+// Weight gradient with the update in its epilogue: acc = sum_k X(m,k) W(n,k) is the gradient of
+// parameter element [m, n] (row pitch ldo), which the lane that holds it applies at once to p (and
+// m, v, w16) exactly as launch_optim would; the gradient itself is stored only when a.out is non-null.
+// Requires x_kmajor = w_kmajor = 0, out_f32, and no bias/pre/gate/resid/mul/activation.
+struct GemmUpdate {
+  int opt;
+  float* p[MAXG];
+  float* m[MAXG];
+  float* v[MAXG];
+  bf16_t* w16[MAXG];  // all-or-none across the group
+  OptimHp hp[MAXG];
+};
+hipError_t launch_gemm_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s);
 
 // ---- LayerNorm (layernorm.hip) --------------------------------------------------------------------------
 // y = (x-mean)*rstd*gamma + beta over rows of width d (d % 8 == 0, d <= 4096); mean/rstd fp32 per row.

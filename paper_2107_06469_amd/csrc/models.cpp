@@ -18,6 +18,7 @@ static void add_tensor(Model& m, const std::string& name, int rows, int cols, in
   t.init = init;
   t.a = a;
   t.unit = unit;
+  t.fused = rows > 1 && name != "tok_emb" && name != "pos_emb";  // embedding gradients come from a scatter, not a GEMM
   t.off = m.n_block;
   m.n_block += rup(t.n, 64);
   m.tensors.push_back(t);
@@ -96,6 +97,7 @@ hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts) 
   for (Shard& old : m.shards) {
     if (old.loaded_ev) (void)hipEventDestroy(old.loaded_ev);
     if (old.updated_ev) (void)hipEventDestroy(old.updated_ev);
+    if (old.tail_chunks || (c->dry && old.n_tail_chunks)) ctx_free(c, old.tail_chunks, (size_t)old.n_tail_chunks * sizeof(uint2));
   }
   m.shards.clear();
   const int nt = (int)m.tensors.size();
@@ -209,6 +211,27 @@ hydra_status alloc_models(hydra_ctx* c) {
     if (m.w16) HYDRA_HIP(c, launch_cast_bf16(m.p, m.w16, n, s));
   }
   if (!c->dry) HYDRA_HIP(c, hipStreamSynchronize(s));
+  return HYDRA_OK;
+}
+
+hydra_status build_update_chunks(hydra_ctx* c) {
+  for (Model& m : c->models)
+    for (Shard& sh : m.shards) {
+      if (sh.n_tail_chunks) continue;
+      std::vector<uint2> tab;
+      sh.n_tail = 0;
+      for (int j = sh.t0; j < sh.t1; ++j) {
+        const Tensor& t = m.tensors[j];
+        if (t.fused) continue;
+        const size_t first = (t.off - sh.off) / 4, nv = rup(t.n, 64) / 4;  // the padding is updated too (it stays zero)
+        for (size_t v = 0; v < nv; v += 256) tab.push_back(make_uint2((unsigned)(first + v), (unsigned)std::min<size_t>(256, nv - v)));
+        sh.n_tail += nv * 4;
+      }
+      if (tab.empty()) continue;
+      ALLOC_OR_FAIL(c, sh.tail_chunks, uint2*, tab.size() * sizeof(uint2));
+      sh.n_tail_chunks = (int)tab.size();
+      if (!c->dry) HYDRA_HIP(c, hipMemcpy(sh.tail_chunks, tab.data(), tab.size() * sizeof(uint2), hipMemcpyHostToDevice));
+    }
   return HYDRA_OK;
 }
 

@@ -36,14 +36,16 @@ static uint64_t sm_at(uint64_t s, uint64_t n) {
   return z ^ (z >> 31);
 }
 
-extern "C" {
+// {lr, b1, b2, eps, bc1, bc2} in double -> the kernels' fp32 hyper-parameters (1 - b rounded once from double)
+static OptimHp hp_row(const double* r) {
+  OptimHp h;
+  h.lr = (float)r[0]; h.b1 = (float)r[1]; h.b2 = (float)r[2];
+  h.c1 = (float)(1.0 - r[1]); h.c2 = (float)(1.0 - r[2]);
+  h.eps = (float)r[3]; h.bc1 = (float)r[4]; h.bc2 = (float)r[5];
+  return h;
+}
 
-const char* hydra_ops_last_error(void) { return g_ops_err.c_str(); }
-
-int hydra_op_gemm(const hydra_gemm_desc* d, void* stream) {
-  if (!d || !d->X || !d->W || !d->out || d->G < 1 || d->G > MAXG) return bad("hydra_op_gemm: NULL table or G out of range");
-  if (int st = ensure_init()) return st;
-  GemmArgs a{};
+static void fill_gemm(const hydra_gemm_desc* d, GemmArgs& a) {
   a.dtype = d->dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
   a.M = d->M; a.N = d->N; a.K = d->K;
   a.x_kmajor = d->x_kmajor; a.w_kmajor = d->w_kmajor;
@@ -52,13 +54,44 @@ int hydra_op_gemm(const hydra_gemm_desc* d, void* stream) {
   for (int g = 0; g < d->G; ++g) {
     a.X[g] = d->X[g];
     a.W[g] = d->W[g];
-    a.out[g] = d->out[g];
+    a.out[g] = d->out ? d->out[g] : nullptr;
     a.bias[g] = d->bias ? d->bias[g] : nullptr;
     a.pre[g] = d->pre ? d->pre[g] : nullptr;
     a.gate[g] = d->gate ? d->gate[g] : nullptr;
     a.resid[g] = d->resid ? d->resid[g] : nullptr;
   }
+}
+
+extern "C" {
+
+const char* hydra_ops_last_error(void) { return g_ops_err.c_str(); }
+
+int hydra_op_gemm(const hydra_gemm_desc* d, void* stream) {
+  if (!d || !d->X || !d->W || !d->out || d->G < 1 || d->G > MAXG) return bad("hydra_op_gemm: NULL table or G out of range");
+  if (int st = ensure_init()) return st;
+  GemmArgs a{};
+  fill_gemm(d, a);
   return done(launch_gemm(a, static_cast<hipStream_t>(stream)), "hydra_op_gemm");
+}
+
+int hydra_op_gemm_update(const hydra_gemm_desc* d, int opt, float* const* p, float* const* m, float* const* v,
+                         void* const* w16, const double* hp, void* stream) {
+  if (!d || !d->X || !d->W || !p || !hp || d->G < 1 || d->G > MAXG || (opt != 0 && opt != 1))
+    return bad("hydra_op_gemm_update: NULL table, bad opt or G out of range");
+  if (opt == 1 && (!m || !v)) return bad("hydra_op_gemm_update: Adam needs m and v");
+  if (int st = ensure_init()) return st;
+  GemmArgs a{};
+  fill_gemm(d, a);
+  GemmUpdate u{};
+  u.opt = opt;
+  for (int i = 0; i < d->G; ++i) {
+    u.p[i] = p[i];
+    u.m[i] = m ? m[i] : nullptr;
+    u.v[i] = v ? v[i] : nullptr;
+    u.w16[i] = w16 ? static_cast<bf16_t*>(w16[i]) : nullptr;
+    u.hp[i] = hp_row(hp + 6 * i);
+  }
+  return done(launch_gemm_update(a, u, static_cast<hipStream_t>(stream)), "hydra_op_gemm_update");
 }
 
 size_t hydra_op_colsum_part_floats(int M, int N) { return colsum_part_floats(M, N); }
@@ -107,9 +140,7 @@ int hydra_op_optim(int opt, size_t n, int G, float* const* p, const float* const
     a.m[i] = m ? m[i] : nullptr;
     a.v[i] = v ? v[i] : nullptr;
     a.w16[i] = w16 ? static_cast<bf16_t*>(w16[i]) : nullptr;
-    a.lr[i] = (float)hp[6 * i]; a.b1[i] = (float)hp[6 * i + 1]; a.b2[i] = (float)hp[6 * i + 2];
-    a.c1[i] = (float)(1.0 - hp[6 * i + 1]); a.c2[i] = (float)(1.0 - hp[6 * i + 2]);
-    a.eps[i] = (float)hp[6 * i + 3]; a.bc1[i] = (float)hp[6 * i + 4]; a.bc2[i] = (float)hp[6 * i + 5];
+    a.hp[i] = hp_row(hp + 6 * i);
   }
   return done(launch_optim(a, static_cast<hipStream_t>(stream)), "hydra_op_optim");
 }

@@ -8,6 +8,7 @@
 // the bf16 copy) for Adam.  Each lane moves 16-byte vectors; G models share a grid (blockIdx.y), each
 // with its own hyper-parameters.
 #include "kernels.h"
+#include "optim_math.h"
 
 namespace hydra {
 namespace {
@@ -17,43 +18,49 @@ __device__ __forceinline__ bf16_t f2bf(float v) {
   return __builtin_bit_cast(bf16_t, h);
 }
 
+// one 16-byte vector of each state array
+template <int OPT, bool W16>
+__device__ __forceinline__ void update4(const OptimArgs& a, int g, size_t i, const OptimHp& h) {
+  float4* __restrict__ p = reinterpret_cast<float4*>(a.p[g]);
+  const float4* __restrict__ gr = reinterpret_cast<const float4*>(a.g[g]);
+  float4 pv = p[i];
+  const float4 gv = gr[i];
+  float pe[4] = {pv.x, pv.y, pv.z, pv.w};
+  const float ge[4] = {gv.x, gv.y, gv.z, gv.w};
+  float me[4] = {0.f, 0.f, 0.f, 0.f}, ve[4] = {0.f, 0.f, 0.f, 0.f};
+  if (OPT == 1) {
+    const float4 mv = reinterpret_cast<const float4*>(a.m[g])[i], vv = reinterpret_cast<const float4*>(a.v[g])[i];
+    me[0] = mv.x; me[1] = mv.y; me[2] = mv.z; me[3] = mv.w;
+    ve[0] = vv.x; ve[1] = vv.y; ve[2] = vv.z; ve[3] = vv.w;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) optim_step<OPT>(pe[e], me[e], ve[e], ge[e], h);
+  if (OPT == 1) {
+    reinterpret_cast<float4*>(a.m[g])[i] = make_float4(me[0], me[1], me[2], me[3]);
+    reinterpret_cast<float4*>(a.v[g])[i] = make_float4(ve[0], ve[1], ve[2], ve[3]);
+  }
+  p[i] = make_float4(pe[0], pe[1], pe[2], pe[3]);
+  if (W16)
+    reinterpret_cast<uint2*>(a.w16[g])[i] = make_uint2((uint32_t)f2bf(pe[0]) | ((uint32_t)f2bf(pe[1]) << 16),
+                                                       (uint32_t)f2bf(pe[2]) | ((uint32_t)f2bf(pe[3]) << 16));
+}
+
 template <int OPT, bool W16>
 __global__ __launch_bounds__(256) void optim_kernel(const OptimArgs a) {
   const int g = blockIdx.y;
+  const OptimHp h = a.hp[g];
   const size_t n4 = a.n >> 2;
-  float4* __restrict__ p = reinterpret_cast<float4*>(a.p[g]);
-  const float4* __restrict__ gr = reinterpret_cast<const float4*>(a.g[g]);
-  float4* __restrict__ m = reinterpret_cast<float4*>(a.m[g]);
-  float4* __restrict__ v = reinterpret_cast<float4*>(a.v[g]);
-  uint2* __restrict__ w16 = reinterpret_cast<uint2*>(a.w16[g]);
-  const float lr = a.lr[g], b1 = a.b1[g], b2 = a.b2[g], eps = a.eps[g], bc1 = a.bc1[g], bc2 = a.bc2[g];
-  const float c1 = a.c1[g], c2 = a.c2[g];
   const size_t stride = (size_t)gridDim.x * 256;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-    float4 pv = p[i];
-    const float4 gv = gr[i];
-    float pe[4] = {pv.x, pv.y, pv.z, pv.w};
-    const float ge[4] = {gv.x, gv.y, gv.z, gv.w};
-    if (OPT == 0) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) pe[e] = pe[e] - lr * ge[e];
-    } else {
-      float4 mv = m[i], vv = v[i];
-      float me[4] = {mv.x, mv.y, mv.z, mv.w}, ve[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        me[e] = b1 * me[e] + c1 * ge[e];
-        ve[e] = b2 * ve[e] + c2 * ge[e] * ge[e];
-        pe[e] = pe[e] - lr * (me[e] * bc1) / (sqrtf(ve[e] * bc2) + eps);
-      }
-      m[i] = make_float4(me[0], me[1], me[2], me[3]);
-      v[i] = make_float4(ve[0], ve[1], ve[2], ve[3]);
-    }
-    p[i] = make_float4(pe[0], pe[1], pe[2], pe[3]);
-    if (W16)
-      w16[i] = make_uint2((uint32_t)f2bf(pe[0]) | ((uint32_t)f2bf(pe[1]) << 16),
-                          (uint32_t)f2bf(pe[2]) | ((uint32_t)f2bf(pe[3]) << 16));
-  }
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) update4<OPT, W16>(a, g, i, h);
+}
+
+// one chunk of at most 256 vectors per workgroup
+template <int OPT, bool W16>
+__global__ __launch_bounds__(256) void optim_chunks_kernel(const OptimArgs a) {
+  const int g = blockIdx.y;
+  const OptimHp h = a.hp[g];
+  const uint2 ch = a.chunks[blockIdx.x];
+  if (threadIdx.x < ch.y) update4<OPT, W16>(a, g, (size_t)ch.x + threadIdx.x, h);
 }
 
 }  // namespace
@@ -65,6 +72,18 @@ hipError_t launch_optim(const OptimArgs& a, hipStream_t s) {
   for (int g = 0; g < a.G; ++g) {
     if (!a.p[g] || !a.g[g] || (w16 != (a.w16[g] != nullptr))) return hipErrorInvalidValue;
     if (a.opt == 1 && (!a.m[g] || !a.v[g])) return hipErrorInvalidValue;
+  }
+  if (a.chunks) {
+    if (a.n_chunks < 1) return a.n_chunks == 0 ? hipSuccess : hipErrorInvalidValue;
+    dim3 grid((unsigned)a.n_chunks, a.G);
+    if (a.opt == 0) {
+      if (w16) hipLaunchKernelGGL((optim_chunks_kernel<0, true>), grid, dim3(256), 0, s, a);
+      else hipLaunchKernelGGL((optim_chunks_kernel<0, false>), grid, dim3(256), 0, s, a);
+    } else {
+      if (w16) hipLaunchKernelGGL((optim_chunks_kernel<1, true>), grid, dim3(256), 0, s, a);
+      else hipLaunchKernelGGL((optim_chunks_kernel<1, false>), grid, dim3(256), 0, s, a);
+    }
+    return hipGetLastError();
   }
   size_t n4 = a.n >> 2;
   size_t bx = (n4 + 255) / 256;

@@ -29,6 +29,7 @@ def _L():
     if not _ready:
         vp, pp = C.c_void_p, C.POINTER(C.c_void_p)
         L.hydra_op_gemm.argtypes = [C.POINTER(hydra_gemm_desc), vp]
+        L.hydra_op_gemm_update.argtypes = [C.POINTER(hydra_gemm_desc), C.c_int, pp, pp, pp, pp, C.POINTER(C.c_double), vp]
         L.hydra_op_colsum.argtypes = [C.c_int] * 5 + [pp, pp, pp, vp]
         L.hydra_op_colsum_part_floats.argtypes = [C.c_int, C.c_int]
         L.hydra_op_colsum_part_floats.restype = C.c_size_t
@@ -75,6 +76,19 @@ def hydra_op_gemm(dtype, M, N, K, X, W, out, *, x_kmajor, w_kmajor, ldx, ldw, ld
         if t is not None:
             setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
     _check(_L().hydra_op_gemm(C.byref(d), _stream()))
+
+
+def hydra_op_gemm_update(dtype, M, N, K, X, W, opt, p, m, v, w16, hp_rows, *, ldx, ldw, ldo, out=None, tile=0):
+    """Weight gradient dW[M,N] = sum_k X(k,m) W(k,n) with the optimizer step of hydra_op_optim in its epilogue."""
+    d = hydra_gemm_desc()
+    d.dtype, d.M, d.N, d.K, d.x_kmajor, d.w_kmajor = dtype, M, N, K, 0, 0
+    d.ldx, d.ldw, d.ldo, d.ldg, d.ldr, d.act, d.out_f32, d.tile, d.G = ldx, ldw, ldo, 0, 0, EPI_NONE, 1, tile, len(X)
+    tabs = [_tab(t) for t in (X, W, out)]
+    for name, t in zip(("X", "W", "out"), tabs):
+        if t is not None:
+            setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
+    flat = (C.c_double * (6 * len(p)))(*[float(x) for row in hp_rows for x in row])
+    _check(_L().hydra_op_gemm_update(C.byref(d), opt, _tab(p), _tab(m), _tab(v), _tab(w16), flat, _stream()))
 
 
 def hydra_op_colsum_part_floats(M, N) -> int:

@@ -259,6 +259,49 @@ def test_optimizer_step_matches_oracle(torch, ops, opt, w16):
             assert torch.equal(W16[g], P[g].to(torch.bfloat16))
 
 
+@pytest.mark.parametrize("opt", [0, 1])
+@pytest.mark.parametrize("dtype_name,tile,M,N,K", [("bf16", 1, 384, 512, 200), ("bf16", 2, 200, 264, 96), ("bf16", 3, 72, 320, 50),
+                                                   ("f32", 2, 136, 200, 64), ("f32", 0, 72, 40, 30)])
+def test_update_in_the_gradient_kernel_equals_gradient_then_optimizer(torch, ops, opt, dtype_name, tile, M, N, K):
+    # the same gradient GEMM, once stored and applied by the optimizer kernel, once applied in the epilogue:
+    # parameters, moments and working copy must agree bit for bit (and the optimizer kernel is checked
+    # against the oracle above)
+    bf = dtype_name == "bf16"
+    td = torch.bfloat16 if bf else torch.float32
+    dt = ops.BF16 if bf else ops.F32
+    r = np.random.default_rng(M + N + K + opt)
+    G, E = 2, (8 if bf else 4)
+    ldx, ldw = (M + E - 1) // E * E, (N + E - 1) // E * E
+    n = M * N
+    X = [torch.from_numpy(r.normal(size=(K, ldx)).astype(np.float32)).cuda().to(td) for _ in range(G)]
+    W = [torch.from_numpy(r.normal(size=(K, ldw)).astype(np.float32)).cuda().to(td) for _ in range(G)]
+    hp_rows = [(1e-3 * (g + 1), 0.9, 0.999, 1e-8, 1 / (1 - 0.9 ** (2 + g)), 1 / (1 - 0.999 ** (2 + g))) for g in range(G)]
+
+    def state():
+        rr = np.random.default_rng(5)
+        return ([torch.from_numpy(rr.normal(size=n).astype(np.float32)).cuda() for _ in range(G)],
+                [torch.from_numpy((rr.normal(size=n) * 0.05).astype(np.float32)).cuda() for _ in range(G)],
+                [torch.from_numpy((rr.random(size=n) * 0.01).astype(np.float32)).cuda() for _ in range(G)],
+                [torch.zeros(n, dtype=torch.bfloat16, device="cuda") for _ in range(G)] if bf else None)
+    # two-kernel path
+    P1, M1, V1, W1 = state()
+    Gr = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(G)]
+    ops.hydra_op_gemm(dt, M, N, K, X, W, Gr, x_kmajor=False, w_kmajor=False, ldx=ldx, ldw=ldw, ldo=N, out_f32=True, tile=tile)
+    ops.hydra_op_optim(opt, n, P1, Gr, M1, V1, W1, hp_rows)
+    # fused path, with and without storing the gradient
+    P2, M2, V2, W2 = state()
+    ops.hydra_op_gemm_update(dt, M, N, K, X, W, opt, P2, M2, V2, W2, hp_rows, ldx=ldx, ldw=ldw, ldo=N, tile=tile)
+    P3, M3, V3, W3 = state()
+    Gr3 = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(G)]
+    ops.hydra_op_gemm_update(dt, M, N, K, X, W, opt, P3, M3, V3, W3, hp_rows, ldx=ldx, ldw=ldw, ldo=N, out=Gr3, tile=tile)
+    torch.cuda.synchronize()
+    for g in range(G):
+        assert not torch.equal(P1[g], state()[0][g])
+        for a, b, c in ((P1, P2, P3), (M1, M2, M3), (V1, V2, V3)) + (((W1, W2, W3),) if bf else ()):
+            assert torch.equal(a[g], b[g]) and torch.equal(a[g], c[g])
+        assert torch.equal(Gr[g], Gr3[g])
+
+
 def test_seeded_initialisation_is_bit_identical_to_the_oracle(torch, ops):
     for (seed, model, tensor, n, a) in [(42, 0, 0, 65536, math.sqrt(6 / 256)), (42, 7, 33, 1000, 0.02 * math.sqrt(3)),
                                         (2 ** 40 + 5, 15, 2, 4097, 1.0)]:

@@ -129,9 +129,12 @@ def test_config0_fp32_sgd_matches_oracle_and_every_schedule_gives_the_same_bits(
     for k in range(wg.K):
         _assert_fp32_parity(gotg[k], refg[k], _names(wg.archs[k]))
     # exact replication: sequential model-parallel order, unsharded models, other cuts, an explicit
-    # round-robin order and a single stream must reproduce the same bits
+    # round-robin order, a single stream, and updates applied by separate update tasks instead of inside
+    # the gradient kernels must reproduce the same bits
     variants = [
         dict(policy=H.SCHED_SEQUENTIAL),
+        dict(policy=H.SCHED_SHARD_PARALLEL, keep_grads=True),
+        dict(policy=H.SCHED_SEQUENTIAL, keep_grads=True, cuts=[[2]] * w.K),
         dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[]] * w.K),
         dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[1, 3, 4]] * w.K, n_streams=1),
         dict(policy=H.SCHED_SEQUENTIAL, cuts=[[1], [2], [3], [4]]),
@@ -174,10 +177,39 @@ def test_scaled_config1_gelu_adam_matches_oracle(H, dtype):
         assert all(np.array_equal(a, b) for a, b in zip(seq[k][1], got[k][1]))
 
 
+@pytest.mark.parametrize("dtype", [C.DTYPE_F32, C.DTYPE_BF16])
+def test_update_inside_gradient_kernels_equals_separate_update_tasks(H, dtype):
+    # Adam, 5 layers of width 320 (several 128x128 tiles and ragged 256x256 ones), 72 classes
+    w = scaled_workload(1, steps=4)
+    for a in w.archs:
+        a["dtype"] = dtype
+    data = make_data(w)
+    fused, fs = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL)
+    plain, ps = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL, keep_grads=True)
+    for k in range(w.K):
+        assert np.array_equal(fused[k][0], plain[k][0])
+        for a, b in zip(fused[k][1], plain[k][1]):
+            assert np.array_equal(a, b)
+
+
+def test_gradients_are_refused_when_they_are_not_kept(H):
+    w = scaled_workload(1, steps=1)
+    data = make_data(w)
+    ctx = H.hydra_create(n_streams=1)
+    H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+    H.hydra_shard(ctx, -1, w.boundaries[0])
+    H.hydra_set_data(ctx, data["inputs"], None, data["targets"])
+    H.hydra_train_epoch(ctx)
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_read_grads(ctx, 0)
+    assert e.value.status == 7
+    H.hydra_destroy(ctx)
+
+
 def test_first_step_gradients_bf16(H):
     w = scaled_workload(1, steps=1)
     data = make_data(w)
-    ctx = H.hydra_create(n_streams=2)
+    ctx = H.hydra_create(n_streams=2, keep_grads=True)
     H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
     H.hydra_shard(ctx, -1, w.boundaries[0])
     H.hydra_set_data(ctx, data["inputs"], None, data["targets"])

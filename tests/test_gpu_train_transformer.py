@@ -68,6 +68,7 @@ def test_scaled_transformer_workloads_match_oracle_and_schedules_agree_bitwise(H
         p0 = [p.astype(np.float64) for p in OM.init_params(w.archs[k], w.init_seed, k)]
         _check_bf16(got[k], ref[k], _names(w.archs[k]), p0, max_step=w.hparams[k]["lr"] * w.steps)
     variants = [dict(policy=H.SCHED_SEQUENTIAL), dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[]] * w.K, n_streams=1),
+                dict(policy=H.SCHED_SHARD_PARALLEL, keep_grads=True),   # updates by update tasks, not inside gradient kernels
                 dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[1]] * w.K, n_streams=2)]
     for v in variants:
         other, _ = H.train_workload(w, data, **v)
@@ -81,7 +82,7 @@ def test_scaled_transformer_workloads_match_oracle_and_schedules_agree_bitwise(H
 def test_first_step_gradients_transformer(H, i):
     w = scaled_workload(i, steps=1)
     data = make_data(w)
-    ctx = H.hydra_create(n_streams=2)
+    ctx = H.hydra_create(n_streams=2, keep_grads=True)
     H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
     for k in range(w.K):
         H.hydra_shard(ctx, k, w.boundaries[k])
