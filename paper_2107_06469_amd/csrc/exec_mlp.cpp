@@ -162,7 +162,7 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int s
         up.hp[i] = step_hparams(m, step);
       }
       HYDRA_LAUNCH(c, HYDRA_K_WGRAD_UPDATE, s, 2.0 * w.M * w.N * w.K * G,
-                   fused_update_bytes(up.opt, bf) * w.M * w.N * G, launch_gemm_update(w, up, s));
+                   (fused_update_bytes(up.opt, bf) * w.M * w.N + (double)es * w.K * (w.M + w.N)) * G, launch_gemm_update(w, up, s));
     } else {
       HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, s, 2.0 * w.M * w.N * w.K * G, 0.0, launch_gemm(w, s));
     }

@@ -219,7 +219,7 @@ static hydra_status wgrad(Ctx& x, int step, int rows, int n_out, int k_in, int l
       up.hp[i] = step_hparams(x.model(i), step);
     }
     HYDRA_LAUNCH(c, HYDRA_K_WGRAD_UPDATE, x.s, 2.0 * w.M * w.N * w.K * x.G,
-                 fused_update_bytes(up.opt, true) * w.M * w.N * x.G, launch_gemm_update(w, up, x.s));
+                 (fused_update_bytes(up.opt, true) * w.M * w.N + 2.0 * w.K * (w.M + w.N)) * x.G, launch_gemm_update(w, up, x.s));
   } else {
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, x.s, 2.0 * w.M * w.N * w.K * x.G, 0.0, launch_gemm(w, x.s));
   }

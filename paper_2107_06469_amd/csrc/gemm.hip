@@ -319,7 +319,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
   const int per_xcd = (n_tiles + 7) >> 3;
   const int t_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (t_id >= n_tiles) return;
-  const int tm = t_id % tiles_m, tn = (t_id / tiles_m) % tiles_n, g = t_id / (tiles_m * tiles_n);
+  // Consecutive tiles share W columns (tm fastest).  With the update in the epilogue the state traffic
+  // dominates: consecutive tiles then walk along a row band of the parameter matrix (tn fastest), so the
+  // workgroups running together stream contiguous memory.
+  const int g = t_id / (tiles_m * tiles_n);
+  const int tm = UPD ? (t_id / tiles_n) % tiles_m : t_id % tiles_m;
+  const int tn = UPD ? t_id % tiles_n : (t_id / tiles_m) % tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
 
   const T* X = static_cast<const T*>(a.X[g]);
@@ -566,7 +571,11 @@ int choose_tile(const GemmArgs& a) {
 
 template <typename T>
 hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
-  switch (choose_tile(a)) {
+  int tile = choose_tile(a);
+  // the state traffic of the epilogue dominates: with two workgroups per CU one streams state while the
+  // other runs its k-loop, which the 256x256 tile (one workgroup per CU) cannot do
+  if (!a.tile && tile == 1) tile = 2;
+  switch (tile) {
     case 1: return Tiles<T>::Big::run_update(a, u, s);
     case 2: return Tiles<T>::Mid::run_update(a, u, s);
     case 3: return Tiles<T>::Small::run_update(a, u, s);
