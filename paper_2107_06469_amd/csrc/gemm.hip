@@ -273,6 +273,15 @@ __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&v)[8]) {
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Streaming load for data read once per launch (optimizer state): the non-temporal hint keeps it from
+// displacing the operand panels that other workgroups of the launch still re-read from L2.  (Stores keep
+// the default policy: non-temporal stores were measured to write 6 % more bytes.)
+__device__ __forceinline__ void load8_stream(const float* p, float (&v)[8]) {
+  const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + 1);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
 // Scheduling hint for one MFMA step: spread NR LDS reads and NMEM memory operations (mask MEMMASK:
 // 0x200 = LDS write, 0x020 = global read) evenly between the step's NM MFMAs.
 template <int NM, int NR, int NMEM, int MEMMASK>
@@ -319,12 +328,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
   const int per_xcd = (n_tiles + 7) >> 3;
   const int t_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (t_id >= n_tiles) return;
-  // Consecutive tiles share W columns (tm fastest).  With the update in the epilogue the state traffic
-  // dominates: consecutive tiles then walk along a row band of the parameter matrix (tn fastest), so the
-  // workgroups running together stream contiguous memory.
-  const int g = t_id / (tiles_m * tiles_n);
-  const int tm = UPD ? (t_id / tiles_n) % tiles_m : t_id % tiles_m;
-  const int tn = UPD ? t_id % tiles_n : (t_id / tiles_m) % tiles_n;
+  // Tile order inside a problem: bands of GM tile rows; inside a band the column index is the slow
+  // one.  The few dozen tiles an XCD runs at a time then form a GM x (a few columns) block that shares
+  // GM X panels and a few W panels in its L2, instead of one long row or column of tiles whose other
+  // operand is streamed from memory again for every tile.
+  constexpr int GM = 8;
+  const int g = t_id / (tiles_m * tiles_n), t_in = t_id % (tiles_m * tiles_n);
+  const int band = t_in / (GM * tiles_n), r_in = t_in % (GM * tiles_n);
+  const int band_rows = min(GM, tiles_m - band * GM);
+  const int tm = band * GM + r_in % band_rows, tn = r_in / band_rows;
   const int m0 = tm * BM, n0 = tn * BN;
 
   const T* X = static_cast<const T*>(a.X[g]);
@@ -450,10 +462,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
         bf16_t* uw = upd.w16[g] ? upd.w16[g] + idx : nullptr;
         // N is a multiple of 8 here (checked by the launcher): every lane holds a full vector
         float pe[8], me[8], ve[8];
-        load8<float>(up, pe);
+        load8_stream(up, pe);
         if (upd.opt == 1) {
-          load8<float>(upd.m[g] + idx, me);
-          load8<float>(upd.v[g] + idx, ve);
+          load8_stream(upd.m[g] + idx, me);
+          load8_stream(upd.v[g] + idx, ve);
 #pragma unroll
           for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
           store8<float>(upd.m[g] + idx, me);
