@@ -568,7 +568,10 @@ struct Cfg {
 };
 
 template <typename T> struct Tiles {
-  typedef Cfg<T, 2, 2, 4, 4, 1, 1> Big;    // 256 x 256, one k-tile in flight in registers (register-bound)
+  // 256 x 256 with 8 waves (2 x 4, each 128 x 64): two waves per SIMD, so one wave's MFMAs run while the
+  // other waits for its loads, LDS reads or the barrier.  (A 4-wave 256 x 256 tile with 4 x 4 accumulators
+  // per wave reads less LDS per MFMA but leaves every wait exposed: measured 8-30 % slower.)
+  typedef Cfg<T, 2, 4, 4, 2, 1, 1> Big;
   typedef Cfg<T, 2, 2, 2, 2, 2, 2> Mid;    // 128 x 128, two k-tiles in flight, two workgroups per CU
   typedef Cfg<T, 1, 4, 1, 1, 1, 1> Small;  // 32 x 128
 };
@@ -576,17 +579,22 @@ template <typename T> struct Tiles {
 int choose_tile(const GemmArgs& a) {
   if (a.tile) return a.tile;
   auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * a.G; };
-  if (a.M >= 192 && tiles(256, 256) >= 192) return 1;
-  if (a.M >= 96 && tiles(128, 128) >= 64) return 2;
+  const long big = tiles(256, 256), mid = tiles(128, 128);
+  if (a.M >= 192 && big >= 192) return 1;  // the big tile fills the chip
+  if (a.M >= 96 && mid >= 64) {
+    // Too few big tiles for 256 CUs: 128 x 128 tiles win while they fit in one pass over the chip (two
+    // workgroups per CU); beyond that a partly filled pass of big tiles is still the faster choice.
+    return (a.M >= 192 && big >= 128 && mid > 512) ? 1 : 2;
+  }
   return 3;
 }
 
 template <typename T>
 hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
   int tile = choose_tile(a);
-  // the state traffic of the epilogue dominates: with two workgroups per CU one streams state while the
-  // other runs its k-loop, which the 256x256 tile (one workgroup per CU) cannot do
-  if (!a.tile && tile == 1) tile = 2;
+  // With a short k-loop the state traffic of the epilogue dominates: with two workgroups per CU one streams
+  // state while the other runs its k-loop, which the 256x256 tile (one workgroup per CU) cannot do.
+  if (!a.tile && tile == 1 && a.K < 2048) tile = 2;
   switch (tile) {
     case 1: return Tiles<T>::Big::run_update(a, u, s);
     case 2: return Tiles<T>::Mid::run_update(a, u, s);
