@@ -22,6 +22,25 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 
 
+def measured_traffic(kernel_class, workload):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, or None when the
+    summary covers another kernel or workload, or the kernel's sources changed since it was taken."""
+    import hashlib
+    if kernel_class != "wgrad_update" or workload != 1:
+        return None
+    path = os.path.join(ROOT, "profiles", "workload1_kernels_hbm_traffic.txt")
+    try:
+        kv = dict(l.split(":", 1) for l in open(path) if ":" in l and not l.startswith("#"))
+        h = hashlib.sha256()
+        for f in ("gemm.hip", "optim_math.h"):
+            h.update(open(os.path.join(ROOT, "paper_2107_06469_amd", "csrc", f), "rb").read())
+        if kv["source_sha256"].strip() != h.hexdigest():
+            return None
+        return float(kv["update_gemm_fetch_bytes"]) + float(kv["update_gemm_write_bytes"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def _set_steps(w, n):
     w.steps = w.n_batches = n
     return w
@@ -128,8 +147,9 @@ def main():
         else:
             ach = p["bytes"] / p["launches"] / (avg_ms * 1e-3) / 1e9
             out["roofline"] = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                               "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": avg_ms,
-                               "launches": p["launches"]}
+                               "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(name, args.workload),
+                               "avg_launch_ms": avg_ms, "launches": p["launches"],
+                               "algorithmic_bytes_per_launch": p["bytes"] / p["launches"]}
         tot = sum(v["total_ms"] for v in prof.values())
         out["kernel_time_ms_per_step"] = {k: v["total_ms"] / args.steps for k, v in prof.items()}
         gemm_ms = sum(v["total_ms"] for k, v in prof.items() if k.startswith("gemm"))

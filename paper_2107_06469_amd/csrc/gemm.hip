@@ -20,8 +20,12 @@
 //  * The sum over k runs in ascending order with one MFMA chain per output element, no split-K and
 //    no atomics, so a result does not depend on tile shape, grid placement or group size.
 //  * Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the tile index is remapped
-//    so each XCD gets a contiguous run of tiles (m fastest) and the M-tiles that share a W tile hit
-//    the same L2.
+//    so each XCD gets a contiguous run of tiles, ordered in bands of 8 tile rows so that the tiles
+//    resident on an XCD at one time share a few X and W panels in its L2.
+//  * With a GemmUpdate the kernel is the weight-gradient GEMM of a Linear layer and its epilogue
+//    applies the optimizer step to the parameters, moments and bf16 working copy of the elements
+//    it holds (optim_math.h): the gradient never goes to memory (paper, Approach, "Desiderata":
+//    same update as unsharded training, so the arithmetic is shared with the optimizer kernel).
 #include "kernels.h"
 #include "optim_math.h"
 
