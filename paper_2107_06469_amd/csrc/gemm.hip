@@ -154,12 +154,19 @@ struct LoaderK {
 };
 
 // operand stored with k as the slow index: memory is [K, ld] with the tile's row index contiguous.
-// Block b = tid + NT*i covers rows [mb*E, mb*E+E) x k [kb*E, kb*E+E), mb = b % (ROWS/E), kb = b / (ROWS/E);
-// it is read as E chunks along the row index and written as E chunks along k.
+// Block b covers rows [mb*E, mb*E+E) x k [kb*E, kb*E+E), mb = b % (ROWS/E), kb = b / (ROWS/E); it is read as E
+// chunks along the row index and written as E chunks along k.  When the tile has fewer blocks than the
+// workgroup has threads, SPLIT = 2 threads share a block (each takes half of its k rows, i.e. half of every
+// 16-byte chunk it writes).  Work unit u maps to (mb, half, kb) with 16 consecutive lanes on consecutive mb
+// (256 contiguous bytes per global load) and the next 16 lanes on the other half: a 32-lane group then writes
+// both halves of 8 distinct chunks, i.e. all LDS banks, instead of one half of them four times over.
 template <typename T, int ROWS, int NT>
 struct LoaderT {
   static constexpr int E = Elem<T>::E;
-  static constexpr int NB = (ROWS / E) * 8;                     // E x E blocks in the tile
+  static constexpr int RB = ROWS / E;                           // blocks along the row index
+  static constexpr int LO = RB < 16 ? RB : 16;                  // consecutive lanes on consecutive blocks
+  static_assert(RB % LO == 0, "tile rows must be a multiple of 16 blocks (or fewer than 16)");
+  static constexpr int NB = RB * 8;                             // E x E blocks in the tile
   static constexpr int SPLIT = (2 * NB <= NT) ? 2 : 1;          // threads sharing a block (halves of its k rows)
   static constexpr int KR = E / SPLIT;                          // k rows per thread
   static constexpr int NU = NB * SPLIT;                         // work units
@@ -176,8 +183,8 @@ struct LoaderT {
     (void)nrows;
 #pragma unroll
     for (int i = 0; i < NBT; ++i) {
-      const int u = tid + NT * i, b = u % NB, half = u / NB;
-      const int mb = b % (ROWS / E), kb = b / (ROWS / E);
+      const int u = tid + NT * i, half = (u / LO) % SPLIT, rest = u / (LO * SPLIT);
+      const int mb = u % LO + LO * (rest % (RB / LO)), kb = rest / (RB / LO);
       const unsigned voff = ((unsigned)(kb * E + half * KR) * (unsigned)ld + (unsigned)(mb * E)) * (unsigned)sizeof(T);
 #pragma unroll
       for (int j = 0; j < KR; ++j) {
@@ -190,9 +197,9 @@ struct LoaderT {
   __device__ __forceinline__ void store(uint4* tile, int tid) const {
 #pragma unroll
     for (int i = 0; i < NBT; ++i) {
-      const int u = tid + NT * i, b = u % NB, half = u / NB;
+      const int u = tid + NT * i, half = (u / LO) % SPLIT, rest = u / (LO * SPLIT);
       if (u >= NU) continue;
-      const int mb = b % (ROWS / E), kb = b / (ROWS / E);
+      const int mb = u % LO + LO * (rest % (RB / LO)), kb = rest / (RB / LO);
       uint32_t in[KR][4];
 #pragma unroll
       for (int j = 0; j < KR; ++j) {
