@@ -47,6 +47,8 @@ typedef struct {
   void* const* pre;
   const void* const* gate;
   const void* const* resid;
+  float* const* rowsum; /* optional, weight-gradient layout (x_kmajor = w_kmajor = 0) only: rowsum_g[m] =
+                           sum_k X_g(m,k) in fp32, M floats each; with X = dY this is the bias gradient */
 } hydra_gemm_desc;
 int hydra_op_gemm(const hydra_gemm_desc* d, void* stream);
 

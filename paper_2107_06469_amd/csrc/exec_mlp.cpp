@@ -4,7 +4,7 @@
 //
 // unit l < L:  z_l = x_l W_l^T + b_l,  h_l = act(z_l),  x_{l+1} = h_l          (x_0 = the batch)
 // unit L:      logits = x_L W_out^T + b_out, softmax cross-entropy
-// backward of unit l given dz_l:  dW_l = dz_l^T x_l;  db_l = column sums of dz_l;
+// backward of unit l given dz_l:  dW_l = dz_l^T x_l;  db_l = column sums of dz_l (same launch);
 //                                 dz_{l-1} = (dz_l W_l) * act'(z_{l-1})         (l > 0)
 #include <cmath>
 
@@ -130,12 +130,6 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int s
     w.ldo = W_of(m0, u).cols;
     w.act = EPI_ACT_NONE;
     w.out_f32 = 1;
-    ColsumArgs cs{};
-    cs.dtype = w.dtype;
-    cs.M = c->B;
-    cs.N = N;
-    cs.ld = lddz;
-    cs.G = G;
     for (int i = 0; i < G; ++i) {
       const Model& m = c->models[b.members[i].first];
       const Shard& sh = m.shards[b.members[i].second];
@@ -143,9 +137,7 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int s
       w.X[i] = dz;
       w.W[i] = u == 0 ? static_cast<const char*>(c->x_staged) + (size_t)batch * c->B * c->ld_in * es : m.mlp.h[u - 1];
       w.out[i] = at(sh.g, sh, W_of(m, u));
-      cs.src[i] = dz;
-      cs.out[i] = at(sh.g, sh, b_of(m, u));
-      cs.part[i] = m.colpart;
+      w.rowsum[i] = at(sh.g, sh, b_of(m, u));  // db = column sums of dz, from the GEMM's own dz fragments
     }
     if (c->fuse) {
       // the update of W_u runs in the epilogue of its gradient GEMM; the gradient is never stored
@@ -166,7 +158,6 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int s
     } else {
       HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, s, 2.0 * w.M * w.N * w.K * G, 0.0, launch_gemm(w, s));
     }
-    HYDRA_LAUNCH(c, HYDRA_K_COLSUM, s, 0.0, (double)G * cs.M * cs.N * es, launch_colsum(cs, s));
   }
   return HYDRA_OK;
 }

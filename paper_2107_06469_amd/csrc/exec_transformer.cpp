@@ -194,7 +194,7 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
 }
 
 // weight gradient dW[N_out, K_in] = dy[rows, N_out]^T x_in[rows, K_in] of tensor jw[i] of member i, plus the
-// bias gradient = column sums of dy.  In fused-update mode the GEMM's epilogue applies the update of
+// bias gradient = column sums of dy (computed by the same launch from the dy fragments it loads).  In fused-update mode the GEMM's epilogue applies the update of
 // the weight, so every reader of the old weight (the matching dgrad) must have been issued before.
 static hydra_status wgrad(Ctx& x, int step, int rows, int n_out, int k_in, int ld_dy, int ld_x, const void* const* dy,
                           const void* const* xin, const int* jw, float* const* db) {
@@ -202,9 +202,7 @@ static hydra_status wgrad(Ctx& x, int step, int rows, int n_out, int k_in, int l
   GemmArgs w{};
   w.dtype = GEMM_BF16; w.M = n_out; w.N = k_in; w.K = rows; w.x_kmajor = w.w_kmajor = 0; w.ldx = ld_dy; w.ldw = ld_x;
   w.ldo = k_in; w.out_f32 = 1; w.G = x.G;
-  ColsumArgs cs{};
-  cs.dtype = GEMM_BF16; cs.M = rows; cs.N = n_out; cs.ld = ld_dy; cs.G = x.G;
-  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = x.g32(i, jw[i]); cs.src[i] = dy[i]; cs.out[i] = db[i]; cs.part[i] = x.model(i).colpart; }
+  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = x.g32(i, jw[i]); w.rowsum[i] = db[i]; }
   if (c->fuse) {
     GemmUpdate up{};
     up.opt = x.model(0).hp.opt == HYDRA_OPT_ADAM ? 1 : 0;
@@ -223,7 +221,6 @@ static hydra_status wgrad(Ctx& x, int step, int rows, int n_out, int k_in, int l
   } else {
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_WGRAD, x.s, 2.0 * w.M * w.N * w.K * x.G, 0.0, launch_gemm(w, x.s));
   }
-  HYDRA_LAUNCH(c, HYDRA_K_COLSUM, x.s, 0.0, (double)x.G * rows * n_out * 2, launch_colsum(cs, x.s));
   return HYDRA_OK;
 }
 

@@ -250,6 +250,27 @@ __device__ __forceinline__ void mma<float>(f32x16& acc, const uint4& wfrag, cons
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(wfrag.w), __uint_as_float(xfrag.w), acc, 0, 0, 0);
 }
 
+// c + the sum of the elements of one 16-byte operand chunk, added in a fixed order
+template <typename T>
+__device__ __forceinline__ float chunk_sum(const uint4& f, float c);
+template <>
+__device__ __forceinline__ float chunk_sum<bf16_t>(const uint4& f, float c) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, f.x), one, c, false);
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, f.y), one, c, false);
+  c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, f.z), one, c, false);
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, f.w), one, c, false);
+}
+template <>
+__device__ __forceinline__ float chunk_sum<float>(const uint4& f, float c) {
+#pragma clang fp contract(off)
+  c = c + __uint_as_float(f.x);
+  c = c + __uint_as_float(f.y);
+  c = c + __uint_as_float(f.z);
+  return c + __uint_as_float(f.w);
+}
+
 // 8 consecutive elements of operand type T <-> 8 floats (16-byte aligned for bf16, 32-byte for fp32)
 template <typename T>
 __device__ __forceinline__ void load8(const T* p, float (&v)[8]);
@@ -402,6 +423,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
     }
   };
   constexpr int NM = FM * FN * (sizeof(T) == 4 ? 4 : 1);  // MFMA instructions per step
+  // Row sums of the X operand, sum_k X(m,k): in the weight-gradient layout X is dY, so this is the bias
+  // gradient of the layer.  Every lane (row, half) adds up the 16-byte chunks it feeds to the MFMAs anyway,
+  // in ascending k (a handful of VALU operations per step, hidden behind the MFMAs); the two halves are added
+  // at the end and the tiles of the first tile column store the result.  The order depends on nothing but
+  // k, like the GEMM's own sums.
+  constexpr bool RS = !X_KMAJ && !W_KMAJ;
+  const bool do_rs = RS && a.rowsum[g] != nullptr && tn == 0;  // uniform over the workgroup
+  float rs[FM];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) rs[i] = 0.f;
   if (FDB) read_frags(lds, 0, xf[0], wf[0]);
   for (int kt = 0; kt < nk; kt += PF) {
 #pragma unroll
@@ -422,6 +453,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
           for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j) mma<T>(acc[i][j], wf[FDB ? (s & 1) : 0][j], xf[FDB ? (s & 1) : 0][i]);
+          if constexpr (RS) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i) rs[i] = chunk_sum<T>(xf[FDB ? (s & 1) : 0][i], rs[i]);
+          }
           // interleave the step's LDS reads and memory operations between its MFMAs
           if (s == 0) sched_interleave<NM, FM + FN, LX::N_STORE, 0x200>();
           if (s == 1) sched_interleave<NM, FM + FN, LW::N_STORE, 0x200>();
@@ -431,6 +466,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
         __syncthreads();
         if (FDB && t + 1 < nk) read_frags(nx, 0, xf[0], wf[0]);
       }
+    }
+  }
+  if (do_rs && wn == 0) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const float total = rs[i] + __shfl_xor(rs[i], 32, 64);  // even chunks + odd chunks
+      const int m = m0 + (wm * FM + i) * 32 + lrow;
+      if (lgrp == 0 && m < a.M) a.rowsum[g][m] = total;
     }
   }
 
@@ -668,6 +711,9 @@ static hipError_t check_gemm(const GemmArgs& a, bool need_out) {
   }
   if (a.gate[0] && a.ldg < a.N) return hipErrorInvalidValue;
   if (a.resid[0] && a.ldr < a.N) return hipErrorInvalidValue;
+  for (int g = 0; g < a.G; ++g)
+    if ((a.rowsum[g] == nullptr) != (a.rowsum[0] == nullptr)) return hipErrorInvalidValue;
+  if (a.rowsum[0] && (a.x_kmajor || a.w_kmajor)) return hipErrorInvalidValue;
   return hipSuccess;
 }
 

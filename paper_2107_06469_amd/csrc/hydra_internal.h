@@ -86,7 +86,6 @@ struct Model {
   bf16_t* w16 = nullptr;
   MlpActs mlp;
   TrActs tr;
-  float* colpart = nullptr;     // scratch of the column-sum kernel
   // spill mode: resident fp32 copy of the vector tensors (offset per tensor, -1 for matrices) and the pinned
   // host home of master weights and Adam moments
   float* pv = nullptr;

@@ -41,6 +41,8 @@ struct GemmArgs {
   const void* gate[MAXG];   // nullable, [M, ldg], operand dtype
   const void* resid[MAXG];  // nullable, [M, ldr], operand dtype
   const void* mul[MAXG];    // nullable, [M, ldo], operand dtype: v *= mul[m,n] after the activation
+  float* rowsum[MAXG];      // nullable, fp32 [M]: receives sum_k X(m,k) (x_kmajor = w_kmajor = 0 only): with X = dY
+                            // of a Linear layer this is its bias gradient
   int ldo, ldg, ldr;
   int act;
   int out_f32;

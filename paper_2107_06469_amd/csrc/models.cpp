@@ -262,8 +262,6 @@ hydra_status alloc_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, t.logits, float*, (size_t)c->B * ldv * 4);
       ALLOC_OR_FAIL(c, t.dlogits, void*, (size_t)c->B * ldv * es);
       ALLOC_OR_FAIL(c, t.rowloss, float*, (size_t)c->B * 4);
-      const size_t cp = std::max(colsum_part_floats(c->B, a.d_model), colsum_part_floats(c->B, a.n_out));
-      if (cp) ALLOC_OR_FAIL(c, m.colpart, float*, cp * 4);
     } else {
       const size_t Tk = (size_t)c->B * c->S, NT = (size_t)c->B * c->P, d = a.d_model, F = a.d_ffn;
       const size_t ldv = rup(a.n_out, 8), bhs = (size_t)c->B * a.n_heads * c->S;
@@ -312,9 +310,6 @@ hydra_status alloc_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, t.da, void*, Tk * d * 2);
       ALLOC_OR_FAIL(c, t.delta, float*, bhs * 4);
       ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)Tk) * 2 * d * 4);
-      const size_t cp = std::max(std::max(colsum_part_floats((int)Tk, 3 * (int)d), colsum_part_floats((int)Tk, (int)F)),
-                                 colsum_part_floats((int)NT, a.n_out));
-      if (cp) ALLOC_OR_FAIL(c, m.colpart, float*, cp * 4);
     }
   }
   c->acts_ready = true;

@@ -59,6 +59,7 @@ static void fill_gemm(const hydra_gemm_desc* d, GemmArgs& a) {
     a.pre[g] = d->pre ? d->pre[g] : nullptr;
     a.gate[g] = d->gate ? d->gate[g] : nullptr;
     a.resid[g] = d->resid ? d->resid[g] : nullptr;
+    a.rowsum[g] = d->rowsum ? d->rowsum[g] : nullptr;
   }
 }
 

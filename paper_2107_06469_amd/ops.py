@@ -17,7 +17,7 @@ EPI_NONE, EPI_RELU, EPI_GELU = 0, 1, 2
 class hydra_gemm_desc(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("dtype", "M", "N", "K", "x_kmajor", "w_kmajor", "ldx", "ldw", "ldo", "ldg", "ldr",
                                        "act", "out_f32", "tile", "G")] + \
-               [(n, C.POINTER(C.c_void_p)) for n in ("X", "W", "bias", "out", "pre", "gate", "resid")]
+               [(n, C.POINTER(C.c_void_p)) for n in ("X", "W", "bias", "out", "pre", "gate", "resid", "rowsum")]
 
 
 _ready = False
@@ -67,24 +67,24 @@ def _check(st: int):
 
 
 def hydra_op_gemm(dtype, M, N, K, X, W, out, *, x_kmajor, w_kmajor, ldx, ldw, ldo, bias=None, pre=None, gate=None,
-                  resid=None, ldg=0, ldr=0, act=EPI_NONE, out_f32=False, tile=0):
+                  resid=None, ldg=0, ldr=0, act=EPI_NONE, out_f32=False, tile=0, rowsum=None):
     d = hydra_gemm_desc()
     d.dtype, d.M, d.N, d.K, d.x_kmajor, d.w_kmajor = dtype, M, N, K, int(x_kmajor), int(w_kmajor)
     d.ldx, d.ldw, d.ldo, d.ldg, d.ldr, d.act, d.out_f32, d.tile, d.G = ldx, ldw, ldo, ldg, ldr, act, int(out_f32), tile, len(X)
-    tabs = [_tab(t) for t in (X, W, bias, out, pre, gate, resid)]
-    for name, t in zip(("X", "W", "bias", "out", "pre", "gate", "resid"), tabs):
+    tabs = [_tab(t) for t in (X, W, bias, out, pre, gate, resid, rowsum)]
+    for name, t in zip(("X", "W", "bias", "out", "pre", "gate", "resid", "rowsum"), tabs):
         if t is not None:
             setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
     _check(_L().hydra_op_gemm(C.byref(d), _stream()))
 
 
-def hydra_op_gemm_update(dtype, M, N, K, X, W, opt, p, m, v, w16, hp_rows, *, ldx, ldw, ldo, out=None, tile=0):
+def hydra_op_gemm_update(dtype, M, N, K, X, W, opt, p, m, v, w16, hp_rows, *, ldx, ldw, ldo, out=None, tile=0, rowsum=None):
     """Weight gradient dW[M,N] = sum_k X(k,m) W(k,n) with the optimizer step of hydra_op_optim in its epilogue."""
     d = hydra_gemm_desc()
     d.dtype, d.M, d.N, d.K, d.x_kmajor, d.w_kmajor = dtype, M, N, K, 0, 0
     d.ldx, d.ldw, d.ldo, d.ldg, d.ldr, d.act, d.out_f32, d.tile, d.G = ldx, ldw, ldo, 0, 0, EPI_NONE, 1, tile, len(X)
-    tabs = [_tab(t) for t in (X, W, out)]
-    for name, t in zip(("X", "W", "out"), tabs):
+    tabs = [_tab(t) for t in (X, W, out, rowsum)]
+    for name, t in zip(("X", "W", "out", "rowsum"), tabs):
         if t is not None:
             setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
     flat = (C.c_double * (6 * len(p)))(*[float(x) for row in hp_rows for x in row])
