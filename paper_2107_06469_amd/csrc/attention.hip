@@ -289,7 +289,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const AttnBwdArgs a) {
 
 // ---- backward, dk and dv -----------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const AttnBwdArgs a) {
+__global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(const AttnBwdArgs a) {
   constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
   extern __shared__ uint4 lds[];
   uint4* tQ = lds;                                              // [64][NCH]

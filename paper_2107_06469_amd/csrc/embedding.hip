@@ -33,18 +33,26 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const EmbedArgs a) {
   for (int c = threadIdx.x; c < a.d; c += 256) x[c] = from_f<T>(to_f<T>(tok[c]) + to_f<T>(pos[c]));
 }
 
-// one workgroup per vocabulary row
+// one workgroup per vocabulary row and 256 columns
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_tok_kernel(const EmbedBwdArgs a) {
-  const int g = blockIdx.y, v = blockIdx.x;
+  const int g = blockIdx.y, v = blockIdx.x, c = blockIdx.z * 256 + threadIdx.x;
+  if (c >= a.d) return;
   const int beg = a.row_ptr[v], end = a.row_ptr[v + 1];
-  const T* dx = static_cast<const T*>(a.dx[g]);
-  float* out = a.dtok[g] + (size_t)v * a.d;
-  for (int c = threadIdx.x; c < a.d; c += 256) {
-    float s = 0.f;
-    for (int i = beg; i < end; ++i) s += to_f<T>(dx[(size_t)a.positions[i] * a.ld + c]);
-    out[c] = s;
+  const T* dx = static_cast<const T*>(a.dx[g]) + c;
+  // A frequent id (the mask token holds 15 % of an encoder batch) makes this a long sequential sum: the
+  // loads of 16 occurrences are issued together, the additions keep the ascending order.
+  float s = 0.f;
+  int i = beg;
+  for (; i + 16 <= end; i += 16) {
+    float w[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) w[u] = to_f<T>(dx[(size_t)a.positions[i + u] * a.ld]);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) s += w[u];
   }
+  for (; i < end; ++i) s += to_f<T>(dx[(size_t)a.positions[i] * a.ld]);
+  a.dtok[g][(size_t)v * a.d + c] = s;
 }
 
 // one workgroup per row of the position table
@@ -116,10 +124,10 @@ hipError_t launch_embed_fwd(const EmbedArgs& a, hipStream_t s) {
 hipError_t launch_embed_bwd(const EmbedBwdArgs& a, hipStream_t s) {
   if (a.G < 1 || a.G > MAXG || a.V < 1 || a.S < 1 || a.B < 1 || a.S_table < a.S || a.ld < a.d) return hipErrorInvalidValue;
   if (a.dtype == GEMM_F32) {
-    hipLaunchKernelGGL(embed_bwd_tok_kernel<float>, dim3(a.V, a.G), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(embed_bwd_tok_kernel<float>, dim3(a.V, a.G, (a.d + 255) / 256), dim3(256), 0, s, a);
     hipLaunchKernelGGL(embed_bwd_pos_kernel<float>, dim3(a.S_table, a.G), dim3(256), 0, s, a);
   } else {
-    hipLaunchKernelGGL(embed_bwd_tok_kernel<bf16_t>, dim3(a.V, a.G), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(embed_bwd_tok_kernel<bf16_t>, dim3(a.V, a.G, (a.d + 255) / 256), dim3(256), 0, s, a);
     hipLaunchKernelGGL(embed_bwd_pos_kernel<bf16_t>, dim3(a.S_table, a.G), dim3(256), 0, s, a);
   }
   return hipGetLastError();
