@@ -13,8 +13,11 @@
 //   forward and dq:  S^T[j,i] = K Q^T  (lane = query i, rows = keys j)  ->  O^T[c,i] += Vt[c,j] P^T[j,i]
 //   dk/dv:           S[i,j]   = Q K^T  (lane = key j, rows = queries i) ->  dV^T[c,j] += dOt[c,i] P[i,j]
 // The A operand of the second contraction walks the tile along its slow index, so those tiles (V, K, Q,
-// dO) are also kept transposed in LDS (transposed in registers while loading), with an XOR swizzle of the
-// 8-byte chunk index against bank conflicts.  Softmax statistics of a query live in the two lanes l and
+// dO) are also kept transposed in LDS, with an XOR swizzle of the 8-byte chunk index against bank
+// conflicts.  They are filled from head-transposed copies [B*H*DH][S rounded up to 64] that a small
+// transpose kernel writes into the caller's work buffer before the attention kernel runs (one copy for
+// the forward pass, three for the backward pass): every tile load is then a plain 16-byte row copy by
+// all threads.  Softmax statistics of a query live in the two lanes l and
 // l^32 and are combined with one cross-lane exchange.  A wavefront owns 32 queries (or 32 keys) and loops
 // over tiles of 64 keys (queries) shared through LDS by the four wavefronts of the workgroup.  All sums run
 // in a fixed order; dq and dk/dv are separate kernels so that no atomics are needed.
@@ -30,6 +33,10 @@ namespace {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float NEG_BIG = -1.0e30f;
+
+// 2^x by the hardware instruction alone: arguments here are <= 0 up to rounding, results below the normal
+// range may flush to zero, which is what a softmax weight that small is worth.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
   __bf16 x = (__bf16)a, y = (__bf16)b;
@@ -58,32 +65,47 @@ __device__ __forceinline__ void load_rows(uint4* tile, const bf16_t* src, int ld
   }
 }
 
+// Fills a "transposed" tile from a head-transposed copy of the source: xt holds, for one (batch, head),
+// DH rows of S_ld values (row c = column c of the source over all sequence positions, zero beyond S), so
+// row c of the tile is the 128 contiguous bytes at xt + c*S_ld + row0.
 template <int DH>
-__device__ __forceinline__ void load_transposed(uint2* tile, const bf16_t* src, int ld, int row0, int nrows, int tid) {
-  constexpr int NCH = DH / 8;
-  if (tid < 8 * NCH) {
-    const int cb = tid % NCH, jb = tid / NCH;
-    uint32_t in[8][4];
+__device__ __forceinline__ void load_tr_rows(uint2* tile, const bf16_t* xt, int S_ld, int row0, int tid) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      const int row = row0 + 8 * jb + r;
-      if (row < nrows) v = *reinterpret_cast<const uint4*>(src + (size_t)row * ld + 8 * cb);
-      in[r][0] = v.x; in[r][1] = v.y; in[r][2] = v.z; in[r][3] = v.w;
-    }
+  for (int i = 0; i < DH * 8 / 256; ++i) {
+    const int u = tid + 256 * i, c = u >> 3, pc = u & 7;
+    const uint4 v = *reinterpret_cast<const uint4*>(xt + (size_t)c * S_ld + row0 + 8 * pc);
+    tile[c * 16 + ((2 * pc) ^ (c & 15))] = make_uint2(v.x, v.y);
+    tile[c * 16 + ((2 * pc + 1) ^ (c & 15))] = make_uint2(v.z, v.w);
+  }
+}
+
+// Head transpose: dst[(b*H + h)*DH + c][i] = src[b*S + i][col0 + h*DH + c] for i < S, zero for S <= i < S_ld.
+// One workgroup moves 64 sequence positions of one (batch, head) through LDS.
+struct HeadTrArgs {
+  int S, S_ld, H, DH, ld, col0, G;
+  const bf16_t* src[MAXG];
+  bf16_t* dst[MAXG];
+};
+__global__ __launch_bounds__(256) void head_transpose_kernel(const HeadTrArgs a) {
+  __shared__ bf16_t t[64][128 + 2];
+  const int tid = threadIdx.x, g = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H, i0 = blockIdx.x * 64;
+  const bf16_t* src = a.src[g] + (size_t)b * a.S * a.ld + a.col0 + h * a.DH;
+  const int nch = a.DH / 8;  // 16-byte chunks per source row
+  for (int u = tid; u < 64 * nch; u += 256) {
+    const int r = u / nch, kc = u % nch;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (i0 + r < a.S) v = *reinterpret_cast<const uint4*>(src + (size_t)(i0 + r) * a.ld + 8 * kc);
+    uint32_t* p = reinterpret_cast<uint32_t*>(&t[r][8 * kc]);
+    p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w;
+  }
+  __syncthreads();
+  bf16_t* dst = a.dst[g] + (size_t)bh * a.DH * a.S_ld + i0;
+  for (int u = tid; u < a.DH * 8; u += 256) {
+    const int c = u >> 3, pc = u & 7;
+    uint32_t w[4];
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      uint32_t o[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const uint32_t lo = (in[2 * q][m >> 1] >> (16 * (m & 1))) & 0xffffu;
-        const uint32_t hi = (in[2 * q + 1][m >> 1] >> (16 * (m & 1))) & 0xffffu;
-        o[q] = lo | (hi << 16);
-      }
-      const int c = 8 * cb + m;
-      tile[c * 16 + ((2 * jb) ^ (c & 15))] = make_uint2(o[0], o[1]);
-      tile[c * 16 + ((2 * jb + 1) ^ (c & 15))] = make_uint2(o[2], o[3]);
-    }
+    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)t[8 * pc + 2 * e][c] | ((uint32_t)t[8 * pc + 2 * e + 1][c] << 16);
+    *reinterpret_cast<uint4*>(dst + (size_t)c * a.S_ld + 8 * pc) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
 
@@ -118,6 +140,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const A
   const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
+  const int S_ld = (a.S + 63) / 64 * 64;
+  const bf16_t* vt = a.work[gi] + (size_t)bh * DH * S_ld;  // head-transposed v
   const int iq = blockIdx.x * 128 + wave * 32 + li;  // this lane's query
   uint4 qf[NK];
 #pragma unroll
@@ -138,7 +162,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const A
     const int j0 = t * 64;
     __syncthreads();
     load_rows<DH>(tK, base + d, a.ld_qkv, j0, a.S, tid);
-    load_transposed<DH>(tVt, base + 2 * d, a.ld_qkv, j0, a.S, tid);
+    load_tr_rows<DH>(tVt, vt, S_ld, j0, tid);
     __syncthreads();
     f32x16 s[2];
 #pragma unroll
@@ -148,26 +172,32 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const A
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) s[sub] = mfma(read_rows<DH>(tK, sub * 32 + li, 2 * kk + g), qf[kk], s[sub]);
     }
+    // Masking is needed only in tiles that reach past the sequence end or, with a causal mask, past the
+    // wave's first query; the scale is folded into the exponent's multiply-add.
+    const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blockIdx.x * 128 + wave * 32);
     float mx = NEG_BIG;
+    if (edge) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (j >= a.S || (a.causal && j > iq)) s[sub][r] = NEG_BIG;
+        }
+    }
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        float v = s[sub][r] * sc;
-        if (j >= a.S || (a.causal && j > iq)) v = NEG_BIG;
-        s[sub][r] = v;
-        mx = fmaxf(mx, v);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = exp2f(m_run - m_new);
+    const float m_new = fmaxf(m_run, mx * sc);
+    const float alpha = fast_exp2(m_run - m_new);
     float rs = 0.f;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[sub][r] - m_new);
+        const float p = fast_exp2(fmaf(s[sub][r], sc, -m_new));
         s[sub][r] = p;
         rs += p;
       }
@@ -214,6 +244,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(cons
   const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
+  const int S_ld = (a.S + 63) / 64 * 64;
+  const bf16_t* kt = a.work[gi] + (size_t)bh * DH * S_ld;  // head-transposed k
   const int iq = blockIdx.x * 128 + wave * 32 + li;
   uint4 qf[NK], dof[NK];
   float delta = 0.f;
@@ -246,8 +278,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(cons
     __syncthreads();
     load_rows<DH>(tK, base + d, a.ld_qkv, j0, a.S, tid);
     load_rows<DH>(tV, base + 2 * d, a.ld_qkv, j0, a.S, tid);
-    load_transposed<DH>(tKt, base + d, a.ld_qkv, j0, a.S, tid);
+    load_tr_rows<DH>(tKt, kt, S_ld, j0, tid);
     __syncthreads();
+    const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blockIdx.x * 128 + wave * 32);
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16 s, dp;
@@ -258,13 +291,15 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(cons
         s = mfma(read_rows<DH>(tK, sub * 32 + li, 2 * kk + g), qf[kk], s);
         dp = mfma(read_rows<DH>(tV, sub * 32 + li, 2 * kk + g), dof[kk], dp);
       }
+      if (edge) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        float p = exp2f(s[r] * sc - lse2);
-        if (j >= a.S || (a.causal && j > iq)) p = 0.f;
-        s[r] = p * (dp[r] - delta);
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (j >= a.S || (a.causal && j > iq)) s[r] = NEG_BIG;
+        }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = fast_exp2(fmaf(s[r], sc, -lse2)) * (dp[r] - delta);
 #pragma unroll
       for (int x = 0; x < 2; ++x) {
         const uint4 df = pack_half(s, x);
@@ -302,6 +337,10 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
   const bf16_t* dobase = a.dout[gi] + (size_t)b * a.S * a.ld_o + h * DH;
+  const int S_ld = (a.S + 63) / 64 * 64;
+  const size_t one = (size_t)a.B * a.H * DH * S_ld;  // elements of one head-transposed copy
+  const bf16_t* qt = a.work[gi] + one + (size_t)bh * DH * S_ld;       // head-transposed q
+  const bf16_t* dot = a.work[gi] + 2 * one + (size_t)bh * DH * S_ld;  // head-transposed dout
   const int jk = blockIdx.x * 128 + wave * 32 + li;  // this lane's key
   uint4 kf[NK], vf[NK];
 #pragma unroll
@@ -325,8 +364,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
     __syncthreads();
     load_rows<DH>(tQ, base, a.ld_qkv, i0, a.S, tid);
     load_rows<DH>(tdO, dobase, a.ld_o, i0, a.S, tid);
-    load_transposed<DH>(tQt, base, a.ld_qkv, i0, a.S, tid);
-    load_transposed<DH>(tdOt, dobase, a.ld_o, i0, a.S, tid);
+    load_tr_rows<DH>(tQt, qt, S_ld, i0, tid);
+    load_tr_rows<DH>(tdOt, dot, S_ld, i0, tid);
     if (tid < 128) {
       const int i = i0 + (tid & 63);
       float v = 0.f;
@@ -334,6 +373,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
       st[tid] = v;
     }
     __syncthreads();
+    // queries past the end, or (causal) queries that precede some key of this wave, need the mask
+    const bool edge = i0 + 64 > a.S || (a.causal && i0 < blockIdx.x * 128 + wave * 32 + 31);
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16 s, dp;
@@ -345,11 +386,17 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
         dp = mfma(read_rows<DH>(tdO, sub * 32 + li, 2 * kk + g), vf[kk], dp);
       }
       f32x16 ds;
+      if (edge) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = i0 + sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (i >= a.S || (a.causal && jk > i)) s[r] = NEG_BIG;
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int il = sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3), i = i0 + il;
-        float p = exp2f(s[r] * sc - st[il]);
-        if (i >= a.S || (a.causal && jk > i)) p = 0.f;
+        const int il = sub * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+        const float p = fast_exp2(fmaf(s[r], sc, -st[il]));
         s[r] = p;
         ds[r] = p * (dp[r] - st[64 + il]);
       }
@@ -400,8 +447,28 @@ hipError_t attn_init() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dq_lds<128>());
 }
 
+size_t attn_work_elems(int B, int S, int H, int DH, bool backward) {
+  return (size_t)(backward ? 3 : 1) * B * H * DH * ((S + 63) / 64 * 64);
+}
+
+// one head-transposed copy (columns [col0, col0 + H*DH) of src) per problem
+static void head_transpose(const void* const* src, int ld, int col0, bf16_t* const* work, size_t offset, int B, int S, int H,
+                           int DH, int G, hipStream_t s) {
+  HeadTrArgs t{};
+  t.S = S; t.S_ld = (S + 63) / 64 * 64; t.H = H; t.DH = DH; t.ld = ld; t.col0 = col0; t.G = G;
+  for (int g = 0; g < G; ++g) {
+    t.src[g] = static_cast<const bf16_t*>(src[g]);
+    t.dst[g] = work[g] + offset;
+  }
+  hipLaunchKernelGGL(head_transpose_kernel, dim3(t.S_ld / 64, B * H, G), dim3(256), 0, s, t);
+}
+
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
+  for (int g = 0; g < a.G; ++g)
+    if (!a.work[g] || ((uintptr_t)a.work[g] & 15)) return hipErrorInvalidValue;
+  const int d = a.H * a.DH;
+  head_transpose(reinterpret_cast<const void* const*>(a.qkv), a.ld_qkv, 2 * d, a.work, 0, a.B, a.S, a.H, a.DH, a.G, s);
   dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
   if (a.DH == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), fwd_lds<64>(), s, a);
   else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), fwd_lds<128>(), s, a);
@@ -410,6 +477,13 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bwd(const AttnBwdArgs& a, hipStream_t s) {
   if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
+  for (int g = 0; g < a.G; ++g)
+    if (!a.work[g] || ((uintptr_t)a.work[g] & 15)) return hipErrorInvalidValue;
+  const int d = a.H * a.DH;
+  const size_t one = attn_work_elems(a.B, a.S, a.H, a.DH, false);
+  head_transpose(reinterpret_cast<const void* const*>(a.qkv), a.ld_qkv, d, a.work, 0, a.B, a.S, a.H, a.DH, a.G, s);        // k
+  head_transpose(reinterpret_cast<const void* const*>(a.qkv), a.ld_qkv, 0, a.work, one, a.B, a.S, a.H, a.DH, a.G, s);      // q
+  head_transpose(reinterpret_cast<const void* const*>(a.dout), a.ld_o, 0, a.work, 2 * one, a.B, a.S, a.H, a.DH, a.G, s);   // dout
   dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
   if (a.DH == 64) {
     hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), dq_lds<64>(), s, a);

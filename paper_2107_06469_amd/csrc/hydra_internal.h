@@ -72,6 +72,7 @@ struct TrActs {
   void *dhm = nullptr, *dz1 = nullptr, *dzg = nullptr, *df = nullptr, *dx1 = nullptr, *dob = nullptr,
        *dqkv = nullptr, *da = nullptr;
   float *delta = nullptr, *lnpart = nullptr;
+  void* attn_work = nullptr;  // head-transposed copies for the attention kernels (three for the backward pass)
 };
 
 struct Model {

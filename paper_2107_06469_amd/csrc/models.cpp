@@ -309,6 +309,7 @@ hydra_status alloc_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, t.dqkv, void*, Tk * 3 * d * 2);
       ALLOC_OR_FAIL(c, t.da, void*, Tk * d * 2);
       ALLOC_OR_FAIL(c, t.delta, float*, bhs * 4);
+      ALLOC_OR_FAIL(c, t.attn_work, void*, attn_work_elems(c->B, c->S, a.n_heads, a.d_model / a.n_heads, true) * 2);
       ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)Tk) * 2 * d * 4);
     }
   }
