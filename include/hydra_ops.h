@@ -37,7 +37,9 @@ enum { HYDRA_EPI_NONE = 0, HYDRA_EPI_RELU = 1, HYDRA_EPI_GELU = 2 };
  * Leading dimensions count elements; ldx, ldw multiples of 16 bytes and >= the contiguous extent
  * rounded up to 16 bytes; ldo, ldg, ldr multiples of 8 and >= N.  bias is fp32 [N].  out is fp32
  * when out_f32, else the operand dtype; pre, gate, resid have the operand dtype.  Optional tables
- * may be NULL.  tile: 0 = automatic, 1 = 256x256, 2 = 128x128, 3 = 32x128 workgroup tiles. */
+ * may be NULL.  tile: 0 = automatic, 1 = 256x256, 2 = 128x128, 3 = 32x128 workgroup tiles, 4 = 256x256 with
+ * operands staged through registers (1 loads bf16 k-contiguous operands straight into LDS).  All give the
+ * same bits. */
 typedef struct {
   int dtype, M, N, K, x_kmajor, w_kmajor, ldx, ldw, ldo, ldg, ldr, act, out_f32, tile, G;
   const void* const* X;

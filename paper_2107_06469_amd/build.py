@@ -22,7 +22,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 # packed fp32 instructions are disabled for all device code
 FLAGS = ["--offload-arch=" + ARCH, "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-pass-failed", "-I", INCLUDE]
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-pass-failed", "-Wno-inline-asm", "-I", INCLUDE]
 
 
 def sources():

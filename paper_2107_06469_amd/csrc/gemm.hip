@@ -340,6 +340,125 @@ struct NoUpdate {};
 template <bool UPD> struct UpdSel { typedef NoUpdate type; };
 template <> struct UpdSel<true> { typedef GemmUpdate type; };
 
+// Orders a wave's own LDS writes before its own later LDS reads (and the reverse): a wave's LDS instructions
+// execute in order, so no hardware barrier is needed, only that the compiler keeps the order.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Epilogue of one wave: its FM x FN accumulators (rows mrow0.., columns ncol0.. of problem g) pass through the
+// wave's own LDS patch (32 x (FN*32+4) floats), one 32-row band at a time, and are read back row-wise so that a
+// lane owns 8 consecutive n of one m: global accesses are 16/32-byte vectors and a row band is written as FN*32
+// contiguous elements.  Only the wave itself touches its patch, so the waves of a workgroup run their epilogues
+// independently.
+template <typename T, int FM, int FN, bool UPD>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patch, const GemmArgs& a,
+                                              const typename UpdSel<UPD>::type& upd, int g, int mrow0, int ncol0, int lane) {
+  constexpr int SP = FN * 32 + 4;          // patch pitch in floats (+4: spreads rows over banks)
+  constexpr int LPR = FN * 4;              // lanes per row (8 elements each)
+  constexpr int RPP = 64 / LPR;            // rows per pass
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  const float* bias = a.bias[g];
+  T* pre = static_cast<T*>(a.pre[g]);
+  const T* gate = static_cast<const T*>(a.gate[g]);
+  const T* resid = static_cast<const T*>(a.resid[g]);
+  const T* mul = static_cast<const T*>(a.mul[g]);
+  const int act = a.act;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    wave_lds_sync();
+    for (int p = 0; p < 32 / RPP; ++p) {
+      const int r = p * RPP + lane / LPR, c = (lane % LPR) * 8;
+      const int m = mrow0 + i * 32 + r, n = ncol0 + c;
+      if (m >= a.M || n >= a.N) continue;
+      float v[8];
+      load8<float>(&patch[r * SP + c], v);
+      const int cnt = a.N - n;  // >= 8: full vector
+      if constexpr (UPD) {
+        const size_t idx = (size_t)m * a.ldo + n;
+        const OptimHp h = upd.hp[g];
+        float* up = upd.p[g] + idx;
+        float* ug = a.out[g] ? static_cast<float*>(a.out[g]) + idx : nullptr;
+        bf16_t* uw = upd.w16[g] ? upd.w16[g] + idx : nullptr;
+        // N is a multiple of 8 here (checked by the launcher): every lane holds a full vector
+        float pe[8], me[8], ve[8];
+        load8_stream(up, pe);
+        if (upd.opt == 1) {
+          load8_stream(upd.m[g] + idx, me);
+          load8_stream(upd.v[g] + idx, ve);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
+          store8<float>(upd.m[g] + idx, me);
+          store8<float>(upd.v[g] + idx, ve);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
+        }
+        store8<float>(up, pe);
+        if (uw) store8<bf16_t>(uw, pe);
+        if (ug) store8<float>(ug, v);
+      } else if (cnt >= 8) {
+        if (bias) {
+          float b[8];
+          load8<float>(bias + n, b);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += b[e];
+        }
+        if (pre) store8<T>(pre + (size_t)m * a.ldo + n, v);
+        if (gate) {
+          float z[8];
+          load8<T>(gate + (size_t)m * a.ldg + n, z);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= act_grad(z[e], act);
+        } else if (act != EPI_ACT_NONE) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = act_fwd(v[e], act);
+        }
+        if (mul) {
+          float z[8];
+          load8<T>(mul + (size_t)m * a.ldo + n, z);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= z[e];
+        }
+        if (resid) {
+          float z[8];
+          load8<T>(resid + (size_t)m * a.ldr + n, z);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += z[e];
+        }
+        if (a.out_f32) store8<float>(static_cast<float*>(a.out[g]) + (size_t)m * a.ldo + n, v);
+        else store8<T>(static_cast<T*>(a.out[g]) + (size_t)m * a.ldo + n, v);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (e < cnt) {
+            float t = v[e];
+            if (bias) t += bias[n + e];
+            if (pre) pre[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
+            if (gate) t *= act_grad(Elem<T>::to_f(gate[(size_t)m * a.ldg + n + e]), act);
+            else t = act_fwd(t, act);
+            if (mul) t *= Elem<T>::to_f(mul[(size_t)m * a.ldo + n + e]);
+            if (resid) t += Elem<T>::to_f(resid[(size_t)m * a.ldr + n + e]);
+            if (a.out_f32) static_cast<float*>(a.out[g])[(size_t)m * a.ldo + n + e] = t;
+            else static_cast<T*>(a.out[g])[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
+          }
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+}
+
+
+
 // UPD: the accumulators are weight gradients and the epilogue applies the parameter update to the
 // elements it holds instead of (or besides) storing them.
 template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF, bool X_KMAJ, bool W_KMAJ, bool UPD>
@@ -478,109 +597,201 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
   }
 
   // ---- epilogue -----------------------------------------------------------------------------------
-  // Each wave passes its accumulators through its own LDS patch, one 32-row band (32 x FN*32 fp32)
-  // at a time, and reads them back row-wise so that a lane owns 8 consecutive n of one m: global
-  // accesses are 16/32-byte vectors and a row band is written as FN*32 contiguous elements.
-  constexpr int SP = FN * 32 + 4;          // patch pitch in floats (+4: spreads rows over banks)
-  constexpr int LPR = FN * 4;              // lanes per row (8 elements each)
-  constexpr int RPP = 64 / LPR;            // rows per pass
+  // (the k-loop ended with a barrier: every wave is done with the operand tiles, whose LDS the patches reuse)
+  constexpr int SP = FN * 32 + 4;
   static_assert((size_t)WM * WN * 32 * SP * 4 <= 2 * (size_t)STAGE * 16, "epilogue patch exceeds LDS");
   float* patch = reinterpret_cast<float*>(lds) + wave * (32 * SP);
-  const float* bias = a.bias[g];
-  T* pre = static_cast<T*>(a.pre[g]);
-  const T* gate = static_cast<const T*>(a.gate[g]);
-  const T* resid = static_cast<const T*>(a.resid[g]);
-  const T* mul = static_cast<const T*>(a.mul[g]);
-  const int act = a.act;
+  tile_epilogue<T, FM, FN, UPD>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane);
+}
+
+// ---- bf16 forward layout (both operands k-contiguous): operand tiles go from memory straight into LDS ----------
+//
+// The k-loop advances in sub-tiles of 32 k (64-byte rows, four 16-byte chunks per row) through a ring of NS LDS
+// stages.  Every wave issues its share of a sub-tile as wave-wide buffer loads whose destination is LDS (lane l
+// of a load fills the 16-byte slot base + l), NS-1 sub-tiles ahead of the one being multiplied, so no operand
+// passes through registers on its way in and a load has NS-2 sub-tiles of MFMAs to arrive.  The chunk position
+// inside a row is XOR-ed with ((row>>2)&3)^(row&2): the lanes pick their global chunk accordingly (a row's four
+// lanes still cover its 64 contiguous bytes) and the 32-row fragment reads spread over all banks.
+// One barrier per sub-tile sits between its two MFMA steps: before it a wave has the step-1 fragments of the
+// current stage in registers and waits until all but its newest (NS-2) groups of loads have landed; after it the
+// step-0 fragments of the next stage are read while step 1 computes.  The sum over k is the same ascending chain of
+// 16-wide MFMA steps as in gemm_kernel, so both kernels give the same bits.
+__device__ __forceinline__ int swz4(int row) { return ((row >> 2) & 3) ^ (row & 2); }
+
+// 128-bit buffer descriptor (base, stride 0, size in bytes, raw dword format) for bytes [first, total) of a matrix;
+// reads beyond it return zero
+__device__ __forceinline__ u32x4 rsrc_words(const void* base, long first, long total) {
+  long rem = total - first;
+  rem = rem < 0 ? 0 : (rem > 0x7fffffffL ? 0x7fffffffL : rem);
+  const uint64_t p = (uint64_t)(uintptr_t)base + (uint64_t)(rem > 0 ? first : 0);
+  u32x4 r;
+  r.x = __builtin_amdgcn_readfirstlane((unsigned)p);
+  r.y = __builtin_amdgcn_readfirstlane((unsigned)(p >> 32) & 0xffffu);
+  r.z = __builtin_amdgcn_readfirstlane((unsigned)rem);
+  r.w = 0x00020000u;
+  return r;
+}
+// One wave-wide load of 16 bytes per lane from a buffer into LDS: lane l's bytes land at lds_addr + 16 l (lds_addr is
+// a byte address inside the workgroup's LDS, uniform over the wave).  The compiler does not see the LDS write:
+// callers order it against LDS reads with an explicit vmcnt wait and a barrier.
+__device__ __forceinline__ void load_to_lds_b128(u32x4 rs, unsigned lds_addr, unsigned voff) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rs) : "m0");
+}
+
+template <int WM, int WN, int FM, int FN, int NS>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a) {
+  typedef bf16_t T;
+  constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN, BK = 32;
+  constexpr int STAGE = (BM + BN) * 4;                             // 16-byte slots per stage
+  constexpr int NLX = BM * 4 / 64 / NW, NLW = BN * 4 / 64 / NW;    // loads per wave and sub-tile
+  constexpr int NL = NLX + NLW;
+  static_assert(BM * 4 % (64 * NW) == 0 && BN * 4 % (64 * NW) == 0, "tile rows must divide over the waves");
+  extern __shared__ uint4 lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+  const int n_tiles = tiles_m * tiles_n * a.G;
+  const int per_xcd = (n_tiles + 7) >> 3;
+  const int t_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (t_id >= n_tiles) return;
+  constexpr int GM = 8;  // tile order as in gemm_kernel: contiguous runs per XCD, bands of GM tile rows
+  const int g = t_id / (tiles_m * tiles_n), t_in = t_id % (tiles_m * tiles_n);
+  const int band = t_in / (GM * tiles_n), r_in = t_in % (GM * tiles_n);
+  const int band_rows = min(GM, tiles_m - band * GM);
+  const int tm = band * GM + r_in % band_rows, tn = r_in / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int K = a.K;
+
+  // descriptors start at the tile's first row and end with the matrix: rows past it read as zero
+  const u32x4 rx = rsrc_words(a.X[g], (long)m0 * a.ldx * 2, (long)a.M * a.ldx * 2);
+  const u32x4 rw = rsrc_words(a.W[g], (long)n0 * a.ldw * 2, (long)a.N * a.ldw * 2);
+  const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+  // load i of wave w fills slots [(i*NW + w)*64, +64) of the operand's tile; slot s = row*4 + chunk position
+  unsigned vx[NLX], vw[NLW];
+  int kcx[NLX], kcw[NLW];
 #pragma unroll
-  for (int i = 0; i < FM; ++i) {
+  for (int i = 0; i < NLX; ++i) {
+    const int s = (i * NW + wave) * 64 + lane, row = s >> 2;
+    kcx[i] = ((s & 3) ^ swz4(row)) * 8;
+    vx[i] = ((unsigned)row * (unsigned)a.ldx + (unsigned)kcx[i]) * 2u;
+  }
+#pragma unroll
+  for (int i = 0; i < NLW; ++i) {
+    const int s = (i * NW + wave) * 64 + lane, row = s >> 2;
+    kcw[i] = ((s & 3) ^ swz4(row)) * 8;
+    vw[i] = ((unsigned)row * (unsigned)a.ldw + (unsigned)kcw[i]) * 2u;
+  }
+  // nd-th load of sub-tile t (a chunk at or past K is sent out of range and lands as zeros; K % 8 == 0)
+  auto load_one = [&](int t, int nd) {
+    const unsigned st = lds_base + (unsigned)((t % NS) * STAGE * 16);
+    const int k0 = t * BK;
+    if (nd < NLX) {
+      const int i = nd < NLX ? nd : 0;
+      load_to_lds_b128(rx, st + (unsigned)((i * NW + wave) * 64 * 16), k0 + kcx[i] < K ? vx[i] + (unsigned)k0 * 2u : 0xfffffff0u);
+    } else {
+      const int i = nd >= NLX ? nd - NLX : 0;
+      load_to_lds_b128(rw, st + (unsigned)((BM * 4 + (i * NW + wave) * 64) * 16),
+                       k0 + kcw[i] < K ? vw[i] + (unsigned)k0 * 2u : 0xfffffff0u);
+    }
+  };
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
-            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-    __syncthreads();
-    for (int p = 0; p < 32 / RPP; ++p) {
-      const int r = p * RPP + lane / LPR, c = (lane % LPR) * 8;
-      const int m = m0 + (wm * FM + i) * 32 + r, n = n0 + wn * FN * 32 + c;
-      if (m >= a.M || n >= a.N) continue;
-      float v[8];
-      load8<float>(&patch[r * SP + c], v);
-      const int cnt = a.N - n;  // >= 8: full vector
-      if constexpr (UPD) {
-        const size_t idx = (size_t)m * a.ldo + n;
-        const OptimHp h = upd.hp[g];
-        float* up = upd.p[g] + idx;
-        float* ug = a.out[g] ? static_cast<float*>(a.out[g]) + idx : nullptr;
-        bf16_t* uw = upd.w16[g] ? upd.w16[g] + idx : nullptr;
-        // N is a multiple of 8 here (checked by the launcher): every lane holds a full vector
-        float pe[8], me[8], ve[8];
-        load8_stream(up, pe);
-        if (upd.opt == 1) {
-          load8_stream(upd.m[g] + idx, me);
-          load8_stream(upd.v[g] + idx, ve);
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const int nk = (K + BK - 1) / BK;
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  int ox[2][FM], ow[2][FN];  // fragment slots inside a stage for MFMA step 0 / 1
 #pragma unroll
-          for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
-          store8<float>(upd.m[g] + idx, me);
-          store8<float>(upd.v[g] + idx, ve);
-        } else {
+  for (int s = 0; s < 2; ++s) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
-        }
-        store8<float>(up, pe);
-        if (uw) store8<bf16_t>(uw, pe);
-        if (ug) store8<float>(ug, v);
-      } else if (cnt >= 8) {
-        if (bias) {
-          float b[8];
-          load8<float>(bias + n, b);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += b[e];
-        }
-        if (pre) store8<T>(pre + (size_t)m * a.ldo + n, v);
-        if (gate) {
-          float z[8];
-          load8<T>(gate + (size_t)m * a.ldg + n, z);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= act_grad(z[e], act);
-        } else if (act != EPI_ACT_NONE) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = act_fwd(v[e], act);
-        }
-        if (mul) {
-          float z[8];
-          load8<T>(mul + (size_t)m * a.ldo + n, z);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= z[e];
-        }
-        if (resid) {
-          float z[8];
-          load8<T>(resid + (size_t)m * a.ldr + n, z);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += z[e];
-        }
-        if (a.out_f32) store8<float>(static_cast<float*>(a.out[g]) + (size_t)m * a.ldo + n, v);
-        else store8<T>(static_cast<T*>(a.out[g]) + (size_t)m * a.ldo + n, v);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          if (e < cnt) {
-            float t = v[e];
-            if (bias) t += bias[n + e];
-            if (pre) pre[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
-            if (gate) t *= act_grad(Elem<T>::to_f(gate[(size_t)m * a.ldg + n + e]), act);
-            else t = act_fwd(t, act);
-            if (mul) t *= Elem<T>::to_f(mul[(size_t)m * a.ldo + n + e]);
-            if (resid) t += Elem<T>::to_f(resid[(size_t)m * a.ldr + n + e]);
-            if (a.out_f32) static_cast<float*>(a.out[g])[(size_t)m * a.ldo + n + e] = t;
-            else static_cast<T*>(a.out[g])[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
-          }
-        }
-      }
+    for (int i = 0; i < FM; ++i) {
+      const int row = (wm * FM + i) * 32 + lrow;
+      ox[s][i] = row * 4 + ((2 * s + lgrp) ^ swz4(row));
     }
-    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int row = (wn * FN + j) * 32 + lrow;
+      ow[s][j] = BM * 4 + row * 4 + ((2 * s + lgrp) ^ swz4(row));
+    }
   }
+  constexpr int ALLOW = (NS - 2) * NL;  // loads of this wave that may still be in flight when the next sub-tile must have landed
+  static_assert(ALLOW < 64, "vmcnt field");
+  constexpr int WAIT_VM = (ALLOW & 15) | ((ALLOW >> 4) << 14) | (7 << 4);  // s_waitcnt vmcnt(ALLOW) lgkmcnt(0)
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+#pragma unroll
+    for (int nd = 0; nd < NL; ++nd) load_one(t, nd);
+  __builtin_amdgcn_s_waitcnt(WAIT_VM | (15 << 8));
+  __builtin_amdgcn_s_barrier();
+  uint4 xa[FM], wa[FN], xb[FM], wb[FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) xa[i] = lds[ox[0][i]];
+#pragma unroll
+  for (int j = 0; j < FN; ++j) wa[j] = lds[ow[0][j]];
+  // One MFMA step on the fragments (xc, wc) while the fragments of the following step are read from stage sn into
+  // (xn, wn) and, with tl >= 0, the loads of sub-tile tl are issued; the order is pinned so that LDS reads and
+  // loads sit between the MFMAs that hide them.
+  auto step = [&](uint4(&xc)[FM], uint4(&wc)[FN], uint4(&xn)[FM], uint4(&wn_)[FN], const uint4* sn, int s, int tl) {
+    int nr = 0, nd = 0;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int q = i * FN + j;
+        if (tl >= 0 && nd < NL && nd * (FM * FN) <= q * NL) {
+          load_one(tl, nd);
+          ++nd;
+        }
+        if (nr < FM + FN) {
+          if (nr < FM) xn[nr] = sn[ox[s][nr]];
+          else wn_[nr - FM] = sn[ow[s][nr - FM]];
+          ++nr;
+        }
+        mma<T>(acc[i][j], wc[j], xc[i]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  };
+  for (int t = 0; t < nk; ++t) {
+    const uint4* st = lds + (t % NS) * STAGE;
+    const uint4* sn = lds + ((t + 1) % NS) * STAGE;
+    step(xa, wa, xb, wb, st, 1, t + NS - 1);
+    __builtin_amdgcn_s_waitcnt(WAIT_VM);
+    __builtin_amdgcn_s_barrier();
+    step(xb, wb, xa, wa, sn, 0, -1);
+  }
+  // the trailing (all-zero) loads must have landed and every wave must be done with the ring before patches reuse it
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  constexpr int SP = FN * 32 + 4;
+  static_assert((size_t)NW * 32 * SP * 4 <= (size_t)NS * STAGE * 16, "epilogue patch exceeds LDS");
+  float* patch = reinterpret_cast<float*>(lds) + wave * (32 * SP);
+  tile_epilogue<T, FM, FN, false>(acc, patch, a, NoUpdate(), g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane);
+}
+
+struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages of 32 KB
+  static constexpr int WM = 2, WN = 4, FM = 4, FN = 2, NS = 4;
+  static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NT = WM * WN * 64;
+  static constexpr size_t LDS = (size_t)NS * (BM + BN) * 4 * 16;
+  static hipError_t run(const GemmArgs& a, hipStream_t s) {
+    int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
+    int grid = ((tiles + 7) / 8) * 8;
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS>), dim3(grid), dim3(NT), LDS, s, a);
+    return hipGetLastError();
+  }
+  static hipError_t attr() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+  }
+};
+// the direct-to-LDS kernel takes bf16 problems whose operands are both k-contiguous with K a multiple of 8 (a 16-byte
+// chunk is then entirely inside or outside the matrix)
+inline bool dma_eligible(const GemmArgs& a) {
+  return a.dtype == GEMM_BF16 && a.x_kmajor && a.w_kmajor && a.K % 8 == 0 && !a.rowsum[0];
 }
 
 template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF>
@@ -660,8 +871,10 @@ hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s
 template <typename T>
 hipError_t dispatch(const GemmArgs& a, hipStream_t s) {
   const int tile = choose_tile(a);
+  if (tile == 1 && dma_eligible(a)) return DmaBig::run(a, s);
   switch (tile) {
-    case 1: return Tiles<T>::Big::run(a, s);
+    case 1:
+    case 4: return Tiles<T>::Big::run(a, s);
     case 2: return Tiles<T>::Mid::run(a, s);
     case 3: return Tiles<T>::Small::run(a, s);
   }
@@ -679,7 +892,9 @@ hipError_t init_tiles() {
 }  // namespace
 
 hipError_t gemm_init() {
-  hipError_t e = init_tiles<bf16_t>();
+  hipError_t e = DmaBig::attr();
+  if (e != hipSuccess) return e;
+  e = init_tiles<bf16_t>();
   return e != hipSuccess ? e : init_tiles<float>();
 }
 

@@ -46,7 +46,8 @@ struct GemmArgs {
   int ldo, ldg, ldr;
   int act;
   int out_f32;
-  int tile;  // 0 = choose by problem size; 1 = 256x256, 2 = 128x128, 3 = 32x128 (tests, tuning)
+  int tile;  // 0 = choose by problem size; 1 = 256x256, 2 = 128x128, 3 = 32x128, 4 = 256x256 with operands staged
+             // through registers even where the direct-to-LDS kernel applies (tests, tuning)
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 // Must be called once per process before the first launch_gemm (sets the kernels' LDS limits).

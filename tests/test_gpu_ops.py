@@ -58,7 +58,7 @@ SHAPES = [  # (M, N, K)
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 @pytest.mark.parametrize("layout", ["fwd", "dgrad", "wgrad"])
 def test_gemm_layouts_tiles_and_ragged_shapes(torch, ops, dtype, tile, layout):
     r = np.random.default_rng(100 * dtype + 10 * tile + len(layout))
@@ -147,7 +147,8 @@ def test_gemm_dgrad_epilogue_gate_and_residual(torch, ops, dtype, act):
 
 
 def test_gemm_result_is_independent_of_tile_and_group(torch, ops):
-    """Bitwise: the same problem alone, inside a group, and with every tile shape gives the same bits."""
+    """Bitwise: the same problem alone, inside a group, and with every tile shape gives the same bits (tile 1
+    loads the operands straight into LDS here, tile 4 is the same tile staged through registers)."""
     r = np.random.default_rng(5)
     M, N, K = 160, 264, 328
     xd, _ = _dev(torch, r.normal(size=(M, K)), 1)
@@ -155,7 +156,7 @@ def test_gemm_result_is_independent_of_tile_and_group(torch, ops):
     other_x, _ = _dev(torch, r.normal(size=(M, K)), 1)
     other_w, _ = _dev(torch, r.normal(size=(N, K)), 1)
     ref = None
-    for tile in (1, 2, 3):
+    for tile in (1, 2, 3, 4):
         for group in ([(xd, wd)], [(other_x, other_w), (xd, wd), (other_x, wd)]):
             outs = [torch.zeros((M, _ld(N)), dtype=torch.float32, device="cuda") for _ in group]
             ops.hydra_op_gemm(1, M, N, K, [g[0] for g in group], [g[1] for g in group], outs, x_kmajor=1, w_kmajor=1,
