@@ -604,18 +604,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
   tile_epilogue<T, FM, FN, UPD>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane);
 }
 
-// ---- bf16 forward layout (both operands k-contiguous): operand tiles go from memory straight into LDS ----------
+// ---- bf16: operand tiles go from memory straight into LDS ----------------------------------------------------
 //
-// The k-loop advances in sub-tiles of 32 k (64-byte rows, four 16-byte chunks per row) through a ring of NS LDS
-// stages.  Every wave issues its share of a sub-tile as wave-wide buffer loads whose destination is LDS (lane l
-// of a load fills the 16-byte slot base + l), NS-1 sub-tiles ahead of the one being multiplied, so no operand
-// passes through registers on its way in and a load has NS-2 sub-tiles of MFMAs to arrive.  The chunk position
-// inside a row is XOR-ed with ((row>>2)&3)^(row&2): the lanes pick their global chunk accordingly (a row's four
-// lanes still cover its 64 contiguous bytes) and the 32-row fragment reads spread over all banks.
+// The k-loop advances in sub-tiles of 32 k through a ring of NS LDS stages.  Every wave issues its share of a
+// sub-tile as wave-wide buffer loads whose destination is LDS (lane l of a load fills the 16-byte slot base + l),
+// NS-1 sub-tiles ahead of the one being multiplied, so no operand passes through registers on its way in and a
+// load has NS-2 sub-tiles of MFMAs to arrive.  A tile keeps the layout it has in memory:
+//  * k-contiguous operand: rows of 64 bytes (four 16-byte chunks); the chunk position inside a row is XOR-ed with
+//    ((row>>2)&3)^(row&2).  The lanes pick their global chunk accordingly (a row's four lanes still cover its 64
+//    contiguous bytes); a fragment is one 16-byte read per lane and 32-row fragment reads spread over all banks.
+//  * operand with k as the slow index: 32 k-rows of ROWS elements (ROWS/8 chunks); the chunk position inside a
+//    k-row is XOR-ed with (k&3)<<2.  A fragment is two transposing 8-byte LDS reads (ds_read_b64_tr_b16): within
+//    a group of 16 lanes, source lane j supplies four consecutive row elements of k-row j/4 at row offset 4(j%4),
+//    and lane i receives element i%4 of source lanes i/4, 4+i/4, 8+i/4, 12+i/4, i.e. four consecutive k for one
+//    row.  The XOR puts the four k-rows a half-wave reads into four different 64-byte bank groups.
 // One barrier per sub-tile sits between its two MFMA steps: before it a wave has the step-1 fragments of the
 // current stage in registers and waits until all but its newest (NS-2) groups of loads have landed; after it the
 // step-0 fragments of the next stage are read while step 1 computes.  The sum over k is the same ascending chain of
-// 16-wide MFMA steps as in gemm_kernel, so both kernels give the same bits.
+// 16-wide MFMA steps as in gemm_kernel, with the same k values in every lane, so both kernels give the same bits.
 __device__ __forceinline__ int swz4(int row) { return ((row >> 2) & 3) ^ (row & 2); }
 
 // 128-bit buffer descriptor (base, stride 0, size in bytes, raw dword format) for bytes [first, total) of a matrix;
@@ -638,14 +644,75 @@ __device__ __forceinline__ void load_to_lds_b128(u32x4 rs, unsigned lds_addr, un
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(rs) : "m0");
 }
 
-template <int WM, int WN, int FM, int FN, int NS>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a) {
+// One operand tile of ROWS rows in the ring: what a lane contributes to the direct loads of a sub-tile and where it
+// reads its MFMA fragments.  NW = waves of the workgroup; load i of wave w fills slots [(i*NW + w)*64, +64).
+template <bool KMAJ, int ROWS, int NW>
+struct RingOperand {
+  static constexpr int NLD = ROWS * 4 / 64 / NW;  // loads per wave and sub-tile (a sub-tile is ROWS*4 slots either way)
+  static_assert(ROWS * 4 % (64 * NW) == 0, "tile rows must divide over the waves");
+  u32x4 rs;
+  unsigned voff[NLD];   // byte offset of the lane's chunk in sub-tile 0, relative to the descriptor's base
+  int kofs[NLD];        // k (inside a sub-tile) of the lane's chunk: a chunk at or past K is loaded as zeros
+  unsigned step;        // bytes from one sub-tile to the next
+  // base/ld/row0/nrows: the matrix, its leading dimension, the tile's first row and the matrix's row count
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int K, int wave, int lane) {
+    if (KMAJ) {
+      rs = rsrc_words(base, (long)row0 * ld * 2, (long)nrows * ld * 2);  // rows past the matrix read as zero
+      step = 64u;
+    } else {
+      rs = rsrc_words(base, (long)row0 * 2, (long)K * ld * 2);           // k-rows past K read as zero
+      step = 64u * (unsigned)ld;
+    }
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int sl = (i * NW + wave) * 64 + lane;
+      if (KMAJ) {
+        const int row = sl >> 2;
+        kofs[i] = ((sl & 3) ^ swz4(row)) * 8;
+        voff[i] = ((unsigned)row * (unsigned)ld + (unsigned)kofs[i]) * 2u;
+      } else {
+        const int k = sl / (ROWS / 8), rc = (sl % (ROWS / 8)) ^ ((k & 3) << 2);
+        kofs[i] = k;
+        voff[i] = ((unsigned)k * (unsigned)ld + (unsigned)rc * 8u) * 2u;
+      }
+    }
+  }
+  // nd-th load of sub-tile t into the operand's part of a stage at LDS byte address st
+  __device__ __forceinline__ void issue(int nd, int t, unsigned st, int K, int wave) const {
+    const int i = nd < NLD ? nd : 0;
+    load_to_lds_b128(rs, st + (unsigned)((i * NW + wave) * 64 * 16), t * 32 + kofs[i] < K ? voff[i] + (unsigned)t * step : 0xfffffff0u);
+  }
+  // byte offset inside the operand's part of a stage of the lane's fragment of rows [rowbase, rowbase+32), MFMA step 0
+  // (k-contiguous: step 1 has its own offset because of the XOR; k-slow: step 1 is 16 k-rows further on)
+  static __device__ __forceinline__ int frag_offset(int rowbase, int lane, int mfma_step) {
+    if (KMAJ) {
+      const int row = rowbase + (lane & 31);
+      return (row * 4 + ((2 * mfma_step + (lane >> 5)) ^ swz4(row))) * 16;
+    }
+    const int j = lane & 15, grp = lane >> 4, k = 16 * mfma_step + 8 * (grp >> 1) + (j >> 2);
+    const int rc = rowbase / 8 + 2 * (grp & 1) + ((j & 3) >> 1);
+    return (k * (ROWS / 8) + (rc ^ ((k & 3) << 2))) * 16 + (j & 1) * 8;
+  }
+  static __device__ __forceinline__ uint4 read_frag(const char* stage_part, int off) {
+    if (KMAJ) return *reinterpret_cast<const uint4*>(stage_part + off);
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const unsigned a0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)(stage_part + off);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)a0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(a0 + 4u * (ROWS / 8) * 16u));  // k + 4
+    uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
+    return make_uint4(l.x, l.y, h.x, h.y);
+  }
+};
+
+template <int WM, int WN, int FM, int FN, int NS, bool X_KMAJ, bool W_KMAJ, bool UPD>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a, const typename UpdSel<UPD>::type upd) {
   typedef bf16_t T;
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN, BK = 32;
-  constexpr int STAGE = (BM + BN) * 4;                             // 16-byte slots per stage
-  constexpr int NLX = BM * 4 / 64 / NW, NLW = BN * 4 / 64 / NW;    // loads per wave and sub-tile
-  constexpr int NL = NLX + NLW;
-  static_assert(BM * 4 % (64 * NW) == 0 && BN * 4 % (64 * NW) == 0, "tile rows must divide over the waves");
+  constexpr int STAGE = (BM + BN) * 4 * 16;  // bytes per stage: X part, then W part
+  typedef RingOperand<X_KMAJ, BM, NW> RX;
+  typedef RingOperand<W_KMAJ, BN, NW> RW;
+  constexpr int NL = RX::NLD + RW::NLD;
   extern __shared__ uint4 lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
@@ -663,37 +730,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a)
   const int m0 = tm * BM, n0 = tn * BN;
   const int K = a.K;
 
-  // descriptors start at the tile's first row and end with the matrix: rows past it read as zero
-  const u32x4 rx = rsrc_words(a.X[g], (long)m0 * a.ldx * 2, (long)a.M * a.ldx * 2);
-  const u32x4 rw = rsrc_words(a.W[g], (long)n0 * a.ldw * 2, (long)a.N * a.ldw * 2);
+  RX ox_;
+  RW ow_;
+  ox_.init(static_cast<const T*>(a.X[g]), a.ldx, m0, a.M, K, wave, lane);
+  ow_.init(static_cast<const T*>(a.W[g]), a.ldw, n0, a.N, K, wave, lane);
+  const char* lds_c = reinterpret_cast<const char*>(lds);
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-  // load i of wave w fills slots [(i*NW + w)*64, +64) of the operand's tile; slot s = row*4 + chunk position
-  unsigned vx[NLX], vw[NLW];
-  int kcx[NLX], kcw[NLW];
-#pragma unroll
-  for (int i = 0; i < NLX; ++i) {
-    const int s = (i * NW + wave) * 64 + lane, row = s >> 2;
-    kcx[i] = ((s & 3) ^ swz4(row)) * 8;
-    vx[i] = ((unsigned)row * (unsigned)a.ldx + (unsigned)kcx[i]) * 2u;
-  }
-#pragma unroll
-  for (int i = 0; i < NLW; ++i) {
-    const int s = (i * NW + wave) * 64 + lane, row = s >> 2;
-    kcw[i] = ((s & 3) ^ swz4(row)) * 8;
-    vw[i] = ((unsigned)row * (unsigned)a.ldw + (unsigned)kcw[i]) * 2u;
-  }
-  // nd-th load of sub-tile t (a chunk at or past K is sent out of range and lands as zeros; K % 8 == 0)
-  auto load_one = [&](int t, int nd) {
-    const unsigned st = lds_base + (unsigned)((t % NS) * STAGE * 16);
-    const int k0 = t * BK;
-    if (nd < NLX) {
-      const int i = nd < NLX ? nd : 0;
-      load_to_lds_b128(rx, st + (unsigned)((i * NW + wave) * 64 * 16), k0 + kcx[i] < K ? vx[i] + (unsigned)k0 * 2u : 0xfffffff0u);
-    } else {
-      const int i = nd >= NLX ? nd - NLX : 0;
-      load_to_lds_b128(rw, st + (unsigned)((BM * 4 + (i * NW + wave) * 64) * 16),
-                       k0 + kcw[i] < K ? vw[i] + (unsigned)k0 * 2u : 0xfffffff0u);
-    }
+  auto load_one = [&](int t, int nd) {  // nd-th direct load of sub-tile t
+    const unsigned st = lds_base + (unsigned)((t % NS) * STAGE);
+    if (nd < RX::NLD) ox_.issue(nd, t, st, K, wave);
+    else ow_.issue(nd - RX::NLD, t, st + (unsigned)(BM * 4 * 16), K, wave);
   };
 
   f32x16 acc[FM][FN];
@@ -705,19 +751,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a)
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   const int nk = (K + BK - 1) / BK;
   const int lrow = lane & 31, lgrp = lane >> 5;
-  int ox[2][FM], ow[2][FN];  // fragment slots inside a stage for MFMA step 0 / 1
+  int fx[2][FM], fw[2][FN];  // fragment byte offsets inside a stage for MFMA step 0 / 1
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-      const int row = (wm * FM + i) * 32 + lrow;
-      ox[s][i] = row * 4 + ((2 * s + lgrp) ^ swz4(row));
-    }
+    for (int i = 0; i < FM; ++i) fx[s][i] = RX::frag_offset((wm * FM + i) * 32, lane, s);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int row = (wn * FN + j) * 32 + lrow;
-      ow[s][j] = BM * 4 + row * 4 + ((2 * s + lgrp) ^ swz4(row));
-    }
+    for (int j = 0; j < FN; ++j) fw[s][j] = BM * 4 * 16 + RW::frag_offset((wn * FN + j) * 32, lane, s);
   }
   constexpr int ALLOW = (NS - 2) * NL;  // loads of this wave that may still be in flight when the next sub-tile must have landed
   static_assert(ALLOW < 64, "vmcnt field");
@@ -730,13 +770,20 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a)
   __builtin_amdgcn_s_barrier();
   uint4 xa[FM], wa[FN], xb[FM], wb[FN];
 #pragma unroll
-  for (int i = 0; i < FM; ++i) xa[i] = lds[ox[0][i]];
+  for (int i = 0; i < FM; ++i) xa[i] = RX::read_frag(lds_c, fx[0][i]);
 #pragma unroll
-  for (int j = 0; j < FN; ++j) wa[j] = lds[ow[0][j]];
+  for (int j = 0; j < FN; ++j) wa[j] = RW::read_frag(lds_c, fw[0][j]);
+  // Row sums of the X operand (the bias gradient when X = dY), as in gemm_kernel: every lane adds up the chunks it
+  // feeds to the MFMAs, in ascending k
+  constexpr bool RS = !X_KMAJ && !W_KMAJ;
+  const bool do_rs = RS && a.rowsum[g] != nullptr && tn == 0;
+  float rs[FM];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) rs[i] = 0.f;
   // One MFMA step on the fragments (xc, wc) while the fragments of the following step are read from stage sn into
   // (xn, wn) and, with tl >= 0, the loads of sub-tile tl are issued; the order is pinned so that LDS reads and
   // loads sit between the MFMAs that hide them.
-  auto step = [&](uint4(&xc)[FM], uint4(&wc)[FN], uint4(&xn)[FM], uint4(&wn_)[FN], const uint4* sn, int s, int tl) {
+  auto step = [&](uint4(&xc)[FM], uint4(&wc)[FN], uint4(&xn)[FM], uint4(&wn_)[FN], const char* sn, int s, int tl) {
     int nr = 0, nd = 0;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -748,50 +795,84 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a)
           ++nd;
         }
         if (nr < FM + FN) {
-          if (nr < FM) xn[nr] = sn[ox[s][nr]];
-          else wn_[nr - FM] = sn[ow[s][nr - FM]];
+          if (nr < FM) xn[nr] = RX::read_frag(sn, fx[s][nr]);
+          else wn_[nr - FM] = RW::read_frag(sn, fw[s][nr - FM]);
           ++nr;
         }
         mma<T>(acc[i][j], wc[j], xc[i]);
+        if (RS && j == 0) rs[i] = chunk_sum<T>(xc[i], rs[i]);
         __builtin_amdgcn_sched_barrier(0);
       }
   };
   for (int t = 0; t < nk; ++t) {
-    const uint4* st = lds + (t % NS) * STAGE;
-    const uint4* sn = lds + ((t + 1) % NS) * STAGE;
+    const char* st = lds_c + (t % NS) * STAGE;
+    const char* sn = lds_c + ((t + 1) % NS) * STAGE;
     step(xa, wa, xb, wb, st, 1, t + NS - 1);
     __builtin_amdgcn_s_waitcnt(WAIT_VM);
     __builtin_amdgcn_s_barrier();
     step(xb, wb, xa, wa, sn, 0, -1);
   }
+  if (do_rs && wn == 0) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const float total = rs[i] + __shfl_xor(rs[i], 32, 64);  // even chunks + odd chunks
+      const int m = m0 + (wm * FM + i) * 32 + lrow;
+      if (lgrp == 0 && m < a.M) a.rowsum[g][m] = total;
+    }
+  }
   // the trailing (all-zero) loads must have landed and every wave must be done with the ring before patches reuse it
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   constexpr int SP = FN * 32 + 4;
-  static_assert((size_t)NW * 32 * SP * 4 <= (size_t)NS * STAGE * 16, "epilogue patch exceeds LDS");
+  static_assert((size_t)NW * 32 * SP * 4 <= (size_t)NS * STAGE, "epilogue patch exceeds LDS");
   float* patch = reinterpret_cast<float*>(lds) + wave * (32 * SP);
-  tile_epilogue<T, FM, FN, false>(acc, patch, a, NoUpdate(), g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane);
+  tile_epilogue<T, FM, FN, UPD>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane);
 }
 
 struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages of 32 KB
   static constexpr int WM = 2, WN = 4, FM = 4, FN = 2, NS = 4;
   static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NT = WM * WN * 64;
   static constexpr size_t LDS = (size_t)NS * (BM + BN) * 4 * 16;
-  static hipError_t run(const GemmArgs& a, hipStream_t s) {
+  static int grid_of(const GemmArgs& a) {
     int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
-    int grid = ((tiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS>), dim3(grid), dim3(NT), LDS, s, a);
+    return ((tiles + 7) / 8) * 8;
+  }
+  template <bool XK, bool WK>
+  static hipError_t run1(const GemmArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, false>), dim3(grid_of(a)), dim3(NT), LDS, s, a, NoUpdate());
     return hipGetLastError();
   }
-  static hipError_t attr() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS>),
+  static hipError_t run(const GemmArgs& a, hipStream_t s) {
+    if (a.x_kmajor) return a.w_kmajor ? run1<true, true>(a, s) : run1<true, false>(a, s);
+    return a.w_kmajor ? run1<false, true>(a, s) : run1<false, false>(a, s);
+  }
+  static hipError_t run_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, false, false, true>), dim3(grid_of(a)), dim3(NT), LDS, s, a, u);
+    return hipGetLastError();
+  }
+  template <bool XK, bool WK, bool UPD>
+  static hipError_t attr1() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, UPD>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   }
+  static hipError_t attr() {
+    hipError_t e;
+    if ((e = attr1<true, true, false>()) != hipSuccess) return e;
+    if ((e = attr1<true, false, false>()) != hipSuccess) return e;
+    if ((e = attr1<false, true, false>()) != hipSuccess) return e;
+    if ((e = attr1<false, false, false>()) != hipSuccess) return e;
+    return attr1<false, false, true>();
+  }
 };
-// the direct-to-LDS kernel takes bf16 problems whose operands are both k-contiguous with K a multiple of 8 (a 16-byte
-// chunk is then entirely inside or outside the matrix)
+// The direct-to-LDS kernel takes bf16 problems.  A k-contiguous operand needs K to be a multiple of 8 (a 16-byte
+// chunk is then entirely inside or outside the matrix); an operand with k as the slow index is addressed from the
+// tile's first element with 32-bit offsets, so its K x ld bytes must stay below 2 GiB.
 inline bool dma_eligible(const GemmArgs& a) {
-  return a.dtype == GEMM_BF16 && a.x_kmajor && a.w_kmajor && a.K % 8 == 0 && !a.rowsum[0];
+  if (a.dtype != GEMM_BF16) return false;
+  if ((a.x_kmajor || a.w_kmajor) && a.K % 8 != 0) return false;
+  if (!a.x_kmajor && (long)a.K * a.ldx * 2 >= 0x7fffffffL) return false;
+  if (!a.w_kmajor && (long)a.K * a.ldw * 2 >= 0x7fffffffL) return false;
+  return true;
 }
 
 template <typename T, int WM, int WN, int FM, int FN, int PFX, int PF>
@@ -860,8 +941,10 @@ hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s
   // With a short k-loop the state traffic of the epilogue dominates: with two workgroups per CU one streams
   // state while the other runs its k-loop, which the 256x256 tile (one workgroup per CU) cannot do.
   if (!a.tile && tile == 1 && a.K < 2048) tile = 2;
+  if (tile == 1 && dma_eligible(a)) return DmaBig::run_update(a, u, s);
   switch (tile) {
-    case 1: return Tiles<T>::Big::run_update(a, u, s);
+    case 1:
+    case 4: return Tiles<T>::Big::run_update(a, u, s);
     case 2: return Tiles<T>::Mid::run_update(a, u, s);
     case 3: return Tiles<T>::Small::run_update(a, u, s);
   }

@@ -146,26 +146,30 @@ def test_gemm_dgrad_epilogue_gate_and_residual(torch, ops, dtype, act):
         _check(outs[g][:, :N].double().cpu().numpy(), wants[g], bounds[g], dtype == 1, "dgrad epilogue")
 
 
-def test_gemm_result_is_independent_of_tile_and_group(torch, ops):
+@pytest.mark.parametrize("layout", ["fwd", "dgrad", "wgrad"])
+def test_gemm_result_is_independent_of_tile_and_group(torch, ops, layout):
     """Bitwise: the same problem alone, inside a group, and with every tile shape gives the same bits (tile 1
-    loads the operands straight into LDS here, tile 4 is the same tile staged through registers)."""
+    loads bf16 operands straight into LDS, tile 4 is the same tile staged through registers)."""
     r = np.random.default_rng(5)
     M, N, K = 160, 264, 328
-    xd, _ = _dev(torch, r.normal(size=(M, K)), 1)
-    wd, _ = _dev(torch, r.normal(size=(N, K)), 1)
-    other_x, _ = _dev(torch, r.normal(size=(M, K)), 1)
-    other_w, _ = _dev(torch, r.normal(size=(N, K)), 1)
+    xk, wk = layout != "wgrad", layout == "fwd"
+
+    def operands():
+        x, w = r.normal(size=(M, K)), r.normal(size=(N, K))
+        return _dev(torch, x if xk else x.T.copy(), 1)[0], _dev(torch, w if wk else w.T.copy(), 1)[0]
+    xd, wd = operands()
+    other_x, other_w = operands()
     ref = None
     for tile in (1, 2, 3, 4):
         for group in ([(xd, wd)], [(other_x, other_w), (xd, wd), (other_x, wd)]):
             outs = [torch.zeros((M, _ld(N)), dtype=torch.float32, device="cuda") for _ in group]
-            ops.hydra_op_gemm(1, M, N, K, [g[0] for g in group], [g[1] for g in group], outs, x_kmajor=1, w_kmajor=1,
-                              ldx=xd.shape[1], ldw=wd.shape[1], ldo=_ld(N), out_f32=True, tile=tile)
+            ops.hydra_op_gemm(1, M, N, K, [g[0] for g in group], [g[1] for g in group], outs, x_kmajor=int(xk),
+                              w_kmajor=int(wk), ldx=xd.shape[1], ldw=wd.shape[1], ldo=_ld(N), out_f32=True, tile=tile)
             torch.cuda.synchronize()
             mine = outs[[i for i, g in enumerate(group) if g[0] is xd and g[1] is wd][0]].cpu().numpy()
             if ref is None:
                 ref = mine
-            assert np.array_equal(ref, mine), f"tile {tile}, group of {len(group)}"
+            assert np.array_equal(ref, mine), f"{layout}: tile {tile}, group of {len(group)}"
 
 
 def test_gemm_rejects_bad_arguments(torch, ops):
