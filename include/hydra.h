@@ -87,6 +87,14 @@ typedef struct {
                                   is then refused); 1: every gradient is stored and the update task
                                   applies all of them.  Both give the same parameters bit for bit.
                                   Spilled state always keeps gradients                               */
+  size_t activation_budget_bytes; /* 0 = every activation a backward pass needs is kept from the forward
+                                  pass.  Otherwise an upper bound on the device bytes of per-block
+                                  activations and backward scratch (Transformer models): when keeping
+                                  everything would exceed it, a forward task keeps only the shard's
+                                  input and output, the per-block buffers come from a pool of shard-sized
+                                  workspaces that fit the bound, and a backward task first runs the
+                                  shard's forward again.  The arithmetic, and hence every bit of the
+                                  result, is unchanged.  With a bound set, shard before hydra_set_data  */
 } hydra_options;
 
 typedef struct {

@@ -64,6 +64,22 @@ struct Ctx {
   }
   const Model& model(int i) const { return c->models[b.members[i].first]; }
   const Shard& shard(int i) const { return model(i).shards[b.members[i].second]; }
+  // Where member i keeps the activations of its shard.  Normally everything is the model's own; in recomputation
+  // mode only the shard's input and output (and their gradients) are, and the rest is the workspace of
+  // (stream, position in the group).
+  const TrWorkspace* wsp(int i) const { return c->recompute ? &c->ws[(size_t)b.stream * c->ws_group + i] : nullptr; }
+  void* xin(int i, int r) const {   // input of the shard's r-th block; r = number of blocks: the shard's output
+    const Shard& sh = shard(i);
+    if (!c->recompute || r == 0 || r == sh.u1 - sh.u0) return model(i).tr.x[sh.u0 + r];
+    return wsp(i)->xi[r];
+  }
+  void* dxin(int i, int r) const {
+    const Shard& sh = shard(i);
+    if (!c->recompute || r == 0 || r == sh.u1 - sh.u0) return model(i).tr.dx[sh.u0 + r];
+    return wsp(i)->dxi[r];
+  }
+  const TrBlockActs& blk(int i, int r) const { return c->recompute ? wsp(i)->blk[r] : model(i).tr.blk[shard(i).u0 + r]; }
+  const TrActs& scratch(int i) const { return c->recompute ? wsp(i)->sc : model(i).tr; }
   // pointers into the shard's state blocks for tensor j of member i
   const bf16_t* w16(int i, int j) const { return shard(i).w16 + (model(i).tensors[j].off - shard(i).off); }
   // fp32 vector tensors (biases, LayerNorm gains): the resident copy when the state is spilled
@@ -87,17 +103,17 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     EmbedArgs e{};
     e.dtype = GEMM_BF16; e.tokens = Tk; e.S = c->S; e.d = d; e.ld = d; e.G = x.G;
     e.ids = c->ids + (size_t)batch * Tk;
-    FOR_G { e.tok[i] = x.w16(i, 0); e.pos[i] = x.w16(i, 1); e.x[i] = x.model(i).tr.x[0]; }
+    FOR_G { e.tok[i] = x.w16(i, 0); e.pos[i] = x.w16(i, 1); e.x[i] = x.xin(i, 0); }
     HYDRA_LAUNCH(c, HYDRA_K_EMBED, x.s, 0.0, (double)x.G * Tk * d * 2 * 3, launch_embed_fwd(e, x.s));
   }
   for (int r = 0; r < n_units; ++r) {
     auto L = [&](int i) { return x.shard(i).u0 + r; };
-    auto A = [&](int i) -> const TrBlockActs& { return x.model(i).tr.blk[L(i)]; };
+    auto A = [&](int i) -> const TrBlockActs& { return x.blk(i, r); };
     // a = LN1(x)
     LnArgs ln{};
     ln.dtype = GEMM_BF16; ln.rows = Tk; ln.d = d; ln.ld = d; ln.G = x.G; ln.eps = 1e-5f;
     FOR_G {
-      ln.x[i] = x.model(i).tr.x[L(i)]; ln.y[i] = A(i).a; ln.gamma[i] = x.p32(i, x.ix.ln1g(L(i)));
+      ln.x[i] = x.xin(i, r); ln.y[i] = A(i).a; ln.gamma[i] = x.p32(i, x.ix.ln1g(L(i)));
       ln.beta[i] = x.p32(i, x.ix.ln1b(L(i))); ln.mean[i] = A(i).mu1; ln.rstd[i] = A(i).rs1;
     }
     HYDRA_LAUNCH(c, HYDRA_K_LAYERNORM, x.s, 0.0, (double)x.G * Tk * d * 4, launch_ln_fwd(ln, x.s));
@@ -112,7 +128,7 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     at.scale = (float)(1.0 / std::sqrt((double)x.DH));
     FOR_G {
       at.qkv[i] = static_cast<const bf16_t*>(A(i).qkv); at.o[i] = static_cast<bf16_t*>(A(i).o); at.lse[i] = A(i).lse;
-      at.work[i] = static_cast<bf16_t*>(x.model(i).tr.attn_work);
+      at.work[i] = static_cast<bf16_t*>(x.scratch(i).attn_work);
     }
     const double att_fl = 4.0 * c->B * x.H * (double)c->S * c->S * x.DH * (x.a.causal ? 0.5 : 1.0) * x.G;
     HYDRA_LAUNCH(c, HYDRA_K_ATTENTION, x.s, att_fl, 0.0, launch_attn_fwd(at, x.s));
@@ -121,7 +137,7 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     o.dtype = GEMM_BF16; o.M = Tk; o.N = d; o.K = d; o.x_kmajor = o.w_kmajor = 1; o.ldx = d; o.ldw = d; o.ldo = d; o.ldr = d; o.G = x.G;
     FOR_G {
       o.X[i] = A(i).o; o.W[i] = x.w16(i, x.ix.wo(L(i))); o.bias[i] = x.p32(i, x.ix.bo(L(i)));
-      o.resid[i] = x.model(i).tr.x[L(i)]; o.out[i] = A(i).x1;
+      o.resid[i] = x.xin(i, r); o.out[i] = A(i).x1;
     }
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, x.s, 2.0 * o.M * o.N * o.K * x.G, 0.0, launch_gemm(o, x.s));
     // f = LN2(x1)
@@ -156,7 +172,7 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     f2.dtype = GEMM_BF16; f2.M = Tk; f2.N = d; f2.K = F; f2.x_kmajor = f2.w_kmajor = 1; f2.ldx = F; f2.ldw = F; f2.ldo = d; f2.ldr = d; f2.G = x.G;
     FOR_G {
       f2.X[i] = A(i).hmid; f2.W[i] = x.w16(i, x.ix.w2(L(i))); f2.bias[i] = x.p32(i, x.ix.b2(L(i)));
-      f2.resid[i] = A(i).x1; f2.out[i] = x.model(i).tr.x[L(i) + 1];
+      f2.resid[i] = A(i).x1; f2.out[i] = x.xin(i, r + 1);
     }
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, x.s, 2.0 * f2.M * f2.N * f2.K * x.G, 0.0, launch_gemm(f2, x.s));
   }
@@ -166,21 +182,23 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     ln.dtype = GEMM_BF16; ln.rows = Tk; ln.d = d; ln.ld = d; ln.G = x.G; ln.eps = 1e-5f;
     FOR_G {
       const Model& m = x.model(i);
-      ln.x[i] = m.tr.x[m.arch.n_layers]; ln.y[i] = m.tr.xf; ln.gamma[i] = x.p32(i, Idx(m.arch).lnfg());
-      ln.beta[i] = x.p32(i, Idx(m.arch).lnfb()); ln.mean[i] = m.tr.muf; ln.rstd[i] = m.tr.rsf;
+      const TrActs& sc = x.scratch(i);
+      ln.x[i] = x.xin(i, n_units); ln.y[i] = sc.xf; ln.gamma[i] = x.p32(i, Idx(m.arch).lnfg());
+      ln.beta[i] = x.p32(i, Idx(m.arch).lnfb()); ln.mean[i] = sc.muf; ln.rstd[i] = sc.rsf;
     }
     HYDRA_LAUNCH(c, HYDRA_K_LAYERNORM, x.s, 0.0, (double)x.G * Tk * d * 4, launch_ln_fwd(ln, x.s));
     RowsArgs ga{};
     ga.dtype = GEMM_BF16; ga.n = NT; ga.d = d; ga.ld_src = d; ga.ld_dst = d; ga.G = x.G;
     ga.rows = c->tgt_pos + (size_t)batch * NT;
-    FOR_G { ga.src[i] = x.model(i).tr.xf; ga.dst[i] = x.model(i).tr.xt; }
+    FOR_G { ga.src[i] = x.scratch(i).xf; ga.dst[i] = x.scratch(i).xt; }
     HYDRA_LAUNCH(c, HYDRA_K_ELEMENTWISE, x.s, 0.0, (double)x.G * NT * d * 4, launch_gather_rows(ga, x.s));
     GemmArgs hd{};
     hd.dtype = GEMM_BF16; hd.M = NT; hd.N = V; hd.K = d; hd.x_kmajor = hd.w_kmajor = 1; hd.ldx = d; hd.ldw = d; hd.ldo = x.ldv;
     hd.out_f32 = 1; hd.G = x.G;
     FOR_G {
       const Model& m = x.model(i);
-      hd.X[i] = m.tr.xt; hd.W[i] = x.w16(i, Idx(m.arch).whead()); hd.bias[i] = x.p32(i, Idx(m.arch).bhead()); hd.out[i] = m.tr.logits;
+      hd.X[i] = x.scratch(i).xt; hd.W[i] = x.w16(i, Idx(m.arch).whead()); hd.bias[i] = x.p32(i, Idx(m.arch).bhead());
+      hd.out[i] = x.scratch(i).logits;
     }
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, x.s, 2.0 * hd.M * hd.N * hd.K * x.G, 0.0, launch_gemm(hd, x.s));
     SoftmaxCeArgs ce{};
@@ -188,7 +206,8 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     ce.labels = c->targets + (size_t)batch * NT;
     FOR_G {
       const Model& m = x.model(i);
-      ce.logits[i] = m.tr.logits; ce.dz[i] = m.tr.dlogits; ce.rowloss[i] = m.tr.rowloss; ce.loss_out[i] = m.loss_dev + step;
+      const TrActs& sc = x.scratch(i);
+      ce.logits[i] = sc.logits; ce.dz[i] = sc.dlogits; ce.rowloss[i] = sc.rowloss; ce.loss_out[i] = m.loss_dev + step;
     }
     ++c->launches;
     HYDRA_LAUNCH(c, HYDRA_K_SOFTMAX_CE, x.s, 0.0, (double)x.G * NT * V * 10, launch_softmax_ce(ce, x.s));
@@ -267,26 +286,28 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
     FOR_G {
       const Model& m = x.model(i);
       Idx ix(m.arch);
-      pa[i] = m.tr.dlogits; pb[i] = m.tr.xt; jw[i] = ix.whead(); pbias[i] = x.g32(i, ix.bhead());
-      pc[i] = x.w16(i, ix.whead()); po[i] = m.tr.dxt;
+      const TrActs& sc = x.scratch(i);
+      pa[i] = sc.dlogits; pb[i] = sc.xt; jw[i] = ix.whead(); pbias[i] = x.g32(i, ix.bhead());
+      pc[i] = x.w16(i, ix.whead()); po[i] = sc.dxt;
     }
     TRY(dgrad(x, NT, V, d, x.ldv, pa, pc, po, nullptr, nullptr));
     TRY(wgrad(x, step, NT, V, d, x.ldv, d, pa, pb, jw, pbias));
     // scatter the target rows into a zero [Tk, d] gradient of the final LayerNorm's output
     FOR_G HYDRA_LAUNCH(c, HYDRA_K_ELEMENTWISE, x.s, 0.0, (double)Tk * d * 2,
-                       launch_fill_u32(static_cast<uint32_t*>(x.model(i).tr.dxf), (size_t)Tk * d / 2, 0u, x.s));
+                       launch_fill_u32(static_cast<uint32_t*>(x.scratch(i).dxf), (size_t)Tk * d / 2, 0u, x.s));
     RowsArgs sc{};
     sc.dtype = GEMM_BF16; sc.n = NT; sc.d = d; sc.ld_src = d; sc.ld_dst = d; sc.G = G;
     sc.rows = c->tgt_pos + (size_t)batch * NT;
-    FOR_G { sc.src[i] = x.model(i).tr.dxt; sc.dst[i] = x.model(i).tr.dxf; }
+    FOR_G { sc.src[i] = x.scratch(i).dxt; sc.dst[i] = x.scratch(i).dxf; }
     HYDRA_LAUNCH(c, HYDRA_K_ELEMENTWISE, x.s, 0.0, (double)G * NT * d * 4, launch_scatter_rows(sc, x.s));
     LnBwdArgs lb{};
     lb.dtype = GEMM_BF16; lb.rows = Tk; lb.d = d; lb.ld = d; lb.G = G;
     FOR_G {
       const Model& m = x.model(i);
       Idx ix(m.arch);
-      lb.x[i] = m.tr.x[m.arch.n_layers]; lb.dy[i] = m.tr.dxf; lb.add[i] = nullptr; lb.dx[i] = m.tr.dx[m.arch.n_layers];
-      lb.gamma[i] = x.p32(i, ix.lnfg()); lb.mean[i] = m.tr.muf; lb.rstd[i] = m.tr.rsf; lb.part[i] = m.tr.lnpart;
+      const TrActs& ws = x.scratch(i);
+      lb.x[i] = x.xin(i, n_units); lb.dy[i] = ws.dxf; lb.add[i] = nullptr; lb.dx[i] = x.dxin(i, n_units);
+      lb.gamma[i] = x.p32(i, ix.lnfg()); lb.mean[i] = ws.muf; lb.rstd[i] = ws.rsf; lb.part[i] = ws.lnpart;
       lb.dgamma[i] = x.g32(i, ix.lnfg()); lb.dbeta[i] = x.g32(i, ix.lnfb());
     }
     ++c->launches;
@@ -294,11 +315,11 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
   }
   for (int r = n_units - 1; r >= 0; --r) {
     auto L = [&](int i) { return x.shard(i).u0 + r; };
-    auto A = [&](int i) -> const TrBlockActs& { return x.model(i).tr.blk[L(i)]; };
-    auto T = [&](int i) -> const TrActs& { return x.model(i).tr; };
+    auto A = [&](int i) -> const TrBlockActs& { return x.blk(i, r); };
+    auto T = [&](int i) -> const TrActs& { return x.scratch(i); };
     // FFN2: dW2 = dx2^T hmid, db2; dh = dx2 W2 (gated by GeLU'(z1) when the block is not gated)
     FOR_G {
-      pa[i] = T(i).dx[L(i) + 1]; pb[i] = A(i).hmid; jw[i] = x.ix.w2(L(i)); pbias[i] = x.g32(i, x.ix.b2(L(i)));
+      pa[i] = x.dxin(i, r + 1); pb[i] = A(i).hmid; jw[i] = x.ix.w2(L(i)); pbias[i] = x.g32(i, x.ix.b2(L(i)));
       pc[i] = x.w16(i, x.ix.w2(L(i))); pd[i] = A(i).z1;
       po[i] = x.a.ffn_gated ? T(i).dhm : T(i).dz1;
     }
@@ -329,7 +350,7 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
     LnBwdArgs lb{};
     lb.dtype = GEMM_BF16; lb.rows = Tk; lb.d = d; lb.ld = d; lb.G = G;
     FOR_G {
-      lb.x[i] = A(i).x1; lb.dy[i] = T(i).df; lb.add[i] = T(i).dx[L(i) + 1]; lb.dx[i] = T(i).dx1;
+      lb.x[i] = A(i).x1; lb.dy[i] = T(i).df; lb.add[i] = x.dxin(i, r + 1); lb.dx[i] = T(i).dx1;
       lb.gamma[i] = x.p32(i, x.ix.ln2g(L(i))); lb.mean[i] = A(i).mu2; lb.rstd[i] = A(i).rs2; lb.part[i] = T(i).lnpart;
       lb.dgamma[i] = x.g32(i, x.ix.ln2g(L(i))); lb.dbeta[i] = x.g32(i, x.ix.ln2b(L(i)));
     }
@@ -363,7 +384,7 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
     TRY(wgrad(x, step, Tk, 3 * d, d, 3 * d, d, pa, pb, jw, pbias));
     // LN1: dx = LN1'(da) + dx1
     FOR_G {
-      lb.x[i] = T(i).x[L(i)]; lb.dy[i] = T(i).da; lb.add[i] = T(i).dx1; lb.dx[i] = T(i).dx[L(i)];
+      lb.x[i] = x.xin(i, r); lb.dy[i] = T(i).da; lb.add[i] = T(i).dx1; lb.dx[i] = x.dxin(i, r);
       lb.gamma[i] = x.p32(i, x.ix.ln1g(L(i))); lb.mean[i] = A(i).mu1; lb.rstd[i] = A(i).rs1;
       lb.dgamma[i] = x.g32(i, x.ix.ln1g(L(i))); lb.dbeta[i] = x.g32(i, x.ix.ln1b(L(i)));
     }
@@ -375,7 +396,7 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
     e.dtype = GEMM_BF16; e.V = x.V; e.S = c->S; e.S_table = x.a.max_seq; e.B = c->B; e.d = d; e.ld = d; e.G = G;
     e.row_ptr = c->csr_ptr + (size_t)batch * (x.V + 1);
     e.positions = c->csr_pos + (size_t)batch * Tk;
-    FOR_G { e.dx[i] = x.model(i).tr.dx[0]; e.dtok[i] = x.g32(i, 0); e.dpos[i] = x.g32(i, 1); }
+    FOR_G { e.dx[i] = x.dxin(i, 0); e.dtok[i] = x.g32(i, 0); e.dpos[i] = x.g32(i, 1); }
     ++c->launches;
     HYDRA_LAUNCH(c, HYDRA_K_EMBED, x.s, 0.0, (double)G * ((double)Tk * d * 2 + ((double)x.V + x.a.max_seq) * d * 4),
                  launch_embed_bwd(e, x.s));
@@ -385,6 +406,19 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
 
 hydra_status tr_run(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   Ctx x(c, b, s);
+  if (c->recompute) {
+    // A shard's block activations live in a workspace only while one of its tasks runs.  The forward task of every
+    // shard but the last leaves the shard's output for the next shard; the backward task runs the forward again
+    // (same kernels, same inputs, same bits) and then the backward.  The last shard's forward would be repeated
+    // at once by its backward, so it is left to that task: the loss of the step is then written there.
+    const bool last = x.shard(0).u1 == x.a.n_layers;
+    if (b.ph == HYDRA_PHASE_F) return last ? HYDRA_OK : tr_forward(x, batch, step);
+    if (b.ph == HYDRA_PHASE_B) {
+      hydra_status st = tr_forward(x, batch, step);
+      return st != HYDRA_OK ? st : tr_backward(x, batch, step);
+    }
+    return run_update(c, b, step, s);
+  }
   if (b.ph == HYDRA_PHASE_F) return tr_forward(x, batch, step);
   if (b.ph == HYDRA_PHASE_B) return tr_backward(x, batch, step);
   return run_update(c, b, step, s);

@@ -169,6 +169,8 @@ hydra_status hydra_shard(hydra_ctx* c, int model, const int32_t* cuts, int n_cut
   if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "define models before sharding them");
   if (model < -1 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
   if (n_cuts < 0 || (n_cuts > 0 && !cuts)) return c->fail(HYDRA_ERR_INVALID_ARG, "n_cuts < 0 or cuts is NULL");
+  if (c->state == ST_DATA && c->opt.activation_budget_bytes > 0 && c->models[0].arch.kind != HYDRA_KIND_MLP)
+    return c->fail(HYDRA_ERR_BAD_STATE, "with an activation budget the hand-off buffers follow the cuts: shard before hydra_set_data");
   // validate every affected model before changing any
   for (int k = 0; k < c->K; ++k) {
     if (model != -1 && model != k) continue;

@@ -75,6 +75,14 @@ struct TrActs {
   void* attn_work = nullptr;  // head-transposed copies for the attention kernels (three for the backward pass)
 };
 
+// Recomputation mode: the per-block activations and the backward scratch of one shard task.  A pool of these
+// replaces the per-model buffers; a task uses the workspace of (its stream, its position in the launch group).
+struct TrWorkspace {
+  std::vector<TrBlockActs> blk;  // one per unit of the largest shard
+  std::vector<void*> xi, dxi;    // block inputs / their gradients strictly inside a shard
+  TrActs sc;                     // head buffers and backward scratch (x, dx, blk unused)
+};
+
 struct Model {
   hydra_arch arch{};
   hydra_hparams hp{};
@@ -135,6 +143,10 @@ struct hydra_ctx {
   size_t csr_ptr_bytes = 0, csr_pos_bytes = 0;
   int32_t* targets = nullptr;    // [n_batches, B] or [n_batches, B, P]
   bool acts_ready = false;
+  // activation_budget_bytes forces recomputation: workspaces [stream][member], ws_streams * ws_group of them
+  bool recompute = false;
+  std::vector<hydra::TrWorkspace> ws;
+  int ws_streams = 0, ws_group = 0;
   // streams / events
   std::vector<hipStream_t> streams;
   bool own_streams = false;

@@ -235,6 +235,154 @@ hydra_status build_update_chunks(hydra_ctx* c) {
   return HYDRA_OK;
 }
 
+// ---- Transformer activations --------------------------------------------------------------------------------
+struct TrDims {
+  size_t Tk, NT, d, F, ldv, bhs, H;
+  bool gated;
+};
+
+static hydra_status alloc_block_acts(hydra_ctx* c, TrBlockActs& b, const TrDims& q) {
+  ALLOC_OR_FAIL(c, b.a, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, b.qkv, void*, q.Tk * 3 * q.d * 2);
+  ALLOC_OR_FAIL(c, b.o, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, b.x1, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, b.f, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, b.z1, void*, q.Tk * q.F * 2);
+  if (q.gated) ALLOC_OR_FAIL(c, b.zg, void*, q.Tk * q.F * 2);
+  ALLOC_OR_FAIL(c, b.hmid, void*, q.Tk * q.F * 2);
+  ALLOC_OR_FAIL(c, b.mu1, float*, q.Tk * 4);
+  ALLOC_OR_FAIL(c, b.rs1, float*, q.Tk * 4);
+  ALLOC_OR_FAIL(c, b.mu2, float*, q.Tk * 4);
+  ALLOC_OR_FAIL(c, b.rs2, float*, q.Tk * 4);
+  ALLOC_OR_FAIL(c, b.lse, float*, q.bhs * 4);
+  return HYDRA_OK;
+}
+
+// head buffers and backward scratch of one model (or one workspace)
+static hydra_status alloc_scratch(hydra_ctx* c, TrActs& t, const TrDims& q, int B, int S) {
+  ALLOC_OR_FAIL(c, t.xf, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, t.dxf, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, t.xt, void*, q.NT * q.d * 2);
+  ALLOC_OR_FAIL(c, t.dxt, void*, q.NT * q.d * 2);
+  ALLOC_OR_FAIL(c, t.logits, float*, q.NT * q.ldv * 4);
+  ALLOC_OR_FAIL(c, t.dlogits, void*, q.NT * q.ldv * 2);
+  ALLOC_OR_FAIL(c, t.rowloss, float*, q.NT * 4);
+  ALLOC_OR_FAIL(c, t.muf, float*, q.Tk * 4);
+  ALLOC_OR_FAIL(c, t.rsf, float*, q.Tk * 4);
+  if (q.gated) {
+    ALLOC_OR_FAIL(c, t.dhm, void*, q.Tk * q.F * 2);
+    ALLOC_OR_FAIL(c, t.dzg, void*, q.Tk * q.F * 2);
+  }
+  ALLOC_OR_FAIL(c, t.dz1, void*, q.Tk * q.F * 2);
+  ALLOC_OR_FAIL(c, t.df, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, t.dx1, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, t.dob, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, t.dqkv, void*, q.Tk * 3 * q.d * 2);
+  ALLOC_OR_FAIL(c, t.da, void*, q.Tk * q.d * 2);
+  ALLOC_OR_FAIL(c, t.delta, float*, q.bhs * 4);
+  ALLOC_OR_FAIL(c, t.attn_work, void*, attn_work_elems(B, S, (int)q.H, (int)(q.d / q.H), true) * 2);
+  ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4);
+  return HYDRA_OK;
+}
+
+static TrDims dims_of(const hydra_ctx* c, const hydra_arch& a) {
+  TrDims q{};
+  q.Tk = (size_t)c->B * c->S;
+  q.NT = (size_t)c->B * c->P;
+  q.d = a.d_model;
+  q.F = a.d_ffn;
+  q.ldv = rup(a.n_out, 8);
+  q.H = a.n_heads;
+  q.bhs = (size_t)c->B * a.n_heads * c->S;
+  q.gated = a.ffn_gated != 0;
+  return q;
+}
+
+static size_t block_bytes(const TrDims& q) {
+  return q.Tk * q.d * 2 * 7 + q.Tk * q.F * 2 * (q.gated ? 3 : 2) + q.Tk * 16 + q.bhs * 4;  // a, qkv (3), o, x1, f; z1, (zg,) hmid
+}
+static size_t scratch_bytes(const hydra_ctx* c, const TrDims& q) {
+  return q.Tk * q.d * 2 * 6 + q.Tk * 3 * q.d * 2 + q.NT * q.d * 4 + q.NT * q.ldv * 6 + q.NT * 4 + q.Tk * 8 +
+         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 +
+         attn_work_elems(c->B, c->S, (int)q.H, (int)(q.d / q.H), true) * 2 + (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4;
+}
+
+// Keeps every block's activations per model, or, when that exceeds activation_budget_bytes, only the hand-off
+// buffers between shards per model plus a pool of shard-sized workspaces (the backward task of a shard then runs
+// its forward again: same kernels on the same inputs, hence the same bits).
+static hydra_status alloc_transformer_activations(hydra_ctx* c) {
+  size_t keep_all = 0;
+  for (const Model& m : c->models) {
+    const TrDims q = dims_of(c, m.arch);
+    keep_all += (size_t)m.arch.n_layers * block_bytes(q) + scratch_bytes(c, q);
+  }
+  c->recompute = c->opt.activation_budget_bytes > 0 && keep_all > c->opt.activation_budget_bytes;
+  for (int k = 0; k < c->K; ++k) {
+    Model& m = c->models[k];
+    const hydra_arch& a = m.arch;
+    const TrDims q = dims_of(c, a);
+    TrActs& t = m.tr;
+    t.x.assign(a.n_layers + 1, nullptr);
+    t.dx.assign(a.n_layers + 1, nullptr);
+    t.blk.assign(a.n_layers, TrBlockActs());
+    std::vector<char> boundary(a.n_layers + 1, c->recompute ? 0 : 1);
+    for (const Shard& sh : m.shards) boundary[sh.u0] = boundary[sh.u1] = 1;
+    for (int l = 0; l <= a.n_layers; ++l) {
+      if (!boundary[l]) continue;  // inside a shard: lives in the workspace of the running task
+      ALLOC_OR_FAIL(c, t.x[l], void*, q.Tk * q.d * 2);
+      ALLOC_OR_FAIL(c, t.dx[l], void*, q.Tk * q.d * 2);
+    }
+    if (c->recompute) continue;
+    for (int l = 0; l < a.n_layers; ++l) {
+      hydra_status st = alloc_block_acts(c, t.blk[l], q);
+      if (st != HYDRA_OK) return st;
+    }
+    hydra_status st = alloc_scratch(c, t, q, c->B, c->S);
+    if (st != HYDRA_OK) return st;
+  }
+  if (!c->recompute) return HYDRA_OK;
+  // one workspace serves the largest shard of the widest model
+  TrDims q = dims_of(c, c->models[0].arch);
+  int max_units = 1;
+  for (const Model& m : c->models) {
+    const TrDims r = dims_of(c, m.arch);
+    q.d = std::max(q.d, r.d);
+    q.F = std::max(q.F, r.F);
+    q.ldv = std::max(q.ldv, r.ldv);
+    q.bhs = std::max(q.bhs, r.bhs);
+    q.H = std::max(q.H, r.H);
+    q.gated = q.gated || r.gated;
+    for (const Shard& sh : m.shards) max_units = std::max(max_units, sh.u1 - sh.u0);
+  }
+  if (q.d % q.H) q.H = c->models[0].arch.n_heads;  // mixed head counts: size the attention scratch by the first model
+  const size_t one = (size_t)max_units * block_bytes(q) + (size_t)(max_units - 1) * q.Tk * q.d * 4 + scratch_bytes(c, q);
+  const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
+  const int nc = ns >= 2 ? std::max(1, ns / 2) : 1;  // compute streams of the shard-parallel policy
+  size_t n_ws = c->opt.activation_budget_bytes / one;
+  if (n_ws < 1)
+    return c->fail(HYDRA_ERR_OOM_DEVICE, "activation budget of %zu bytes is smaller than one shard's workspace (%zu bytes)",
+                   c->opt.activation_budget_bytes, one);
+  n_ws = std::min<size_t>(n_ws, (size_t)nc * MAXG);
+  c->ws_streams = (int)std::min<size_t>(nc, n_ws);
+  c->ws_group = (int)(n_ws / c->ws_streams);
+  c->ws.assign((size_t)c->ws_streams * c->ws_group, TrWorkspace());
+  for (TrWorkspace& w : c->ws) {
+    w.blk.assign(max_units, TrBlockActs());
+    w.xi.assign(max_units, nullptr);
+    w.dxi.assign(max_units, nullptr);
+    for (int u = 0; u < max_units; ++u) {
+      hydra_status st = alloc_block_acts(c, w.blk[u], q);
+      if (st != HYDRA_OK) return st;
+      if (u == 0) continue;
+      ALLOC_OR_FAIL(c, w.xi[u], void*, q.Tk * q.d * 2);
+      ALLOC_OR_FAIL(c, w.dxi[u], void*, q.Tk * q.d * 2);
+    }
+    hydra_status st = alloc_scratch(c, w.sc, q, c->B, c->S);
+    if (st != HYDRA_OK) return st;
+  }
+  return HYDRA_OK;
+}
+
 hydra_status alloc_activations(hydra_ctx* c) {
   for (int k = 0; k < c->K; ++k) {  // the loss buffer holds one float per step of an epoch
     Model& m = c->models[k];
@@ -262,56 +410,11 @@ hydra_status alloc_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, t.logits, float*, (size_t)c->B * ldv * 4);
       ALLOC_OR_FAIL(c, t.dlogits, void*, (size_t)c->B * ldv * es);
       ALLOC_OR_FAIL(c, t.rowloss, float*, (size_t)c->B * 4);
-    } else {
-      const size_t Tk = (size_t)c->B * c->S, NT = (size_t)c->B * c->P, d = a.d_model, F = a.d_ffn;
-      const size_t ldv = rup(a.n_out, 8), bhs = (size_t)c->B * a.n_heads * c->S;
-      TrActs& t = m.tr;
-      t.x.assign(a.n_layers + 1, nullptr);
-      t.dx.assign(a.n_layers + 1, nullptr);
-      t.blk.assign(a.n_layers, TrBlockActs());
-      for (int l = 0; l <= a.n_layers; ++l) {
-        ALLOC_OR_FAIL(c, t.x[l], void*, Tk * d * 2);
-        ALLOC_OR_FAIL(c, t.dx[l], void*, Tk * d * 2);
-      }
-      for (int l = 0; l < a.n_layers; ++l) {
-        TrBlockActs& b = t.blk[l];
-        ALLOC_OR_FAIL(c, b.a, void*, Tk * d * 2);
-        ALLOC_OR_FAIL(c, b.qkv, void*, Tk * 3 * d * 2);
-        ALLOC_OR_FAIL(c, b.o, void*, Tk * d * 2);
-        ALLOC_OR_FAIL(c, b.x1, void*, Tk * d * 2);
-        ALLOC_OR_FAIL(c, b.f, void*, Tk * d * 2);
-        ALLOC_OR_FAIL(c, b.z1, void*, Tk * F * 2);
-        if (a.ffn_gated) ALLOC_OR_FAIL(c, b.zg, void*, Tk * F * 2);
-        ALLOC_OR_FAIL(c, b.hmid, void*, Tk * F * 2);
-        ALLOC_OR_FAIL(c, b.mu1, float*, Tk * 4);
-        ALLOC_OR_FAIL(c, b.rs1, float*, Tk * 4);
-        ALLOC_OR_FAIL(c, b.mu2, float*, Tk * 4);
-        ALLOC_OR_FAIL(c, b.rs2, float*, Tk * 4);
-        ALLOC_OR_FAIL(c, b.lse, float*, bhs * 4);
-      }
-      ALLOC_OR_FAIL(c, t.xf, void*, Tk * d * 2);
-      ALLOC_OR_FAIL(c, t.dxf, void*, Tk * d * 2);
-      ALLOC_OR_FAIL(c, t.xt, void*, NT * d * 2);
-      ALLOC_OR_FAIL(c, t.dxt, void*, NT * d * 2);
-      ALLOC_OR_FAIL(c, t.logits, float*, NT * ldv * 4);
-      ALLOC_OR_FAIL(c, t.dlogits, void*, NT * ldv * 2);
-      ALLOC_OR_FAIL(c, t.rowloss, float*, NT * 4);
-      ALLOC_OR_FAIL(c, t.muf, float*, Tk * 4);
-      ALLOC_OR_FAIL(c, t.rsf, float*, Tk * 4);
-      if (a.ffn_gated) {
-        ALLOC_OR_FAIL(c, t.dhm, void*, Tk * F * 2);
-        ALLOC_OR_FAIL(c, t.dzg, void*, Tk * F * 2);
-      }
-      ALLOC_OR_FAIL(c, t.dz1, void*, Tk * F * 2);
-      ALLOC_OR_FAIL(c, t.df, void*, Tk * d * 2);
-      ALLOC_OR_FAIL(c, t.dx1, void*, Tk * d * 2);
-      ALLOC_OR_FAIL(c, t.dob, void*, Tk * d * 2);
-      ALLOC_OR_FAIL(c, t.dqkv, void*, Tk * 3 * d * 2);
-      ALLOC_OR_FAIL(c, t.da, void*, Tk * d * 2);
-      ALLOC_OR_FAIL(c, t.delta, float*, bhs * 4);
-      ALLOC_OR_FAIL(c, t.attn_work, void*, attn_work_elems(c->B, c->S, a.n_heads, a.d_model / a.n_heads, true) * 2);
-      ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)Tk) * 2 * d * 4);
     }
+  }
+  if (c->models[0].arch.kind != HYDRA_KIND_MLP) {
+    hydra_status st = alloc_transformer_activations(c);
+    if (st != HYDRA_OK) return st;
   }
   c->acts_ready = true;
   return HYDRA_OK;

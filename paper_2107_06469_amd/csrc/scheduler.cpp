@@ -34,7 +34,8 @@ static const char* ph_name(int ph) { return ph == 0 ? "F" : (ph == 1 ? "B" : "U"
 hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan) {
   plan.clear();
   const int K = c->K;
-  const int maxg = c->spill ? std::min(MAXG, spill_max_group(c)) : MAXG;  // a group holds one slot per member
+  int maxg = c->spill ? std::min(MAXG, spill_max_group(c)) : MAXG;  // a group holds one slot per member
+  if (c->recompute) maxg = std::min(maxg, c->ws_group);                  // ... and one activation workspace
   const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
   size_t total = 0;
   for (int k = 0; k < K; ++k) total += 3 * c->models[k].shards.size();
@@ -87,7 +88,8 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
   if (sch->policy != HYDRA_SCHED_SHARD_PARALLEL) return c->fail(HYDRA_ERR_INVALID_ARG, "unknown policy %d", sch->policy);
 
   // wavefronts of ready tasks; inside a wavefront tasks are bucketed by (phase, signature)
-  const int nc = ns >= 2 ? std::max(1, ns / 2) : 1;  // streams [0,nc): F and B; [nc,ns): U
+  int nc = ns >= 2 ? std::max(1, ns / 2) : 1;  // streams [0,nc): F and B; [nc,ns): U
+  if (c->recompute) nc = std::min(nc, c->ws_streams);  // every compute stream needs its own activation workspaces
   const int nu = ns - nc;
   int next_u = 0;
   std::set<Task> issued;
