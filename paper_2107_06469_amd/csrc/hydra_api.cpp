@@ -338,7 +338,7 @@ static hydra_status copy_out(hydra_ctx* c, int model, int tensor, float* dst, si
     size_t o2 = 0;
     for (int j = 0; j < nt; ++j) {
       if (tensor != -1 && tensor != j) continue;
-      memcpy(dst + o2, m.host_p + m.tensors[j].off, m.tensors[j].n * 4);
+      m.host_p.pieces(m.tensors[j].off, m.tensors[j].n, [&](float* h, size_t at, size_t take) { memcpy(dst + o2 + at, h, take * 4); });
       o2 += m.tensors[j].n;
     }
     *n_written = need;
@@ -388,7 +388,7 @@ hydra_status hydra_write_params(hydra_ctx* c, int model, int tensor, const float
     if (tensor != -1 && tensor != j) continue;
     const Tensor& t = m.tensors[j];
     if (c->spill) {
-      memcpy(m.host_p + t.off, src + o, t.n * 4);
+      m.host_p.pieces(t.off, t.n, [&](float* h, size_t at, size_t take) { memcpy(h, src + o + at, take * 4); });
       float* tmp = static_cast<float*>(ctx_alloc(c, t.n * 4));
       if (!tmp) return c->fail(HYDRA_ERR_OOM_DEVICE, "device allocation failed");
       HYDRA_HIP(c, hipMemcpy(tmp, src + o, t.n * 4, hipMemcpyHostToDevice));

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <map>
@@ -83,6 +84,24 @@ struct TrWorkspace {
   TrActs sc;                     // head buffers and backward scratch (x, dx, blk unused)
 };
 
+// A model-sized fp32 array in pinned host memory, held as chunks of at most CHUNK elements (one pinned allocation
+// each: very large single pinned allocations are refused by the runtime).
+struct HostBlock {
+  static constexpr size_t CHUNK = (size_t)512 << 20;  // elements per chunk (2 GiB)
+  std::vector<float*> chunk;
+  size_t n = 0;
+  // calls f(host pointer, offset into the range, elements) for every piece of elements [off, off+cnt)
+  template <class F>
+  void pieces(size_t off, size_t cnt, F f) const {
+    size_t done = 0;
+    while (done < cnt) {
+      const size_t at = off + done, ci = at / CHUNK, in = at % CHUNK, take = std::min(cnt - done, CHUNK - in);
+      f(chunk[ci] + in, done, take);
+      done += take;
+    }
+  }
+};
+
 struct Model {
   hydra_arch arch{};
   hydra_hparams hp{};
@@ -100,7 +119,7 @@ struct Model {
   float* pv = nullptr;
   std::vector<long> voff;
   size_t n_vec = 0;
-  float *host_p = nullptr, *host_m = nullptr, *host_v = nullptr;
+  HostBlock host_p, host_m, host_v;
   float* loss_dev = nullptr;    // one float per step of the current epoch
   int loss_cap = 0;
   std::vector<float> losses;    // all steps so far (host)

@@ -19,19 +19,42 @@ namespace hydra {
 
 static size_t rup(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-static hydra_status host_alloc(hydra_ctx* c, float** out, size_t bytes) {
+// n zero-filled floats of pinned host memory
+static hydra_status host_alloc(hydra_ctx* c, HostBlock* out, size_t n) {
+  const size_t bytes = n * 4;
   c->host_bytes += bytes;
   c->peak_host_bytes = std::max(c->peak_host_bytes, c->host_bytes);
   if (c->opt.host_budget_bytes && c->host_bytes > c->opt.host_budget_bytes)
     return c->fail(HYDRA_ERR_OOM_HOST, "pinned host memory for spilled state (%zu bytes) exceeds the host budget", c->host_bytes);
-  *out = nullptr;
+  out->chunk.clear();
+  out->n = n;
   if (c->dry) return HYDRA_OK;
-  void* p = nullptr;
-  if (hipHostMalloc(&p, bytes, hipHostMallocDefault) != hipSuccess)
-    return c->fail(HYDRA_ERR_OOM_HOST, "hipHostMalloc of %zu bytes failed", bytes);
-  c->host_allocs.push_back(p);
-  *out = static_cast<float*>(p);
+  for (size_t at = 0; at < n; at += HostBlock::CHUNK) {
+    const size_t take = std::min(HostBlock::CHUNK, n - at);
+    void* p = nullptr;
+    if (hipHostMalloc(&p, take * 4, hipHostMallocDefault) != hipSuccess)
+      return c->fail(HYDRA_ERR_OOM_HOST, "hipHostMalloc of %zu bytes failed (%zu bytes of pinned memory held)", take * 4, c->host_bytes);
+    c->host_allocs.push_back(p);
+    out->chunk.push_back(static_cast<float*>(p));
+    memset(p, 0, take * 4);
+  }
   return HYDRA_OK;
+}
+
+// copies elements [off, off+cnt) between a host block and device memory, piece by piece, on stream s
+static hipError_t copy_in_pieces(const HostBlock& hb, size_t off, size_t cnt, float* dev, hipStream_t s) {
+  hipError_t e = hipSuccess;
+  hb.pieces(off, cnt, [&](float* h, size_t at, size_t take) {
+    if (e == hipSuccess) e = hipMemcpyAsync(dev + at, h, take * 4, hipMemcpyHostToDevice, s);
+  });
+  return e;
+}
+static hipError_t copy_out_pieces(const HostBlock& hb, size_t off, size_t cnt, const float* dev, hipStream_t s) {
+  hipError_t e = hipSuccess;
+  hb.pieces(off, cnt, [&](float* h, size_t at, size_t take) {
+    if (e == hipSuccess) e = hipMemcpyAsync(h, dev + at, take * 4, hipMemcpyDeviceToHost, s);
+  });
+  return e;
 }
 
 // bytes the resident path would hold for parameters, gradients, optimizer state and working copies
@@ -68,13 +91,10 @@ hydra_status spill_alloc_models(hydra_ctx* c) {
     if (!c->dry && (!m.w16 || !m.pv)) return c->fail(HYDRA_ERR_OOM_DEVICE, "device allocation failed");
     c->state_bytes += m.n_block * 2 + std::max<size_t>(m.n_vec, 64) * 4;
     hydra_status st;
-    if ((st = host_alloc(c, &m.host_p, m.n_block * 4)) != HYDRA_OK) return st;
-    if ((st = host_alloc(c, &m.host_m, m.n_block * 4)) != HYDRA_OK) return st;
-    if ((st = host_alloc(c, &m.host_v, m.n_block * 4)) != HYDRA_OK) return st;
+    if ((st = host_alloc(c, &m.host_p, m.n_block)) != HYDRA_OK) return st;
+    if ((st = host_alloc(c, &m.host_m, m.n_block)) != HYDRA_OK) return st;
+    if ((st = host_alloc(c, &m.host_v, m.n_block)) != HYDRA_OK) return st;
     if (c->dry) continue;
-    memset(m.host_p, 0, m.n_block * 4);
-    memset(m.host_m, 0, m.n_block * 4);
-    memset(m.host_v, 0, m.n_block * 4);
     HYDRA_HIP(c, launch_fill_u32(reinterpret_cast<uint32_t*>(m.w16), m.n_block / 2, 0u, s));
     HYDRA_HIP(c, launch_fill_f32(m.pv, std::max<size_t>(m.n_vec, 64), 0.f, s));
     for (size_t j = 0; j < m.tensors.size(); ++j) {
@@ -84,7 +104,7 @@ hydra_status spill_alloc_models(hydra_ctx* c) {
       else HYDRA_HIP(c, launch_init_uniform(tmp, t.n, tensor_key(c->seed, k, (int)j), t.a, s));
       HYDRA_HIP(c, launch_cast_bf16(tmp, m.w16 + t.off, t.n, s));
       if (m.voff[j] >= 0) HYDRA_HIP(c, hipMemcpyAsync(m.pv + m.voff[j], tmp, t.n * 4, hipMemcpyDeviceToDevice, s));
-      HYDRA_HIP(c, hipMemcpyAsync(m.host_p + t.off, tmp, t.n * 4, hipMemcpyDeviceToHost, s));
+      HYDRA_HIP(c, copy_out_pieces(m.host_p, t.off, t.n, tmp, s));
       HYDRA_HIP(c, hipStreamSynchronize(s));
     }
   }
@@ -161,9 +181,9 @@ hydra_status spill_acquire(hydra_ctx* c, int k, int s, hipStream_t compute, bool
     if (in != compute) HYDRA_HIP(c, hipStreamWaitEvent(compute, sl.free_ev, 0));
   }
   sl.used = true;
-  HYDRA_HIP(c, hipMemcpyAsync(sh.p, m.host_p + sh.off, bytes, hipMemcpyHostToDevice, in));
-  HYDRA_HIP(c, hipMemcpyAsync(sh.m, m.host_m + sh.off, bytes, hipMemcpyHostToDevice, in));
-  HYDRA_HIP(c, hipMemcpyAsync(sh.v, m.host_v + sh.off, bytes, hipMemcpyHostToDevice, in));
+  HYDRA_HIP(c, copy_in_pieces(m.host_p, sh.off, sh.n, sh.p, in));
+  HYDRA_HIP(c, copy_in_pieces(m.host_m, sh.off, sh.n, sh.m, in));
+  HYDRA_HIP(c, copy_in_pieces(m.host_v, sh.off, sh.n, sh.v, in));
   if (!sh.loaded_ev) HYDRA_HIP(c, hipEventCreateWithFlags(&sh.loaded_ev, hipEventDisableTiming));
   HYDRA_HIP(c, hipEventRecord(sh.loaded_ev, in));
   return HYDRA_OK;
@@ -200,9 +220,9 @@ hydra_status spill_after_update(hydra_ctx* c, int k, int s, hipStream_t compute,
     HYDRA_HIP(c, hipEventRecord(sh.updated_ev, compute));
     HYDRA_HIP(c, hipStreamWaitEvent(out, sh.updated_ev, 0));
   }
-  HYDRA_HIP(c, hipMemcpyAsync(m.host_p + sh.off, sh.p, bytes, hipMemcpyDeviceToHost, out));
-  HYDRA_HIP(c, hipMemcpyAsync(m.host_m + sh.off, sh.m, bytes, hipMemcpyDeviceToHost, out));
-  HYDRA_HIP(c, hipMemcpyAsync(m.host_v + sh.off, sh.v, bytes, hipMemcpyDeviceToHost, out));
+  HYDRA_HIP(c, copy_out_pieces(m.host_p, sh.off, sh.n, sh.p, out));
+  HYDRA_HIP(c, copy_out_pieces(m.host_m, sh.off, sh.n, sh.m, out));
+  HYDRA_HIP(c, copy_out_pieces(m.host_v, sh.off, sh.n, sh.v, out));
   HYDRA_HIP(c, hipEventRecord(sl.free_ev, out));
   sh.p = sh.m = sh.v = sh.g = nullptr;
   sh.slot = -1;

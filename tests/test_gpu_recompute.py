@@ -109,3 +109,20 @@ def test_activation_budget_errors(H):
         assert e2.value.status == 2
     finally:
         H.hydra_destroy(ctx)
+
+
+def test_7b_width_decoders_spilled_and_recomputed_replicate_the_resident_run(H):
+    """The largest workload's layer shapes (d=4096, 32 heads of 128, gated FFN 11008, vocabulary 32000, S=2048,
+    batch 8, causal) at reduced depth and K: two 4-block decoders in two shards, state spilled to pinned host
+    memory (one slot), activations recomputed (one workspace).  Shard-parallel, sequential and model 0 alone with
+    resident state must agree bit for bit; first losses sit near ln(32000) + sigma^2/2 of the initial logits."""
+    from paper_2107_06469_amd import large_models
+    lines = []
+    ok = large_models.compare(K=2, steps=2, layers=4, device_budget=16 << 30, activation_budget=12 << 30, n_shards=2,
+                              out=lines.append)
+    print("\n".join(lines))
+    assert ok, "\n".join(lines[-3:])
+    import json
+    rep = json.loads(lines[0])
+    assert rep["h2d_GB"] > 0 and rep["peak_host_GiB"] > 20
+    assert all(10.3 < l[0] < 11.6 for l in rep["losses"])
