@@ -138,3 +138,26 @@ def test_config2_full_size_one_step_sampled_against_oracle(H):
     for kk in range(w.K):
         assert abs(got[kk][0][0] - np.log(30522)) < 0.3
         assert all(np.all(np.isfinite(p)) for p in got[kk][1])
+
+
+def test_config3_full_size_one_step_sampled_against_oracle(H):
+    """Full-size workload 3 (K=16 encoders of depth 12/18/24, d=1024, 16 heads, S=512, batch 16, vocabulary 32000,
+    shards of 6 blocks: 2, 3 or 4 shards per model, i.e. unequal shard queues) for one step in the benchmark's launch
+    configuration.  The oracle recomputes the first loss of one 12-block model (forward only, fp64); every first
+    loss must be finite and sit near ln(32000); models of equal depth share launch groups."""
+    w = workload(3)
+    w.steps = w.n_batches = 1
+    data = make_data(w)
+    got, stats = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL)
+    depths = w.extra["depths"]
+    assert set(depths) == {12, 18, 24}
+    assert stats[0]["grouped_tasks"] > 0
+    k = depths.index(12)
+    params = OM.init_params(w.archs[k], w.init_seed, k)
+    x, batch = None, OT.batch_at(data, 1)
+    for u in range(OM.n_units(w.archs[k])):
+        x, _ = OM.unit_fwd(w.archs[k], params, u, x, batch)
+    assert abs(got[k][0][0] - float(x)) <= 2e-2 * float(x)
+    for kk in range(w.K):
+        assert abs(got[kk][0][0] - np.log(32000)) < 0.4
+        assert all(np.all(np.isfinite(p)) for p in got[kk][1])
