@@ -106,17 +106,13 @@ size_t hydra_op_layernorm_part_floats(int rows, int d);
 
 /* Attention, bf16, head width DH in {64,128}.  qkv_g [B*S, ld_qkv]: q of head h at columns [h*DH,(h+1)*DH),
  * k at H*DH + the same, v at 2*H*DH + the same.  o_g [B*S, ld_o].  P = softmax(q k^T * scale (+ causal mask)),
- * o = P v, lse_g [B*H*S] = log-sum-exp of the scaled scores.  work_g: device scratch of
- * hydra_op_attention_work_bytes(B, S, H, DH, 0) bytes, 16-byte aligned (head-transposed copy of v). */
-size_t hydra_op_attention_work_bytes(int B, int S, int H, int DH, int backward);
+ * o = P v, lse_g [B*H*S] = log-sum-exp of the scaled scores. */
 int hydra_op_attention_fwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
-                           const void* const* qkv, void* const* o, float* const* lse, void* const* work, void* stream);
-/* Adjoint given dout_g [B*S, ld_o] (gradient w.r.t. o): dqkv_g in the layout of qkv; delta_g [B*H*S] scratch;
- * work_g: hydra_op_attention_work_bytes(B, S, H, DH, 1) bytes (head-transposed k, q, dout). */
+                           const void* const* qkv, void* const* o, float* const* lse, void* stream);
+/* Adjoint given dout_g [B*S, ld_o] (gradient w.r.t. o): dqkv_g in the layout of qkv; delta_g [B*H*S] scratch. */
 int hydra_op_attention_bwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
                            const void* const* qkv, const void* const* o, const void* const* dout,
-                           const float* const* lse, float* const* delta, void* const* dqkv, void* const* work,
-                           void* stream);
+                           const float* const* lse, float* const* delta, void* const* dqkv, void* stream);
 
 /* x_g[t,:] = tok_g[ids[t],:] + pos_g[t mod S,:]; ids int32 [tokens] shared by the group; tables in the operand dtype. */
 int hydra_op_embed_fwd(int dtype, int tokens, int S, int d, int ld, int G, const int32_t* ids, const void* const* tok,

@@ -12,15 +12,15 @@
 // (k index = accumulator row), i.e. probabilities never go through LDS:
 //   forward and dq:  S^T[j,i] = K Q^T  (lane = query i, rows = keys j)  ->  O^T[c,i] += Vt[c,j] P^T[j,i]
 //   dk/dv:           S[i,j]   = Q K^T  (lane = key j, rows = queries i) ->  dV^T[c,j] += dOt[c,i] P[i,j]
-// The A operand of the second contraction walks the tile along its slow index, so those tiles (V, K, Q,
-// dO) are also kept transposed in LDS, with an XOR swizzle of the 8-byte chunk index against bank
-// conflicts.  They are filled from head-transposed copies [B*H*DH][S rounded up to 64] that a small
-// transpose kernel writes into the caller's work buffer before the attention kernel runs (one copy for
-// the forward pass, three for the backward pass): every tile load is then a plain 16-byte row copy by
-// all threads.  Softmax statistics of a query live in the two lanes l and
-// l^32 and are combined with one cross-lane exchange.  A wavefront owns 32 queries (or 32 keys) and loops
-// over tiles of 64 keys (queries) shared through LDS by the four wavefronts of the workgroup.  All sums run
-// in a fixed order; dq and dk/dv are separate kernels so that no atomics are needed.
+// The A operand of the second contraction walks a tile along its slow index (eight keys, or queries, of one
+// column).  The tiles stay row-major in LDS (rows of DH values, 16-byte chunks XOR-swizzled by the row) and that
+// operand comes from transposing LDS reads (ds_read_b64_tr_b16: within 16 lanes, source lane j supplies four
+// consecutive columns of row j/4 and lane i receives column i of rows 0..3), two per fragment, so every tile is
+// loaded once and nothing is transposed in memory.  Tile loads are software-pipelined: the global loads of tile
+// t+1 are issued into registers before the products of tile t and stored to LDS after them.  Softmax statistics
+// of a query live in the two lanes l and l^32 and are combined with one cross-lane exchange.  A wavefront owns 32
+// queries (or 32 keys) and loops over tiles of 64 keys (queries) shared through LDS by the four wavefronts of the
+// workgroup.  All sums run in a fixed order; dq and dk/dv are separate kernels so that no atomics are needed.
 #include "kernels.h"
 
 namespace hydra {
@@ -50,72 +50,49 @@ __device__ __forceinline__ f32x16 mfma(const uint4& a, const uint4& b, f32x16 c)
 }
 
 // ---- LDS tiles of 64 rows x DH columns ---------------------------------------------------------------
-// "row-major" tile: uint4 chunk (row, kc) at row*NCH + (kc ^ (row & (NCH-1))), NCH = DH/8.
-// "transposed" tile: 8-byte chunk (c, q8) (c = column of the source, q8 = source row / 4) at
-//  c*16 + (q8 ^ (c & 15)) in units of 8 bytes.
+// uint4 chunk (row, kc) sits at row*NCH + (kc ^ (row & (NCH-1))), NCH = DH/8.
+// A tile load is split in two so that it can be pipelined: fetch (global -> registers, rows past nrows as zero)
+// and put (registers -> LDS).
 template <int DH>
-__device__ __forceinline__ void load_rows(uint4* tile, const bf16_t* src, int ld, int row0, int nrows, int tid) {
-  constexpr int NCH = DH / 8;
+struct TileRegs {
+  static constexpr int NCH = DH / 8, N = 64 * NCH / 256;
+  uint4 r[N];
+  __device__ __forceinline__ void fetch(const bf16_t* src, int ld, int row0, int nrows, int tid) {
 #pragma unroll
-  for (int i = 0; i < 64 * NCH / 256; ++i) {
-    const int c = tid + 256 * i, row = c / NCH, kc = c % NCH;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * ld + 8 * kc);
-    tile[row * NCH + (kc ^ (row & (NCH - 1)))] = v;
+    for (int i = 0; i < N; ++i) {
+      const int c = tid + 256 * i, row = c / NCH, kc = c % NCH;
+      r[i] = make_uint4(0, 0, 0, 0);
+      if (row0 + row < nrows) r[i] = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * ld + 8 * kc);
+    }
   }
-}
-
-// Fills a "transposed" tile from a head-transposed copy of the source: xt holds, for one (batch, head),
-// DH rows of S_ld values (row c = column c of the source over all sequence positions, zero beyond S), so
-// row c of the tile is the 128 contiguous bytes at xt + c*S_ld + row0.
-template <int DH>
-__device__ __forceinline__ void load_tr_rows(uint2* tile, const bf16_t* xt, int S_ld, int row0, int tid) {
+  __device__ __forceinline__ void put(uint4* tile, int tid) const {
 #pragma unroll
-  for (int i = 0; i < DH * 8 / 256; ++i) {
-    const int u = tid + 256 * i, c = u >> 3, pc = u & 7;
-    const uint4 v = *reinterpret_cast<const uint4*>(xt + (size_t)c * S_ld + row0 + 8 * pc);
-    tile[c * 16 + ((2 * pc) ^ (c & 15))] = make_uint2(v.x, v.y);
-    tile[c * 16 + ((2 * pc + 1) ^ (c & 15))] = make_uint2(v.z, v.w);
+    for (int i = 0; i < N; ++i) {
+      const int c = tid + 256 * i, row = c / NCH, kc = c % NCH;
+      tile[row * NCH + (kc ^ (row & (NCH - 1)))] = r[i];
+    }
   }
-}
-
-// Head transpose: dst[(b*H + h)*DH + c][i] = src[b*S + i][col0 + h*DH + c] for i < S, zero for S <= i < S_ld.
-// One workgroup moves 64 sequence positions of one (batch, head) through LDS.
-struct HeadTrArgs {
-  int S, S_ld, H, DH, ld, col0, G;
-  const bf16_t* src[MAXG];
-  bf16_t* dst[MAXG];
 };
-__global__ __launch_bounds__(256) void head_transpose_kernel(const HeadTrArgs a) {
-  __shared__ bf16_t t[64][128 + 2];
-  const int tid = threadIdx.x, g = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H, i0 = blockIdx.x * 64;
-  const bf16_t* src = a.src[g] + (size_t)b * a.S * a.ld + a.col0 + h * a.DH;
-  const int nch = a.DH / 8;  // 16-byte chunks per source row
-  for (int u = tid; u < 64 * nch; u += 256) {
-    const int r = u / nch, kc = u % nch;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (i0 + r < a.S) v = *reinterpret_cast<const uint4*>(src + (size_t)(i0 + r) * a.ld + 8 * kc);
-    uint32_t* p = reinterpret_cast<uint32_t*>(&t[r][8 * kc]);
-    p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w;
-  }
-  __syncthreads();
-  bf16_t* dst = a.dst[g] + (size_t)bh * a.DH * a.S_ld + i0;
-  for (int u = tid; u < a.DH * 8; u += 256) {
-    const int c = u >> 3, pc = u & 7;
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = (uint32_t)t[8 * pc + 2 * e][c] | ((uint32_t)t[8 * pc + 2 * e + 1][c] << 16);
-    *reinterpret_cast<uint4*>(dst + (size_t)c * a.S_ld + 8 * pc) = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
 
-// A operand (8 values along the slow index) for accumulator rows of sub-tile `sub`, MFMA half x:
-// source rows sub*32 + 16x + 4g + {0..3} and + 8
-__device__ __forceinline__ uint4 read_transposed(const uint2* tile, int c, int sub, int x, int g) {
-  const int q8 = sub * 8 + 4 * x + g;
-  const uint2 a = tile[c * 16 + (q8 ^ (c & 15))];
-  const uint2 b = tile[c * 16 + ((q8 + 2) ^ (c & 15))];
-  return make_uint4(a.x, a.y, b.x, b.y);
+// A operand along the slow index of a row-major tile: lane l gets, for column col0 + l%32, the values of rows
+// row0 + 4g + {0..3} and row0 + 8 + 4g + {0..3} (g = l/32), the k order the accumulator rows of the first product
+// have.  Two transposing reads: in the 16-lane group, source lane j reads 8 bytes at row 4g + j/4, column
+// 16*(group&1) + 4*(j%4) of the block.
+template <int DH>
+__device__ __forceinline__ uint4 read_cols(const uint4* tile, int col0, int row0, int lane) {
+  constexpr int NCH = DH / 8;
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const int j = lane & 15, grp = lane >> 4;
+  const int col = col0 + 16 * (grp & 1) + 4 * (j & 3), kc = col >> 3, half = (col >> 2) & 1;
+  const int r0 = row0 + 4 * (grp >> 1) + (j >> 2), r1 = r0 + 8;
+  const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tile);
+  const unsigned a0 = base + (unsigned)((r0 * NCH + (kc ^ (r0 & (NCH - 1)))) * 16 + half * 8);
+  const unsigned a1 = base + (unsigned)((r1 * NCH + (kc ^ (r1 & (NCH - 1)))) * 16 + half * 8);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)a0);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)a1);
+  const uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
+  return make_uint4(l.x, l.y, h.x, h.y);
 }
 
 template <int DH>
@@ -134,14 +111,12 @@ template <int DH>
 __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const AttnArgs a) {
   constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
   extern __shared__ uint4 lds[];
-  uint4* tK = lds;                                        // [64][NCH]
-  uint2* tVt = reinterpret_cast<uint2*>(lds + 64 * NCH);  // [DH][16]
+  uint4* tK = lds;             // [64][NCH]
+  uint4* tV = lds + 64 * NCH;  // [64][NCH]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
   const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
-  const int S_ld = (a.S + 63) / 64 * 64;
-  const bf16_t* vt = a.work[gi] + (size_t)bh * DH * S_ld;  // head-transposed v
   const int iq = blockIdx.x * 128 + wave * 32 + li;  // this lane's query
   uint4 qf[NK];
 #pragma unroll
@@ -158,12 +133,19 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const A
   const float sc = a.scale * LOG2E;
   const int q_hi = min(a.S, blockIdx.x * 128 + 128) - 1;          // last query of the workgroup
   const int n_tiles = a.causal ? (q_hi / 64 + 1) : (a.S + 63) / 64;
+  TileRegs<DH> pk, pv;
+  pk.fetch(base + d, a.ld_qkv, 0, a.S, tid);
+  pv.fetch(base + 2 * d, a.ld_qkv, 0, a.S, tid);
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * 64;
     __syncthreads();
-    load_rows<DH>(tK, base + d, a.ld_qkv, j0, a.S, tid);
-    load_tr_rows<DH>(tVt, vt, S_ld, j0, tid);
+    pk.put(tK, tid);
+    pv.put(tV, tid);
     __syncthreads();
+    if (t + 1 < n_tiles) {  // in flight while this tile is multiplied
+      pk.fetch(base + d, a.ld_qkv, j0 + 64, a.S, tid);
+      pv.fetch(base + 2 * d, a.ld_qkv, j0 + 64, a.S, tid);
+    }
     f32x16 s[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -214,7 +196,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const A
       for (int x = 0; x < 2; ++x) {
         const uint4 pf = pack_half(s[sub], x);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) oacc[c] = mfma(read_transposed(tVt, c * 32 + li, sub, x, g), pf, oacc[c]);
+        for (int c = 0; c < NC; ++c) oacc[c] = mfma(read_cols<DH>(tV, c * 32, sub * 32 + 16 * x, lane), pf, oacc[c]);
       }
   }
   if (iq < a.S) {
@@ -237,15 +219,12 @@ template <int DH>
 __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(const AttnBwdArgs a) {
   constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
   extern __shared__ uint4 lds[];
-  uint4* tK = lds;                                            // [64][NCH]
-  uint4* tV = lds + 64 * NCH;                                 // [64][NCH]
-  uint2* tKt = reinterpret_cast<uint2*>(lds + 2 * 64 * NCH);  // [DH][16]
+  uint4* tK = lds;             // [64][NCH]
+  uint4* tV = lds + 64 * NCH;  // [64][NCH]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
   const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
-  const int S_ld = (a.S + 63) / 64 * 64;
-  const bf16_t* kt = a.work[gi] + (size_t)bh * DH * S_ld;  // head-transposed k
   const int iq = blockIdx.x * 128 + wave * 32 + li;
   uint4 qf[NK], dof[NK];
   float delta = 0.f;
@@ -273,13 +252,19 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(cons
   const float sc = a.scale * LOG2E;
   const int q_hi = min(a.S, blockIdx.x * 128 + 128) - 1;
   const int n_tiles = a.causal ? (q_hi / 64 + 1) : (a.S + 63) / 64;
+  TileRegs<DH> pk, pv;
+  pk.fetch(base + d, a.ld_qkv, 0, a.S, tid);
+  pv.fetch(base + 2 * d, a.ld_qkv, 0, a.S, tid);
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * 64;
     __syncthreads();
-    load_rows<DH>(tK, base + d, a.ld_qkv, j0, a.S, tid);
-    load_rows<DH>(tV, base + 2 * d, a.ld_qkv, j0, a.S, tid);
-    load_tr_rows<DH>(tKt, kt, S_ld, j0, tid);
+    pk.put(tK, tid);
+    pv.put(tV, tid);
     __syncthreads();
+    if (t + 1 < n_tiles) {
+      pk.fetch(base + d, a.ld_qkv, j0 + 64, a.S, tid);
+      pv.fetch(base + 2 * d, a.ld_qkv, j0 + 64, a.S, tid);
+    }
     const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blockIdx.x * 128 + wave * 32);
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -304,7 +289,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(cons
       for (int x = 0; x < 2; ++x) {
         const uint4 df = pack_half(s, x);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) acc[c] = mfma(read_transposed(tKt, c * 32 + li, sub, x, g), df, acc[c]);
+        for (int c = 0; c < NC; ++c) acc[c] = mfma(read_cols<DH>(tK, c * 32, sub * 32 + 16 * x, lane), df, acc[c]);
       }
     }
   }
@@ -327,20 +312,14 @@ template <int DH>
 __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(const AttnBwdArgs a) {
   constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
   extern __shared__ uint4 lds[];
-  uint4* tQ = lds;                                              // [64][NCH]
-  uint4* tdO = lds + 64 * NCH;                                  // [64][NCH]
-  uint2* tQt = reinterpret_cast<uint2*>(lds + 2 * 64 * NCH);    // [DH][16]
-  uint2* tdOt = tQt + DH * 16;                                  // [DH][16]
-  float* st = reinterpret_cast<float*>(tdOt + DH * 16);         // [2][64]: lse*log2e, delta
+  uint4* tQ = lds;                                        // [64][NCH]
+  uint4* tdO = lds + 64 * NCH;                            // [64][NCH]
+  float* st = reinterpret_cast<float*>(lds + 2 * 64 * NCH);  // [2][64]: lse*log2e, delta
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
   const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
   const bf16_t* dobase = a.dout[gi] + (size_t)b * a.S * a.ld_o + h * DH;
-  const int S_ld = (a.S + 63) / 64 * 64;
-  const size_t one = (size_t)a.B * a.H * DH * S_ld;  // elements of one head-transposed copy
-  const bf16_t* qt = a.work[gi] + one + (size_t)bh * DH * S_ld;       // head-transposed q
-  const bf16_t* dot = a.work[gi] + 2 * one + (size_t)bh * DH * S_ld;  // head-transposed dout
   const int jk = blockIdx.x * 128 + wave * 32 + li;  // this lane's key
   uint4 kf[NK], vf[NK];
 #pragma unroll
@@ -359,20 +338,30 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
   const float sc = a.scale * LOG2E;
   const int t0 = a.causal ? (blockIdx.x * 128) / 64 : 0;  // queries before the workgroup's first key see none of its keys
   const int n_tiles = (a.S + 63) / 64;
+  TileRegs<DH> pq, pdo;
+  float pst = 0.f;
+  auto fetch_stats = [&](int i0) {  // threads 0..63: lse*log2e, 64..127: delta of query i0 + tid%64
+    pst = 0.f;
+    const int i = i0 + (tid & 63);
+    if (tid < 128 && i < a.S) pst = tid < 64 ? a.lse[gi][(size_t)bh * a.S + i] * LOG2E : a.delta[gi][(size_t)bh * a.S + i];
+  };
+  if (t0 < n_tiles) {
+    pq.fetch(base, a.ld_qkv, t0 * 64, a.S, tid);
+    pdo.fetch(dobase, a.ld_o, t0 * 64, a.S, tid);
+    fetch_stats(t0 * 64);
+  }
   for (int t = t0; t < n_tiles; ++t) {
     const int i0 = t * 64;
     __syncthreads();
-    load_rows<DH>(tQ, base, a.ld_qkv, i0, a.S, tid);
-    load_rows<DH>(tdO, dobase, a.ld_o, i0, a.S, tid);
-    load_tr_rows<DH>(tQt, qt, S_ld, i0, tid);
-    load_tr_rows<DH>(tdOt, dot, S_ld, i0, tid);
-    if (tid < 128) {
-      const int i = i0 + (tid & 63);
-      float v = 0.f;
-      if (i < a.S) v = tid < 64 ? a.lse[gi][(size_t)bh * a.S + i] * LOG2E : a.delta[gi][(size_t)bh * a.S + i];
-      st[tid] = v;
-    }
+    pq.put(tQ, tid);
+    pdo.put(tdO, tid);
+    if (tid < 128) st[tid] = pst;
     __syncthreads();
+    if (t + 1 < n_tiles) {
+      pq.fetch(base, a.ld_qkv, i0 + 64, a.S, tid);
+      pdo.fetch(dobase, a.ld_o, i0 + 64, a.S, tid);
+      fetch_stats(i0 + 64);
+    }
     // queries past the end, or (causal) queries that precede some key of this wave, need the mask
     const bool edge = i0 + 64 > a.S || (a.causal && i0 < blockIdx.x * 128 + wave * 32 + 31);
 #pragma unroll
@@ -405,8 +394,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
         const uint4 pf = pack_half(s, x), df = pack_half(ds, x);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          dv[c] = mfma(read_transposed(tdOt, c * 32 + li, sub, x, g), pf, dv[c]);
-          dk[c] = mfma(read_transposed(tQt, c * 32 + li, sub, x, g), df, dk[c]);
+          dv[c] = mfma(read_cols<DH>(tdO, c * 32, sub * 32 + 16 * x, lane), pf, dv[c]);
+          dk[c] = mfma(read_cols<DH>(tQ, c * 32, sub * 32 + 16 * x, lane), df, dk[c]);
         }
       }
     }
@@ -428,9 +417,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
   }
 }
 
-template <int DH> constexpr size_t fwd_lds() { return (size_t)64 * (DH / 8) * 16 + (size_t)DH * 16 * 8; }
-template <int DH> constexpr size_t dq_lds() { return (size_t)2 * 64 * (DH / 8) * 16 + (size_t)DH * 16 * 8; }
-template <int DH> constexpr size_t dkv_lds() { return (size_t)2 * 64 * (DH / 8) * 16 + (size_t)2 * DH * 16 * 8 + 128 * 4; }
+template <int DH> constexpr size_t fwd_lds() { return (size_t)2 * 64 * (DH / 8) * 16; }
+template <int DH> constexpr size_t dq_lds() { return (size_t)2 * 64 * (DH / 8) * 16; }
+template <int DH> constexpr size_t dkv_lds() { return (size_t)2 * 64 * (DH / 8) * 16 + 128 * 4; }
 
 bool attn_ok(int B, int S, int H, int DH, int ld_qkv, int ld_o, int G) {
   return G >= 1 && G <= MAXG && B >= 1 && S >= 1 && H >= 1 && (DH == 64 || DH == 128) && ld_qkv >= 3 * H * DH &&
@@ -439,36 +428,10 @@ bool attn_ok(int B, int S, int H, int DH, int ld_qkv, int ld_o, int G) {
 
 }  // namespace
 
-hipError_t attn_init() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkv_kernel<128>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)dkv_lds<128>());
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<128>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)dq_lds<128>());
-}
-
-size_t attn_work_elems(int B, int S, int H, int DH, bool backward) {
-  return (size_t)(backward ? 3 : 1) * B * H * DH * ((S + 63) / 64 * 64);
-}
-
-// one head-transposed copy (columns [col0, col0 + H*DH) of src) per problem
-static void head_transpose(const void* const* src, int ld, int col0, bf16_t* const* work, size_t offset, int B, int S, int H,
-                           int DH, int G, hipStream_t s) {
-  HeadTrArgs t{};
-  t.S = S; t.S_ld = (S + 63) / 64 * 64; t.H = H; t.DH = DH; t.ld = ld; t.col0 = col0; t.G = G;
-  for (int g = 0; g < G; ++g) {
-    t.src[g] = static_cast<const bf16_t*>(src[g]);
-    t.dst[g] = work[g] + offset;
-  }
-  hipLaunchKernelGGL(head_transpose_kernel, dim3(t.S_ld / 64, B * H, G), dim3(256), 0, s, t);
-}
+hipError_t attn_init() { return hipSuccess; }  // every kernel stays below the default LDS limit
 
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
-  for (int g = 0; g < a.G; ++g)
-    if (!a.work[g] || ((uintptr_t)a.work[g] & 15)) return hipErrorInvalidValue;
-  const int d = a.H * a.DH;
-  head_transpose(reinterpret_cast<const void* const*>(a.qkv), a.ld_qkv, 2 * d, a.work, 0, a.B, a.S, a.H, a.DH, a.G, s);
   dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
   if (a.DH == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), fwd_lds<64>(), s, a);
   else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), fwd_lds<128>(), s, a);
@@ -477,13 +440,6 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bwd(const AttnBwdArgs& a, hipStream_t s) {
   if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
-  for (int g = 0; g < a.G; ++g)
-    if (!a.work[g] || ((uintptr_t)a.work[g] & 15)) return hipErrorInvalidValue;
-  const int d = a.H * a.DH;
-  const size_t one = attn_work_elems(a.B, a.S, a.H, a.DH, false);
-  head_transpose(reinterpret_cast<const void* const*>(a.qkv), a.ld_qkv, d, a.work, 0, a.B, a.S, a.H, a.DH, a.G, s);        // k
-  head_transpose(reinterpret_cast<const void* const*>(a.qkv), a.ld_qkv, 0, a.work, one, a.B, a.S, a.H, a.DH, a.G, s);      // q
-  head_transpose(reinterpret_cast<const void* const*>(a.dout), a.ld_o, 0, a.work, 2 * one, a.B, a.S, a.H, a.DH, a.G, s);   // dout
   dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
   if (a.DH == 64) {
     hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), dq_lds<64>(), s, a);

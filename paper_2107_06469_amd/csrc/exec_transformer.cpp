@@ -128,7 +128,6 @@ static hydra_status tr_forward(Ctx& x, int batch, int step) {
     at.scale = (float)(1.0 / std::sqrt((double)x.DH));
     FOR_G {
       at.qkv[i] = static_cast<const bf16_t*>(A(i).qkv); at.o[i] = static_cast<bf16_t*>(A(i).o); at.lse[i] = A(i).lse;
-      at.work[i] = static_cast<bf16_t*>(x.scratch(i).attn_work);
     }
     const double att_fl = 4.0 * c->B * x.H * (double)c->S * c->S * x.DH * (x.a.causal ? 0.5 : 1.0) * x.G;
     HYDRA_LAUNCH(c, HYDRA_K_ATTENTION, x.s, att_fl, 0.0, launch_attn_fwd(at, x.s));
@@ -370,7 +369,7 @@ static hydra_status tr_backward(Ctx& x, int batch, int step) {
     FOR_G {
       ab.qkv[i] = static_cast<const bf16_t*>(A(i).qkv); ab.o[i] = static_cast<const bf16_t*>(A(i).o);
       ab.dout[i] = static_cast<const bf16_t*>(T(i).dob); ab.lse[i] = A(i).lse; ab.delta[i] = T(i).delta;
-      ab.dqkv[i] = static_cast<bf16_t*>(T(i).dqkv); ab.work[i] = static_cast<bf16_t*>(T(i).attn_work);
+      ab.dqkv[i] = static_cast<bf16_t*>(T(i).dqkv);
     }
     const double att_fl = 10.0 * c->B * x.H * (double)c->S * c->S * x.DH * (x.a.causal ? 0.5 : 1.0) * G;
     ++c->launches;

@@ -73,7 +73,6 @@ struct TrActs {
   void *dhm = nullptr, *dz1 = nullptr, *dzg = nullptr, *df = nullptr, *dx1 = nullptr, *dob = nullptr,
        *dqkv = nullptr, *da = nullptr;
   float *delta = nullptr, *lnpart = nullptr;
-  void* attn_work = nullptr;  // head-transposed copies for the attention kernels (three for the backward pass)
 };
 
 // Recomputation mode: the per-block activations and the backward scratch of one shard task.  A pool of these

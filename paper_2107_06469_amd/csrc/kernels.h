@@ -208,10 +208,7 @@ struct AttnArgs {
   const bf16_t* qkv[MAXG];
   bf16_t* o[MAXG];
   float* lse[MAXG];  // [B*H*S]
-  bf16_t* work[MAXG];  // scratch, attn_work_elems(B, S, H, DH, false) elements, 16-byte aligned
 };
-// elements of the work buffer: head-transposed copies [B*H*DH][S rounded up to 64], one forward, three backward
-size_t attn_work_elems(int B, int S, int H, int DH, bool backward);
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 struct AttnBwdArgs {
   int B, S, H, DH, ld_qkv, ld_o, causal, G;
@@ -222,7 +219,6 @@ struct AttnBwdArgs {
   const float* lse[MAXG];
   float* delta[MAXG];  // [B*H*S] scratch, written by the dq kernel and read by the dk/dv kernel
   bf16_t* dqkv[MAXG];
-  bf16_t* work[MAXG];  // scratch, attn_work_elems(B, S, H, DH, true) elements, 16-byte aligned
 };
 hipError_t launch_attn_bwd(const AttnBwdArgs& a, hipStream_t s);
 hipError_t attn_init();

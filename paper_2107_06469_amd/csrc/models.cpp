@@ -259,7 +259,7 @@ static hydra_status alloc_block_acts(hydra_ctx* c, TrBlockActs& b, const TrDims&
 }
 
 // head buffers and backward scratch of one model (or one workspace)
-static hydra_status alloc_scratch(hydra_ctx* c, TrActs& t, const TrDims& q, int B, int S) {
+static hydra_status alloc_scratch(hydra_ctx* c, TrActs& t, const TrDims& q) {
   ALLOC_OR_FAIL(c, t.xf, void*, q.Tk * q.d * 2);
   ALLOC_OR_FAIL(c, t.dxf, void*, q.Tk * q.d * 2);
   ALLOC_OR_FAIL(c, t.xt, void*, q.NT * q.d * 2);
@@ -280,7 +280,6 @@ static hydra_status alloc_scratch(hydra_ctx* c, TrActs& t, const TrDims& q, int 
   ALLOC_OR_FAIL(c, t.dqkv, void*, q.Tk * 3 * q.d * 2);
   ALLOC_OR_FAIL(c, t.da, void*, q.Tk * q.d * 2);
   ALLOC_OR_FAIL(c, t.delta, float*, q.bhs * 4);
-  ALLOC_OR_FAIL(c, t.attn_work, void*, attn_work_elems(B, S, (int)q.H, (int)(q.d / q.H), true) * 2);
   ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4);
   return HYDRA_OK;
 }
@@ -301,10 +300,9 @@ static TrDims dims_of(const hydra_ctx* c, const hydra_arch& a) {
 static size_t block_bytes(const TrDims& q) {
   return q.Tk * q.d * 2 * 7 + q.Tk * q.F * 2 * (q.gated ? 3 : 2) + q.Tk * 16 + q.bhs * 4;  // a, qkv (3), o, x1, f; z1, (zg,) hmid
 }
-static size_t scratch_bytes(const hydra_ctx* c, const TrDims& q) {
+static size_t scratch_bytes(const TrDims& q) {
   return q.Tk * q.d * 2 * 6 + q.Tk * 3 * q.d * 2 + q.NT * q.d * 4 + q.NT * q.ldv * 6 + q.NT * 4 + q.Tk * 8 +
-         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 +
-         attn_work_elems(c->B, c->S, (int)q.H, (int)(q.d / q.H), true) * 2 + (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4;
+         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 + (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4;
 }
 
 // Keeps every block's activations per model, or, when that exceeds activation_budget_bytes, only the hand-off
@@ -314,7 +312,7 @@ static hydra_status alloc_transformer_activations(hydra_ctx* c) {
   size_t keep_all = 0;
   for (const Model& m : c->models) {
     const TrDims q = dims_of(c, m.arch);
-    keep_all += (size_t)m.arch.n_layers * block_bytes(q) + scratch_bytes(c, q);
+    keep_all += (size_t)m.arch.n_layers * block_bytes(q) + scratch_bytes(q);
   }
   c->recompute = c->opt.activation_budget_bytes > 0 && keep_all > c->opt.activation_budget_bytes;
   for (int k = 0; k < c->K; ++k) {
@@ -337,7 +335,7 @@ static hydra_status alloc_transformer_activations(hydra_ctx* c) {
       hydra_status st = alloc_block_acts(c, t.blk[l], q);
       if (st != HYDRA_OK) return st;
     }
-    hydra_status st = alloc_scratch(c, t, q, c->B, c->S);
+    hydra_status st = alloc_scratch(c, t, q);
     if (st != HYDRA_OK) return st;
   }
   if (!c->recompute) return HYDRA_OK;
@@ -354,8 +352,7 @@ static hydra_status alloc_transformer_activations(hydra_ctx* c) {
     q.gated = q.gated || r.gated;
     for (const Shard& sh : m.shards) max_units = std::max(max_units, sh.u1 - sh.u0);
   }
-  if (q.d % q.H) q.H = c->models[0].arch.n_heads;  // mixed head counts: size the attention scratch by the first model
-  const size_t one = (size_t)max_units * block_bytes(q) + (size_t)(max_units - 1) * q.Tk * q.d * 4 + scratch_bytes(c, q);
+  const size_t one = (size_t)max_units * block_bytes(q) + (size_t)(max_units - 1) * q.Tk * q.d * 4 + scratch_bytes(q);
   const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
   const int nc = ns >= 2 ? std::max(1, ns / 2) : 1;  // compute streams of the shard-parallel policy
   size_t n_ws = c->opt.activation_budget_bytes / one;
@@ -377,7 +374,7 @@ static hydra_status alloc_transformer_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, w.xi[u], void*, q.Tk * q.d * 2);
       ALLOC_OR_FAIL(c, w.dxi[u], void*, q.Tk * q.d * 2);
     }
-    hydra_status st = alloc_scratch(c, w.sc, q, c->B, c->S);
+    hydra_status st = alloc_scratch(c, w.sc, q);
     if (st != HYDRA_OK) return st;
   }
   return HYDRA_OK;

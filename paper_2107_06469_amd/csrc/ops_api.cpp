@@ -184,28 +184,25 @@ int hydra_op_layernorm_bwd(int dtype, int rows, int d, int ld, int G, const void
   return done(launch_ln_bwd(a, static_cast<hipStream_t>(stream)), "hydra_op_layernorm_bwd");
 }
 
-size_t hydra_op_attention_work_bytes(int B, int S, int H, int DH, int backward) {
-  return attn_work_elems(B, S, H, DH, backward != 0) * sizeof(bf16_t);
-}
 
 int hydra_op_attention_fwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
-                           const void* const* qkv, void* const* o, float* const* lse, void* const* work, void* stream) {
-  if (!qkv || !o || !lse || !work || G < 1 || G > MAXG) return bad("hydra_op_attention_fwd: NULL table or G out of range");
+                           const void* const* qkv, void* const* o, float* const* lse, void* stream) {
+  if (!qkv || !o || !lse || G < 1 || G > MAXG) return bad("hydra_op_attention_fwd: NULL table or G out of range");
   if (int st = ensure_init()) return st;
   AttnArgs a{};
   a.B = B; a.S = S; a.H = H; a.DH = DH; a.ld_qkv = ld_qkv; a.ld_o = ld_o; a.causal = causal; a.G = G; a.scale = scale;
   for (int g = 0; g < G; ++g) {
     a.qkv[g] = static_cast<const bf16_t*>(qkv[g]); a.o[g] = static_cast<bf16_t*>(o[g]); a.lse[g] = lse[g];
-    a.work[g] = static_cast<bf16_t*>(work[g]);
+   
   }
   return done(launch_attn_fwd(a, static_cast<hipStream_t>(stream)), "hydra_op_attention_fwd");
 }
 
 int hydra_op_attention_bwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, int causal, float scale, int G,
                            const void* const* qkv, const void* const* o, const void* const* dout,
-                           const float* const* lse, float* const* delta, void* const* dqkv, void* const* work,
+                           const float* const* lse, float* const* delta, void* const* dqkv,
                            void* stream) {
-  if (!qkv || !o || !dout || !lse || !delta || !dqkv || !work || G < 1 || G > MAXG)
+  if (!qkv || !o || !dout || !lse || !delta || !dqkv || G < 1 || G > MAXG)
     return bad("hydra_op_attention_bwd: NULL table or G out of range");
   if (int st = ensure_init()) return st;
   AttnBwdArgs a{};
@@ -213,7 +210,7 @@ int hydra_op_attention_bwd(int B, int S, int H, int DH, int ld_qkv, int ld_o, in
   for (int g = 0; g < G; ++g) {
     a.qkv[g] = static_cast<const bf16_t*>(qkv[g]); a.o[g] = static_cast<const bf16_t*>(o[g]);
     a.dout[g] = static_cast<const bf16_t*>(dout[g]); a.lse[g] = lse[g]; a.delta[g] = delta[g];
-    a.dqkv[g] = static_cast<bf16_t*>(dqkv[g]); a.work[g] = static_cast<bf16_t*>(work[g]);
+    a.dqkv[g] = static_cast<bf16_t*>(dqkv[g]);
   }
   return done(launch_attn_bwd(a, static_cast<hipStream_t>(stream)), "hydra_op_attention_bwd");
 }

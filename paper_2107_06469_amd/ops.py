@@ -41,10 +41,8 @@ def _L():
         L.hydra_op_layernorm_bwd.argtypes = [C.c_int] * 5 + [pp] * 10 + [vp]
         L.hydra_op_layernorm_part_floats.argtypes = [C.c_int, C.c_int]
         L.hydra_op_layernorm_part_floats.restype = C.c_size_t
-        L.hydra_op_attention_fwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int, pp, pp, pp, pp, vp]
-        L.hydra_op_attention_bwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int] + [pp] * 7 + [vp]
-        L.hydra_op_attention_work_bytes.argtypes = [C.c_int] * 5
-        L.hydra_op_attention_work_bytes.restype = C.c_size_t
+        L.hydra_op_attention_fwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int, pp, pp, pp, vp]
+        L.hydra_op_attention_bwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int] + [pp] * 6 + [vp]
         L.hydra_op_embed_fwd.argtypes = [C.c_int] * 6 + [vp, pp, pp, pp, vp]
         L.hydra_op_embed_bwd.argtypes = [C.c_int] * 8 + [vp, vp, pp, pp, pp, vp]
         L.hydra_ops_last_error.restype = C.c_char_p
@@ -134,27 +132,14 @@ def hydra_op_layernorm_bwd(dtype, rows, d, ld, x, dy, add, dx, gamma, mean, rstd
                                        _tab(mean), _tab(rstd), _tab(part), _tab(dgamma), _tab(dbeta), _stream()))
 
 
-def hydra_op_attention_work_bytes(B, S, H, DH, backward) -> int:
-    return int(_L().hydra_op_attention_work_bytes(B, S, H, DH, int(backward)))
-
-
-def _attn_work(B, S, H, DH, backward, n):
-    import torch
-    nb = hydra_op_attention_work_bytes(B, S, H, DH, backward)
-    return [torch.empty(nb, dtype=torch.uint8, device="cuda") for _ in range(n)]
-
-
-def hydra_op_attention_fwd(B, S, H, DH, ld_qkv, ld_o, causal, scale, qkv, o, lse, work=None):
-    """work: per problem a device buffer of hydra_op_attention_work_bytes(..., False) bytes (allocated here if None)."""
-    work = work if work is not None else _attn_work(B, S, H, DH, False, len(qkv))
+def hydra_op_attention_fwd(B, S, H, DH, ld_qkv, ld_o, causal, scale, qkv, o, lse):
     _check(_L().hydra_op_attention_fwd(B, S, H, DH, ld_qkv, ld_o, int(causal), scale, len(qkv), _tab(qkv), _tab(o),
-                                       _tab(lse), _tab(work), _stream()))
+                                       _tab(lse), _stream()))
 
 
-def hydra_op_attention_bwd(B, S, H, DH, ld_qkv, ld_o, causal, scale, qkv, o, dout, lse, delta, dqkv, work=None):
-    work = work if work is not None else _attn_work(B, S, H, DH, True, len(qkv))
+def hydra_op_attention_bwd(B, S, H, DH, ld_qkv, ld_o, causal, scale, qkv, o, dout, lse, delta, dqkv):
     _check(_L().hydra_op_attention_bwd(B, S, H, DH, ld_qkv, ld_o, int(causal), scale, len(qkv), _tab(qkv), _tab(o),
-                                       _tab(dout), _tab(lse), _tab(delta), _tab(dqkv), _tab(work), _stream()))
+                                       _tab(dout), _tab(lse), _tab(delta), _tab(dqkv), _stream()))
 
 
 def hydra_op_embed_fwd(dtype, tokens, S, d, ld, ids, tok, pos, x):
