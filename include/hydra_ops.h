@@ -51,7 +51,15 @@ typedef struct {
   const void* const* resid;
   float* const* rowsum; /* optional, weight-gradient layout (x_kmajor = w_kmajor = 0) only: rowsum_g[m] =
                            sum_k X_g(m,k) in fp32, M floats each; with X = dY this is the bias gradient */
+  void* const* ws;      /* optional device scratch, 32-byte aligned, ws_bytes each: a bf16 weight-gradient problem
+                           (x_kmajor = w_kmajor = 0, out_f32, no bias/pre/gate/resid, no activation) with
+                           hydra_op_gemm_split_k(M, N, K) = S > 1 then sums S contiguous ranges of k separately and
+                           adds the partial sums in ascending order in a second launch.  S depends on the shape
+                           alone.  Without scratch (or with too little) the sum runs in one chain */
+  size_t ws_bytes;
 } hydra_gemm_desc;
+int hydra_op_gemm_split_k(int M, int N, int K);                   /* 1 = this shape is never split   */
+size_t hydra_op_gemm_split_ws_bytes(int M, int N, int K, int ldo);  /* scratch bytes per problem, 0 if S = 1 */
 int hydra_op_gemm(const hydra_gemm_desc* d, void* stream);
 
 /* out_g[n] = sum_{m<M} src_g[m,n]; src has the operand dtype and leading dimension ld, out is fp32.

@@ -223,7 +223,8 @@ static hydra_status wgrad(Ctx& x, int step, int rows, int n_out, int k_in, int l
   GemmArgs w{};
   w.dtype = GEMM_BF16; w.M = n_out; w.N = k_in; w.K = rows; w.x_kmajor = w.w_kmajor = 0; w.ldx = ld_dy; w.ldw = ld_x;
   w.ldo = k_in; w.out_f32 = 1; w.G = x.G;
-  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = x.g32(i, jw[i]); w.rowsum[i] = db[i]; }
+  FOR_G { w.X[i] = dy[i]; w.W[i] = xin[i]; w.out[i] = x.g32(i, jw[i]); w.rowsum[i] = db[i]; w.ws[i] = x.scratch(i).splitk; }
+  w.ws_bytes = x.scratch(0).splitk_bytes;
   if (c->fuse) {
     GemmUpdate up{};
     up.opt = x.model(0).hp.opt == HYDRA_OPT_ADAM ? 1 : 0;

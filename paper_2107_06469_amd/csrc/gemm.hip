@@ -26,6 +26,8 @@
 //    applies the optimizer step to the parameters, moments and bf16 working copy of the elements
 //    it holds (optim_math.h): the gradient never goes to memory (paper, Approach, "Desiderata":
 //    same update as unsharded training, so the arithmetic is shared with the optimizer kernel).
+#include <algorithm>
+
 #include "kernels.h"
 #include "optim_math.h"
 
@@ -355,7 +357,8 @@ __device__ __forceinline__ void wave_lds_sync() {
 // independently.
 template <typename T, int FM, int FN, bool UPD>
 __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patch, const GemmArgs& a,
-                                              const typename UpdSel<UPD>::type& upd, int g, int mrow0, int ncol0, int lane) {
+                                              const typename UpdSel<UPD>::type& upd, int g, int mrow0, int ncol0, int lane,
+                                              size_t out_off = 0) {
   constexpr int SP = FN * 32 + 4;          // patch pitch in floats (+4: spreads rows over banks)
   constexpr int LPR = FN * 4;              // lanes per row (8 elements each)
   constexpr int RPP = 64 / LPR;            // rows per pass
@@ -434,7 +437,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += z[e];
         }
-        if (a.out_f32) store8<float>(static_cast<float*>(a.out[g]) + (size_t)m * a.ldo + n, v);
+        if (a.out_f32) store8<float>(static_cast<float*>(a.out[g]) + out_off + (size_t)m * a.ldo + n, v);
         else store8<T>(static_cast<T*>(a.out[g]) + (size_t)m * a.ldo + n, v);
       } else {
 #pragma unroll
@@ -447,7 +450,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
             else t = act_fwd(t, act);
             if (mul) t *= Elem<T>::to_f(mul[(size_t)m * a.ldo + n + e]);
             if (resid) t += Elem<T>::to_f(resid[(size_t)m * a.ldr + n + e]);
-            if (a.out_f32) static_cast<float*>(a.out[g])[(size_t)m * a.ldo + n + e] = t;
+            if (a.out_f32) static_cast<float*>(a.out[g])[out_off + (size_t)m * a.ldo + n + e] = t;
             else static_cast<T*>(a.out[g])[(size_t)m * a.ldo + n + e] = Elem<T>::from_f(t);
           }
         }
@@ -705,8 +708,11 @@ struct RingOperand {
   }
 };
 
-template <int WM, int WN, int FM, int FN, int NS, bool X_KMAJ, bool W_KMAJ, bool UPD>
+// SPLITK: the grid holds a.split_k copies of every tile; copy sp sums the sp-th contiguous range of sub-tiles and
+// stores its fp32 partial tile at element offset sp*M*ldo of out (row sums at sp*M); splitk_finish_kernel adds them.
+template <int WM, int WN, int FM, int FN, int NS, bool X_KMAJ, bool W_KMAJ, bool UPD, bool SPLITK = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a, const typename UpdSel<UPD>::type upd) {
+  static_assert(!SPLITK || !UPD, "partial sums are stored plainly");
   typedef bf16_t T;
   constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN, BK = 32;
   constexpr int STAGE = (BM + BN) * 4 * 16;  // bytes per stage: X part, then W part
@@ -719,9 +725,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
 
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const int n_tiles = tiles_m * tiles_n * a.G;
-  const int per_xcd = (n_tiles + 7) >> 3;
-  const int t_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (t_id >= n_tiles) return;
+  const int n_work = SPLITK ? n_tiles * a.split_k : n_tiles;
+  const int per_xcd = (n_work + 7) >> 3;
+  const int w_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (w_id >= n_work) return;
+  const int sp = SPLITK ? w_id / n_tiles : 0, t_id = SPLITK ? w_id % n_tiles : w_id;  // neighbouring ids: same k range
   constexpr int GM = 8;  // tile order as in gemm_kernel: contiguous runs per XCD, bands of GM tile rows
   const int g = t_id / (tiles_m * tiles_n), t_in = t_id % (tiles_m * tiles_n);
   const int band = t_in / (GM * tiles_n), r_in = t_in % (GM * tiles_n);
@@ -736,10 +744,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
   ow_.init(static_cast<const T*>(a.W[g]), a.ldw, n0, a.N, K, wave, lane);
   const char* lds_c = reinterpret_cast<const char*>(lds);
   const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-  auto load_one = [&](int t, int nd) {  // nd-th direct load of sub-tile t
+  // this workgroup's range of sub-tiles
+  const int nk_all = (K + BK - 1) / BK;
+  const int nk_per = SPLITK ? (nk_all + a.split_k - 1) / a.split_k : nk_all;
+  const int kb = sp * nk_per;
+  const int nk = max(0, min(nk_all, kb + nk_per) - kb);
+  const int K_end = min(K, (kb + nk) * BK);  // chunks at or past it load as zeros
+  auto load_one = [&](int t, int nd) {  // nd-th direct load of the range's sub-tile t
     const unsigned st = lds_base + (unsigned)((t % NS) * STAGE);
-    if (nd < RX::NLD) ox_.issue(nd, t, st, K, wave);
-    else ow_.issue(nd - RX::NLD, t, st + (unsigned)(BM * 4 * 16), K, wave);
+    if (nd < RX::NLD) ox_.issue(nd, kb + t, st, K_end, wave);
+    else ow_.issue(nd - RX::NLD, kb + t, st + (unsigned)(BM * 4 * 16), K_end, wave);
   };
 
   f32x16 acc[FM][FN];
@@ -749,7 +763,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  const int nk = (K + BK - 1) / BK;
   const int lrow = lane & 31, lgrp = lane >> 5;
   int fx[2][FM], fw[2][FN];  // fragment byte offsets inside a stage for MFMA step 0 / 1
 #pragma unroll
@@ -817,7 +830,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
     for (int i = 0; i < FM; ++i) {
       const float total = rs[i] + __shfl_xor(rs[i], 32, 64);  // even chunks + odd chunks
       const int m = m0 + (wm * FM + i) * 32 + lrow;
-      if (lgrp == 0 && m < a.M) a.rowsum[g][m] = total;
+      if (lgrp == 0 && m < a.M) a.rowsum[g][(size_t)sp * a.M + m] = total;
     }
   }
   // the trailing (all-zero) loads must have landed and every wave must be done with the ring before patches reuse it
@@ -826,7 +839,67 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
   constexpr int SP = FN * 32 + 4;
   static_assert((size_t)NW * 32 * SP * 4 <= (size_t)NS * STAGE, "epilogue patch exceeds LDS");
   float* patch = reinterpret_cast<float*>(lds) + wave * (32 * SP);
-  tile_epilogue<T, FM, FN, UPD>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane);
+  tile_epilogue<T, FM, FN, UPD>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane,
+                                SPLITK ? (size_t)sp * a.M * a.ldo : 0);
+}
+
+// Second launch of a split weight gradient: element (m, n) of problem g = the S partial sums added in ascending
+// order, then stored (fp32) and/or fed to the parameter update exactly as the one-launch epilogue would.
+struct SplitFinishArgs {
+  int M, N, ldo, S, G, opt, upd;
+  const float* ws[MAXG];      // [S][M][ldo] partial sums, then [S][M] partial row sums
+  float* out[MAXG];           // nullable
+  float* rowsum[MAXG];        // nullable
+  float* p[MAXG];
+  float* m[MAXG];
+  float* v[MAXG];
+  bf16_t* w16[MAXG];
+  OptimHp hp[MAXG];
+};
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArgs a) {
+  const int g = blockIdx.y;
+  const size_t plane = (size_t)a.M * a.ldo;
+  const int n8 = a.N / 8;  // N is a multiple of 8
+  const size_t total = (size_t)a.M * n8;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const int m = (int)(i / n8), n = (int)(i % n8) * 8;
+    const size_t idx = (size_t)m * a.ldo + n;
+    float v[8];
+    load8_stream(a.ws[g] + idx, v);
+    for (int s = 1; s < a.S; ++s) {
+      float w[8];
+      load8_stream(a.ws[g] + (size_t)s * plane + idx, w);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += w[e];
+    }
+    if (a.upd) {
+      const OptimHp h = a.hp[g];
+      float pe[8], me[8], ve[8];
+      load8<float>(a.p[g] + idx, pe);
+      if (a.opt == 1) {
+        load8<float>(a.m[g] + idx, me);
+        load8<float>(a.v[g] + idx, ve);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
+        store8<float>(a.m[g] + idx, me);
+        store8<float>(a.v[g] + idx, ve);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
+      }
+      store8<float>(a.p[g] + idx, pe);
+      if (a.w16[g]) store8<bf16_t>(a.w16[g] + idx, pe);
+    }
+    if (a.out[g]) store8<float>(a.out[g] + idx, v);
+  }
+  if (a.rowsum[g] && blockIdx.x == 0) {
+    const float* rs = a.ws[g] + (size_t)a.S * plane;
+    for (int m = threadIdx.x; m < a.M; m += 256) {
+      float t = rs[m];
+      for (int s = 1; s < a.S; ++s) t += rs[(size_t)s * a.M + m];
+      a.rowsum[g][m] = t;
+    }
+  }
 }
 
 struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages of 32 KB
@@ -850,6 +923,11 @@ struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages 
     hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, false, false, true>), dim3(grid_of(a)), dim3(NT), LDS, s, a, u);
     return hipGetLastError();
   }
+  static hipError_t run_split(const GemmArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, false, false, false, true>), dim3(grid_of(a) * a.split_k), dim3(NT), LDS,
+                       s, a, NoUpdate());
+    return hipGetLastError();
+  }
   template <bool XK, bool WK, bool UPD>
   static hipError_t attr1() {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, UPD>),
@@ -861,6 +939,9 @@ struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages 
     if ((e = attr1<true, false, false>()) != hipSuccess) return e;
     if ((e = attr1<false, true, false>()) != hipSuccess) return e;
     if ((e = attr1<false, false, false>()) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, false, false, false, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS)) != hipSuccess)
+      return e;
     return attr1<false, false, true>();
   }
 };
@@ -922,6 +1003,52 @@ template <typename T> struct Tiles {
   typedef Cfg<T, 1, 4, 1, 1, 1, 1> Small;  // 32 x 128
 };
 
+// A weight gradient whose output has few 256x256 tiles leaves most of the device idle while its sum over k is long.
+// The split depends on the shape alone (never on the group), so it cannot make a result depend on the schedule.
+int split_of(int M, int N, int K) {
+  const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (tiles >= 64 || N % 8) return 1;
+  // about half the device's compute units for one problem: a group of a few models then fills it, and the partial
+  // sums (S fp32 copies of the gradient, written and read once) stay a small part of the traffic
+  long s = std::min<long>(8, 128 / tiles);
+  s = std::min<long>(s, K / 1024);  // at least 1024 k per range
+  return s < 2 ? 1 : (int)s;
+}
+
+// the two launches of a split problem; u = nullptr: plain store
+hipError_t run_split(const GemmArgs& a, const GemmUpdate* u, int S, hipStream_t s) {
+  GemmArgs b = a;
+  SplitFinishArgs f{};
+  f.M = a.M; f.N = a.N; f.ldo = a.ldo; f.S = S; f.G = a.G; f.upd = u != nullptr; f.opt = u ? u->opt : 0;
+  const size_t plane = (size_t)a.M * a.ldo;
+  for (int g = 0; g < a.G; ++g) {
+    float* ws = static_cast<float*>(a.ws[g]);
+    b.out[g] = ws;
+    b.rowsum[g] = a.rowsum[g] ? ws + (size_t)S * plane : nullptr;
+    f.ws[g] = ws;
+    f.out[g] = static_cast<float*>(a.out[g]);
+    f.rowsum[g] = a.rowsum[g];
+    if (u) { f.p[g] = u->p[g]; f.m[g] = u->m[g]; f.v[g] = u->v[g]; f.w16[g] = u->w16[g]; f.hp[g] = u->hp[g]; }
+  }
+  b.out_f32 = 1;
+  b.split_k = S;
+  hipError_t e = DmaBig::run_split(b, s);
+  if (e != hipSuccess) return e;
+  const size_t vecs = (size_t)a.M * (a.N / 8);
+  const unsigned bx = (unsigned)std::min<size_t>((vecs + 255) / 256, 4096);
+  hipLaunchKernelGGL(splitk_finish_kernel, dim3(bx, a.G), dim3(256), 0, s, f);
+  return hipGetLastError();
+}
+
+// S > 1 when the problem is to be split: weight-gradient layout, bf16, plain fp32 output (or the update), scratch given
+int split_for(const GemmArgs& a) {
+  if (!a.ws[0] || a.dtype != GEMM_BF16 || a.x_kmajor || a.w_kmajor || !a.out_f32 || !dma_eligible(a)) return 1;
+  if (a.bias[0] || a.pre[0] || a.gate[0] || a.resid[0] || a.mul[0] || a.act != EPI_ACT_NONE) return 1;
+  const int S = split_of(a.M, a.N, a.K);
+  if (S > 1 && a.ws_bytes < ((size_t)S * a.M * a.ldo + (size_t)S * a.M) * 4) return 1;
+  return S;
+}
+
 int choose_tile(const GemmArgs& a) {
   if (a.tile) return a.tile;
   auto tiles = [&](int bm, int bn) { return (long)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * a.G; };
@@ -937,6 +1064,7 @@ int choose_tile(const GemmArgs& a) {
 
 template <typename T>
 hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
+  if (const int S = split_for(a); S > 1) return run_split(a, &u, S, s);
   int tile = choose_tile(a);
   // With a short k-loop the state traffic of the epilogue dominates: with two workgroups per CU one streams
   // state while the other runs its k-loop, which the 256x256 tile (one workgroup per CU) cannot do.
@@ -953,6 +1081,7 @@ hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s
 
 template <typename T>
 hipError_t dispatch(const GemmArgs& a, hipStream_t s) {
+  if (const int S = split_for(a); S > 1) return run_split(a, nullptr, S, s);
   const int tile = choose_tile(a);
   if (tile == 1 && dma_eligible(a)) return DmaBig::run(a, s);
   switch (tile) {
@@ -1010,9 +1139,17 @@ static hipError_t check_gemm(const GemmArgs& a, bool need_out) {
   if (a.gate[0] && a.ldg < a.N) return hipErrorInvalidValue;
   if (a.resid[0] && a.ldr < a.N) return hipErrorInvalidValue;
   for (int g = 0; g < a.G; ++g)
-    if ((a.rowsum[g] == nullptr) != (a.rowsum[0] == nullptr)) return hipErrorInvalidValue;
+    if ((a.rowsum[g] == nullptr) != (a.rowsum[0] == nullptr) || (a.ws[g] == nullptr) != (a.ws[0] == nullptr) ||
+        ((uintptr_t)a.ws[g] & 31))
+      return hipErrorInvalidValue;
   if (a.rowsum[0] && (a.x_kmajor || a.w_kmajor)) return hipErrorInvalidValue;
   return hipSuccess;
+}
+
+int gemm_split_k(int M, int N, int K) { return split_of(M, N, K); }
+size_t gemm_split_ws_bytes(int M, int N, int K, int ldo) {
+  const int S = split_of(M, N, K);
+  return S > 1 ? ((size_t)S * M * ldo + (size_t)S * M) * 4 : 0;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {

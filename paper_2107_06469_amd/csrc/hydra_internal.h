@@ -73,6 +73,8 @@ struct TrActs {
   void *dhm = nullptr, *dz1 = nullptr, *dzg = nullptr, *df = nullptr, *dx1 = nullptr, *dob = nullptr,
        *dqkv = nullptr, *da = nullptr;
   float *delta = nullptr, *lnpart = nullptr;
+  void* splitk = nullptr;   // partial sums of weight gradients whose sum over the tokens is split (gemm_split_k)
+  size_t splitk_bytes = 0;
 };
 
 // Recomputation mode: the per-block activations and the backward scratch of one shard task.  A pool of these

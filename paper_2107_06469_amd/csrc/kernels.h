@@ -46,10 +46,20 @@ struct GemmArgs {
   int ldo, ldg, ldr;
   int act;
   int out_f32;
+  // Optional scratch for weight-gradient problems (x_kmajor = w_kmajor = 0, bf16) whose output has too few tiles to
+  // fill the device: with ws non-null (all-or-none, 32-byte aligned, ws_bytes each) and gemm_split_k(M, N, K) = S > 1
+  // the sum over k is cut into S contiguous ranges whose partial sums go to ws and are added in ascending order by a
+  // second launch, which also applies the epilogue (plain store or update).  S depends on the shape alone, so a
+  // result depends on neither the group nor the tile code; gemm_split_ws_bytes gives the bytes S needs.
+  void* ws[MAXG];
+  size_t ws_bytes;
+  int split_k;  // set by the launcher
   int tile;  // 0 = choose by problem size; 1 = 256x256, 2 = 128x128, 3 = 32x128, 4 = 256x256 with operands staged
              // through registers even where the direct-to-LDS kernel applies (tests, tuning)
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+int gemm_split_k(int M, int N, int K);              // 1 = no split
+size_t gemm_split_ws_bytes(int M, int N, int K, int ldo);  // 0 when gemm_split_k is 1
 // Must be called once per process before the first launch_gemm (sets the kernels' LDS limits).
 hipError_t gemm_init();
 

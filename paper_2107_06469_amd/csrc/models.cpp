@@ -237,7 +237,7 @@ hydra_status build_update_chunks(hydra_ctx* c) {
 
 // ---- Transformer activations --------------------------------------------------------------------------------
 struct TrDims {
-  size_t Tk, NT, d, F, ldv, bhs, H;
+  size_t Tk, NT, d, F, V, ldv, bhs, H;
   bool gated;
 };
 
@@ -259,7 +259,19 @@ static hydra_status alloc_block_acts(hydra_ctx* c, TrBlockActs& b, const TrDims&
 }
 
 // head buffers and backward scratch of one model (or one workspace)
+// scratch of the largest split weight gradient of a block or of the head
+static size_t splitk_bytes(const TrDims& q) {
+  const int d = (int)q.d, F = (int)q.F, Tk = (int)q.Tk;
+  size_t b = gemm_split_ws_bytes(3 * d, d, Tk, d);
+  b = std::max(b, gemm_split_ws_bytes(d, d, Tk, d));
+  b = std::max(b, gemm_split_ws_bytes(F, d, Tk, d));
+  b = std::max(b, gemm_split_ws_bytes(d, F, Tk, F));
+  return std::max(b, gemm_split_ws_bytes((int)q.V, d, (int)q.NT, d));
+}
+
 static hydra_status alloc_scratch(hydra_ctx* c, TrActs& t, const TrDims& q) {
+  t.splitk_bytes = splitk_bytes(q);
+  if (t.splitk_bytes) ALLOC_OR_FAIL(c, t.splitk, void*, t.splitk_bytes);
   ALLOC_OR_FAIL(c, t.xf, void*, q.Tk * q.d * 2);
   ALLOC_OR_FAIL(c, t.dxf, void*, q.Tk * q.d * 2);
   ALLOC_OR_FAIL(c, t.xt, void*, q.NT * q.d * 2);
@@ -290,6 +302,7 @@ static TrDims dims_of(const hydra_ctx* c, const hydra_arch& a) {
   q.NT = (size_t)c->B * c->P;
   q.d = a.d_model;
   q.F = a.d_ffn;
+  q.V = a.n_out;
   q.ldv = rup(a.n_out, 8);
   q.H = a.n_heads;
   q.bhs = (size_t)c->B * a.n_heads * c->S;
@@ -302,7 +315,7 @@ static size_t block_bytes(const TrDims& q) {
 }
 static size_t scratch_bytes(const TrDims& q) {
   return q.Tk * q.d * 2 * 6 + q.Tk * 3 * q.d * 2 + q.NT * q.d * 4 + q.NT * q.ldv * 6 + q.NT * 4 + q.Tk * 8 +
-         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 + (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4;
+         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 + (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4 + splitk_bytes(q);
 }
 
 // Keeps every block's activations per model, or, when that exceeds activation_budget_bytes, only the hand-off
@@ -347,6 +360,7 @@ static hydra_status alloc_transformer_activations(hydra_ctx* c) {
     q.d = std::max(q.d, r.d);
     q.F = std::max(q.F, r.F);
     q.ldv = std::max(q.ldv, r.ldv);
+    q.V = std::max(q.V, r.V);
     q.bhs = std::max(q.bhs, r.bhs);
     q.H = std::max(q.H, r.H);
     q.gated = q.gated || r.gated;

@@ -60,12 +60,17 @@ static void fill_gemm(const hydra_gemm_desc* d, GemmArgs& a) {
     a.gate[g] = d->gate ? d->gate[g] : nullptr;
     a.resid[g] = d->resid ? d->resid[g] : nullptr;
     a.rowsum[g] = d->rowsum ? d->rowsum[g] : nullptr;
+    a.ws[g] = d->ws ? d->ws[g] : nullptr;
   }
+  a.ws_bytes = d->ws ? d->ws_bytes : 0;
 }
 
 extern "C" {
 
 const char* hydra_ops_last_error(void) { return g_ops_err.c_str(); }
+
+int hydra_op_gemm_split_k(int M, int N, int K) { return gemm_split_k(M, N, K); }
+size_t hydra_op_gemm_split_ws_bytes(int M, int N, int K, int ldo) { return gemm_split_ws_bytes(M, N, K, ldo); }
 
 int hydra_op_gemm(const hydra_gemm_desc* d, void* stream) {
   if (!d || !d->X || !d->W || !d->out || d->G < 1 || d->G > MAXG) return bad("hydra_op_gemm: NULL table or G out of range");

@@ -17,7 +17,8 @@ EPI_NONE, EPI_RELU, EPI_GELU = 0, 1, 2
 class hydra_gemm_desc(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("dtype", "M", "N", "K", "x_kmajor", "w_kmajor", "ldx", "ldw", "ldo", "ldg", "ldr",
                                        "act", "out_f32", "tile", "G")] + \
-               [(n, C.POINTER(C.c_void_p)) for n in ("X", "W", "bias", "out", "pre", "gate", "resid", "rowsum")]
+               [(n, C.POINTER(C.c_void_p)) for n in ("X", "W", "bias", "out", "pre", "gate", "resid", "rowsum", "ws")] + \
+               [("ws_bytes", C.c_size_t)]
 
 
 _ready = False
@@ -33,6 +34,9 @@ def _L():
         L.hydra_op_colsum.argtypes = [C.c_int] * 5 + [pp, pp, pp, vp]
         L.hydra_op_colsum_part_floats.argtypes = [C.c_int, C.c_int]
         L.hydra_op_colsum_part_floats.restype = C.c_size_t
+        L.hydra_op_gemm_split_k.argtypes = [C.c_int] * 3
+        L.hydra_op_gemm_split_ws_bytes.argtypes = [C.c_int] * 4
+        L.hydra_op_gemm_split_ws_bytes.restype = C.c_size_t
         L.hydra_op_softmax_ce.argtypes = [C.c_int] * 5 + [C.c_float, C.c_int, pp, vp, pp, pp, pp, vp]
         L.hydra_op_optim.argtypes = [C.c_int, C.c_size_t, C.c_int, pp, pp, pp, pp, pp, C.POINTER(C.c_double), vp]
         L.hydra_op_init_uniform.argtypes = [vp, C.c_size_t, C.c_uint64, C.c_uint64, C.c_float, vp]
@@ -67,26 +71,38 @@ def _check(st: int):
 
 
 def hydra_op_gemm(dtype, M, N, K, X, W, out, *, x_kmajor, w_kmajor, ldx, ldw, ldo, bias=None, pre=None, gate=None,
-                  resid=None, ldg=0, ldr=0, act=EPI_NONE, out_f32=False, tile=0, rowsum=None):
+                  resid=None, ldg=0, ldr=0, act=EPI_NONE, out_f32=False, tile=0, rowsum=None, ws=None):
+    """ws: optional per-problem scratch tensors (uint8, hydra_op_gemm_split_ws_bytes bytes) that allow a split sum over k."""
     d = hydra_gemm_desc()
     d.dtype, d.M, d.N, d.K, d.x_kmajor, d.w_kmajor = dtype, M, N, K, int(x_kmajor), int(w_kmajor)
     d.ldx, d.ldw, d.ldo, d.ldg, d.ldr, d.act, d.out_f32, d.tile, d.G = ldx, ldw, ldo, ldg, ldr, act, int(out_f32), tile, len(X)
-    tabs = [_tab(t) for t in (X, W, bias, out, pre, gate, resid, rowsum)]
-    for name, t in zip(("X", "W", "bias", "out", "pre", "gate", "resid", "rowsum"), tabs):
+    tabs = [_tab(t) for t in (X, W, bias, out, pre, gate, resid, rowsum, ws)]
+    for name, t in zip(("X", "W", "bias", "out", "pre", "gate", "resid", "rowsum", "ws"), tabs):
         if t is not None:
             setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
+    d.ws_bytes = 0 if ws is None else min(int(t.numel() * t.element_size()) for t in ws)
     _check(_L().hydra_op_gemm(C.byref(d), _stream()))
 
 
-def hydra_op_gemm_update(dtype, M, N, K, X, W, opt, p, m, v, w16, hp_rows, *, ldx, ldw, ldo, out=None, tile=0, rowsum=None):
+def hydra_op_gemm_split_k(M, N, K) -> int:
+    return int(_L().hydra_op_gemm_split_k(M, N, K))
+
+
+def hydra_op_gemm_split_ws_bytes(M, N, K, ldo) -> int:
+    return int(_L().hydra_op_gemm_split_ws_bytes(M, N, K, ldo))
+
+
+def hydra_op_gemm_update(dtype, M, N, K, X, W, opt, p, m, v, w16, hp_rows, *, ldx, ldw, ldo, out=None, tile=0, rowsum=None,
+                         ws=None):
     """Weight gradient dW[M,N] = sum_k X(k,m) W(k,n) with the optimizer step of hydra_op_optim in its epilogue."""
     d = hydra_gemm_desc()
     d.dtype, d.M, d.N, d.K, d.x_kmajor, d.w_kmajor = dtype, M, N, K, 0, 0
     d.ldx, d.ldw, d.ldo, d.ldg, d.ldr, d.act, d.out_f32, d.tile, d.G = ldx, ldw, ldo, 0, 0, EPI_NONE, 1, tile, len(X)
-    tabs = [_tab(t) for t in (X, W, out, rowsum)]
-    for name, t in zip(("X", "W", "out", "rowsum"), tabs):
+    tabs = [_tab(t) for t in (X, W, out, rowsum, ws)]
+    for name, t in zip(("X", "W", "out", "rowsum", "ws"), tabs):
         if t is not None:
             setattr(d, name, C.cast(t, C.POINTER(C.c_void_p)))
+    d.ws_bytes = 0 if ws is None else min(int(t.numel() * t.element_size()) for t in ws)
     flat = (C.c_double * (6 * len(p)))(*[float(x) for row in hp_rows for x in row])
     _check(_L().hydra_op_gemm_update(C.byref(d), opt, _tab(p), _tab(m), _tab(v), _tab(w16), flat, _stream()))
 

@@ -362,3 +362,68 @@ def test_bf16_cast_rounds_to_nearest_even(torch, ops):
     bits = x.view(np.uint32).astype(np.uint64)
     rounded = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16).astype(np.uint16)
     assert np.array_equal(d.view(torch.int16).cpu().numpy().view(np.uint16), rounded)
+
+
+def test_split_weight_gradient_matches_oracle_and_ignores_tile_and_group(torch, ops):
+    """A weight gradient with few output tiles and a long sum over the tokens is cut into S ranges of k (S from the
+    shape alone) when scratch is given: the result stays within the fp32 dot-product bound of the oracle, equals the
+    one-chain result up to that bound, and is bit-identical for every tile code, alone or inside a group; the update
+    epilogue applied by the second launch equals gradient-then-optimizer bit for bit; the bias gradient (row sums) too."""
+    r = np.random.default_rng(11)
+    M, N, K = 264, 200, 4100            # weight [M, N], K tokens (ragged everywhere)
+    S = ops.hydra_op_gemm_split_k(M, N, K)
+    assert S > 1 and ops.hydra_op_gemm_split_k(4096, 4096, 512) == 1 and ops.hydra_op_gemm_split_k(M, N, 1000) == 1
+    nbytes = ops.hydra_op_gemm_split_ws_bytes(M, N, K, _ld(N))
+    assert nbytes == (S * M * _ld(N) + S * M) * 4
+
+    def operands():
+        dy, x = r.normal(size=(K, M)), r.normal(size=(K, N))
+        a, av = _dev(torch, dy, 1)
+        b, bv = _dev(torch, x, 1)
+        return a, b, av, bv
+    dyd, xd, dyv, xv = operands()
+    o_dy, o_x, _, _ = operands()
+    want = dyv.T @ xv
+    bound = 2 * K * EPS32 * (np.abs(dyv).T @ np.abs(xv))
+
+    def ws(n):
+        return [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(n)]
+    ref = None
+    for tile in (0, 1, 2, 4):
+        for group in ([(dyd, xd)], [(o_dy, o_x), (dyd, xd), (o_dy, xd)]):
+            outs = [torch.zeros((M, _ld(N)), dtype=torch.float32, device="cuda") for _ in group]
+            rs = [torch.zeros(M, dtype=torch.float32, device="cuda") for _ in group]
+            ops.hydra_op_gemm(1, M, N, K, [g[0] for g in group], [g[1] for g in group], outs, x_kmajor=0, w_kmajor=0,
+                              ldx=dyd.shape[1], ldw=xd.shape[1], ldo=_ld(N), out_f32=True, tile=tile, rowsum=rs, ws=ws(len(group)))
+            torch.cuda.synchronize()
+            i = [j for j, g in enumerate(group) if g[0] is dyd and g[1] is xd][0]
+            mine = (outs[i].cpu().numpy(), rs[i].cpu().numpy())
+            if ref is None:
+                ref = mine
+            assert np.array_equal(ref[0], mine[0]) and np.array_equal(ref[1], mine[1]), f"tile {tile}, group of {len(group)}"
+    assert np.all(np.abs(ref[0][:, :N] - want) <= bound)
+    assert np.all(np.abs(ref[1] - dyv.sum(axis=0)) <= 2 * K * EPS32 * np.abs(dyv).sum(axis=0))
+    one = torch.zeros((M, _ld(N)), dtype=torch.float32, device="cuda")
+    ops.hydra_op_gemm(1, M, N, K, [dyd], [xd], [one], x_kmajor=0, w_kmajor=0, ldx=dyd.shape[1], ldw=xd.shape[1], ldo=_ld(N),
+                      out_f32=True)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(one.cpu().numpy()[:, :N] - ref[0][:, :N]) <= 2 * bound)
+    # update in the second launch == stored gradient followed by the optimizer kernel
+    n = M * _ld(N)
+    hp = [(1e-3, 0.9, 0.999, 1e-8, 10.0, 1000.0)]
+    P0 = torch.randn(n, device="cuda")
+    P1, P2 = P0.clone(), P0.clone()
+    M1, V1 = torch.rand(n, device="cuda") * 1e-3, torch.rand(n, device="cuda") * 1e-6
+    M2, V2 = M1.clone(), V1.clone()
+    W1 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    W2 = torch.zeros_like(W1)
+    G1 = torch.from_numpy(ref[0]).cuda().reshape(-1).contiguous()
+    ops.hydra_op_optim(1, n, [P1], [G1], [M1], [V1], [W1], hp)
+    ops.hydra_op_gemm_update(1, M, N, K, [dyd], [xd], 1, [P2], [M2], [V2], [W2], hp, ldx=dyd.shape[1], ldw=xd.shape[1],
+                             ldo=_ld(N), ws=ws(1))
+    torch.cuda.synchronize()
+    keep = np.zeros((M, _ld(N)), dtype=bool)
+    keep[:, :N] = True
+    keep = keep.reshape(-1)
+    for a, b in ((P1, P2), (M1, M2), (V1, V2), (W1.float(), W2.float())):
+        assert np.array_equal(a.cpu().numpy()[keep], b.cpu().numpy()[keep])
