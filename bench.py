@@ -85,7 +85,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
     ap.add_argument("--sequential-steps", type=int, default=3,
-                    help="steps of the one-shard-at-a-time model-parallel schedule timed beside (0 = skip)")
+                    help="steps of the sequential model-parallel and of the task-parallel schedule timed beside (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -165,6 +165,10 @@ def main():
         out["model_parallel_baseline"] = {"value": w.K * w.batch * args.sequential_steps / dts, "unit": "samples/s",
                                           "schedule": "one shard task at a time, one stream, ungrouped launches",
                                           "steps": args.sequential_steps}
+        dtt, _ = run(args.sequential_steps, H.SCHED_TASK_PARALLEL, False)
+        out["task_parallel_baseline"] = {"value": w.K * w.batch * args.sequential_steps / dtt, "unit": "samples/s",
+                                         "schedule": "one stream per model (4 streams), ungrouped launches",
+                                         "steps": args.sequential_steps}
     H.hydra_destroy(ctx)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(workload(args.workload))

@@ -17,6 +17,6 @@ from a seeded generator.
 from .configs import (  # noqa: F401
     KIND_MLP, KIND_ENCODER, KIND_DECODER, ACT_RELU, ACT_GELU,
     DTYPE_F32, DTYPE_BF16, OPT_SGD, OPT_ADAM,
-    Workload, workload, scaled_workload, n_workloads, INIT_SEED,
+    Workload, workload, scaled_workload, paper_shaped_workload, n_workloads, INIT_SEED,
 )
 from .data import make_data, mask_positions  # noqa: F401

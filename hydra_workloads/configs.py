@@ -118,6 +118,27 @@ def workload(i: int) -> Workload:
     raise IndexError(i)
 
 
+def paper_shaped_workload(name: str, K: int = 4) -> Workload:
+    """Workloads with the shapes the paper's own evaluation names (Evaluation, "Workloads"), on synthetic data:
+    "ffn_1p2m": a feed-forward network of about 1.2 M parameters (the model the paper compares sharded against
+    single-device training with); "bert_large_384": a BERT-Large-shaped encoder (24 blocks, d=1024, 16 heads,
+    FFN 4096, sequences of 384 tokens as in span-extraction fine-tuning).  K configurations differ in learning rate."""
+    if name == "ffn_1p2m":
+        # 784 -> 768 -> 768 -> 10: 784*768 + 768 + 768*768 + 768 + 768*10 + 10 = 1,201,162 parameters.  The paper
+        # names no activation; GeLU (smooth) lets single and double precision agree to rounding.
+        a = mlp_arch(2, 784, 768, 10, ACT_GELU, DTYPE_F32)
+        lrs = [0.1 * 0.5 ** k for k in range(K)]
+        return Workload("ffn_1p2m_f32_sgd", 5, [dict(a) for _ in range(K)], [hparams(OPT_SGD, lr) for lr in lrs],
+                        [[1, 2]] * K, 64, 0, 0, 12, 4, _DATA_SEED0 + 5, notes="3 epochs over 4 batches")
+    if name == "bert_large_384":
+        S = 384
+        a = transformer_arch(KIND_ENCODER, 24, 1024, 16, 4096, 30522, S, 0, DTYPE_BF16)
+        lrs = [5e-5, 3e-5, 2e-5, 1e-4][:K] + [1e-5 * (k + 1) for k in range(max(0, K - 4))]
+        return Workload("bert_large_384_bf16_adam", 6, [dict(a) for _ in range(K)], [hparams(OPT_ADAM, lr) for lr in lrs],
+                        [[6, 12, 18]] * K, 8, S, int(0.15 * S), 3, 3, _DATA_SEED0 + 6)
+    raise KeyError(name)
+
+
 def scaled_workload(i: int, **kw) -> Workload:
     """Reduced-size replicas of workload i that exercise the same code path
     (same kinds of layers, optimizer, number of shards, ragged sizes) at a cost

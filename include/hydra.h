@@ -66,7 +66,11 @@ enum { HYDRA_SCHED_SEQUENTIAL = 0,   /* model-major, one shard task at a time, o
        HYDRA_SCHED_SHARD_PARALLEL = 1,/* every ready shard task is issued; same-shaped tasks of
                                         different models share one grouped launch, the rest spread
                                         over streams (Approach, first paragraph)                     */
-       HYDRA_SCHED_EXPLICIT = 2 };   /* caller-given order for one step, replayed every step        */
+       HYDRA_SCHED_EXPLICIT = 2,     /* caller-given order for one step, replayed every step        */
+       HYDRA_SCHED_TASK_PARALLEL = 3 };/* every model is one task of its own (paper, Introduction,
+                                        "Motivation": task parallelism): its shard tasks run in model
+                                        order on the model's stream (model k on stream k mod n_streams),
+                                        nothing is grouped across models                             */
 
 /* Memory and streams come from the caller (PyTorch in the Python binding).  Every field may be
  * zero/NULL: the library then uses hipMalloc/hipFree and creates its own streams. */
@@ -148,6 +152,23 @@ hydra_status hydra_define_models(hydra_ctx* ctx, int K, const hydra_arch* archs,
  * increasing interior layer-unit indices (paper, Introduction: a shard is a contiguous piece of the
  * model; Figure 1).  n_cuts = 0 keeps the model whole.  Calling it again re-cuts. */
 hydra_status hydra_shard(hydra_ctx* ctx, int model, const int32_t* cuts, int n_cuts);
+
+/* Automatic sharder (the step the paper names as next, Discussion: choosing the partition instead of taking it
+ * from the caller).  Cuts model `model` (-1: every model) into the fewest shards whose parameter, gradient and
+ * optimizer-state bytes each stay within max_shard_bytes and, among the partitions with that many shards, one
+ * that minimises the largest shard (contiguous partition of the layer units by dynamic programming).  With
+ * max_shard_bytes = 0 the model is cut into exactly n_shards balanced shards (n_shards >= 1, at most the number
+ * of layer units); otherwise n_shards is a lower bound (0 = none).  The cuts are applied as by hydra_shard and,
+ * for model >= 0, written to cuts_out (cap entries; n_cuts receives the count; both may be NULL).
+ * HYDRA_ERR_INVALID_ARG when one layer unit alone exceeds max_shard_bytes. */
+hydra_status hydra_auto_shard(hydra_ctx* ctx, int model, size_t max_shard_bytes, int n_shards, int32_t* cuts_out,
+                              int cap, int* n_cuts);
+
+/* Model selection (paper, Introduction, "Model Selection Integration"): a model marked inactive is left out of
+ * the following epochs (its tasks are not scheduled, its state stays where it is and can still be read); the
+ * other models' results do not change by a bit.  Every model starts active.  An EXPLICIT schedule lists the
+ * tasks of the active models only. */
+hydra_status hydra_set_active(hydra_ctx* ctx, int model, int active);
 
 /* The training data, shared by all models, copied to the device.
  *  MLP:         inputs fp32 [n_batches, B, d_in]; targets int32 [n_batches, B]; target_pos NULL;

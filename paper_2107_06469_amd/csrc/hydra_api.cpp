@@ -185,6 +185,87 @@ hydra_status hydra_shard(hydra_ctx* c, int model, const int32_t* cuts, int n_cut
   HYDRA_CATCH(c)
 }
 
+// Smallest possible largest-shard cost of a contiguous partition of cost[0..U) into exactly S parts, and its cuts.
+static size_t balanced_partition(const std::vector<size_t>& cost, int S, std::vector<int32_t>& cuts) {
+  const int U = (int)cost.size();
+  std::vector<size_t> pre(U + 1, 0);
+  for (int i = 0; i < U; ++i) pre[i + 1] = pre[i] + cost[i];
+  const size_t INF = ~(size_t)0;
+  // best[s][i]: minimal largest part when the first i units form s parts
+  std::vector<std::vector<size_t>> best(S + 1, std::vector<size_t>(U + 1, INF));
+  std::vector<std::vector<int>> from(S + 1, std::vector<int>(U + 1, 0));
+  best[0][0] = 0;
+  for (int s = 1; s <= S; ++s)
+    for (int i = s; i <= U; ++i)
+      for (int j = s - 1; j < i; ++j) {
+        if (best[s - 1][j] == INF) continue;
+        const size_t v = std::max(best[s - 1][j], pre[i] - pre[j]);
+        if (v < best[s][i]) {  // strict: ties keep the earliest cut, which makes the result unique
+          best[s][i] = v;
+          from[s][i] = j;
+        }
+      }
+  cuts.clear();
+  for (int s = S, i = U; s > 1; --s) {
+    i = from[s][i];
+    cuts.insert(cuts.begin(), i);
+  }
+  return best[S][U];
+}
+
+hydra_status hydra_auto_shard(hydra_ctx* c, int model, size_t max_shard_bytes, int n_shards, int32_t* cuts_out, int cap,
+                              int* n_cuts) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "define models before sharding them");
+  if (model < -1 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  if (n_shards < 0 || (max_shard_bytes == 0 && n_shards < 1))
+    return c->fail(HYDRA_ERR_INVALID_ARG, "give a byte bound, a shard count, or both");
+  std::vector<std::vector<int32_t>> chosen(c->K);
+  for (int k = 0; k < c->K; ++k) {
+    if (model != -1 && model != k) continue;
+    const Model& m = c->models[k];
+    // bytes a shard holds per parameter: master, gradient, (Adam moments,) (bf16 working copy)
+    const size_t per = 8 + (m.hp.opt == HYDRA_OPT_ADAM ? 8 : 0) + (m.arch.dtype == HYDRA_DTYPE_BF16 ? 2 : 0);
+    std::vector<size_t> cost(m.n_units, 0);
+    for (const Tensor& t : m.tensors) cost[t.unit] += (t.n + 63) / 64 * 64 * per;
+    if (n_shards > m.n_units) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d has %d layer units, fewer than %d shards", k, m.n_units, n_shards);
+    int S = std::max(1, n_shards);
+    std::vector<int32_t> cuts;
+    size_t worst = balanced_partition(cost, S, cuts);
+    while (max_shard_bytes && worst > max_shard_bytes) {
+      if (S == m.n_units)
+        return c->fail(HYDRA_ERR_INVALID_ARG, "model %d: one layer unit alone holds %zu bytes, more than the bound of %zu", k, worst,
+                       max_shard_bytes);
+      worst = balanced_partition(cost, ++S, cuts);
+    }
+    chosen[k] = cuts;
+  }
+  if (model >= 0) {
+    if (n_cuts) *n_cuts = (int)chosen[model].size();
+    if (cuts_out) {
+      if (cap < (int)chosen[model].size())
+        return c->fail(HYDRA_ERR_BUFFER_TOO_SMALL, "need room for %zu cuts, got %d", chosen[model].size(), cap);
+      std::copy(chosen[model].begin(), chosen[model].end(), cuts_out);
+    }
+  }
+  for (int k = 0; k < c->K; ++k) {
+    if (model != -1 && model != k) continue;
+    hydra_status st = hydra_shard(c, k, chosen[k].data(), (int)chosen[k].size());
+    if (st != HYDRA_OK) return st;
+  }
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_set_active(hydra_ctx* c, int model, int active) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  c->models[model].active = active != 0;
+  return HYDRA_OK;
+}
+
 hydra_status hydra_set_data(hydra_ctx* c, const void* inputs, const int32_t* tgt_pos, const int32_t* targets, int n_batches,
                             int B, int S_or_d, int P) {
   if (!c) return HYDRA_ERR_INVALID_ARG;
@@ -308,7 +389,8 @@ hydra_status hydra_train_epoch(hydra_ctx* c, const hydra_schedule* sch, hydra_ep
   hydra_epoch_stats local{};
   st = run_epoch(c, plan, &local);
   if (st != HYDRA_OK) return st;
-  for (Model& m : c->models) m.t += c->n_batches;
+  for (Model& m : c->models)
+    if (m.active) m.t += c->n_batches;
   if (stats) *stats = local;
   return HYDRA_OK;
   HYDRA_CATCH(c)

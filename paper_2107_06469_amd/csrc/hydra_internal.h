@@ -125,6 +125,7 @@ struct Model {
   int loss_cap = 0;
   std::vector<float> losses;    // all steps so far (host)
   long t = 0;                   // optimizer steps taken
+  bool active = true;           // inactive models are left out of the epochs that follow (model selection)
 };
 
 struct Task {

@@ -38,10 +38,13 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
   if (c->recompute) maxg = std::min(maxg, c->ws_group);                  // ... and one activation workspace
   const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
   size_t total = 0;
-  for (int k = 0; k < K; ++k) total += 3 * c->models[k].shards.size();
+  for (int k = 0; k < K; ++k)
+    if (c->models[k].active) total += 3 * c->models[k].shards.size();
+  if (total == 0) return c->fail(HYDRA_ERR_BAD_STATE, "no model is active");
 
   if (sch->policy == HYDRA_SCHED_SEQUENTIAL) {
     for (int k = 0; k < K; ++k) {
+      if (!c->models[k].active) continue;
       const int S = (int)c->models[k].shards.size();
       for (int s = 0; s < S; ++s) plan.push_back({HYDRA_PHASE_F, {{k, s}}, 0});
       for (int s = S - 1; s >= 0; --s) {
@@ -52,6 +55,35 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
     return HYDRA_OK;
   }
 
+  if (sch->policy == HYDRA_SCHED_TASK_PARALLEL) {
+    // one task list per model (forward through its shards, then backward and update shard by shard), each on the
+    // model's own stream; the lists are interleaved position by position so the host feeds all streams evenly
+    int nstr = std::max(1, ns);
+    if (c->recompute) nstr = std::min(nstr, c->ws_streams);  // a stream's tasks share its activation workspace
+    std::vector<std::vector<Bucket>> lists;
+    size_t longest = 0;
+    for (int k = 0; k < K; ++k) {
+      if (!c->models[k].active) continue;
+      const int S = (int)c->models[k].shards.size(), str = (int)(lists.size() % nstr);
+      std::vector<Bucket> l;
+      for (int s = 0; s < S; ++s) l.push_back({HYDRA_PHASE_F, {{k, s}}, str});
+      for (int s = S - 1; s >= 0; --s) {
+        l.push_back({HYDRA_PHASE_B, {{k, s}}, str});
+        l.push_back({HYDRA_PHASE_U, {{k, s}}, str});
+      }
+      longest = std::max(longest, l.size());
+      lists.push_back(l);
+    }
+    if (c->spill && (int)c->slots.size() < (int)std::min<size_t>(lists.size(), nstr))
+      nstr = std::max<int>(1, (int)c->slots.size());  // one state slot per model in flight
+    for (auto& l : lists)
+      for (Bucket& b : l) b.stream %= nstr;
+    for (size_t pos = 0; pos < longest; ++pos)
+      for (const auto& l : lists)
+        if (pos < l.size()) plan.push_back(l[pos]);
+    return HYDRA_OK;
+  }
+
   if (sch->policy == HYDRA_SCHED_EXPLICIT) {
     if (!sch->tasks || sch->n_tasks <= 0) return c->fail(HYDRA_ERR_INVALID_ARG, "explicit schedule without tasks");
     std::set<Task> done;
@@ -59,6 +91,7 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
       Task t{sch->tasks[3 * i], sch->tasks[3 * i + 1], sch->tasks[3 * i + 2]};
       if (t.k < 0 || t.k >= K || t.s < 0 || t.s >= (int)c->models[t.k].shards.size() || t.ph < 0 || t.ph > 2)
         return c->fail(HYDRA_ERR_BAD_SCHEDULE, "task %d = (%d,%d,%d) does not exist", i, t.k, t.s, t.ph);
+      if (!c->models[t.k].active) return c->fail(HYDRA_ERR_BAD_SCHEDULE, "task %d belongs to model %d, which is inactive", i, t.k);
       if (done.count(t))
         return c->fail(HYDRA_ERR_BAD_SCHEDULE, "task %d: %s(%d,%d) listed twice", i, ph_name(t.ph), t.k, t.s);
       for (const Task& p : preds_of(c, t))
@@ -96,7 +129,7 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
   while (issued.size() < total) {
     std::vector<Task> ready, also_issued;
     for (int k = 0; k < K; ++k)
-      for (int s = 0; s < (int)c->models[k].shards.size(); ++s)
+      for (int s = 0; c->models[k].active && s < (int)c->models[k].shards.size(); ++s)
         for (int ph = 0; ph < 3; ++ph) {
           Task t{k, s, ph};
           if (issued.count(t)) continue;
@@ -216,6 +249,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
   // losses of this epoch
   for (int k = 0; k < c->K; ++k) {
     Model& m = c->models[k];
+    if (!m.active) continue;
     std::vector<float> l(c->n_batches, 0.f);
     if (!c->dry) HYDRA_HIP(c, hipMemcpy(l.data(), m.loss_dev, l.size() * 4, hipMemcpyDeviceToHost));
     m.losses.insert(m.losses.end(), l.begin(), l.end());

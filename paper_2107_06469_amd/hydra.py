@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libhydra.so")
 STATUS = {0: "HYDRA_OK", 1: "HYDRA_ERR_INVALID_ARG", 2: "HYDRA_ERR_BAD_STATE", 3: "HYDRA_ERR_BAD_SCHEDULE",
           4: "HYDRA_ERR_OOM_DEVICE", 5: "HYDRA_ERR_OOM_HOST", 6: "HYDRA_ERR_DEVICE", 7: "HYDRA_ERR_UNSUPPORTED",
           8: "HYDRA_ERR_BUFFER_TOO_SMALL"}
-SCHED_SEQUENTIAL, SCHED_SHARD_PARALLEL, SCHED_EXPLICIT = 0, 1, 2
+SCHED_SEQUENTIAL, SCHED_SHARD_PARALLEL, SCHED_EXPLICIT, SCHED_TASK_PARALLEL = 0, 1, 2, 3
 PHASE_F, PHASE_B, PHASE_U = 0, 1, 2
 
 
@@ -92,6 +92,8 @@ def lib() -> C.CDLL:
         L.hydra_tensor_count.argtypes = [vp, C.c_int, C.POINTER(C.c_int)]
         L.hydra_tensor_shape.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.hydra_shard_count.argtypes = [vp, C.c_int, C.POINTER(C.c_int)]
+        L.hydra_auto_shard.argtypes = [vp, C.c_int, C.c_size_t, C.c_int, i32p, C.c_int, C.POINTER(C.c_int)]
+        L.hydra_set_active.argtypes = [vp, C.c_int, C.c_int]
         L.hydra_profile_enable.argtypes = [vp, C.c_int]
         L.hydra_profile_read.argtypes = [vp, C.c_int, C.c_int, C.POINTER(hydra_kernel_profile)]
         L.hydra_last_error.argtypes = [vp]
@@ -187,6 +189,22 @@ def hydra_define_models(ctx: Context, archs: Sequence[Dict], grid: Sequence[Dict
 def hydra_shard(ctx: Context, model: int, cuts: Sequence[int]):
     a = _i32(list(cuts))
     _check(ctx.handle, lib().hydra_shard(ctx.handle, model, _ptr(a, C.POINTER(C.c_int32)), len(cuts)))
+
+
+def hydra_auto_shard(ctx: Context, model: int, max_shard_bytes: int = 0, n_shards: int = 0) -> Optional[List[int]]:
+    """Cuts `model` (-1: all) automatically; returns the chosen cut points for model >= 0."""
+    if model < 0:
+        _check(ctx.handle, lib().hydra_auto_shard(ctx.handle, model, max_shard_bytes, n_shards, None, 0, None))
+        return None
+    cuts = np.zeros(4096, dtype=np.int32)
+    n = C.c_int(0)
+    _check(ctx.handle, lib().hydra_auto_shard(ctx.handle, model, max_shard_bytes, n_shards,
+                                              cuts.ctypes.data_as(C.POINTER(C.c_int32)), cuts.size, C.byref(n)))
+    return cuts[:n.value].tolist()
+
+
+def hydra_set_active(ctx: Context, model: int, active: bool):
+    _check(ctx.handle, lib().hydra_set_active(ctx.handle, model, 1 if active else 0))
 
 
 def hydra_set_data(ctx: Context, inputs: np.ndarray, target_pos: Optional[np.ndarray], targets: np.ndarray):

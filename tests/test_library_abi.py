@@ -150,3 +150,74 @@ def test_read_buffers_report_required_size():
     st = H.lib().hydra_read_params(ctx.handle, 0, 8, None, 0, C.byref(n))
     assert st == 8 and n.value == 2560
     H.hydra_destroy(ctx)
+
+
+def _brute_force_partition(cost, S):
+    """Smallest possible largest part over all contiguous partitions into S parts (exhaustive)."""
+    from itertools import combinations
+    U, best = len(cost), None
+    for cuts in combinations(range(1, U), S - 1):
+        b = (0,) + cuts + (U,)
+        worst = max(sum(cost[b[i]:b[i + 1]]) for i in range(S))
+        best = worst if best is None else min(best, worst)
+    return best
+
+
+def test_automatic_sharder_balances_and_respects_the_byte_bound():
+    # transformer with a heavy first unit (embeddings) and last unit (output matrix): 6 blocks
+    w = scaled_workload(2, K=2, depths=[6, 6])
+    ctx = H.hydra_create(dry_run=True)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        shapes = H.hydra_tensor_shapes(ctx, 0)
+        per = 18                                     # master, gradient, two Adam moments, bf16 copy
+        pad = [(r * c + 63) // 64 * 64 * per for r, c in shapes]
+        cost = [sum(pad[:2 + 12])] + [sum(pad[2 + 12 * l:14 + 12 * l]) for l in range(1, 5)] + [sum(pad[2 + 60:])]
+        for S in (1, 2, 3, 4, 6):
+            cuts = H.hydra_auto_shard(ctx, 0, n_shards=S)
+            assert len(cuts) == S - 1 and H.hydra_shard_count(ctx, 0) == S
+            b = [0] + cuts + [6]
+            worst = max(sum(cost[b[i]:b[i + 1]]) for i in range(S))
+            assert worst == _brute_force_partition(cost, S), (S, cuts)
+        # byte bound: fewest shards that respect it
+        bound = _brute_force_partition(cost, 3)
+        cuts = H.hydra_auto_shard(ctx, 0, max_shard_bytes=bound)
+        assert len(cuts) == 2
+        cuts = H.hydra_auto_shard(ctx, 0, max_shard_bytes=bound - 1)
+        assert len(cuts) >= 3
+        assert H.hydra_auto_shard(ctx, 1, max_shard_bytes=bound, n_shards=5) is not None and H.hydra_shard_count(ctx, 1) == 5
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_auto_shard(ctx, 0, max_shard_bytes=max(cost) - 1)
+        assert e.value.status == 1 and "one layer unit" in str(e.value)
+        with pytest.raises(H.HydraError):
+            H.hydra_auto_shard(ctx, 0, n_shards=7)
+        H.hydra_auto_shard(ctx, -1, n_shards=2)
+        assert H.hydra_shard_count(ctx, 0) == H.hydra_shard_count(ctx, 1) == 2
+    finally:
+        H.hydra_destroy(ctx)
+
+
+def test_task_parallel_plan_and_inactive_models():
+    w = workload(0)
+    d = make_data(w)
+    ctx = _dry(w, d)
+    try:
+        par = H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL)
+        task = H.hydra_train_epoch(ctx, H.SCHED_TASK_PARALLEL)
+        seq = H.hydra_train_epoch(ctx, H.SCHED_SEQUENTIAL)
+        assert task["grouped_tasks"] == 0 and task["launches"] == seq["launches"] > par["launches"]
+        H.hydra_set_active(ctx, 1, False)
+        H.hydra_set_active(ctx, 3, False)
+        half = H.hydra_train_epoch(ctx, H.SCHED_SEQUENTIAL)
+        assert half["launches"] * 2 == seq["launches"]
+        assert len(H.hydra_read_loss(ctx, 1)) == 3 * w.steps and len(H.hydra_read_loss(ctx, 0)) == 4 * w.steps
+        with pytest.raises(H.HydraError) as e:   # an explicit order may not name an inactive model
+            H.hydra_train_epoch(ctx, H.SCHED_EXPLICIT, [(1, 0, H.PHASE_F)])
+        assert e.value.status == 3
+        for k in (0, 2):
+            H.hydra_set_active(ctx, k, False)
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL)
+        assert e.value.status == 2
+    finally:
+        H.hydra_destroy(ctx)
