@@ -307,6 +307,25 @@ __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&v)[8]) {
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Streaming (non-temporal) store of 8 outputs: a large activation tensor is written once and read by a later
+// launch, long after these lines would have left the caches
+template <typename T>
+__device__ __forceinline__ void store8_stream(T* p, const float (&v)[8]);
+template <>
+__device__ __forceinline__ void store8_stream<float>(float* p, const float (&v)[8]) {
+  const f32x4 a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+  __builtin_nontemporal_store(a, reinterpret_cast<f32x4*>(p));
+  __builtin_nontemporal_store(b, reinterpret_cast<f32x4*>(p) + 1);
+}
+template <>
+__device__ __forceinline__ void store8_stream<bf16_t>(bf16_t* p, const float (&v)[8]) {
+  u32x4 w;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = (uint32_t)Elem<bf16_t>::from_f(v[2 * i]) | ((uint32_t)Elem<bf16_t>::from_f(v[2 * i + 1]) << 16);
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
+
 // Streaming load for data read once per launch (optimizer state): the non-temporal hint keeps it from
 // displacing the operand panels that other workgroups of the launch still re-read from L2.  (Stores keep
 // the default policy: non-temporal stores were measured to write 6 % more bytes.)
@@ -415,7 +434,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += b[e];
         }
-        if (pre) store8<T>(pre + (size_t)m * a.ldo + n, v);
+        if (pre) store8_stream<T>(pre + (size_t)m * a.ldo + n, v);
         if (gate) {
           float z[8];
           load8<T>(gate + (size_t)m * a.ldg + n, z);
@@ -438,7 +457,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
           for (int e = 0; e < 8; ++e) v[e] += z[e];
         }
         if (a.out_f32) store8<float>(static_cast<float*>(a.out[g]) + out_off + (size_t)m * a.ldo + n, v);
-        else store8<T>(static_cast<T*>(a.out[g]) + (size_t)m * a.ldo + n, v);
+        else store8_stream<T>(static_cast<T*>(a.out[g]) + (size_t)m * a.ldo + n, v);
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
