@@ -99,6 +99,10 @@ typedef struct {
                                   workspaces that fit the bound, and a backward task first runs the
                                   shard's forward again.  The arithmetic, and hence every bit of the
                                   result, is unchanged.  With a bound set, shard before hydra_set_data  */
+  int max_group;               /* largest number of same-shaped shard tasks of different models that share one
+                                  grouped launch under the shard-parallel and explicit schedules: 0 = as many
+                                  as are ready (at most 16), 1..16 = that many; the ready tasks beyond a group
+                                  go to the next compute stream.  Results do not depend on it           */
 } hydra_options;
 
 typedef struct {

@@ -33,6 +33,11 @@ hydra_status hydra_create(const hydra_options* opts, hydra_ctx** out) {
   }
   if (opts) c->opt = *opts;
   c->dry = c->opt.dry_run != 0;
+  if (c->opt.max_group < 0 || c->opt.max_group > hydra::MAXG) {
+    g_create_error = "hydra_create: max_group must be 0 (automatic) or 1..16";
+    delete c;
+    return HYDRA_ERR_INVALID_ARG;
+  }
   if (c->opt.n_streams < 0 || (c->opt.n_streams > 0 && !c->opt.streams && !c->dry) ||
       ((c->opt.dev_alloc == nullptr) != (c->opt.dev_free == nullptr))) {
     g_create_error = "hydra_create: inconsistent options (streams / allocator callbacks)";

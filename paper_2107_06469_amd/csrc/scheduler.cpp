@@ -36,6 +36,7 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
   const int K = c->K;
   int maxg = c->spill ? std::min(MAXG, spill_max_group(c)) : MAXG;  // a group holds one slot per member
   if (c->recompute) maxg = std::min(maxg, c->ws_group);                  // ... and one activation workspace
+  if (c->opt.max_group > 0) maxg = std::min(maxg, c->opt.max_group);
   const int ns = c->dry ? std::max(1, c->opt.n_streams) : (int)c->streams.size();
   size_t total = 0;
   for (int k = 0; k < K; ++k)

@@ -38,7 +38,7 @@ class hydra_options(C.Structure):
     _fields_ = [("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("user", C.c_void_p),
                 ("streams", C.POINTER(C.c_void_p)), ("n_streams", C.c_int),
                 ("device_budget_bytes", C.c_size_t), ("host_budget_bytes", C.c_size_t), ("dry_run", C.c_int), ("keep_grads", C.c_int),
-                ("activation_budget_bytes", C.c_size_t)]
+                ("activation_budget_bytes", C.c_size_t), ("max_group", C.c_int)]
 
 
 class hydra_arch(C.Structure):
@@ -125,7 +125,7 @@ class Context:
 
 def hydra_create(n_streams: int = 4, dry_run: bool = False, use_torch: bool = True,
                  device_budget_bytes: int = 0, host_budget_bytes: int = 0, keep_grads: bool = False,
-                 activation_budget_bytes: int = 0) -> Context:
+                 activation_budget_bytes: int = 0, max_group: int = 0) -> Context:
     """keep_grads: store every gradient and apply all updates in the update task (needed by hydra_read_grads).
     use_torch: device memory comes from torch's allocator and streams are torch.cuda.Stream objects."""
     opts = hydra_options()
@@ -134,6 +134,7 @@ def hydra_create(n_streams: int = 4, dry_run: bool = False, use_torch: bool = Tr
     opts.host_budget_bytes = host_budget_bytes
     opts.keep_grads = 1 if keep_grads else 0
     opts.activation_budget_bytes = activation_budget_bytes
+    opts.max_group = max_group
     keep: Dict = {}
     if dry_run:
         opts.n_streams = n_streams
@@ -310,11 +311,12 @@ def hydra_profile_read(ctx: Context, reset: bool = True) -> Dict[str, Dict]:
 
 
 def train_workload(w, data, policy: int = SCHED_SHARD_PARALLEL, n_streams: int = 4, epochs: int = 1, tasks=None,
-                   cuts=None, device_budget_bytes: int = 0, keep_grads: bool = False, activation_budget_bytes: int = 0):
+                   cuts=None, device_budget_bytes: int = 0, keep_grads: bool = False, activation_budget_bytes: int = 0,
+                   max_group: int = 0):
     """Convenience used by tests and the benchmark: runs a hydra_workloads.Workload through the
     boundary and returns ({model: (losses, params)}, [stats per epoch])."""
     ctx = hydra_create(n_streams=n_streams, device_budget_bytes=device_budget_bytes, keep_grads=keep_grads,
-                       activation_budget_bytes=activation_budget_bytes)
+                       activation_budget_bytes=activation_budget_bytes, max_group=max_group)
     try:
         hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
         for k in range(w.K):
