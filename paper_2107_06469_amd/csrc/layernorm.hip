@@ -197,16 +197,27 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const LnBwdArgs a) {
   }
 }
 
-// dgamma[col] = sum_b part[b][0][col], dbeta[col] = sum_b part[b][1][col], b ascending
+// dgamma[col] = sum_b part[b][0][col], dbeta[col] = sum_b part[b][1][col].  A workgroup owns 16 columns; thread
+// (w, col) adds the w-th of 16 contiguous ranges of b in ascending order and the 16 range sums are then added in
+// ascending w: a fixed order that depends on the number of row blocks only.
 __global__ __launch_bounds__(256) void ln_reduce_kernel(const LnBwdArgs a, int nblocks) {
-  const int g = blockIdx.y;
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= 2 * a.d) return;
+  __shared__ float sh[16][17];
+  const int g = blockIdx.y, cl = threadIdx.x & 15, w = threadIdx.x >> 4;
+  const int j = blockIdx.x * 16 + cl, n2 = 2 * a.d;
+  const int per = (nblocks + 15) / 16, b0 = w * per, b1 = min(nblocks, b0 + per);
   const float* part = a.part[g];
   float t = 0.f;
-  for (int b = 0; b < nblocks; ++b) t += part[(size_t)b * 2 * a.d + j];
-  if (j < a.d) a.dgamma[g][j] = t;
-  else a.dbeta[g][j - a.d] = t;
+  if (j < n2)
+    for (int b = b0; b < b1; ++b) t += part[(size_t)b * n2 + j];
+  sh[w][cl] = t;
+  __syncthreads();
+  if (w == 0 && j < n2) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += sh[i][cl];
+    if (j < a.d) a.dgamma[g][j] = s;
+    else a.dbeta[g][j - a.d] = s;
+  }
 }
 
 }  // namespace
@@ -251,7 +262,7 @@ hipError_t launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
   if (!ln_shape_ok(a.G, a.rows, a.d, a.ld)) return hipErrorInvalidValue;
   hipError_t e = a.dtype == GEMM_F32 ? ln_bwd_pick<float>(a, s) : ln_bwd_pick<bf16_t>(a, s);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(ln_reduce_kernel, dim3((2 * a.d + 255) / 256, a.G), dim3(256), 0, s, a, ln_bwd_blocks(a.rows));
+  hipLaunchKernelGGL(ln_reduce_kernel, dim3((2 * a.d + 15) / 16, a.G), dim3(256), 0, s, a, ln_bwd_blocks(a.rows));
   return hipGetLastError();
 }
 
