@@ -108,7 +108,7 @@ __device__ __forceinline__ uint4 pack_half(const f32x16& p, int x) {
 
 // ---- forward ---------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const AttnArgs a) {
   constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
   extern __shared__ uint4 lds[];
   uint4* tK = lds;             // [64][NCH]
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_fwd_kernel(const A
 
 // ---- backward, dq (also writes delta) ------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, DH == 64 ? 3 : 1) void attn_bwd_dq_kernel(const AttnBwdArgs a) {
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(const AttnBwdArgs a) {
   constexpr int NK = DH / 16, NC = DH / 32, NCH = DH / 8;
   extern __shared__ uint4 lds[];
   uint4* tK = lds;             // [64][NCH]
