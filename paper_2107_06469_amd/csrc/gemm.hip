@@ -396,6 +396,57 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
       for (int q = 0; q < 4; ++q)
         *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
             make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    if constexpr (UPD) {
+      // The optimizer state of a pass (8 rows of the band) depends on addresses only, so the loads of LA passes are
+      // issued together, ahead of the values they will be combined with: more bytes in flight per wave while the
+      // accumulators still travel through the patch.
+      constexpr int NP = 32 / RPP;
+      constexpr int LA = FM * FN <= 4 ? NP : 2;  // passes in flight (registers permitting)
+      static_assert(NP % LA == 0, "passes per band");
+      const OptimHp h = upd.hp[g];
+      wave_lds_sync();
+#pragma unroll
+      for (int p0 = 0; p0 < NP; p0 += LA) {
+        float pe[LA][8], me[LA][8], ve[LA][8];
+        size_t idx[LA];
+        bool ok[LA];
+#pragma unroll
+        for (int q = 0; q < LA; ++q) {
+          const int r = (p0 + q) * RPP + lane / LPR, c = (lane % LPR) * 8;
+          const int m = mrow0 + i * 32 + r, n = ncol0 + c;
+          ok[q] = m < a.M && n < a.N;  // N is a multiple of 8 here (checked by the launcher): full vectors only
+          idx[q] = (size_t)m * a.ldo + n;
+          if (ok[q]) {
+            load8_stream(upd.p[g] + idx[q], pe[q]);
+            if (upd.opt == 1) {
+              load8_stream(upd.m[g] + idx[q], me[q]);
+              load8_stream(upd.v[g] + idx[q], ve[q]);
+            }
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < LA; ++q) {
+          if (!ok[q]) continue;
+          const int r = (p0 + q) * RPP + lane / LPR, c = (lane % LPR) * 8;
+          float v[8];
+          load8<float>(&patch[r * SP + c], v);
+          if (upd.opt == 1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) optim_step<1>(pe[q][e], me[q][e], ve[q][e], v[e], h);
+            store8<float>(upd.m[g] + idx[q], me[q]);
+            store8<float>(upd.v[g] + idx[q], ve[q]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) optim_step<0>(pe[q][e], me[q][e], ve[q][e], v[e], h);
+          }
+          store8<float>(upd.p[g] + idx[q], pe[q]);
+          if (upd.w16[g]) store8<bf16_t>(upd.w16[g] + idx[q], pe[q]);
+          if (a.out[g]) store8<float>(static_cast<float*>(a.out[g]) + idx[q], v);
+        }
+      }
+      wave_lds_sync();
+      continue;
+    }
     wave_lds_sync();
     for (int p = 0; p < 32 / RPP; ++p) {
       const int r = p * RPP + lane / LPR, c = (lane % LPR) * 8;
@@ -404,30 +455,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
       float v[8];
       load8<float>(&patch[r * SP + c], v);
       const int cnt = a.N - n;  // >= 8: full vector
-      if constexpr (UPD) {
-        const size_t idx = (size_t)m * a.ldo + n;
-        const OptimHp h = upd.hp[g];
-        float* up = upd.p[g] + idx;
-        float* ug = a.out[g] ? static_cast<float*>(a.out[g]) + idx : nullptr;
-        bf16_t* uw = upd.w16[g] ? upd.w16[g] + idx : nullptr;
-        // N is a multiple of 8 here (checked by the launcher): every lane holds a full vector
-        float pe[8], me[8], ve[8];
-        load8_stream(up, pe);
-        if (upd.opt == 1) {
-          load8_stream(upd.m[g] + idx, me);
-          load8_stream(upd.v[g] + idx, ve);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
-          store8<float>(upd.m[g] + idx, me);
-          store8<float>(upd.v[g] + idx, ve);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
-        }
-        store8<float>(up, pe);
-        if (uw) store8<bf16_t>(uw, pe);
-        if (ug) store8<float>(ug, v);
-      } else if (cnt >= 8) {
+      if (cnt >= 8) {
         if (bias) {
           float b[8];
           load8<float>(bias + n, b);
