@@ -5,6 +5,9 @@ counter gives bytes per launch and the copy gives the counter's scale.
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT/fetch -- python3 -m paper_2107_06469_amd.traffic_probe
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT/write -- python3 -m paper_2107_06469_amd.traffic_probe
     python3 -m paper_2107_06469_amd.traffic_probe --summarise OUT/fetch OUT/write
+    rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 --output-format csv -d OUT/mfma \
+        -- python3 -m paper_2107_06469_amd.traffic_probe
+    python3 -m paper_2107_06469_amd.traffic_probe --mfma OUT/mfma
 
 Shapes are workload 1's (8 models, 4096 x 4096 layers, batch 512, bf16 with fp32 Adam state).
 The summary prints, per kernel, the mean counter value per launch (KiB), the copy's reading and the
@@ -94,12 +97,44 @@ def summarise(fetch_dir, write_dir):
         print(f"  {k:90s} {sum(d.values()) / 1e6:10.1f}")
 
 
+N_SIMD = 256 * 4          # SIMDs of the chip; one issues 1024 bf16 MFMA flops per clock
+N_XCD = 8                 # GRBM_GUI_ACTIVE comes back summed over the 8 XCDs' counters
+
+
+def mfma(dirname):
+    """Matrix-core occupancy from hardware counters: busy cycles of the MFMA pipes over the clock cycles the
+    kernel was active (the chip's own clock, whatever it ran at), the flops the counters saw, and the clock
+    itself (active cycles / dispatch duration)."""
+    per = defaultdict(lambda: defaultdict(list))
+    for path in glob.glob(os.path.join(dirname, "**", "*counter_collection.csv"), recursive=True):
+        with open(path, newline="") as f:
+            for r in csv.DictReader(f):
+                if "hydra" not in r["Kernel_Name"]:
+                    continue
+                d = per[_label(r["Kernel_Name"])]
+                d[r["Counter_Name"]].append(float(r["Counter_Value"]))
+                if r["Counter_Name"] == "GRBM_GUI_ACTIVE":
+                    d["ns"].append(float(r["End_Timestamp"]) - float(r["Start_Timestamp"]))
+    print(f"{'kernel':72s} {'us':>8s} {'clock GHz':>9s} {'MFMA busy %':>11s} {'TFLOP (counter)':>15s} {'TFLOP/s':>8s} {'of 2.5 PF':>9s}")
+    for k, d in sorted(per.items()):
+        mean = {c: sum(v) / len(v) for c, v in d.items()}
+        if not all(c in mean for c in ("GRBM_GUI_ACTIVE", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_INSTS_VALU_MFMA_MOPS_BF16", "ns")):
+            continue
+        act, busy, fl = mean["GRBM_GUI_ACTIVE"] / N_XCD, mean["SQ_VALU_MFMA_BUSY_CYCLES"], mean["SQ_INSTS_VALU_MFMA_MOPS_BF16"] * 512
+        rate = fl / (mean["ns"] * 1e-9) / 1e12
+        print(f"{k[:72]:72s} {mean['ns'] / 1e3:8.1f} {act / mean['ns']:9.2f} {100 * busy / (act * N_SIMD):11.1f} "
+              f"{fl / 1e12:15.4f} {rate:8.0f} {rate / 2500:9.3f}")
+
+
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--summarise", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"))
+    ap.add_argument("--mfma", metavar="DIR")
     a = ap.parse_args()
     if a.summarise:
         summarise(*a.summarise)
+    elif a.mfma:
+        mfma(a.mfma)
     else:
         run()
     sys.exit(0)
