@@ -202,11 +202,13 @@ def test_colsum(torch, ops, dtype):
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
-@pytest.mark.parametrize("shape", [(32, 10), (64, 1000), (24, 30522)])
+@pytest.mark.parametrize("shape", [(32, 10), (64, 1000), (24, 30522), (5, 8190), (7, 1003, "tight"), (3, 40000)])
 def test_softmax_cross_entropy(torch, ops, dtype, shape):
-    M, Cn = shape
+    """Rows of up to 32768 padded logits with aligned storage take the register-resident kernel (three sizes of it:
+    up to 1024, 8192, 32768); a row pitch that is not a multiple of 4 ("tight") and longer rows take the three-pass one."""
+    M, Cn = shape[:2]
     r = np.random.default_rng(Cn)
-    ldz = _ld(Cn)
+    ldz = Cn if len(shape) > 2 else _ld(Cn)
     y = r.integers(0, Cn, size=M).astype(np.int32)
     yd = torch.from_numpy(y).cuda()
     logits, dzs, rls, ls, wants = [], [], [], [], []
