@@ -673,6 +673,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_kernel(const GemmArgs a, con
 // step-0 fragments of the next stage are read while step 1 computes.  The sum over k is the same ascending chain of
 // 16-wide MFMA steps as in gemm_kernel, with the same k values in every lane, so both kernels give the same bits.
 __device__ __forceinline__ int swz4(int row) { return ((row >> 2) & 3) ^ (row & 2); }
+// chunk permutation of a 128-byte row (8 chunks): 16 consecutive rows, read at one chunk index, spread over all banks
+__device__ __forceinline__ int swz8(int row) { return ((row >> 1) & 3) | (((row & 1) ^ ((row >> 3) & 1)) << 2); }
 
 // 128-bit buffer descriptor (base, stride 0, size in bytes, raw dword format) for bytes [first, total) of a matrix;
 // reads beyond it return zero
@@ -696,10 +698,14 @@ __device__ __forceinline__ void load_to_lds_b128(u32x4 rs, unsigned lds_addr, un
 
 // One operand tile of ROWS rows in the ring: what a lane contributes to the direct loads of a sub-tile and where it
 // reads its MFMA fragments.  NW = waves of the workgroup; load i of wave w fills slots [(i*NW + w)*64, +64).
-template <bool KMAJ, int ROWS, int NW>
+// BKW = k per sub-tile: 32, or 64 (a k-contiguous row is then 128 contiguous bytes per load: whole cache lines).
+template <bool KMAJ, int ROWS, int NW, int BKW = 32>
 struct RingOperand {
-  static constexpr int NLD = ROWS * 4 / 64 / NW;  // loads per wave and sub-tile (a sub-tile is ROWS*4 slots either way)
-  static_assert(ROWS * 4 % (64 * NW) == 0, "tile rows must divide over the waves");
+  static constexpr int CPR = BKW / 8;                 // 16-byte chunks per k-contiguous row
+  static constexpr int NLD = ROWS * CPR / 64 / NW;    // loads per wave and sub-tile (a sub-tile is ROWS*CPR slots either way)
+  static_assert(ROWS * CPR % (64 * NW) == 0, "tile rows must divide over the waves");
+  static_assert(BKW == 32 || BKW == 64, "sub-tile depth");
+  static __device__ __forceinline__ int swz(int row) { return BKW == 32 ? swz4(row) : swz8(row); }
   u32x4 rs;
   unsigned voff[NLD];   // byte offset of the lane's chunk in sub-tile 0, relative to the descriptor's base
   int kofs[NLD];        // k (inside a sub-tile) of the lane's chunk: a chunk at or past K is loaded as zeros
@@ -708,17 +714,17 @@ struct RingOperand {
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int K, int wave, int lane) {
     if (KMAJ) {
       rs = rsrc_words(base, (long)row0 * ld * 2, (long)nrows * ld * 2);  // rows past the matrix read as zero
-      step = 64u;
+      step = 2u * BKW;
     } else {
       rs = rsrc_words(base, (long)row0 * 2, (long)K * ld * 2);           // k-rows past K read as zero
-      step = 64u * (unsigned)ld;
+      step = 2u * BKW * (unsigned)ld;
     }
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const int sl = (i * NW + wave) * 64 + lane;
       if (KMAJ) {
-        const int row = sl >> 2;
-        kofs[i] = ((sl & 3) ^ swz4(row)) * 8;
+        const int row = sl / CPR;
+        kofs[i] = ((sl % CPR) ^ swz(row)) * 8;
         voff[i] = ((unsigned)row * (unsigned)ld + (unsigned)kofs[i]) * 2u;
       } else {
         const int k = sl / (ROWS / 8), rc = (sl % (ROWS / 8)) ^ ((k & 3) << 2);
@@ -730,14 +736,14 @@ struct RingOperand {
   // nd-th load of sub-tile t into the operand's part of a stage at LDS byte address st
   __device__ __forceinline__ void issue(int nd, int t, unsigned st, int K, int wave) const {
     const int i = nd < NLD ? nd : 0;
-    load_to_lds_b128(rs, st + (unsigned)((i * NW + wave) * 64 * 16), t * 32 + kofs[i] < K ? voff[i] + (unsigned)t * step : 0xfffffff0u);
+    load_to_lds_b128(rs, st + (unsigned)((i * NW + wave) * 64 * 16), t * BKW + kofs[i] < K ? voff[i] + (unsigned)t * step : 0xfffffff0u);
   }
-  // byte offset inside the operand's part of a stage of the lane's fragment of rows [rowbase, rowbase+32), MFMA step 0
-  // (k-contiguous: step 1 has its own offset because of the XOR; k-slow: step 1 is 16 k-rows further on)
+  // byte offset inside the operand's part of a stage of the lane's fragment of rows [rowbase, rowbase+32) for MFMA step
+  // mfma_step of the sub-tile (k-contiguous: every step has its own offset because of the XOR; k-slow: 16 k-rows each)
   static __device__ __forceinline__ int frag_offset(int rowbase, int lane, int mfma_step) {
     if (KMAJ) {
       const int row = rowbase + (lane & 31);
-      return (row * 4 + ((2 * mfma_step + (lane >> 5)) ^ swz4(row))) * 16;
+      return (row * CPR + ((2 * mfma_step + (lane >> 5)) ^ swz(row))) * 16;
     }
     const int j = lane & 15, grp = lane >> 4, k = 16 * mfma_step + 8 * (grp >> 1) + (j >> 2);
     const int rc = rowbase / 8 + 2 * (grp & 1) + ((j & 3) >> 1);
@@ -757,14 +763,18 @@ struct RingOperand {
 
 // SPLITK: the grid holds a.split_k copies of every tile; copy sp sums the sp-th contiguous range of sub-tiles and
 // stores its fp32 partial tile at element offset sp*M*ldo of out (row sums at sp*M); splitk_finish_kernel adds them.
-template <int WM, int WN, int FM, int FN, int NS, bool X_KMAJ, bool W_KMAJ, bool UPD, bool SPLITK = false>
+// BK = 64 (with NS = 2): sub-tiles of 64 k, so that a load of a k-contiguous operand covers 128 contiguous bytes per
+// row; one barrier per sub-tile, before its last MFMA step, and the loads of sub-tile t+2 follow that barrier.
+template <int WM, int WN, int FM, int FN, int NS, bool X_KMAJ, bool W_KMAJ, bool UPD, bool SPLITK = false, int BK = 32>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a, const typename UpdSel<UPD>::type upd) {
   static_assert(!SPLITK || !UPD, "partial sums are stored plainly");
+  static_assert(BK == 32 || (BK == 64 && NS == 2), "ring shape");
   typedef bf16_t T;
-  constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN, BK = 32;
-  constexpr int STAGE = (BM + BN) * 4 * 16;  // bytes per stage: X part, then W part
-  typedef RingOperand<X_KMAJ, BM, NW> RX;
-  typedef RingOperand<W_KMAJ, BN, NW> RW;
+  constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN;
+  constexpr int XPART = BM * (BK / 8) * 16;          // bytes of the X part of a stage
+  constexpr int STAGE = (BM + BN) * (BK / 8) * 16;   // bytes per stage: X part, then W part
+  typedef RingOperand<X_KMAJ, BM, NW, BK> RX;
+  typedef RingOperand<W_KMAJ, BN, NW, BK> RW;
   constexpr int NL = RX::NLD + RW::NLD;
   extern __shared__ uint4 lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -800,7 +810,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
   auto load_one = [&](int t, int nd) {  // nd-th direct load of the range's sub-tile t
     const unsigned st = lds_base + (unsigned)((t % NS) * STAGE);
     if (nd < RX::NLD) ox_.issue(nd, kb + t, st, K_end, wave);
-    else ow_.issue(nd - RX::NLD, kb + t, st + (unsigned)(BM * 4 * 16), K_end, wave);
+    else ow_.issue(nd - RX::NLD, kb + t, st + (unsigned)XPART, K_end, wave);
   };
 
   f32x16 acc[FM][FN];
@@ -811,22 +821,27 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   const int lrow = lane & 31, lgrp = lane >> 5;
-  int fx[2][FM], fw[2][FN];  // fragment byte offsets inside a stage for MFMA step 0 / 1
+  constexpr int NSTEP = BK / 16;   // MFMA steps per sub-tile
+  int fx[NSTEP][FM], fw[NSTEP][FN];  // fragment byte offsets inside a stage per MFMA step
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
+  for (int s = 0; s < NSTEP; ++s) {
 #pragma unroll
     for (int i = 0; i < FM; ++i) fx[s][i] = RX::frag_offset((wm * FM + i) * 32, lane, s);
 #pragma unroll
-    for (int j = 0; j < FN; ++j) fw[s][j] = BM * 4 * 16 + RW::frag_offset((wn * FN + j) * 32, lane, s);
+    for (int j = 0; j < FN; ++j) fw[s][j] = XPART + RW::frag_offset((wn * FN + j) * 32, lane, s);
   }
-  constexpr int ALLOW = (NS - 2) * NL;  // loads of this wave that may still be in flight when the next sub-tile must have landed
-  static_assert(ALLOW < 64, "vmcnt field");
+  // loads of this wave that may still be in flight when the next sub-tile must have landed (BK = 64: none, the loads
+  // of the sub-tile after it are issued behind the barrier); in the prologue sub-tile 0 must have landed
+  constexpr int ALLOW = BK == 32 ? (NS - 2) * NL : 0;
+  constexpr int ALLOW0 = BK == 32 ? ALLOW : NL;
+  static_assert(ALLOW < 64 && ALLOW0 < 64, "vmcnt field");
   constexpr int WAIT_VM = (ALLOW & 15) | ((ALLOW >> 4) << 14) | (7 << 4);  // s_waitcnt vmcnt(ALLOW) lgkmcnt(0)
+  constexpr int WAIT_VM0 = (ALLOW0 & 15) | ((ALLOW0 >> 4) << 14) | (7 << 4) | (15 << 8);  // vmcnt(ALLOW0) only
 #pragma unroll
-  for (int t = 0; t < NS - 1; ++t)
+  for (int t = 0; t < (BK == 32 ? NS - 1 : 2); ++t)
 #pragma unroll
     for (int nd = 0; nd < NL; ++nd) load_one(t, nd);
-  __builtin_amdgcn_s_waitcnt(WAIT_VM | (15 << 8));
+  __builtin_amdgcn_s_waitcnt(WAIT_VM0);
   __builtin_amdgcn_s_barrier();
   uint4 xa[FM], wa[FN], xb[FM], wb[FN];
 #pragma unroll
@@ -867,10 +882,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
   for (int t = 0; t < nk; ++t) {
     const char* st = lds_c + (t % NS) * STAGE;
     const char* sn = lds_c + ((t + 1) % NS) * STAGE;
-    step(xa, wa, xb, wb, st, 1, t + NS - 1);
-    __builtin_amdgcn_s_waitcnt(WAIT_VM);
-    __builtin_amdgcn_s_barrier();
-    step(xb, wb, xa, wa, sn, 0, -1);
+    if constexpr (BK == 32) {
+      step(xa, wa, xb, wb, st, 1, t + NS - 1);
+      __builtin_amdgcn_s_waitcnt(WAIT_VM);
+      __builtin_amdgcn_s_barrier();
+      step(xb, wb, xa, wa, sn, 0, -1);
+    } else {
+      step(xa, wa, xb, wb, st, 1, -1);
+      step(xb, wb, xa, wa, st, 2, -1);
+      step(xa, wa, xb, wb, st, 3, -1);
+      __builtin_amdgcn_s_waitcnt(WAIT_VM);  // sub-tile t+1 (issued one sub-tile ago) has landed; own reads of stage t are done
+      __builtin_amdgcn_s_barrier();
+      step(xb, wb, xa, wa, sn, 0, t + 2);    // stage t is free: sub-tile t+2 goes there
+    }
   }
   if (do_rs && wn == 0) {
 #pragma unroll
@@ -949,7 +973,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArg
   }
 }
 
-struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages of 32 KB
+struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages of 32 KB (or 2 of 64 KB)
   static constexpr int WM = 2, WN = 4, FM = 4, FN = 2, NS = 4;
   static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NT = WM * WN * 64;
   static constexpr size_t LDS = (size_t)NS * (BM + BN) * 4 * 16;
@@ -957,9 +981,14 @@ struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages 
     int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
     return ((tiles + 7) / 8) * 8;
   }
+  // with both operands k-contiguous (forward) the ring is two stages of 64 k (same LDS bytes): measured 3-7 % faster;
+  // with one of them k-slow (its rows are 512 contiguous bytes already) the deeper ring of 32 k is level or better
   template <bool XK, bool WK>
   static hipError_t run1(const GemmArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, false>), dim3(grid_of(a)), dim3(NT), LDS, s, a, NoUpdate());
+    if constexpr (XK && WK)
+      hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, 2, XK, WK, false, false, 64>), dim3(grid_of(a)), dim3(NT), LDS, s, a, NoUpdate());
+    else
+      hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, false>), dim3(grid_of(a)), dim3(NT), LDS, s, a, NoUpdate());
     return hipGetLastError();
   }
   static hipError_t run(const GemmArgs& a, hipStream_t s) {
@@ -977,8 +1006,12 @@ struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages 
   }
   template <bool XK, bool WK, bool UPD>
   static hipError_t attr1() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, UPD>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+    if constexpr (XK && WK && !UPD)
+      return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, 2, XK, WK, false, false, 64>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+    else
+      return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, UPD>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
   }
   static hipError_t attr() {
     hipError_t e;
