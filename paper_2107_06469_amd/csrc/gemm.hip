@@ -389,6 +389,8 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
   const T* resid = static_cast<const T*>(a.resid[g]);
   const T* mul = static_cast<const T*>(a.mul[g]);
   const int act = a.act;
+  const bool plain_f32 = !UPD && a.out_f32 && !bias && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
+  const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
 #pragma unroll
@@ -401,54 +403,95 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
       // The optimizer state of a pass (8 rows of the band) depends on addresses only, so the loads of LA passes are
       // issued together, ahead of the values they will be combined with: more bytes in flight per wave while the
       // accumulators still travel through the patch.
+      // A lane takes 4 consecutive columns in two rows (RPP/2 apart) rather than 8 in one, so that each 16-byte
+      // load or store instruction of the wave covers whole contiguous row segments (FN*128 bytes per row).
       constexpr int NP = 32 / RPP;
       constexpr int LA = FM * FN <= 4 ? NP : 2;  // passes in flight (registers permitting)
-      static_assert(NP % LA == 0, "passes per band");
+      constexpr int LPR4 = FN * 8, RPH = 64 / LPR4;  // lanes per row with 4 columns each; rows per instruction
+      static_assert(NP % LA == 0 && RPH * 2 == RPP, "passes per band");
       const OptimHp h = upd.hp[g];
       wave_lds_sync();
 #pragma unroll
       for (int p0 = 0; p0 < NP; p0 += LA) {
-        float pe[LA][8], me[LA][8], ve[LA][8];
-        size_t idx[LA];
-        bool ok[LA];
+        f32x4 pe[LA][2], me[LA][2], ve[LA][2];
+        size_t idx[LA][2];
+        bool ok[LA][2];
 #pragma unroll
-        for (int q = 0; q < LA; ++q) {
-          const int r = (p0 + q) * RPP + lane / LPR, c = (lane % LPR) * 8;
-          const int m = mrow0 + i * 32 + r, n = ncol0 + c;
-          ok[q] = m < a.M && n < a.N;  // N is a multiple of 8 here (checked by the launcher): full vectors only
-          idx[q] = (size_t)m * a.ldo + n;
-          if (ok[q]) {
-            load8_stream(upd.p[g] + idx[q], pe[q]);
-            if (upd.opt == 1) {
-              load8_stream(upd.m[g] + idx[q], me[q]);
-              load8_stream(upd.v[g] + idx[q], ve[q]);
+        for (int q = 0; q < LA; ++q)
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            const int r = (p0 + q) * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
+            const int m = mrow0 + i * 32 + r, n = ncol0 + c;
+            ok[q][hf] = m < a.M && n < a.N;  // N is a multiple of 8 here (checked by the launcher): full vectors only
+            idx[q][hf] = (size_t)m * a.ldo + n;
+            if (ok[q][hf]) {
+              pe[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(upd.p[g] + idx[q][hf]));
+              if (upd.opt == 1) {
+                me[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(upd.m[g] + idx[q][hf]));
+                ve[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(upd.v[g] + idx[q][hf]));
+              }
             }
           }
-        }
 #pragma unroll
-        for (int q = 0; q < LA; ++q) {
-          if (!ok[q]) continue;
-          const int r = (p0 + q) * RPP + lane / LPR, c = (lane % LPR) * 8;
-          float v[8];
-          load8<float>(&patch[r * SP + c], v);
-          if (upd.opt == 1) {
+        for (int q = 0; q < LA; ++q)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) optim_step<1>(pe[q][e], me[q][e], ve[q][e], v[e], h);
-            store8_stream<float>(upd.m[g] + idx[q], me[q]);
-            store8_stream<float>(upd.v[g] + idx[q], ve[q]);
-          } else {
+          for (int hf = 0; hf < 2; ++hf) {
+            if (!ok[q][hf]) continue;
+            const int r = (p0 + q) * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
+            const float4 gv = *reinterpret_cast<const float4*>(&patch[r * SP + c]);
+            const float v[4] = {gv.x, gv.y, gv.z, gv.w};
+            float pp[4] = {pe[q][hf].x, pe[q][hf].y, pe[q][hf].z, pe[q][hf].w};
+            float mm[4] = {0.f, 0.f, 0.f, 0.f}, vv[4] = {0.f, 0.f, 0.f, 0.f};
+            const size_t ix = idx[q][hf];
+            if (upd.opt == 1) {
+              mm[0] = me[q][hf].x; mm[1] = me[q][hf].y; mm[2] = me[q][hf].z; mm[3] = me[q][hf].w;
+              vv[0] = ve[q][hf].x; vv[1] = ve[q][hf].y; vv[2] = ve[q][hf].z; vv[3] = ve[q][hf].w;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) optim_step<0>(pe[q][e], me[q][e], ve[q][e], v[e], h);
+              for (int e = 0; e < 4; ++e) optim_step<1>(pp[e], mm[e], vv[e], v[e], h);
+              const f32x4 mo = {mm[0], mm[1], mm[2], mm[3]}, vo = {vv[0], vv[1], vv[2], vv[3]};
+              __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(upd.m[g] + ix));
+              __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(upd.v[g] + ix));
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) optim_step<0>(pp[e], mm[e], vv[e], v[e], h);
+            }
+            const f32x4 po = {pp[0], pp[1], pp[2], pp[3]};
+            __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(upd.p[g] + ix));
+            if (upd.w16[g])
+              *reinterpret_cast<uint2*>(upd.w16[g] + ix) =
+                  make_uint2((uint32_t)Elem<bf16_t>::from_f(pp[0]) | ((uint32_t)Elem<bf16_t>::from_f(pp[1]) << 16),
+                             (uint32_t)Elem<bf16_t>::from_f(pp[2]) | ((uint32_t)Elem<bf16_t>::from_f(pp[3]) << 16));
+            if (a.out[g]) *reinterpret_cast<float4*>(static_cast<float*>(a.out[g]) + ix) = gv;
           }
-          store8_stream<float>(upd.p[g] + idx[q], pe[q]);
-          if (upd.w16[g]) store8<bf16_t>(upd.w16[g] + idx[q], pe[q]);
-          if (a.out[g]) store8<float>(static_cast<float*>(a.out[g]) + idx[q], v);
-        }
       }
       wave_lds_sync();
       continue;
     }
     wave_lds_sync();
+    if (plain_f32) {
+      // fp32 sums stored as they are (a gradient, or a partial sum of a split one): 4 consecutive columns per lane in
+      // two rows, so that each 16-byte store instruction of the wave covers contiguous row segments
+      constexpr int LPR4 = FN * 8, RPH = 64 / LPR4;
+      float* o = static_cast<float*>(a.out[g]) + out_off;
+#pragma unroll
+      for (int p = 0; p < 32 / RPP; ++p)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const int r = p * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
+          const int m = mrow0 + i * 32 + r, n = ncol0 + c;
+          if (m >= a.M || n >= a.N) continue;
+          const float4 v = *reinterpret_cast<const float4*>(&patch[r * SP + c]);
+          if (n + 4 <= a.N && vec4_ok) *reinterpret_cast<float4*>(o + (size_t)m * a.ldo + n) = v;
+          else {
+            const float e4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < a.N) o[(size_t)m * a.ldo + n + e] = e4[e];
+          }
+        }
+      wave_lds_sync();
+      continue;
+    }
     for (int p = 0; p < 32 / RPP; ++p) {
       const int r = p * RPP + lane / LPR, c = (lane % LPR) * 8;
       const int m = mrow0 + i * 32 + r, n = ncol0 + c;
@@ -928,41 +971,56 @@ struct SplitFinishArgs {
   bf16_t* w16[MAXG];
   OptimHp hp[MAXG];
 };
+// A thread takes 4 consecutive columns, so that every 16-byte access of a wave covers contiguous memory; the S
+// partial sums are all requested before the first is used and added in ascending order of s.
+constexpr int SPLIT_MAX = 8;
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArgs a) {
   const int g = blockIdx.y;
   const size_t plane = (size_t)a.M * a.ldo;
-  const int n8 = a.N / 8;  // N is a multiple of 8
-  const size_t total = (size_t)a.M * n8;
+  const int n4 = a.N / 4;  // N is a multiple of 8
+  const size_t total = (size_t)a.M * n4;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-    const int m = (int)(i / n8), n = (int)(i % n8) * 8;
+    const int m = (int)(i / n4), n = (int)(i % n4) * 4;
     const size_t idx = (size_t)m * a.ldo + n;
-    float v[8];
-    load8_stream(a.ws[g] + idx, v);
-    for (int s = 1; s < a.S; ++s) {
-      float w[8];
-      load8_stream(a.ws[g] + (size_t)s * plane + idx, w);
+    f32x4 part[SPLIT_MAX];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += w[e];
+    for (int s = 0; s < SPLIT_MAX; ++s)
+      if (s < a.S) part[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.ws[g] + (size_t)s * plane + idx));
+    f32x4 pv, mv, vv;
+    if (a.upd) {
+      pv = *reinterpret_cast<const f32x4*>(a.p[g] + idx);
+      if (a.opt == 1) {
+        mv = *reinterpret_cast<const f32x4*>(a.m[g] + idx);
+        vv = *reinterpret_cast<const f32x4*>(a.v[g] + idx);
+      }
     }
+    float v[4] = {part[0].x, part[0].y, part[0].z, part[0].w};
+#pragma unroll
+    for (int s = 1; s < SPLIT_MAX; ++s)
+      if (s < a.S) {
+        v[0] += part[s].x; v[1] += part[s].y; v[2] += part[s].z; v[3] += part[s].w;
+      }
     if (a.upd) {
       const OptimHp h = a.hp[g];
-      float pe[8], me[8], ve[8];
-      load8<float>(a.p[g] + idx, pe);
+      float pe[4] = {pv.x, pv.y, pv.z, pv.w}, me[4] = {0.f, 0.f, 0.f, 0.f}, ve[4] = {0.f, 0.f, 0.f, 0.f};
       if (a.opt == 1) {
-        load8<float>(a.m[g] + idx, me);
-        load8<float>(a.v[g] + idx, ve);
+        me[0] = mv.x; me[1] = mv.y; me[2] = mv.z; me[3] = mv.w;
+        ve[0] = vv.x; ve[1] = vv.y; ve[2] = vv.z; ve[3] = vv.w;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
-        store8<float>(a.m[g] + idx, me);
-        store8<float>(a.v[g] + idx, ve);
+        for (int e = 0; e < 4; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
+        *reinterpret_cast<float4*>(a.m[g] + idx) = make_float4(me[0], me[1], me[2], me[3]);
+        *reinterpret_cast<float4*>(a.v[g] + idx) = make_float4(ve[0], ve[1], ve[2], ve[3]);
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
+        for (int e = 0; e < 4; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
       }
-      store8<float>(a.p[g] + idx, pe);
-      if (a.w16[g]) store8<bf16_t>(a.w16[g] + idx, pe);
+      *reinterpret_cast<float4*>(a.p[g] + idx) = make_float4(pe[0], pe[1], pe[2], pe[3]);
+      if (a.w16[g])
+        *reinterpret_cast<uint2*>(a.w16[g] + idx) =
+            make_uint2((uint32_t)Elem<bf16_t>::from_f(pe[0]) | ((uint32_t)Elem<bf16_t>::from_f(pe[1]) << 16),
+                       (uint32_t)Elem<bf16_t>::from_f(pe[2]) | ((uint32_t)Elem<bf16_t>::from_f(pe[3]) << 16));
     }
-    if (a.out[g]) store8<float>(a.out[g] + idx, v);
+    if (a.out[g]) *reinterpret_cast<float4*>(a.out[g] + idx) = make_float4(v[0], v[1], v[2], v[3]);
   }
   if (a.rowsum[g] && blockIdx.x == 0) {
     const float* rs = a.ws[g] + (size_t)a.S * plane;
@@ -1100,6 +1158,7 @@ int split_of(int M, int N, int K) {
 hipError_t run_split(const GemmArgs& a, const GemmUpdate* u, int S, hipStream_t s) {
   GemmArgs b = a;
   SplitFinishArgs f{};
+  if (S > SPLIT_MAX) return hipErrorInvalidValue;
   f.M = a.M; f.N = a.N; f.ldo = a.ldo; f.S = S; f.G = a.G; f.upd = u != nullptr; f.opt = u ? u->opt : 0;
   const size_t plane = (size_t)a.M * a.ldo;
   for (int g = 0; g < a.G; ++g) {
