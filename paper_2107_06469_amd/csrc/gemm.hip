@@ -988,10 +988,10 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArg
       if (s < a.S) part[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.ws[g] + (size_t)s * plane + idx));
     f32x4 pv, mv, vv;
     if (a.upd) {
-      pv = *reinterpret_cast<const f32x4*>(a.p[g] + idx);
+      pv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.p[g] + idx));
       if (a.opt == 1) {
-        mv = *reinterpret_cast<const f32x4*>(a.m[g] + idx);
-        vv = *reinterpret_cast<const f32x4*>(a.v[g] + idx);
+        mv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.m[g] + idx));
+        vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.v[g] + idx));
       }
     }
     float v[4] = {part[0].x, part[0].y, part[0].z, part[0].w};
@@ -1008,13 +1008,15 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArg
         ve[0] = vv.x; ve[1] = vv.y; ve[2] = vv.z; ve[3] = vv.w;
 #pragma unroll
         for (int e = 0; e < 4; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
-        *reinterpret_cast<float4*>(a.m[g] + idx) = make_float4(me[0], me[1], me[2], me[3]);
-        *reinterpret_cast<float4*>(a.v[g] + idx) = make_float4(ve[0], ve[1], ve[2], ve[3]);
+        const f32x4 mo = {me[0], me[1], me[2], me[3]}, vo = {ve[0], ve[1], ve[2], ve[3]};
+        __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(a.m[g] + idx));
+        __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(a.v[g] + idx));
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
       }
-      *reinterpret_cast<float4*>(a.p[g] + idx) = make_float4(pe[0], pe[1], pe[2], pe[3]);
+      const f32x4 po = {pe[0], pe[1], pe[2], pe[3]};
+      __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(a.p[g] + idx));
       if (a.w16[g])
         *reinterpret_cast<uint2*>(a.w16[g] + idx) =
             make_uint2((uint32_t)Elem<bf16_t>::from_f(pe[0]) | ((uint32_t)Elem<bf16_t>::from_f(pe[1]) << 16),

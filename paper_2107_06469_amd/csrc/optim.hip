@@ -21,25 +21,30 @@ __device__ __forceinline__ bf16_t f2bf(float v) {
 // one 16-byte vector of each state array
 template <int OPT, bool W16>
 __device__ __forceinline__ void update4(const OptimArgs& a, int g, size_t i, const OptimHp& h) {
-  float4* __restrict__ p = reinterpret_cast<float4*>(a.p[g]);
-  const float4* __restrict__ gr = reinterpret_cast<const float4*>(a.g[g]);
-  float4 pv = p[i];
-  const float4 gv = gr[i];
+  // every array is read once and written once per launch: streaming (non-temporal) accesses
+  typedef __attribute__((ext_vector_type(4))) float f32x4;
+  f32x4* __restrict__ p = reinterpret_cast<f32x4*>(a.p[g]);
+  const f32x4* __restrict__ gr = reinterpret_cast<const f32x4*>(a.g[g]);
+  const f32x4 pv = __builtin_nontemporal_load(p + i);
+  const f32x4 gv = __builtin_nontemporal_load(gr + i);
   float pe[4] = {pv.x, pv.y, pv.z, pv.w};
   const float ge[4] = {gv.x, gv.y, gv.z, gv.w};
   float me[4] = {0.f, 0.f, 0.f, 0.f}, ve[4] = {0.f, 0.f, 0.f, 0.f};
   if (OPT == 1) {
-    const float4 mv = reinterpret_cast<const float4*>(a.m[g])[i], vv = reinterpret_cast<const float4*>(a.v[g])[i];
+    const f32x4 mv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.m[g]) + i);
+    const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.v[g]) + i);
     me[0] = mv.x; me[1] = mv.y; me[2] = mv.z; me[3] = mv.w;
     ve[0] = vv.x; ve[1] = vv.y; ve[2] = vv.z; ve[3] = vv.w;
   }
 #pragma unroll
   for (int e = 0; e < 4; ++e) optim_step<OPT>(pe[e], me[e], ve[e], ge[e], h);
   if (OPT == 1) {
-    reinterpret_cast<float4*>(a.m[g])[i] = make_float4(me[0], me[1], me[2], me[3]);
-    reinterpret_cast<float4*>(a.v[g])[i] = make_float4(ve[0], ve[1], ve[2], ve[3]);
+    const f32x4 mo = {me[0], me[1], me[2], me[3]}, vo = {ve[0], ve[1], ve[2], ve[3]};
+    __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(a.m[g]) + i);
+    __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(a.v[g]) + i);
   }
-  p[i] = make_float4(pe[0], pe[1], pe[2], pe[3]);
+  const f32x4 po = {pe[0], pe[1], pe[2], pe[3]};
+  __builtin_nontemporal_store(po, p + i);
   if (W16)
     reinterpret_cast<uint2*>(a.w16[g])[i] = make_uint2((uint32_t)f2bf(pe[0]) | ((uint32_t)f2bf(pe[1]) << 16),
                                                        (uint32_t)f2bf(pe[2]) | ((uint32_t)f2bf(pe[3]) << 16));
