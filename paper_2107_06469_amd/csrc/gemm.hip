@@ -389,8 +389,9 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
   const T* resid = static_cast<const T*>(a.resid[g]);
   const T* mul = static_cast<const T*>(a.mul[g]);
   const int act = a.act;
-  const bool plain_f32 = !UPD && a.out_f32 && !bias && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
-  const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0;
+  const bool plain_f32 = !UPD && a.out_f32 && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
+  const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0 &&
+                      (reinterpret_cast<uintptr_t>(bias) & 15) == 0;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
 #pragma unroll
@@ -480,13 +481,18 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
           const int r = p * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
           const int m = mrow0 + i * 32 + r, n = ncol0 + c;
           if (m >= a.M || n >= a.N) continue;
-          const float4 v = *reinterpret_cast<const float4*>(&patch[r * SP + c]);
-          if (n + 4 <= a.N && vec4_ok) *reinterpret_cast<float4*>(o + (size_t)m * a.ldo + n) = v;
-          else {
+          float4 v = *reinterpret_cast<const float4*>(&patch[r * SP + c]);
+          if (n + 4 <= a.N && vec4_ok) {
+            if (bias) {
+              const float4 bv = *reinterpret_cast<const float4*>(bias + n);
+              v.x += bv.x; v.y += bv.y; v.z += bv.z; v.w += bv.w;
+            }
+            *reinterpret_cast<float4*>(o + (size_t)m * a.ldo + n) = v;
+          } else {
             const float e4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (n + e < a.N) o[(size_t)m * a.ldo + n + e] = e4[e];
+              if (n + e < a.N) o[(size_t)m * a.ldo + n + e] = e4[e] + (bias ? bias[n + e] : 0.f);
           }
         }
       wave_lds_sync();
