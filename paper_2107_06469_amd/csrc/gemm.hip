@@ -326,16 +326,6 @@ __device__ __forceinline__ void store8_stream<bf16_t>(bf16_t* p, const float (&v
   __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
 }
 
-// Streaming load for data read once per launch (optimizer state): the non-temporal hint keeps it from
-// displacing the operand panels that other workgroups of the launch still re-read from L2.  The fp32 state is
-// stored back with the same hint for the same reason: on its own that is slower (about 6 % more bytes reach
-// memory), but with a k-loop of 512 the launch gets 3-5 % faster because the k-loops find their operands in L2.
-__device__ __forceinline__ void load8_stream(const float* p, float (&v)[8]) {
-  const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p) + 1);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-
 // Scheduling hint for one MFMA step: spread NR LDS reads and NMEM memory operations (mask MEMMASK:
 // 0x200 = LDS write, 0x020 = global read) evenly between the step's NM MFMAs.
 template <int NM, int NR, int NMEM, int MEMMASK>
@@ -406,6 +396,8 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
       // accumulators still travel through the patch.
       // A lane takes 4 consecutive columns in two rows (RPP/2 apart) rather than 8 in one, so that each 16-byte
       // load or store instruction of the wave covers whole contiguous row segments (FN*128 bytes per row).
+      // The state is read once and written once per launch: loads and fp32 stores carry the non-temporal hint, so that
+      // the lines do not displace the operand panels that other workgroups' k-loops still re-read from L2.
       constexpr int NP = 32 / RPP;
       constexpr int LA = FM * FN <= 4 ? NP : 2;  // passes in flight (registers permitting)
       constexpr int LPR4 = FN * 8, RPH = 64 / LPR4;  // lanes per row with 4 columns each; rows per instruction
