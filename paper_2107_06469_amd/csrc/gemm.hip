@@ -58,6 +58,13 @@ struct Elem<bf16_t> {
     return __builtin_bit_cast(bf16_t, h);
   }
 };
+// two floats -> two bf16 in one word (round to nearest even): one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 // zero the elements of a 16-byte chunk at positions >= valid
 template <typename T>
@@ -303,7 +310,7 @@ __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&v)[8]) {
   uint32_t w[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    w[i] = (uint32_t)Elem<bf16_t>::from_f(v[2 * i]) | ((uint32_t)Elem<bf16_t>::from_f(v[2 * i + 1]) << 16);
+    w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
@@ -322,7 +329,7 @@ __device__ __forceinline__ void store8_stream<bf16_t>(bf16_t* p, const float (&v
   u32x4 w;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    w[i] = (uint32_t)Elem<bf16_t>::from_f(v[2 * i]) | ((uint32_t)Elem<bf16_t>::from_f(v[2 * i + 1]) << 16);
+    w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
   __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
 }
 
@@ -452,8 +459,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
             __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(upd.p[g] + ix));
             if (upd.w16[g])
               *reinterpret_cast<uint2*>(upd.w16[g] + ix) =
-                  make_uint2((uint32_t)Elem<bf16_t>::from_f(pp[0]) | ((uint32_t)Elem<bf16_t>::from_f(pp[1]) << 16),
-                             (uint32_t)Elem<bf16_t>::from_f(pp[2]) | ((uint32_t)Elem<bf16_t>::from_f(pp[3]) << 16));
+                  make_uint2(pack_bf16x2(pp[0], pp[1]), pack_bf16x2(pp[2], pp[3]));
             if (a.out[g]) *reinterpret_cast<float4*>(static_cast<float*>(a.out[g]) + ix) = gv;
           }
       }
@@ -1017,8 +1023,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArg
       __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(a.p[g] + idx));
       if (a.w16[g])
         *reinterpret_cast<uint2*>(a.w16[g] + idx) =
-            make_uint2((uint32_t)Elem<bf16_t>::from_f(pe[0]) | ((uint32_t)Elem<bf16_t>::from_f(pe[1]) << 16),
-                       (uint32_t)Elem<bf16_t>::from_f(pe[2]) | ((uint32_t)Elem<bf16_t>::from_f(pe[3]) << 16));
+            make_uint2(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]));
     }
     if (a.out[g]) *reinterpret_cast<float4*>(a.out[g] + idx) = make_float4(v[0], v[1], v[2], v[3]);
   }

@@ -19,6 +19,13 @@ __device__ __forceinline__ bf16_t f2bf(float v) {
   __bf16 h = (__bf16)v;
   return __builtin_bit_cast(bf16_t, h);
 }
+// two floats -> two bf16 in one word (round to nearest even): one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 template <typename T>
 __device__ __forceinline__ void ld8(const T* p, float (&v)[8]);
@@ -48,7 +55,7 @@ template <>
 __device__ __forceinline__ void st8<bf16_t>(bf16_t* p, const float (&v)[8]) {
   uint32_t w[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+  for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
