@@ -1089,6 +1089,44 @@ struct DmaBig {  // 256 x 256, 8 waves (2 x 4, each 128 x 64), ring of 4 stages 
     return attr1<false, false, true>();
   }
 };
+// Measured against the register-staged 128 x 128 tile on one model's 8192-token products (d = 1024): forward 8-11 %
+// faster, input gradient 21-31 %, weight gradient 23-46 %; with the update in the epilogue (8 x [4096 x 4096], 512
+// tokens) 720 -> 663 us per launch.
+struct DmaMid {  // 128 x 128, 4 waves (2 x 2, each 64 x 64), ring of 4 stages of 16 KB: two workgroups per CU
+  static constexpr int WM = 2, WN = 2, FM = 2, FN = 2, NS = 4;
+  static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NT = WM * WN * 64;
+  static constexpr size_t LDS = (size_t)NS * (BM + BN) * 4 * 16;
+  template <bool XK, bool WK>
+  static hipError_t run1(const GemmArgs& a, hipStream_t s) {
+    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, false>), dim3((tiles + 7) / 8 * 8), dim3(NT), LDS, s, a, NoUpdate());
+    return hipGetLastError();
+  }
+  static hipError_t run(const GemmArgs& a, hipStream_t s) {
+    if (a.x_kmajor) return a.w_kmajor ? run1<true, true>(a, s) : run1<true, false>(a, s);
+    return a.w_kmajor ? run1<false, true>(a, s) : run1<false, false>(a, s);
+  }
+  static hipError_t run_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s) {
+    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN) * a.G;
+    hipLaunchKernelGGL((gemm_dma_kernel<WM, WN, FM, FN, NS, false, false, true>), dim3((tiles + 7) / 8 * 8), dim3(NT), LDS, s, a, u);
+    return hipGetLastError();
+  }
+  template <bool XK, bool WK>
+  static hipError_t attr1() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, XK, WK, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
+  }
+  static hipError_t attr() {
+    hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<WM, WN, FM, FN, NS, false, false, true>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS)) != hipSuccess)
+      return e;
+    if ((e = attr1<true, true>()) != hipSuccess) return e;
+    if ((e = attr1<true, false>()) != hipSuccess) return e;
+    if ((e = attr1<false, true>()) != hipSuccess) return e;
+    return attr1<false, false>();
+  }
+};
 // The direct-to-LDS kernel takes bf16 problems.  A k-contiguous operand needs K to be a multiple of 8 (a 16-byte
 // chunk is then entirely inside or outside the matrix); an operand with k as the slow index is addressed from the
 // tile's first element with 32-bit offsets, so its K x ld bytes must stay below 2 GiB.
@@ -1215,6 +1253,7 @@ hipError_t dispatch_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s
   // state while the other runs its k-loop, which the 256x256 tile (one workgroup per CU) cannot do.
   if (!a.tile && tile == 1 && a.K < 2048) tile = 2;
   if (tile == 1 && dma_eligible(a)) return DmaBig::run_update(a, u, s);
+  if (tile == 2 && dma_eligible(a)) return DmaMid::run_update(a, u, s);
   switch (tile) {
     case 1:
     case 4: return Tiles<T>::Big::run_update(a, u, s);
@@ -1229,6 +1268,7 @@ hipError_t dispatch(const GemmArgs& a, hipStream_t s) {
   if (const int S = split_for(a); S > 1) return run_split(a, nullptr, S, s);
   const int tile = choose_tile(a);
   if (tile == 1 && dma_eligible(a)) return DmaBig::run(a, s);
+  if (tile == 2 && dma_eligible(a)) return DmaMid::run(a, s);
   switch (tile) {
     case 1:
     case 4: return Tiles<T>::Big::run(a, s);
@@ -1251,6 +1291,7 @@ hipError_t init_tiles() {
 hipError_t gemm_init() {
   hipError_t e = DmaBig::attr();
   if (e != hipSuccess) return e;
+  if ((e = DmaMid::attr()) != hipSuccess) return e;
   e = init_tiles<bf16_t>();
   return e != hipSuccess ? e : init_tiles<float>();
 }
