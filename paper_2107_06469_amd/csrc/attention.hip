@@ -104,6 +104,39 @@ __device__ __forceinline__ uint4 read_rows(const uint4* tile, int row, int kc) {
   return tile[row * NCH + (kc ^ (row & (NCH - 1)))];
 }
 
+// The same two reads with the lane's part of the address computed once: for rows row0 + l%32 (row0 a multiple of
+// NCH) the XOR term depends on the lane alone, so a tile's later row blocks, and a second tile that follows the first
+// in LDS, are constant offsets from one pointer per chunk (they go into the instruction's offset field).
+template <int DH>
+__device__ __forceinline__ const uint4* rows_base(const uint4* tile, int li, int kc) {
+  constexpr int NCH = DH / 8;
+  return tile + li * NCH + (kc ^ (li & (NCH - 1)));
+}
+// byte addresses of read_cols' two reads (rows r0 and r0 + 8) for row0 = 0; row0 (a multiple of 16) adds
+// row0 * NCH * 16 to both
+struct ColsBase { unsigned a0, a1; };
+template <int DH>
+__device__ __forceinline__ ColsBase cols_base(const uint4* tile, int col0, int lane) {
+  constexpr int NCH = DH / 8;
+  const int j = lane & 15, grp = lane >> 4;
+  const int col = col0 + 16 * (grp & 1) + 4 * (j & 3), kc = col >> 3, half = (col >> 2) & 1;
+  const int r0 = 4 * (grp >> 1) + (j >> 2), r1 = r0 + 8;
+  const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tile);
+  ColsBase b;
+  b.a0 = base + (unsigned)((r0 * NCH + (kc ^ (r0 & (NCH - 1)))) * 16 + half * 8);
+  b.a1 = base + (unsigned)((r1 * NCH + (kc ^ (r1 & (NCH - 1)))) * 16 + half * 8);
+  return b;
+}
+template <int DH>
+__device__ __forceinline__ uint4 read_cols_at(const ColsBase& b, unsigned off) {
+  typedef __attribute__((ext_vector_type(4))) short s16x4;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(b.a0 + off));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(b.a1 + off));
+  const uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
+  return make_uint4(l.x, l.y, h.x, h.y);
+}
+
 __device__ __forceinline__ uint4 pack_half(const f32x16& p, int x) {
   return make_uint4(pack2(p[8 * x], p[8 * x + 1]), pack2(p[8 * x + 2], p[8 * x + 3]), pack2(p[8 * x + 4], p[8 * x + 5]),
                     pack2(p[8 * x + 6], p[8 * x + 7]));
@@ -139,6 +172,12 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const A
   TileRegs<DH> pk, pv;
   pk.fetch(base + d, a.ld_qkv, 0, a.S, tid);
   pv.fetch(base + 2 * d, a.ld_qkv, 0, a.S, tid);
+  const uint4* kr[NK];   // K rows l%32, chunk 2kk + g
+  ColsBase vc[NC];       // V columns c*32.., rows from 0
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) kr[kk] = rows_base<DH>(tK, li, 2 * kk + g);
+#pragma unroll
+  for (int c = 0; c < NC; ++c) vc[c] = cols_base<DH>(tV, c * 32, lane);
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * 64;
     __syncthreads();
@@ -155,7 +194,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const A
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) s[sub] = mfma(read_rows<DH>(tK, sub * 32 + li, 2 * kk + g), qf[kk], s[sub]);
+      for (int kk = 0; kk < NK; ++kk) s[sub] = mfma(kr[kk][sub * 32 * NCH], qf[kk], s[sub]);
     }
     // Masking is needed only in tiles that reach past the sequence end or, with a causal mask, past the
     // wave's first query; the scale is folded into the exponent's multiply-add.
@@ -199,7 +238,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const A
       for (int x = 0; x < 2; ++x) {
         const uint4 pf = pack_half(s[sub], x);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) oacc[c] = mfma(read_cols<DH>(tV, c * 32, sub * 32 + 16 * x, lane), pf, oacc[c]);
+        for (int c = 0; c < NC; ++c) oacc[c] = mfma(read_cols_at<DH>(vc[c], (unsigned)((sub * 32 + 16 * x) * NCH * 16)), pf, oacc[c]);
       }
   }
   if (iq < a.S) {
@@ -258,6 +297,12 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(cons
   TileRegs<DH> pk, pv;
   pk.fetch(base + d, a.ld_qkv, 0, a.S, tid);
   pv.fetch(base + 2 * d, a.ld_qkv, 0, a.S, tid);
+  const uint4* kr[NK];   // K rows l%32, chunk 2kk + g; V is 64 rows further on
+  ColsBase kc_[NC];      // K columns c*32.., rows from 0
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) kr[kk] = rows_base<DH>(tK, li, 2 * kk + g);
+#pragma unroll
+  for (int c = 0; c < NC; ++c) kc_[c] = cols_base<DH>(tK, c * 32, lane);
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = t * 64;
     __syncthreads();
@@ -276,8 +321,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(cons
       for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) {
-        s = mfma(read_rows<DH>(tK, sub * 32 + li, 2 * kk + g), qf[kk], s);
-        dp = mfma(read_rows<DH>(tV, sub * 32 + li, 2 * kk + g), dof[kk], dp);
+        s = mfma(kr[kk][sub * 32 * NCH], qf[kk], s);
+        dp = mfma(kr[kk][(64 + sub * 32) * NCH], dof[kk], dp);
       }
       if (edge) {
 #pragma unroll
@@ -292,7 +337,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(cons
       for (int x = 0; x < 2; ++x) {
         const uint4 df = pack_half(s, x);
 #pragma unroll
-        for (int c = 0; c < NC; ++c) acc[c] = mfma(read_cols<DH>(tK, c * 32, sub * 32 + 16 * x, lane), df, acc[c]);
+        for (int c = 0; c < NC; ++c) acc[c] = mfma(read_cols_at<DH>(kc_[c], (unsigned)((sub * 32 + 16 * x) * NCH * 16)), df, acc[c]);
       }
     }
   }
@@ -348,6 +393,12 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
     const int i = i0 + (tid & 63);
     if (tid < 128 && i < a.S) pst = tid < 64 ? a.lse[gi][(size_t)bh * a.S + i] * LOG2E : a.delta[gi][(size_t)bh * a.S + i];
   };
+  const uint4* qr[NK];   // Q rows l%32, chunk 2kk + g; dO is 64 rows further on
+  ColsBase qc[NC];       // Q columns c*32.., rows from 0
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) qr[kk] = rows_base<DH>(tQ, li, 2 * kk + g);
+#pragma unroll
+  for (int c = 0; c < NC; ++c) qc[c] = cols_base<DH>(tQ, c * 32, lane);
   if (t0 < n_tiles) {
     pq.fetch(base, a.ld_qkv, t0 * 64, a.S, tid);
     pdo.fetch(dobase, a.ld_o, t0 * 64, a.S, tid);
@@ -374,8 +425,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
       for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) {
-        s = mfma(read_rows<DH>(tQ, sub * 32 + li, 2 * kk + g), kf[kk], s);
-        dp = mfma(read_rows<DH>(tdO, sub * 32 + li, 2 * kk + g), vf[kk], dp);
+        s = mfma(qr[kk][sub * 32 * NCH], kf[kk], s);
+        dp = mfma(qr[kk][(64 + sub * 32) * NCH], vf[kk], dp);
       }
       f32x16 ds;
       if (edge) {
@@ -397,8 +448,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
         const uint4 pf = pack_half(s, x), df = pack_half(ds, x);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
-          dv[c] = mfma(read_cols<DH>(tdO, c * 32, sub * 32 + 16 * x, lane), pf, dv[c]);
-          dk[c] = mfma(read_cols<DH>(tQ, c * 32, sub * 32 + 16 * x, lane), df, dk[c]);
+          dv[c] = mfma(read_cols_at<DH>(qc[c], (unsigned)((64 + sub * 32 + 16 * x) * NCH * 16)), pf, dv[c]);
+          dk[c] = mfma(read_cols_at<DH>(qc[c], (unsigned)((sub * 32 + 16 * x) * NCH * 16)), df, dk[c]);
         }
       }
     }
