@@ -56,6 +56,21 @@ __device__ __forceinline__ f32x16 mfma(const uint4& a, const uint4& b, f32x16 c)
 // uint4 chunk (row, kc) sits at row*NCH + (kc ^ (row & (NCH-1))), NCH = DH/8.
 // A tile load is split in two so that it can be pipelined: fetch (global -> registers, rows past nrows as zero)
 // and put (registers -> LDS).
+// Work item of a workgroup.  The hardware deals consecutive workgroup ids to the 8 XCDs in turn; items are numbered so
+// that each XCD gets a contiguous run of them, and the 128-row blocks of one (batch, head) are consecutive items: the
+// blocks that read the same K/V (or Q/dO) tiles then run on one XCD and share them through its L2, instead of
+// each XCD fetching them from memory.  Returns false for the padding ids at the end of the grid.
+struct AttnItem { int blk, bh, gi; };
+__device__ __forceinline__ bool attn_item(int n_blk, int n_bh, int n_g, AttnItem& it) {
+  const int total = n_blk * n_bh * n_g, per_xcd = (total + 7) >> 3;
+  const int id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (id >= total || (int)(blockIdx.x >> 3) >= per_xcd) return false;
+  it.blk = id % n_blk;
+  it.bh = (id / n_blk) % n_bh;
+  it.gi = id / (n_blk * n_bh);
+  return true;
+}
+
 template <int DH>
 struct TileRegs {
   static constexpr int NCH = DH / 8, N = 64 * NCH / 256;
@@ -150,10 +165,12 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const A
   uint4* tK = lds;             // [64][NCH]
   uint4* tV = lds + 64 * NCH;  // [64][NCH]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
-  const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  AttnItem item;
+  if (!attn_item((a.S + 127) / 128, a.B * a.H, a.G, item)) return;
+  const int gi = item.gi, bh = item.bh, b = bh / a.H, h = bh % a.H, blk = item.blk;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
-  const int iq = blockIdx.x * 128 + wave * 32 + li;  // this lane's query
+  const int iq = blk * 128 + wave * 32 + li;  // this lane's query
   uint4 qf[NK];
 #pragma unroll
   for (int kk = 0; kk < NK; ++kk) {
@@ -167,7 +184,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const A
     for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
   float m_run = NEG_BIG, l_run = 0.f;
   const float sc = a.scale * LOG2E;
-  const int q_hi = min(a.S, blockIdx.x * 128 + 128) - 1;          // last query of the workgroup
+  const int q_hi = min(a.S, blk * 128 + 128) - 1;          // last query of the workgroup
   const int n_tiles = a.causal ? (q_hi / 64 + 1) : (a.S + 63) / 64;
   TileRegs<DH> pk, pv;
   pk.fetch(base + d, a.ld_qkv, 0, a.S, tid);
@@ -198,7 +215,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_kernel(const A
     }
     // Masking is needed only in tiles that reach past the sequence end or, with a causal mask, past the
     // wave's first query; the scale is folded into the exponent's multiply-add.
-    const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blockIdx.x * 128 + wave * 32);
+    const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blk * 128 + wave * 32);
     float mx = NEG_BIG;
     if (edge) {
 #pragma unroll
@@ -264,10 +281,12 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(cons
   uint4* tK = lds;             // [64][NCH]
   uint4* tV = lds + 64 * NCH;  // [64][NCH]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
-  const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  AttnItem item;
+  if (!attn_item((a.S + 127) / 128, a.B * a.H, a.G, item)) return;
+  const int gi = item.gi, bh = item.bh, b = bh / a.H, h = bh % a.H, blk = item.blk;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
-  const int iq = blockIdx.x * 128 + wave * 32 + li;
+  const int iq = blk * 128 + wave * 32 + li;
   uint4 qf[NK], dof[NK];
   float delta = 0.f;
 #pragma unroll
@@ -292,7 +311,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(cons
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
   const float sc = a.scale * LOG2E;
-  const int q_hi = min(a.S, blockIdx.x * 128 + 128) - 1;
+  const int q_hi = min(a.S, blk * 128 + 128) - 1;
   const int n_tiles = a.causal ? (q_hi / 64 + 1) : (a.S + 63) / 64;
   TileRegs<DH> pk, pv;
   pk.fetch(base + d, a.ld_qkv, 0, a.S, tid);
@@ -313,7 +332,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_kernel(cons
       pk.fetch(base + d, a.ld_qkv, j0 + 64, a.S, tid);
       pv.fetch(base + 2 * d, a.ld_qkv, j0 + 64, a.S, tid);
     }
-    const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blockIdx.x * 128 + wave * 32);
+    const bool edge = j0 + 64 > a.S || (a.causal && j0 + 63 > blk * 128 + wave * 32);
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16 s, dp;
@@ -364,11 +383,13 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
   uint4* tdO = lds + 64 * NCH;                            // [64][NCH]
   float* st = reinterpret_cast<float*>(lds + 2 * 64 * NCH);  // [2][64]: lse*log2e, delta
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, g = lane >> 5;
-  const int gi = blockIdx.z, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  AttnItem item;
+  if (!attn_item((a.S + 127) / 128, a.B * a.H, a.G, item)) return;
+  const int gi = item.gi, bh = item.bh, b = bh / a.H, h = bh % a.H, blk = item.blk;
   const int d = a.H * DH;
   const bf16_t* base = a.qkv[gi] + (size_t)b * a.S * a.ld_qkv + h * DH;
   const bf16_t* dobase = a.dout[gi] + (size_t)b * a.S * a.ld_o + h * DH;
-  const int jk = blockIdx.x * 128 + wave * 32 + li;  // this lane's key
+  const int jk = blk * 128 + wave * 32 + li;  // this lane's key
   uint4 kf[NK], vf[NK];
 #pragma unroll
   for (int kk = 0; kk < NK; ++kk) {
@@ -384,7 +405,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
 #pragma unroll
     for (int r = 0; r < 16; ++r) dk[c][r] = dv[c][r] = 0.f;
   const float sc = a.scale * LOG2E;
-  const int t0 = a.causal ? (blockIdx.x * 128) / 64 : 0;  // queries before the workgroup's first key see none of its keys
+  const int t0 = a.causal ? (blk * 128) / 64 : 0;  // queries before the workgroup's first key see none of its keys
   const int n_tiles = (a.S + 63) / 64;
   TileRegs<DH> pq, pdo;
   float pst = 0.f;
@@ -417,7 +438,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(con
       fetch_stats(i0 + 64);
     }
     // queries past the end, or (causal) queries that precede some key of this wave, need the mask
-    const bool edge = i0 + 64 > a.S || (a.causal && i0 < blockIdx.x * 128 + wave * 32 + 31);
+    const bool edge = i0 + 64 > a.S || (a.causal && i0 < blk * 128 + wave * 32 + 31);
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       f32x16 s, dp;
@@ -486,7 +507,7 @@ hipError_t attn_init() { return hipSuccess; }  // every kernel stays below the d
 
 hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
-  dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
+  dim3 grid(((((a.S + 127) / 128) * a.B * a.H * a.G + 7) / 8) * 8);
   if (a.DH == 64) hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), fwd_lds<64>(), s, a);
   else hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), fwd_lds<128>(), s, a);
   return hipGetLastError();
@@ -494,7 +515,7 @@ hipError_t launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bwd(const AttnBwdArgs& a, hipStream_t s) {
   if (!attn_ok(a.B, a.S, a.H, a.DH, a.ld_qkv, a.ld_o, a.G)) return hipErrorInvalidValue;
-  dim3 grid((a.S + 127) / 128, a.B * a.H, a.G);
+  dim3 grid(((((a.S + 127) / 128) * a.B * a.H * a.G + 7) / 8) * 8);
   if (a.DH == 64) {
     hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), dq_lds<64>(), s, a);
     hipLaunchKernelGGL(attn_bwd_dkv_kernel<64>, grid, dim3(256), dkv_lds<64>(), s, a);
