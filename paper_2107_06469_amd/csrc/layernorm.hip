@@ -135,12 +135,58 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const LnBwdArgs a) {
     if (c < nch) ld8<float>(gamma + 8 * c, ga[i]);
   }
   const int row0 = blockIdx.x * LN_ROWS_PER_WG;
+  // A wave's rows are software-pipelined: the loads of its next row (x, dy, the additive term, the statistics) are
+  // issued before the current row is reduced, and stay in flight as raw registers until that row's turn.
+  // Only where the extra registers cost no spill and little occupancy: 16-bit rows of at most 1024 elements.  The
+  // other shapes fetch each row at its own turn (and its additive term after the reductions).
+  constexpr bool PF = sizeof(T) == 2 && LN_MAXC <= 2;
+  constexpr int RW = sizeof(T) == 2 ? 1 : 2;  // 16-byte pieces per 8 elements
+  uint4 nx[LN_MAXC][RW], ndy[LN_MAXC][RW], nadd[LN_MAXC][RW];
+  float nmu = 0.f, nrstd = 0.f;
+  auto fetch_row = [&](int row) {
+    const uint4* x = reinterpret_cast<const uint4*>(static_cast<const T*>(a.x[g]) + (size_t)row * a.ld);
+    const uint4* dy = reinterpret_cast<const uint4*>(static_cast<const T*>(a.dy[g]) + (size_t)row * a.ld);
+    const uint4* add = a.add[g] ? reinterpret_cast<const uint4*>(static_cast<const T*>(a.add[g]) + (size_t)row * a.ld) : nullptr;
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nch) {
+#pragma unroll
+        for (int q = 0; q < RW; ++q) {
+          nx[i][q] = x[c * RW + q];
+          ndy[i][q] = dy[c * RW + q];
+          if (PF && add) nadd[i][q] = add[c * RW + q];
+        }
+      }
+    }
+    nmu = a.mean[g][row];
+    nrstd = a.rstd[g][row];
+  };
+  auto unpack = [&](const uint4 (&raw)[RW], float (&v)[8]) {
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t w[4] = {raw[0].x, raw[0].y, raw[0].z, raw[0].w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        v[2 * q] = __uint_as_float(w[q] << 16);
+        v[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+      }
+    } else {
+      v[0] = __uint_as_float(raw[0].x); v[1] = __uint_as_float(raw[0].y); v[2] = __uint_as_float(raw[0].z); v[3] = __uint_as_float(raw[0].w);
+      v[4] = __uint_as_float(raw[RW - 1].x); v[5] = __uint_as_float(raw[RW - 1].y); v[6] = __uint_as_float(raw[RW - 1].z); v[7] = __uint_as_float(raw[RW - 1].w);
+    }
+  };
+  if (PF && row0 + wave < a.rows) fetch_row(row0 + wave);
   for (int r = wave; r < LN_ROWS_PER_WG; r += 4) {
     const int row = row0 + r;
     if (row >= a.rows) break;
-    const T* x = static_cast<const T*>(a.x[g]) + (size_t)row * a.ld;
-    const T* dy = static_cast<const T*>(a.dy[g]) + (size_t)row * a.ld;
-    const float mu = a.mean[g][row], rstd = a.rstd[g][row];
+    // this row's values move out of the prefetch registers; then the next row's loads are issued
+    uint4 cx[LN_MAXC][RW], cdy[LN_MAXC][RW], cadd[LN_MAXC][RW];
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i)
+#pragma unroll
+      for (int q = 0; q < RW; ++q) { cx[i][q] = nx[i][q]; cdy[i][q] = ndy[i][q]; cadd[i][q] = nadd[i][q]; }
+    const float mu = PF ? nmu : a.mean[g][row], rstd = PF ? nrstd : a.rstd[g][row];
+    if (PF && r + 4 < LN_ROWS_PER_WG && row + 4 < a.rows) fetch_row(row + 4);
     float xh[LN_MAXC][8], gg[LN_MAXC][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -148,8 +194,13 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const LnBwdArgs a) {
       const int c = lane + 64 * i;
       if (c < nch) {
         float xv[8], dv[8];
-        ld8<T>(x + 8 * c, xv);
-        ld8<T>(dy + 8 * c, dv);
+        if constexpr (PF) {
+          unpack(cx[i], xv);
+          unpack(cdy[i], dv);
+        } else {
+          ld8<T>(static_cast<const T*>(a.x[g]) + (size_t)row * a.ld + 8 * c, xv);
+          ld8<T>(static_cast<const T*>(a.dy[g]) + (size_t)row * a.ld + 8 * c, dv);
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           xh[i][e] = (xv[e] - mu) * rstd;
@@ -163,7 +214,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const LnBwdArgs a) {
     }
     const float c1 = wave_sum(s1) / (float)a.d, c2 = wave_sum(s2) / (float)a.d;
     T* dx = static_cast<T*>(a.dx[g]) + (size_t)row * a.ld;
-    const T* add = a.add[g] ? static_cast<const T*>(a.add[g]) + (size_t)row * a.ld : nullptr;
+    const bool add = a.add[g] != nullptr;
 #pragma unroll
     for (int i = 0; i < LN_MAXC; ++i) {
       const int c = lane + 64 * i;
@@ -173,7 +224,11 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const LnBwdArgs a) {
         for (int e = 0; e < 8; ++e) o[e] = rstd * (gg[i][e] - c1 - xh[i][e] * c2);
         if (add) {
           float av[8];
-          ld8<T>(add + 8 * c, av);
+          if constexpr (PF) {
+            unpack(cadd[i], av);
+          } else {
+            ld8<T>(static_cast<const T*>(a.add[g]) + (size_t)row * a.ld + 8 * c, av);
+          }
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] += av[e];
         }
