@@ -89,7 +89,7 @@ def main():
                     help="steps of the sequential model-parallel and of the task-parallel schedule timed beside (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
         sys.exit(2)
 
     import torch

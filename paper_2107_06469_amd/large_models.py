@@ -7,7 +7,7 @@ then model 0 alone with resident state; losses and four probed tensors must agre
 replication, Approach, "Desiderata").  device_budget_GiB > 0 smaller than the models' state spills master weights
 and Adam moments to pinned host memory; activation_budget_GiB > 0 smaller than the activations makes every
 backward task recompute its shard's forward.  Prints per-step times, spill traffic and per-kernel times as JSON.
-A GPU machine that pins less host memory than 12 bytes per parameter of all K models cannot spill them: reduce K or
+A machine that can pin less host memory than 12 bytes per parameter of all K models cannot spill them: reduce K or
 the depth (the full workload, K=8 x 32 layers, needs 648 GB of pinned memory).
 
 Argument marshalling and reporting only: every step of training runs in libhydra.so.

@@ -1,6 +1,6 @@
 """End-to-end parity of the HIP training path with the CPU oracle, through the C boundary (GPU only).
 
-Tolerances (benchmark spec): fp32 configurations rel 1e-5 on per-step loss and on
+Tolerances: fp32 configurations rel 1e-5 on per-step loss and on
 every parameter tensor; bf16 configurations rel 2e-2 on per-step loss and parameter norms.  Extra,
 stricter evidence for bf16 (a flat loss and slowly moving norms are weak): first-step gradients
 within rel-L2 3e-2 and cosine >= 0.999 of the oracle's, parameter movement norm within 5e-2.
