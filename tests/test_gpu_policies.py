@@ -168,3 +168,41 @@ def test_bert_large_shaped_encoders_one_step_against_oracle(H):
     for kk in range(w.K):
         assert abs(got[kk][0][0] - np.log(30522)) < 0.4
         assert all(np.all(np.isfinite(p)) for p in got[kk][1])
+
+
+def test_profile_accounts_the_algorithmic_work_of_an_epoch(H):
+    """The per-kernel-class counters behind the benchmark's rates: an epoch of workload 0 (4 ReLU MLPs, 256 wide,
+    4 hidden layers + a 10-way head, batch 32, 10 steps, SGD) must be booked with the products' 2·m·n·k each."""
+    w = C.workload(0)
+    data = make_data(w)
+    ctx = H.hydra_create(n_streams=4)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+        H.hydra_set_data(ctx, data["inputs"], data["target_pos"], data["targets"])
+        assert len(H.hydra_tensor_shapes(ctx, 0)) == 2 * 5             # weight and bias of 5 layers
+        H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL, None)          # profiling off: nothing booked
+        assert H.hydra_profile_read(ctx) == {}
+        H.hydra_profile_enable(ctx, True)
+        steps = H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL, None)["steps"]
+        assert steps == w.n_batches
+        prof = H.hydra_profile_read(ctx, reset=False)
+        layers = [(256, 256)] * 4 + [(256, 10)]
+        per_step = lambda ls: sum(2.0 * w.batch * i * o for i, o in ls) * w.K
+        assert prof["gemm_fwd"]["flops"] == pytest.approx(per_step(layers) * steps, rel=1e-12)
+        assert prof["gemm_dgrad"]["flops"] == pytest.approx(per_step(layers[1:]) * steps, rel=1e-12)  # no dX of the input
+        wg = sum(prof[c]["flops"] for c in ("gemm_wgrad", "wgrad_update") if c in prof)
+        assert wg == pytest.approx(per_step(layers) * steps, rel=1e-12)
+        # fused SGD update in fp32: the weight read and written (8 B) plus the two operands of the product
+        upd = sum((8.0 * i * o + 4.0 * w.batch * (i + o)) for i, o in layers) * w.K * steps
+        assert prof["wgrad_update"]["bytes"] == pytest.approx(upd, rel=1e-12)
+        for c, p in prof.items():
+            assert p["launches"] > 0 and p["total_ms"] > 0.0, c
+        assert H.hydra_profile_read(ctx, reset=True) == prof             # reading with reset returns, then clears
+        assert H.hydra_profile_read(ctx) == {}
+        H.hydra_profile_enable(ctx, False)
+        H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL, None)
+        assert H.hydra_profile_read(ctx) == {}
+    finally:
+        H.hydra_destroy(ctx)
