@@ -206,3 +206,34 @@ def test_profile_accounts_the_algorithmic_work_of_an_epoch(H):
         assert H.hydra_profile_read(ctx) == {}
     finally:
         H.hydra_destroy(ctx)
+
+
+@pytest.mark.parametrize("i", [2, 4])
+def test_profile_accounts_the_products_of_transformer_blocks(H, i):
+    """Encoders (workload 2's layers) and gated causal decoders (workload 4's) at reduced size: every weight matrix
+    is booked once per pass with 2·rows·in·out, the attention products with 4 (forward) + 10 (backward) ·B·S²·d,
+    halved under the causal mask."""
+    w = scaled_workload(i, K=2, depths=[2, 4], steps=2)
+    data = make_data(w)
+    ctx = H.hydra_create(n_streams=2)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+        H.hydra_set_data(ctx, data["inputs"], data["target_pos"], data["targets"])
+        H.hydra_profile_enable(ctx, True)
+        steps = H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL, None)["steps"]
+        prof = H.hydra_profile_read(ctx)
+        T, NT = w.batch * w.seq, w.batch * w.n_targets
+        gemm = att = 0.0
+        for a in w.archs:
+            d, F, V, L = a["d_model"], a["d_ffn"], a["n_out"], a["n_layers"]
+            gemm += 2.0 * T * L * (3 * d * d + d * d + (3 if a["ffn_gated"] else 2) * d * F) + 2.0 * NT * d * V
+            att += w.batch * float(w.seq) ** 2 * d * L * (0.5 if a["causal"] else 1.0)
+        assert prof["gemm_fwd"]["flops"] == pytest.approx(gemm * steps, rel=1e-12)
+        assert prof["gemm_dgrad"]["flops"] == pytest.approx(gemm * steps, rel=1e-12)
+        wg = sum(prof[c]["flops"] for c in ("gemm_wgrad", "wgrad_update") if c in prof)
+        assert wg == pytest.approx(gemm * steps, rel=1e-12)
+        assert prof["attention"]["flops"] == pytest.approx(14.0 * att * steps, rel=1e-12)
+    finally:
+        H.hydra_destroy(ctx)
