@@ -221,3 +221,13 @@ def test_task_parallel_plan_and_inactive_models():
         assert e.value.status == 2
     finally:
         H.hydra_destroy(ctx)
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """One GPU is all the library drives: asking the benchmark for more ends with a message, before any device call."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
