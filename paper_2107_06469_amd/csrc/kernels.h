@@ -157,7 +157,7 @@ struct LnArgs {
 };
 hipError_t launch_ln_fwd(const LnArgs& a, hipStream_t s);
 // dx = rstd*(g - mean(g) - xhat*mean(g*xhat)) + add (add optional), g = dy*gamma;
-// dgamma = sum_rows dy*xhat, dbeta = sum_rows dy.  part: scratch of ln_bwd_blocks(rows)*2*d floats.
+// dgamma = sum_rows dy*xhat, dbeta = sum_rows dy.  part: scratch of ln_bwd_blocks(rows, d)*2*d floats.
 struct LnBwdArgs {
   int dtype, rows, d, ld, G;
   const void* x[MAXG];
@@ -171,7 +171,7 @@ struct LnBwdArgs {
   float* dgamma[MAXG];
   float* dbeta[MAXG];
 };
-int ln_bwd_blocks(int rows);
+int ln_bwd_blocks(int rows, int d);
 hipError_t launch_ln_bwd(const LnBwdArgs& a, hipStream_t s);
 hipError_t ln_init();
 

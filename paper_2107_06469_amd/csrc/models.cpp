@@ -292,7 +292,7 @@ static hydra_status alloc_scratch(hydra_ctx* c, TrActs& t, const TrDims& q) {
   ALLOC_OR_FAIL(c, t.dqkv, void*, q.Tk * 3 * q.d * 2);
   ALLOC_OR_FAIL(c, t.da, void*, q.Tk * q.d * 2);
   ALLOC_OR_FAIL(c, t.delta, float*, q.bhs * 4);
-  ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4);
+  ALLOC_OR_FAIL(c, t.lnpart, float*, (size_t)ln_bwd_blocks((int)q.Tk, (int)q.d) * 2 * q.d * 4);
   return HYDRA_OK;
 }
 
@@ -315,7 +315,7 @@ static size_t block_bytes(const TrDims& q) {
 }
 static size_t scratch_bytes(const TrDims& q) {
   return q.Tk * q.d * 2 * 6 + q.Tk * 3 * q.d * 2 + q.NT * q.d * 4 + q.NT * q.ldv * 6 + q.NT * 4 + q.Tk * 8 +
-         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 + (size_t)ln_bwd_blocks((int)q.Tk) * 2 * q.d * 4 + splitk_bytes(q);
+         q.Tk * q.F * 2 * (q.gated ? 3 : 1) + q.bhs * 4 + (size_t)ln_bwd_blocks((int)q.Tk, (int)q.d) * 2 * q.d * 4 + splitk_bytes(q);
 }
 
 // Keeps every block's activations per model, or, when that exceeds activation_budget_bytes, only the hand-off

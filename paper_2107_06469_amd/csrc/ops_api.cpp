@@ -170,7 +170,7 @@ int hydra_op_layernorm_fwd(int dtype, int rows, int d, int ld, float eps, int G,
   return done(launch_ln_fwd(a, static_cast<hipStream_t>(stream)), "hydra_op_layernorm_fwd");
 }
 
-size_t hydra_op_layernorm_part_floats(int rows, int d) { return (size_t)ln_bwd_blocks(rows) * 2 * d; }
+size_t hydra_op_layernorm_part_floats(int rows, int d) { return (size_t)ln_bwd_blocks(rows, d) * 2 * d; }
 
 int hydra_op_layernorm_bwd(int dtype, int rows, int d, int ld, int G, const void* const* x, const void* const* dy,
                            const void* const* add, void* const* dx, const float* const* gamma,

@@ -37,7 +37,7 @@ def _f32(torch, a):
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
-@pytest.mark.parametrize("shape", [(37, 64), (130, 768), (9, 1024), (5, 2048 + 64), (6, 4096)])
+@pytest.mark.parametrize("shape", [(37, 64), (130, 768), (9, 1024), (5, 2048 + 64), (6, 4096), (100, 1536), (70, 4096)])
 def test_layernorm_forward_and_backward(torch, ops, dtype, shape):
     rows, d = shape
     r = np.random.default_rng(rows * d)
