@@ -180,6 +180,7 @@ hydra_status hydra_shard(hydra_ctx* c, int model, const int32_t* cuts, int n_cut
   for (int k = 0; k < c->K; ++k) {
     if (model != -1 && model != k) continue;
     Model tmp = c->models[k];
+    tmp.shards.clear();  // the copy must not release the events and tables the real shards own
     hydra_status st = cut_model(c, tmp, cuts, n_cuts);
     if (st != HYDRA_OK) return st;
   }

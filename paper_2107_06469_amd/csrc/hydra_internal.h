@@ -42,6 +42,7 @@ struct Shard {
   // spill mode: slot held between the shard's backward and the end of its update, and the events that order it
   int slot = -1;
   hipEvent_t loaded_ev = nullptr, updated_ev = nullptr;
+  hipEvent_t stored_ev = nullptr;  // the shard's state has been copied back to host memory after its last update
   // fused-update mode: the pieces of the block that the update task still owns (tensors that are not `fused`),
   // as a device table of (first 16-byte vector, vectors <= 256) pairs relative to the shard's block
   uint2* tail_chunks = nullptr;

@@ -97,6 +97,7 @@ hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts) 
   for (Shard& old : m.shards) {
     if (old.loaded_ev) (void)hipEventDestroy(old.loaded_ev);
     if (old.updated_ev) (void)hipEventDestroy(old.updated_ev);
+    if (old.stored_ev) (void)hipEventDestroy(old.stored_ev);
     if (old.tail_chunks || (c->dry && old.n_tail_chunks)) ctx_free(c, old.tail_chunks, (size_t)old.n_tail_chunks * sizeof(uint2));
   }
   m.shards.clear();
@@ -120,7 +121,8 @@ hydra_status cut_model(hydra_ctx* c, Model& m, const int32_t* cuts, int n_cuts) 
     for (uint64_t v : {(uint64_t)a.kind, (uint64_t)a.dtype, (uint64_t)a.d_model, (uint64_t)a.n_heads, (uint64_t)a.d_ffn,
                        (uint64_t)a.n_out, (uint64_t)a.ffn_gated, (uint64_t)a.causal, (uint64_t)a.act, (uint64_t)a.max_seq,
                        (uint64_t)(sh.u1 - sh.u0), (uint64_t)(sh.u0 == 0), (uint64_t)(sh.u1 == U),
-                       (uint64_t)(sh.u0 == 0 ? a.d_in : 0)})
+                       (uint64_t)(sh.u0 == 0 ? a.d_in : 0),
+                       (uint64_t)m.hp.opt})  // a launch group applies one optimizer to all its members
       h = mix_sig(h, v);
     sh.sig = h;
     point_shard(m, sh);

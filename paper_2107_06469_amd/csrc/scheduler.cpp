@@ -75,13 +75,21 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
       longest = std::max(longest, l.size());
       lists.push_back(l);
     }
-    if (c->spill && (int)c->slots.size() < (int)std::min<size_t>(lists.size(), nstr))
-      nstr = std::max<int>(1, (int)c->slots.size());  // one state slot per model in flight
-    for (auto& l : lists)
-      for (Bucket& b : l) b.stream %= nstr;
-    for (size_t pos = 0; pos < longest; ++pos)
-      for (const auto& l : lists)
-        if (pos < l.size()) plan.push_back(l[pos]);
+    // Spilled state: a model holds one state slot from each backward to the update behind it, so only as many
+    // models as there are slots may be in flight at once; the lists are issued in waves of that many models.
+    size_t wave = lists.size();
+    if (c->spill) {
+      wave = std::max<size_t>(1, std::min(wave, c->slots.size()));
+      nstr = (int)std::min<size_t>(nstr, wave);
+    }
+    for (size_t w0 = 0; w0 < lists.size(); w0 += wave) {
+      const size_t w1 = std::min(lists.size(), w0 + wave);
+      for (size_t i = w0; i < w1; ++i)
+        for (Bucket& b : lists[i]) b.stream = (int)((i - w0) % nstr);
+      for (size_t pos = 0; pos < longest; ++pos)
+        for (size_t i = w0; i < w1; ++i)
+          if (pos < lists[i].size()) plan.push_back(lists[i][pos]);
+    }
     return HYDRA_OK;
   }
 

@@ -161,12 +161,18 @@ int spill_max_group(const hydra_ctx* c) { return std::max<int>(1, (int)c->slots.
 hydra_status spill_acquire(hydra_ctx* c, int k, int s, hipStream_t compute, bool synchronous) {
   Model& m = c->models[k];
   Shard& sh = m.shards[s];
-  hydra_ctx::Slot& sl = c->slots[c->next_slot];
-  if (sl.held)
+  // first slot, in ring order from the one after the last grant, whose tenant's update has been scheduled
+  size_t at = c->next_slot, tried = 0;
+  while (tried < c->slots.size() && c->slots[at].held) {
+    at = (at + 1) % c->slots.size();
+    ++tried;
+  }
+  if (tried == c->slots.size())
     return c->fail(HYDRA_ERR_BAD_SCHEDULE, "backward of (%d,%d): the %zu state slots the device budget allows are all held "
                    "by shards whose update has not been scheduled yet", k, s, c->slots.size());
+  hydra_ctx::Slot& sl = c->slots[at];
   sl.held = true;
-  c->next_slot = (c->next_slot + 1) % c->slots.size();
+  c->next_slot = (at + 1) % c->slots.size();
   sh.p = sl.base;
   sh.m = sl.base + c->slot_elems;
   sh.v = sl.base + 2 * c->slot_elems;
@@ -181,6 +187,9 @@ hydra_status spill_acquire(hydra_ctx* c, int k, int s, hipStream_t compute, bool
     if (in != compute) HYDRA_HIP(c, hipStreamWaitEvent(compute, sl.free_ev, 0));
   }
   sl.used = true;
+  // the shard's own state must have reached host memory: its copy-out of the previous step runs on another stream
+  // and nothing else orders it before this copy-in (the slot's event belongs to whichever shard held the slot last)
+  if (sh.stored_ev) HYDRA_HIP(c, hipStreamWaitEvent(in, sh.stored_ev, 0));
   HYDRA_HIP(c, copy_in_pieces(m.host_p, sh.off, sh.n, sh.p, in));
   HYDRA_HIP(c, copy_in_pieces(m.host_m, sh.off, sh.n, sh.m, in));
   HYDRA_HIP(c, copy_in_pieces(m.host_v, sh.off, sh.n, sh.v, in));
@@ -224,6 +233,8 @@ hydra_status spill_after_update(hydra_ctx* c, int k, int s, hipStream_t compute,
   HYDRA_HIP(c, copy_out_pieces(m.host_m, sh.off, sh.n, sh.m, out));
   HYDRA_HIP(c, copy_out_pieces(m.host_v, sh.off, sh.n, sh.v, out));
   HYDRA_HIP(c, hipEventRecord(sl.free_ev, out));
+  if (!sh.stored_ev) HYDRA_HIP(c, hipEventCreateWithFlags(&sh.stored_ev, hipEventDisableTiming));
+  HYDRA_HIP(c, hipEventRecord(sh.stored_ev, out));
   sh.p = sh.m = sh.v = sh.g = nullptr;
   sh.slot = -1;
   return HYDRA_OK;
@@ -244,6 +255,7 @@ void spill_release_all(hydra_ctx* c) {
     for (Shard& sh : m.shards) {
       if (sh.loaded_ev) (void)hipEventDestroy(sh.loaded_ev);
       if (sh.updated_ev) (void)hipEventDestroy(sh.updated_ev);
+      if (sh.stored_ev) (void)hipEventDestroy(sh.stored_ev);
     }
   for (void* p : c->host_allocs) (void)hipHostFree(p);
   c->host_allocs.clear();

@@ -59,3 +59,78 @@ def test_budget_too_small_for_one_shard_is_reported(H):
     with pytest.raises(H.HydraError) as e:
         H.train_workload(w, data, H.SCHED_SHARD_PARALLEL, device_budget_bytes=sum(nb) * 2 + 300 * 1024)
     assert e.value.status == 4
+
+
+def _run(H, w, data, n_epochs, drop=None, policy=None, tasks=None, budget=0):
+    """Trains n_epochs; drop = {epoch: [models]} marks models inactive before that epoch; tasks = {epoch: list}."""
+    ctx = H.hydra_create(n_streams=4, device_budget_bytes=budget)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+        H.hydra_set_data(ctx, data["inputs"], data["target_pos"], data["targets"])
+        stats = []
+        for e in range(n_epochs):
+            for k in (drop or {}).get(e, []):
+                H.hydra_set_active(ctx, k, False)
+            stats.append(H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL if policy is None else policy,
+                                             None if tasks is None else tasks[e]))
+        return {k: (H.hydra_read_loss(ctx, k), H.hydra_read_params(ctx, k)) for k in range(w.K)}, stats
+    finally:
+        H.hydra_destroy(ctx)
+
+
+def _same(got, ref, what):
+    for k in ref:
+        assert np.array_equal(got[k][0], ref[k][0]), f"loss of model {k} differs ({what})"
+        for j, (a, b) in enumerate(zip(got[k][1], ref[k][1])):
+            assert np.array_equal(a, b), f"tensor {j} of model {k} differs ({what})"
+
+
+def test_spilled_state_with_fewer_active_shards_than_slots(H):
+    """Models dropped by model selection leave fewer shard updates per step than there are state slots, so a shard
+    gets a slot whose last tenant was not the shard's own previous update: the copy-in of its state must still wait
+    for its own copy-out of the step before.  Spilled = resident, bit for bit, over several steps per epoch."""
+    w = scaled_workload(1, K=4, steps=4)
+    data = make_data(w)
+    nb = _blocks(H, w)
+    slot = max(nb) // 2 * 16 + 64 * 1024
+    budget = sum(nb) * 2 + 256 * 1024 + int(5.5 * slot)        # 5 slots; 2 active models x 2 shards = 4 updates per step
+    drop = {1: [1, 3]}
+    ref, _ = _run(H, w, data, 3, drop=drop)
+    for policy in (H.SCHED_SHARD_PARALLEL, H.SCHED_TASK_PARALLEL, H.SCHED_SEQUENTIAL):
+        got, stats = _run(H, w, data, 3, drop=drop, policy=policy, budget=budget)
+        assert stats[0]["h2d_bytes"] > 0 and stats[1]["h2d_bytes"] * 2 == stats[0]["h2d_bytes"]
+        _same(got, ref, f"spilled, models 1 and 3 dropped after the first epoch, policy {policy}")
+
+
+@pytest.mark.parametrize("slots", [2, 3])
+def test_spilled_state_under_an_explicit_order_with_permuted_updates(H, slots):
+    """An explicit order may run a model's updates in another order than its backward tasks (here B(k,1), B(k,0),
+    U(k,0), U(k,1)), so a shard's next slot is not the one its own state left through."""
+    w = scaled_workload(1, K=3, steps=4)
+    data = make_data(w)
+    nb = _blocks(H, w)
+    slot = max(nb) // 2 * 16 + 64 * 1024
+    budget = sum(nb) * 2 + 256 * 1024 + int((slots + 0.5) * slot)
+    F, B, U = H.PHASE_F, H.PHASE_B, H.PHASE_U
+    one = lambda k: [(k, 0, F), (k, 1, F), (k, 1, B), (k, 0, B), (k, 0, U), (k, 1, U)]
+    tasks = [t for k in range(3) for t in one(k)]
+    ref, _ = _run(H, w, data, 2)
+    got, stats = _run(H, w, data, 2, policy=H.SCHED_EXPLICIT, tasks={0: tasks, 1: tasks}, budget=budget)
+    assert stats[0]["h2d_bytes"] > 0
+    _same(got, ref, f"spilled, explicit order with permuted updates, {slots} slots")
+
+
+def test_task_parallel_with_fewer_slots_than_models(H):
+    """Spilled, task-parallel, K = 4 models of equal depth and 2 state slots: the models run in waves of two."""
+    w = scaled_workload(1, K=4, steps=3)
+    data = make_data(w)
+    nb = _blocks(H, w)
+    slot = max(nb) // 2 * 16 + 64 * 1024
+    ref, _ = _run(H, w, data, 1)
+    for slots in (1, 2, 3):
+        budget = sum(nb) * 2 + 256 * 1024 + int((slots + 0.5) * slot)
+        got, stats = _run(H, w, data, 1, policy=H.SCHED_TASK_PARALLEL, budget=budget)
+        assert stats[0]["h2d_bytes"] > 0
+        _same(got, ref, f"spilled, task-parallel, {slots} slots")

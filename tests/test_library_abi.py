@@ -231,3 +231,74 @@ def test_benchmark_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def _padded_blocks(w):
+    ctx = H.hydra_create(dry_run=True)
+    H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+    nb = [sum((r * c + 63) // 64 * 64 for r, c in H.hydra_tensor_shapes(ctx, k)) for k in range(w.K)]
+    H.hydra_destroy(ctx)
+    return nb
+
+
+@pytest.mark.parametrize("slots", [1, 2, 3, 5])
+def test_every_policy_plans_with_fewer_state_slots_than_models(slots):
+    """Spilled state, K = 4 models of equal depth, fewer state slots than models: a slot is held from a shard's
+    backward to its update, so no policy may keep more shards between those two tasks than there are slots."""
+    w = scaled_workload(1, K=4, steps=2)
+    d = make_data(w)
+    nb = _padded_blocks(w)
+    slot = max(nb) // 2 * 16 + 64 * 1024
+    budget = sum(nb) * 2 + 256 * 1024 + int((slots + 0.5) * slot)
+    for n_streams in (1, 4):
+        ctx = H.hydra_create(n_streams=n_streams, dry_run=True, device_budget_bytes=budget)
+        try:
+            H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+            H.hydra_shard(ctx, -1, w.boundaries[0])
+            H.hydra_set_data(ctx, d["inputs"], None, d["targets"])
+            per_epoch = sum(3 * 4 * n for n in nb) * w.steps
+            for policy in (H.SCHED_SEQUENTIAL, H.SCHED_SHARD_PARALLEL, H.SCHED_TASK_PARALLEL):
+                st = H.hydra_train_epoch(ctx, policy)
+                assert st["h2d_bytes"] == st["d2h_bytes"] >= 0.99 * per_epoch, (policy, slots)
+            F, B, U = H.PHASE_F, H.PHASE_B, H.PHASE_U
+            # an explicit order that keeps two shards between backward and update needs two slots
+            one = lambda k: [(k, 0, F), (k, 1, F), (k, 1, B), (k, 0, B), (k, 0, U), (k, 1, U)]
+            tasks = [t for k in range(4) for t in one(k)]
+            if slots >= 2:
+                H.hydra_train_epoch(ctx, H.SCHED_EXPLICIT, tasks)
+            else:
+                with pytest.raises(H.HydraError) as e:
+                    H.hydra_train_epoch(ctx, H.SCHED_EXPLICIT, tasks)
+                assert e.value.status == 3 and "slots" in str(e.value)
+        finally:
+            H.hydra_destroy(ctx)
+
+
+def test_models_with_different_optimizers_never_share_a_launch_group():
+    """A grid may vary the optimizer: a launch group applies one optimizer to all its members, so SGD and Adam models
+    form separate groups (and the epoch plans without error)."""
+    w = scaled_workload(1, K=4, steps=2, dtype=1)
+    for k in (1, 3):
+        w.hparams[k]["opt"] = 0
+    d = make_data(w)
+    ctx = H.hydra_create(n_streams=4, dry_run=True)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        H.hydra_shard(ctx, -1, w.boundaries[0])
+        H.hydra_set_data(ctx, d["inputs"], None, d["targets"])
+        mixed = H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL)
+        seq = H.hydra_train_epoch(ctx, H.SCHED_SEQUENTIAL)
+        assert mixed["grouped_tasks"] == 2 * 4 * 2 * 3            # every task still runs in a group (of two)
+        assert mixed["launches"] * 2 == seq["launches"]            # ... and never in a group of four
+    finally:
+        H.hydra_destroy(ctx)
+    w2 = scaled_workload(1, K=4, steps=2, dtype=1)
+    ctx = H.hydra_create(n_streams=4, dry_run=True)
+    try:
+        H.hydra_define_models(ctx, w2.archs, w2.hparams, w2.init_seed)
+        H.hydra_shard(ctx, -1, w2.boundaries[0])
+        H.hydra_set_data(ctx, d["inputs"], None, d["targets"])
+        same = H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL)
+        assert same["launches"] * 4 == seq["launches"] or same["launches"] < mixed["launches"]
+    finally:
+        H.hydra_destroy(ctx)
