@@ -77,25 +77,25 @@ def attention_fwd(q, k, v, causal):
     """q,k,v: [B,H,S,dh].  P = softmax_rows(q k^T / sqrt(dh) + mask), o = P v.
     mask is -inf strictly above the diagonal when causal, else absent."""
     dh = q.shape[-1]
-    s = np.einsum("bhid,bhjd->bhij", q, k) / np.sqrt(F64(dh))
+    s = np.matmul(q, np.swapaxes(k, -1, -2)) / np.sqrt(F64(dh))
     if causal:
         S = s.shape[-1]
         s = np.where(np.tril(np.ones((S, S), dtype=bool)), s, -np.inf)
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)
     P = e / e.sum(axis=-1, keepdims=True)
-    return np.einsum("bhij,bhjd->bhid", P, v), P
+    return np.matmul(P, v), P
 
 
 def attention_bwd(q, k, v, P, do):
     """Adjoint: dv = P^T do; dP = do v^T; dS = P o (dP - rowsum(dP o P)); dq = dS k / sqrt(dh); dk = dS^T q / sqrt(dh)."""
     dh = q.shape[-1]
-    dv = np.einsum("bhij,bhid->bhjd", P, do)
-    dP = np.einsum("bhid,bhjd->bhij", do, v)
+    dv = np.matmul(np.swapaxes(P, -1, -2), do)
+    dP = np.matmul(do, np.swapaxes(v, -1, -2))
     dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
     scale = 1.0 / np.sqrt(F64(dh))
-    dq = np.einsum("bhij,bhjd->bhid", dS, k) * scale
-    dk = np.einsum("bhij,bhid->bhjd", dS, q) * scale
+    dq = np.matmul(dS, k) * scale
+    dk = np.matmul(np.swapaxes(dS, -1, -2), q) * scale
     return dq, dk, dv
 
 
