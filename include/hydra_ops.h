@@ -68,6 +68,17 @@ int hydra_op_colsum(int dtype, int M, int N, int ld, int G, const void* const* s
                     float* const* part, void* stream);
 size_t hydra_op_colsum_part_floats(int M, int N);
 
+/* hydra_op_colsum for callers that cannot allocate device memory or hand over scratch: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same order of additions and therefore the same
+ * bits as hydra_op_colsum; the partial sums live in an array built into the library (one copy per GPU, held until the
+ * process ends) of hydra_op_colsum_noalloc_max_floats() = 1048576 floats (4 MiB).  A call needs
+ * G * hydra_op_colsum_part_floats(M, N) of them; more returns HYDRA_ERR_INVALID_ARG and nothing is launched.  The
+ * call allocates and frees nothing and does not synchronise.  Every call on a GPU uses that GPU's one array: calls
+ * whose kernels may overlap on one GPU (different streams, or different threads) race; calls on one stream do not. */
+int hydra_op_colsum_noalloc(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out,
+                            void* stream);
+size_t hydra_op_colsum_noalloc_max_floats(void);
+
 /* Softmax cross-entropy over fp32 logits [M, ldz] with C classes and int32 labels [M] (shared by the
  * group): rowloss_g[m] = logsumexp(z_m) - z_m[y_m]; dz_g[m,c] = (softmax(z_m)[c] - [c==y_m]) * inv_n
  * in the operand dtype with leading dimension lddz (columns [C,lddz) are zeroed);

@@ -1,5 +1,14 @@
 // Small memory-bound kernels: seeded initialisation, fills, casts, batch staging, column sums.
+#include <mutex>
+
+#include "../../include/hydra.h"
+#include "../../include/hydra_ops.h"
 #include "kernels.h"
+
+// Partial column sums of hydra_op_colsum_noalloc: one array per GPU, held until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr size_t COLSUM_SCRATCH_FLOATS = (size_t)1 << 20;  // 4 MiB
+static __device__ __align__(256) float scratch[COLSUM_SCRATCH_FLOATS];
 
 namespace hydra {
 namespace {
@@ -141,3 +150,58 @@ hipError_t launch_colsum(const ColsumArgs& a, hipStream_t s) {
 }
 
 }  // namespace hydra
+
+// ---- column sums for callers that cannot allocate ---------------------------------------------------------
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[MAX_DEVICES] = {};  // device address of `scratch` on every GPU seen so far
+
+// address of the current device's copy of the scratch array (looked up once per device)
+hipError_t scratch_of_current_device(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+}  // namespace
+
+extern "C" size_t hydra_op_colsum_noalloc_max_floats(void) { return COLSUM_SCRATCH_FLOATS; }
+
+extern "C" int hydra_op_colsum_noalloc(int dtype, int M, int N, int ld, int G, const void* const* src, float* const* out,
+                                       void* stream) {
+  using namespace hydra;
+  if (!src || !out || G < 1 || G > MAXG) return ops_fail(HYDRA_ERR_INVALID_ARG, "hydra_op_colsum_noalloc: NULL table or G out of range");
+  if (M < 1 || N < 1 || ld < N) return ops_fail(HYDRA_ERR_INVALID_ARG, "hydra_op_colsum_noalloc: need M, N >= 1 and ld >= N");
+  const size_t per = colsum_part_floats(M, N);
+  if (per * (size_t)G > COLSUM_SCRATCH_FLOATS)
+    return ops_fail(HYDRA_ERR_INVALID_ARG,
+                    "hydra_op_colsum_noalloc: the partial sums of this call (G * ceil(M/256) * N floats) exceed the built-in "
+                    "scratch of 1048576 floats; use hydra_op_colsum with caller scratch");
+  float* base = nullptr;
+  hipError_t e = scratch_of_current_device(&base);
+  if (e != hipSuccess) return ops_fail(HYDRA_ERR_DEVICE, "hydra_op_colsum_noalloc: scratch lookup failed", hipGetErrorString(e));
+  ColsumArgs a{};
+  a.dtype = dtype == HYDRA_OPS_F32 ? GEMM_F32 : GEMM_BF16;
+  a.M = M; a.N = N; a.ld = ld; a.G = G;
+  for (int g = 0; g < G; ++g) {
+    if (!src[g] || !out[g]) return ops_fail(HYDRA_ERR_INVALID_ARG, "hydra_op_colsum_noalloc: NULL entry");
+    a.src[g] = src[g];
+    a.out[g] = out[g];
+    a.part[g] = base + (size_t)g * per;  // every partial sum that stage 2 reads is written by stage 1 first: nothing to clear
+  }
+  e = launch_colsum(a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess)
+    return ops_fail(e == hipErrorInvalidValue ? HYDRA_ERR_INVALID_ARG : HYDRA_ERR_DEVICE, "hydra_op_colsum_noalloc", hipGetErrorString(e));
+  return HYDRA_OK;
+}

@@ -89,6 +89,8 @@ struct ColsumArgs {
 };
 size_t colsum_part_floats(int M, int N);
 hipError_t launch_colsum(const ColsumArgs& a, hipStream_t s);
+// records the text hydra_ops_last_error() returns ("what" or "what: detail") and returns `status`
+int ops_fail(int status, const char* what, const char* detail = nullptr);
 
 // Softmax cross-entropy over rows of fp32 logits [M, ldz] with C classes:
 //   rowloss[m] = logsumexp(z_m) - z_m[y_m];  dz[m,c] = (softmax(z_m)[c] - [c == y_m]) * inv_n

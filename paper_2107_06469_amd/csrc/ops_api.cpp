@@ -23,6 +23,11 @@ static int bad(const char* what) {
   return HYDRA_ERR_INVALID_ARG;
 }
 
+int hydra::ops_fail(int status, const char* what, const char* detail) {
+  g_ops_err = detail ? std::string(what) + ": " + detail : std::string(what);
+  return status;
+}
+
 static int ensure_init() {
   std::call_once(g_gemm_once, [] { g_gemm_init = kernels_init(); });
   return g_gemm_init == hipSuccess ? 0 : done(g_gemm_init, "kernel set-up");

@@ -34,6 +34,9 @@ def _L():
         L.hydra_op_colsum.argtypes = [C.c_int] * 5 + [pp, pp, pp, vp]
         L.hydra_op_colsum_part_floats.argtypes = [C.c_int, C.c_int]
         L.hydra_op_colsum_part_floats.restype = C.c_size_t
+        L.hydra_op_colsum_noalloc.argtypes = [C.c_int] * 5 + [pp, pp, vp]
+        L.hydra_op_colsum_noalloc_max_floats.argtypes = []
+        L.hydra_op_colsum_noalloc_max_floats.restype = C.c_size_t
         L.hydra_op_gemm_split_k.argtypes = [C.c_int] * 3
         L.hydra_op_gemm_split_ws_bytes.argtypes = [C.c_int] * 4
         L.hydra_op_gemm_split_ws_bytes.restype = C.c_size_t
@@ -113,6 +116,14 @@ def hydra_op_colsum_part_floats(M, N) -> int:
 
 def hydra_op_colsum(dtype, M, N, ld, src, out, part=None):
     _check(_L().hydra_op_colsum(dtype, M, N, ld, len(src), _tab(src), _tab(out), _tab(part), _stream()))
+
+
+def hydra_op_colsum_noalloc(dtype, M, N, ld, src, out):
+    _check(_L().hydra_op_colsum_noalloc(dtype, M, N, ld, len(src), _tab(src), _tab(out), _stream()))
+
+
+def hydra_op_colsum_noalloc_max_floats() -> int:
+    return int(_L().hydra_op_colsum_noalloc_max_floats())
 
 
 def hydra_op_softmax_ce(dtype, M, Cn, ldz, lddz, inv_n, logits, labels, dz, rowloss, loss):
