@@ -1,11 +1,13 @@
 """Benchmark of the shard-parallel training hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload i] [--no-per-config]
 
-Workload: K=8 MLPs of 16 x Linear(4096,4096)+GeLU and Linear(4096,1000), bf16 working weights with
-fp32 master/Adam state, batch 512, 4 shards per model, shard-parallel schedule.  A step is one
-forward + backward + Adam update of all 8 models on one batch.  Inputs are synthetic and already
-resident in HBM when the timed region starts.  Prints one JSON line.
+Headline workload (default): K=8 MLPs of 16 x Linear(4096,4096)+GeLU and Linear(4096,1000), bf16 working weights
+with fp32 master/Adam state, batch 512, 4 shards per model, shard-parallel schedule.  A step is one forward +
+backward + Adam update of all 8 models on one batch.  Inputs are synthetic and already resident in HBM when the
+timed region starts.  Prints one JSON line; its `per_config` object holds the same measurement, on a few steps
+each, for the other workloads that fit one GPU (the fp32 MLPs, the two encoder workloads, and decoders of the
+largest workload's shape at K=2 with resident state).
 """
 import argparse
 import json
@@ -18,8 +20,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
-PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
-PEAK_F32_TFLOPS = 157.3
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA
+TRAFFIC_FILE = os.path.join("profiles", "workload1_kernels_hbm_traffic.txt")
 
 
 def measured_traffic(kernel_class, workload):
@@ -28,7 +30,7 @@ def measured_traffic(kernel_class, workload):
     import hashlib
     if kernel_class != "wgrad_update" or workload != 1:
         return None
-    path = os.path.join(ROOT, "profiles", "workload1_kernels_hbm_traffic.txt")
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     try:
         kv = dict(l.split(":", 1) for l in open(path) if ":" in l and not l.startswith("#"))
         h = hashlib.sha256()
@@ -48,7 +50,6 @@ def _set_steps(w, n):
 
 def cpu_baseline(w, budget_s=30.0):
     """Times the oracle as it stands on a bounded sample: whole model-steps of model 0."""
-    import numpy as np
     from hydra_workloads import make_data
     from oracle import model as OM
     from oracle import optim as OO
@@ -77,6 +78,118 @@ def cpu_baseline(w, budget_s=30.0):
                        f"{dt:.1f} s of CPU work")
 
 
+def empty_launch_us(torch, n=2000):
+    """Average time of a launch that does nothing, in a chain of n on one stream (microseconds)."""
+    from paper_2107_06469_amd import ops
+    ops.hydra_op_empty_launches(200)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ops.hydra_op_empty_launches(n)
+    torch.cuda.synchronize()
+    return 1e6 * (time.perf_counter() - t0) / n
+
+
+def measure(torch, H, w, label, steps, warmup, workload_index=None, profile=True, baseline_steps=0, n_streams=4,
+            activation_budget_bytes=0):
+    """Runs workload w: `warmup` untimed steps, `steps` timed steps (shard-parallel), the same steps once more with a
+    HIP event pair around every launch (per-kernel times; not the headline because the records cost 2-3 %), and
+    optionally the two comparison schedules.  Returns the figures of one configuration."""
+    from hydra_workloads import make_data
+    ctx = H.hydra_create(n_streams=n_streams, activation_budget_bytes=activation_budget_bytes)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+
+        def run(n_steps, policy, prof_on):
+            d = make_data(_set_steps(w, n_steps))
+            H.hydra_set_data(ctx, d["inputs"], d["target_pos"], d["targets"])       # copies to HBM, untimed
+            H.hydra_profile_enable(ctx, prof_on)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st = H.hydra_train_epoch(ctx, policy)                                   # drains the device at both ends
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0, st
+
+        if warmup > 0:
+            run(warmup, H.SCHED_SHARD_PARALLEL, False)
+        dt, st = run(steps, H.SCHED_SHARD_PARALLEL, False)       # the timed region: nothing but the work on the streams
+        prof, dt_prof, busy = {}, None, None
+        if profile:
+            H.hydra_profile_read(ctx, reset=True)
+            H.hydra_profile_busy(ctx, reset=True)
+            dt_prof, _ = run(steps, H.SCHED_SHARD_PARALLEL, True)
+            prof = H.hydra_profile_read(ctx, reset=True)
+            busy = H.hydra_profile_busy(ctx, reset=True)
+        dtype = "bf16" if w.archs[0]["dtype"] == 1 else "f32"
+        peak = PEAK_TFLOPS[dtype]
+        out = {"label": label, "ms_per_step": 1e3 * dt / steps, "value": w.K * w.batch * steps / dt, "unit": "samples/s",
+               "steps": steps, "warmup": warmup, "dtype": dtype, "launches_per_step": st["launches"] / steps,
+               "final_loss_model0": float(H.hydra_read_loss(ctx, 0)[-1])}
+        if prof:
+            name = max(prof, key=lambda k: prof[k]["total_ms"])
+            p = prof[name]
+            avg_ms = p["total_ms"] / p["launches"]
+            # a kernel with both counts (the gradient GEMM that also streams the optimizer state) is bound by
+            # whichever of its two lower bounds on time is larger
+            if p["flops"] / (peak * 1e12) > p["bytes"] / (PEAK_HBM_GBS * 1e9):
+                ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
+                roof = {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                        "frac": ach / peak, "traffic": None, "avg_launch_ms": avg_ms, "launches": p["launches"],
+                        "algorithmic_flops_per_launch": p["flops"] / p["launches"]}
+            else:
+                ach = p["bytes"] / p["launches"] / (avg_ms * 1e-3) / 1e9
+                roof = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(name, workload_index),
+                        "avg_launch_ms": avg_ms, "launches": p["launches"],
+                        "algorithmic_bytes_per_launch": p["bytes"] / p["launches"]}
+                if roof["traffic"] is not None:
+                    roof["traffic_source"] = (f"{TRAFFIC_FILE}: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of an earlier run, "
+                                              "scaled by a copy kernel's readings; not measured in this run (valid while the "
+                                              "kernel's sources hash to the value stored there)")
+                    roof["traffic_covers"] = ("the 8 x [4096 x 4096] layer launch (16 of the 17 launches of this kernel per "
+                                              "step; 3.557 GB algorithmic)")
+            roof["measured_in"] = (f"second pass over the same {steps} steps with HIP event pairs around every launch "
+                                   f"({1e3 * dt_prof / steps:.3f} ms/step)")
+            out["roofline"] = roof
+            out["kernel_time_ms_per_step"] = {k: v["total_ms"] / steps for k, v in prof.items()}
+            mm = [k for k in prof if k.startswith("gemm") or k == "attention"]
+            mm_ms = sum(prof[k]["total_ms"] for k in mm)
+            mm_fl = sum(prof[k]["flops"] for k in mm)
+            if mm_ms > 0:
+                # products whose kernels do nothing else (forward, input gradient, stored weight gradient, attention)
+                out["mfma_util_gemm_time_weighted"] = mm_fl / (mm_ms * 1e-3) / (peak * 1e12)
+                all_fl = mm_fl + prof.get("wgrad_update", {"flops": 0.0})["flops"]
+                out["mfma_util_whole_epoch"] = all_fl / steps / (dt / steps) / (peak * 1e12)
+                out["mfma_peak_tflops"] = peak
+            tot = sum(v["total_ms"] for v in prof.values())
+            out["kernel_time_sum_over_wall"] = tot * 1e-3 / dt_prof    # > 1 when launches on different streams overlap
+            # union of the launches' event intervals over the epoch's wall time; an interval runs from the end of the
+            # stream's previous work to the kernel's end, so dispatch latency counts as busy (upper estimate; the
+            # rocprofv3 kernel traces under profiles/ give the figure from the kernels' own timestamps)
+            out["gpu_busy_fraction_events"] = busy["busy_ms"] * 1e-3 / dt_prof
+        if baseline_steps > 0:
+            dts, _ = run(baseline_steps, H.SCHED_SEQUENTIAL, False)
+            out["model_parallel_baseline"] = {"value": w.K * w.batch * baseline_steps / dts, "unit": "samples/s",
+                                              "schedule": "one shard task at a time, one stream, ungrouped launches",
+                                              "steps": baseline_steps}
+            dtt, _ = run(baseline_steps, H.SCHED_TASK_PARALLEL, False)
+            out["task_parallel_baseline"] = {"value": w.K * w.batch * baseline_steps / dtt, "unit": "samples/s",
+                                             "schedule": f"one stream per model ({n_streams} streams), ungrouped launches",
+                                             "steps": baseline_steps}
+        return out
+    finally:
+        H.hydra_destroy(ctx)
+        torch.cuda.empty_cache()
+
+
+def describe(w, index):
+    lo, hi = min(len(b) for b in w.boundaries) + 1, max(len(b) for b in w.boundaries) + 1
+    shards = f"{lo}" if lo == hi else f"{lo}-{hi}"
+    return (f"configs[{index}] {w.name}: K={w.K} models, batch {w.batch}, {shards} shards/model, "
+            f"shard-parallel schedule, 4 streams")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,6 +198,7 @@ def main():
     ap.add_argument("--workload", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket kernels with HIP events")
+    ap.add_argument("--no-per-config", action="store_true", help="headline workload only")
     ap.add_argument("--sequential-steps", type=int, default=3,
                     help="steps of the sequential model-parallel and of the task-parallel schedule timed beside (0 = skip)")
     args = ap.parse_args()
@@ -93,96 +207,53 @@ def main():
         sys.exit(2)
 
     import torch
-    from hydra_workloads import make_data, workload
+    from hydra_workloads import workload
     from paper_2107_06469_amd import hydra as H
     if not torch.cuda.is_available():
         print("bench.py: no HIP device", file=sys.stderr)
         sys.exit(1)
 
     w = workload(args.workload)
-    ctx = H.hydra_create(n_streams=4)
-    H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
-    for k in range(w.K):
-        H.hydra_shard(ctx, k, w.boundaries[k])
-
-    def run(n_steps, policy, profile):
-        d = make_data(_set_steps(w, n_steps))
-        H.hydra_set_data(ctx, d["inputs"], d["target_pos"], d["targets"])       # copies to HBM, untimed
-        H.hydra_profile_enable(ctx, profile)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        st = H.hydra_train_epoch(ctx, policy)                                   # drains the device at both ends
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0, st
-
-    if args.warmup > 0:
-        run(args.warmup, H.SCHED_SHARD_PARALLEL, False)
-    # the timed region: K steps with nothing but the work itself on the streams
-    dt, st = run(args.steps, H.SCHED_SHARD_PARALLEL, False)
-    # the same K steps once more with a HIP event pair around every launch (on the launching stream): per-kernel
-    # times for the roofline; the event records cost 2-3 % of step time, which is why this pass is not the headline
-    prof, dt_prof = {}, None
-    if not args.no_profile:
-        H.hydra_profile_read(ctx, reset=True)
-        dt_prof, _ = run(args.steps, H.SCHED_SHARD_PARALLEL, True)
-        prof = H.hydra_profile_read(ctx, reset=True)
-    samples = w.K * w.batch * args.steps
-    losses = [float(H.hydra_read_loss(ctx, k)[-1]) for k in range(w.K)]
-
+    head = measure(torch, H, w, describe(w, args.workload), args.steps, args.warmup, workload_index=args.workload,
+                   profile=not args.no_profile, baseline_steps=args.sequential_steps)
     out = {
         "metric": "aggregate training samples/sec across K models (1 GPU)",
-        "value": samples / dt, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": 1e3 * dt / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.archs[0]["dtype"] == 1 else "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.workload}] {w.name}: K={w.K} models, batch {w.batch}, "
-                               f"{len(w.boundaries[0]) + 1} shards/model, shard-parallel schedule, 4 streams",
-                   "launches_per_step": st["launches"] / args.steps, "final_loss_model0": losses[0]},
+        "value": head["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["label"], "launches_per_step": head["launches_per_step"],
+                   "final_loss_model0": head["final_loss_model0"]},
     }
+    for k in ("roofline", "kernel_time_ms_per_step", "mfma_util_gemm_time_weighted", "mfma_util_whole_epoch",
+              "mfma_peak_tflops", "kernel_time_sum_over_wall", "gpu_busy_fraction_events", "model_parallel_baseline",
+              "task_parallel_baseline"):
+        if k in head:
+            out[k] = head[k]
 
-    # roofline of the dominant kernel class (largest share of kernel time in the timed region)
-    if prof:
-        name = max(prof, key=lambda k: prof[k]["total_ms"])
-        p = prof[name]
-        avg_ms = p["total_ms"] / p["launches"]
-        peak = PEAK_BF16_TFLOPS if out["dtype"] == "bf16" else PEAK_F32_TFLOPS
-        # a kernel with both counts (the gradient GEMM that also streams the optimizer state) is bound by
-        # whichever of its two lower bounds on time is larger
-        if p["flops"] / (peak * 1e12) > p["bytes"] / (PEAK_HBM_GBS * 1e9):
-            ach = p["flops"] / p["launches"] / (avg_ms * 1e-3) / 1e12
-            out["roofline"] = {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                               "frac": ach / peak, "traffic": None, "avg_launch_ms": avg_ms, "launches": p["launches"]}
-        else:
-            ach = p["bytes"] / p["launches"] / (avg_ms * 1e-3) / 1e9
-            out["roofline"] = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                               "frac": ach / PEAK_HBM_GBS, "traffic": measured_traffic(name, args.workload),
-                               "avg_launch_ms": avg_ms, "launches": p["launches"],
-                               "algorithmic_bytes_per_launch": p["bytes"] / p["launches"],
-                               "traffic_covers": "the 8 x [4096 x 4096] layer launch (16 of the 17 launches of this kernel "
-                                                 "per step; 3.557 GB algorithmic), FETCH_SIZE + WRITE_SIZE scaled by a copy"}
-        if out["roofline"].get("traffic") is None:
-            out["roofline"].pop("traffic_covers", None)
-        out["roofline"]["measured_in"] = (f"second pass over the same {args.steps} steps with HIP event pairs around every "
-                                          f"launch ({1e3 * dt_prof / args.steps:.3f} ms/step)")
-        tot = sum(v["total_ms"] for v in prof.values())
-        out["kernel_time_ms_per_step"] = {k: v["total_ms"] / args.steps for k, v in prof.items()}
-        gemm_ms = sum(v["total_ms"] for k, v in prof.items() if k.startswith("gemm"))
-        gemm_fl = sum(v["flops"] for k, v in prof.items() if k.startswith("gemm"))
-        if gemm_ms > 0:
-            out["mfma_util_gemm_time_weighted"] = gemm_fl / (gemm_ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12)
-            all_fl = gemm_fl + prof.get("wgrad_update", {"flops": 0.0})["flops"]
-            out["mfma_util_whole_epoch"] = all_fl / dt / (PEAK_BF16_TFLOPS * 1e12)
-        out["kernel_time_over_wall"] = tot * 1e-3 / dt_prof
+    if not args.no_per_config:
+        per = {}
+        # (workload, timed steps, warm-up steps, steps of the comparison schedules)
+        for i, steps, warm, base in ((0, 200, 20, 20), (2, 5, 2, 2), (3, 3, 1, 1)):
+            if i == args.workload:
+                continue
+            wi = workload(i)
+            r = measure(torch, H, wi, describe(wi, i), steps, warm, workload_index=i, baseline_steps=base)
+            if i == 0:
+                # the whole step is ~0.2 GFLOP and ~13 MB: what bounds it is the chain of dependent launches
+                us = empty_launch_us(torch)
+                r["launch_floor"] = {"empty_launch_us": us, "launches_per_step": r["launches_per_step"],
+                                     "floor_us_per_step": us * r["launches_per_step"], "us_per_step": 1e3 * r["ms_per_step"]}
+            per[f"configs[{i}]"] = r
+        # decoders of the largest workload's shape: K=8 x 32 layers does not fit one GPU's memory nor this pool's pinned
+        # host memory; K=2 with resident state and recomputed activations does
+        from paper_2107_06469_amd.large_models import decoder_workload
+        w4 = decoder_workload(2, 2, 32)
+        per["configs[4] shapes, K=2"] = measure(
+            torch, H, w4, "decoders of configs[4]'s shape (32 layers, d=4096, gated FFN 11008, S=2048, batch 8), K=2 instead "
+            "of 8, 4 shards/model, state resident, activations recomputed per shard (25 GiB workspace budget)", 2, 1,
+            activation_budget_bytes=25 << 30)
+        out["per_config"] = per
 
-    if args.sequential_steps > 0:
-        dts, _ = run(args.sequential_steps, H.SCHED_SEQUENTIAL, False)
-        out["model_parallel_baseline"] = {"value": w.K * w.batch * args.sequential_steps / dts, "unit": "samples/s",
-                                          "schedule": "one shard task at a time, one stream, ungrouped launches",
-                                          "steps": args.sequential_steps}
-        dtt, _ = run(args.sequential_steps, H.SCHED_TASK_PARALLEL, False)
-        out["task_parallel_baseline"] = {"value": w.K * w.batch * args.sequential_steps / dtt, "unit": "samples/s",
-                                         "schedule": "one stream per model (4 streams), ungrouped launches",
-                                         "steps": args.sequential_steps}
-    H.hydra_destroy(ctx)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(workload(args.workload))
     print(json.dumps(out))

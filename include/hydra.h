@@ -157,7 +157,7 @@ hydra_status hydra_define_models(hydra_ctx* ctx, int K, const hydra_arch* archs,
  * model; Figure 1).  n_cuts = 0 keeps the model whole.  Calling it again re-cuts. */
 hydra_status hydra_shard(hydra_ctx* ctx, int model, const int32_t* cuts, int n_cuts);
 
-/* Automatic sharder (the step the paper names as next, Discussion: choosing the partition instead of taking it
+/* Automatic sharder (the step the paper names as next, Evaluation, "Execution Plan": choosing the partition instead of taking it
  * from the caller).  Cuts model `model` (-1: every model) into the fewest shards whose parameter, gradient and
  * optimizer-state bytes each stay within max_shard_bytes and, among the partitions with that many shards, one
  * that minimises the largest shard (contiguous partition of the layer units by dynamic programming).  With
@@ -227,6 +227,11 @@ typedef struct {
 } hydra_kernel_profile;
 hydra_status hydra_profile_enable(hydra_ctx* ctx, int on);
 hydra_status hydra_profile_read(hydra_ctx* ctx, int kernel_class, int reset, hydra_kernel_profile* out);
+/* Device-busy time of the profiled epochs (paper, Approach, "Desiderata", first item: the device is to be kept
+ * utilised throughout): busy_ms = length of the union of all launches' [start, end] intervals (launches on different
+ * streams overlap, so this is at most the wall time, unlike the sum of the durations), span_ms = first start to last
+ * end, summed over the epochs.  Accumulates until read with reset = 1. */
+hydra_status hydra_profile_busy(hydra_ctx* ctx, int reset, double* busy_ms, double* span_ms);
 
 /* Library-owned string, valid until the next call on ctx (ctx may be NULL: last create error). */
 const char* hydra_last_error(const hydra_ctx* ctx);

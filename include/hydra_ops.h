@@ -142,6 +142,11 @@ int hydra_op_embed_bwd(int dtype, int V, int S, int S_table, int B, int d, int l
                        const int32_t* positions, const void* const* dx, float* const* dtok, float* const* dpos,
                        void* stream);
 
+/* Measurement aid: enqueues n launches of a kernel that does nothing (one wave) on `stream`.  The time per launch of
+ * a long run of them is the floor under any step that is a chain of dependent launches, which is what bounds the
+ * smallest workload (its whole step is microseconds of arithmetic). */
+int hydra_op_empty_launches(int n, void* stream);
+
 const char* hydra_ops_last_error(void);
 
 #ifdef __cplusplus

@@ -151,6 +151,18 @@ hipError_t launch_colsum(const ColsumArgs& a, hipStream_t s) {
 
 }  // namespace hydra
 
+// ---- measurement aid: the cost of a kernel launch that does nothing ------------------------------------------
+namespace {
+__global__ void empty_kernel() {}
+}  // namespace
+
+extern "C" int hydra_op_empty_launches(int n, void* stream) {
+  if (n < 0) return hydra::ops_fail(HYDRA_ERR_INVALID_ARG, "hydra_op_empty_launches: n < 0");
+  for (int i = 0; i < n; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream));
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? HYDRA_OK : hydra::ops_fail(HYDRA_ERR_DEVICE, "hydra_op_empty_launches", hipGetErrorString(e));
+}
+
 // ---- column sums for callers that cannot allocate ---------------------------------------------------------
 namespace {
 constexpr int MAX_DEVICES = 64;

@@ -82,6 +82,7 @@ hydra_status hydra_destroy(hydra_ctx* c) {
     for (hipStream_t s : c->streams) (void)hipStreamSynchronize(s);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
+    if (c->prof_origin) (void)hipEventDestroy(c->prof_origin);
     spill_release_all(c);
     ctx_free_all(c);
     if (c->own_streams)

@@ -197,6 +197,8 @@ struct hydra_ctx {
   size_t prof_used = 0;
   struct ProfSum { uint64_t launches = 0; double ms = 0, flops = 0, bytes = 0; };
   ProfSum prof_sum[HYDRA_K_COUNT];
+  hipEvent_t prof_origin = nullptr;   // recorded when a profiled epoch starts, after the streams have drained
+  double prof_busy_ms = 0, prof_span_ms = 0;  // union of the launches' [start, end] intervals / first start to last end
 
   hydra_status fail(hydra_status st, const char* fmt, ...) {
     char buf[512];
@@ -258,6 +260,7 @@ inline hydra_status run_bucket(hydra_ctx* c, const Bucket& b, int batch, int ste
 inline double fused_update_bytes(int opt, bool bf16) { return (opt == 1 ? 24.0 : 8.0) + (bf16 ? 2.0 : 0.0); }
 
 // profile.cpp: event pair around one launch when profiling is on
+hipError_t prof_epoch_begin(hydra_ctx* c);  // records the time origin of a profiled epoch on stream 0
 hipError_t prof_begin(hydra_ctx* c, hipStream_t s, hipEvent_t* a);
 hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double flops, double bytes);
 hydra_status prof_collect(hydra_ctx* c);  // after the streams have drained

@@ -194,6 +194,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
       c->events.push_back(e);
     }
     for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+    if (c->profiling) HYDRA_HIP(c, prof_epoch_begin(c));
   }
   struct Done { hipEvent_t ev; int stream; };
   std::map<Task, Done> last;  // most recent completion event of every task

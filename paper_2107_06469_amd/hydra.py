@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         L.hydra_set_active.argtypes = [vp, C.c_int, C.c_int]
         L.hydra_profile_enable.argtypes = [vp, C.c_int]
         L.hydra_profile_read.argtypes = [vp, C.c_int, C.c_int, C.POINTER(hydra_kernel_profile)]
+        L.hydra_profile_busy.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.hydra_last_error.argtypes = [vp]
         L.hydra_last_error.restype = C.c_char_p
         _lib = L
@@ -308,6 +309,13 @@ def hydra_profile_read(ctx: Context, reset: bool = True) -> Dict[str, Dict]:
         if kp.launches:
             out[name] = dict(launches=int(kp.launches), total_ms=kp.total_ms, flops=kp.flops, bytes=kp.bytes)
     return out
+
+
+def hydra_profile_busy(ctx: Context, reset: bool = True) -> Dict[str, float]:
+    """busy_ms: time with at least one kernel running; span_ms: first launch start to last launch end."""
+    b, sp = C.c_double(0), C.c_double(0)
+    _check(ctx.handle, lib().hydra_profile_busy(ctx.handle, 1 if reset else 0, C.byref(b), C.byref(sp)))
+    return dict(busy_ms=b.value, span_ms=sp.value)
 
 
 def train_workload(w, data, policy: int = SCHED_SHARD_PARALLEL, n_streams: int = 4, epochs: int = 1, tasks=None,

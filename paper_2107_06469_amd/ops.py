@@ -52,6 +52,7 @@ def _L():
         L.hydra_op_attention_bwd.argtypes = [C.c_int] * 7 + [C.c_float, C.c_int] + [pp] * 6 + [vp]
         L.hydra_op_embed_fwd.argtypes = [C.c_int] * 6 + [vp, pp, pp, pp, vp]
         L.hydra_op_embed_bwd.argtypes = [C.c_int] * 8 + [vp, vp, pp, pp, pp, vp]
+        L.hydra_op_empty_launches.argtypes = [C.c_int, vp]
         L.hydra_ops_last_error.restype = C.c_char_p
         _ready = True
     return L
@@ -116,6 +117,10 @@ def hydra_op_colsum_part_floats(M, N) -> int:
 
 def hydra_op_colsum(dtype, M, N, ld, src, out, part=None):
     _check(_L().hydra_op_colsum(dtype, M, N, ld, len(src), _tab(src), _tab(out), _tab(part), _stream()))
+
+
+def hydra_op_empty_launches(n: int):
+    _check(_L().hydra_op_empty_launches(n, _stream()))
 
 
 def hydra_op_colsum_noalloc(dtype, M, N, ld, src, out):

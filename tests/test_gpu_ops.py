@@ -95,6 +95,59 @@ def test_gemm_layouts_tiles_and_ragged_shapes(torch, ops, dtype, tile, layout):
             assert np.all(o[:, N:] == 7.0), "columns beyond N were written"
 
 
+# Linear layers of the measured workloads at their full size: (problems grouped, tokens, in, out).
+FULL_SIZE_LAYERS = [(8, 512, 4096, 4096),      # workload 1: eight models' hidden layer in one launch
+                    (2, 16384, 768, 2304),     # workload 2: the QKV projection (two of its four models)
+                    (1, 16384, 4096, 11008)]   # workload 4: the FFN up-projection of a 4096-wide decoder
+
+
+@pytest.mark.parametrize("layout", ["fwd", "dgrad", "wgrad"])
+@pytest.mark.parametrize("layer", FULL_SIZE_LAYERS)
+def test_gemm_at_the_workloads_full_size(torch, ops, layer, layout):
+    """Element by element against the oracle's Linear at shapes that reach what the small cases cannot: more than 8
+    tile rows (several bands of the tile order), grids whose tile count is not a multiple of the 8 XCDs, k-loops of
+    128 to 512 sub-tiles, and the split sum over 16384 tokens of a weight gradient with few output tiles.
+    The kernels add 16 products per MFMA step and chain K/16 steps in fp32 (K/(16 S) per range, then S partial sums,
+    when split), so |error| <= (K/16 + 16) * 2^-24 * sum_k |x||w|; the test allows twice that with the sum bounded by
+    |x_m| |w_n| (Cauchy-Schwarz), which costs no second matrix product."""
+    G, T, d_in, d_out = layer
+    r = np.random.default_rng(T + d_in + len(layout))
+    if layout == "fwd":
+        M, N, K = T, d_out, d_in
+    elif layout == "dgrad":
+        M, N, K = T, d_in, d_out
+    else:
+        M, N, K = d_out, d_in, T
+    Xs, Ws, outs, wss, refs = [], [], [], [], []
+    split = ops.hydra_op_gemm_split_k(M, N, K) if layout == "wgrad" else 1
+    for g in range(G):
+        # operands as the kernel reads them: X(m,k), W(n,k); stored k-major or k-slow depending on the layout
+        x = r.standard_normal((M, K), dtype=np.float32)
+        w = r.standard_normal((N, K), dtype=np.float32) * np.float32(1.0 / math.sqrt(K))
+        xk, wk = layout != "wgrad", layout == "fwd"
+        xt = torch.from_numpy(x if xk else np.ascontiguousarray(x.T)).to(torch.bfloat16)
+        wt = torch.from_numpy(w if wk else np.ascontiguousarray(w.T)).to(torch.bfloat16)
+        xv, wv = xt.to(torch.float64).numpy(), wt.to(torch.float64).numpy()
+        xv, wv = (xv if xk else xv.T), (wv if wk else wv.T)
+        refs.append((OL.linear_fwd(xv, wv, np.zeros(N)), np.linalg.norm(xv, axis=1), np.linalg.norm(wv, axis=1)))
+        Xs.append(xt.cuda()), Ws.append(wt.cuda())
+        outs.append(torch.full((M, N), 7.0, dtype=torch.float32, device="cuda"))
+        if split > 1:
+            wss.append(torch.zeros(ops.hydra_op_gemm_split_ws_bytes(M, N, K, N), dtype=torch.uint8, device="cuda"))
+    assert (split > 1) == (layout == "wgrad" and layer[1] == 16384 and d_in == 768), "which shapes split is part of the design"
+    ops.hydra_op_gemm(1, M, N, K, Xs, Ws, outs, x_kmajor=int(xk), w_kmajor=int(wk), ldx=Xs[0].shape[1], ldw=Ws[0].shape[1],
+                      ldo=N, out_f32=True, ws=wss or None)
+    torch.cuda.synchronize()
+    for g in range(G):
+        want, nx, nw = refs[g]
+        got = outs[g].cpu().numpy().astype(np.float64)
+        tol = 2 * (K / 16 + 16) * EPS32 * np.outer(nx, nw)
+        bad = np.abs(got - want) > tol
+        assert not bad.any(), f"{layout} {layer} g={g}: {bad.sum()} of {bad.size} off, worst {np.abs(got - want).max()}"
+        # the tolerance is a small fraction of the values it guards: a dropped MFMA step would not pass
+        assert np.median(tol) < 0.03 * np.sqrt((want ** 2).mean())
+
+
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("act", [1, 2])
 def test_gemm_forward_epilogue_bias_activation_preactivation(torch, ops, dtype, act):

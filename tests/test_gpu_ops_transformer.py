@@ -93,7 +93,7 @@ def _attention_case(torch, ops, B, S, H, DH, causal, seed):
         o, P = OL.attention_fwd(q, k, v, causal)
         do = dov.reshape(B, S, H, DH).transpose(0, 2, 1, 3)
         dq, dk, dv = OL.attention_bwd(q, k, v, P, do)
-        sc = np.einsum("bhid,bhjd->bhij", q, k) * scale
+        sc = np.matmul(q, np.swapaxes(k, -1, -2)) * scale
         if causal:
             sc = np.where(np.tril(np.ones((S, S), dtype=bool)), sc, -np.inf)
         lse = np.log(np.exp(sc - sc.max(-1, keepdims=True)).sum(-1)) + sc.max(-1)
@@ -123,6 +123,16 @@ def _attention_case(torch, ops, B, S, H, DH, causal, seed):
 def test_attention_forward_and_backward(torch, ops, causal, shape):
     B, S, H, DH = shape
     _attention_case(torch, ops, B, S, H, DH, causal, seed=S * DH + int(causal))
+
+
+@pytest.mark.parametrize("shape", [(32, 512, 12, 64, False), (2, 2048, 8, 128, True)])
+def test_attention_at_the_workloads_shapes(torch, ops, shape):
+    """The attention of workload 2 at its full per-model size (batch 32, 12 heads of 64, S = 512: 8 key tiles per
+    query block, 384 x 4 workgroups per problem, two problems grouped) and of workload 4's decoders (S = 2048, heads
+    of 128, causal: 32 key tiles, short and long causal blocks dealt over the XCDs), the latter on 2 sequences x 8
+    heads instead of 8 x 32 so that the fp64 oracle's probability matrices fit a test."""
+    B, S, H, DH, causal = shape
+    _attention_case(torch, ops, B, S, H, DH, causal, seed=S + DH)
 
 
 def test_attention_uniform_scores_closed_form(torch, ops):

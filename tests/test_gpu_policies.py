@@ -21,6 +21,29 @@ def H():
     return hydra
 
 
+def _oracle_parity_bf16(w, got, data, steps, models, rel=2e-2):
+    """The bf16 tolerances of the end-to-end tests against the oracle's unsharded, one-model-at-a-time training:
+    per-step loss and parameter norms within 2e-2, parameter movement within 5e-2 (the key third of bqkv, whose exact
+    gradient is zero, is bounded by lr per step instead)."""
+    ref = OT.train_all(w.archs, w.hparams, data, steps, w.init_seed, models=models)
+    for k in models:
+        gl, gp = got[k]
+        rl, rp = ref[k]
+        assert len(gl) == steps and np.all(np.abs(gl - rl) <= rel * np.abs(rl)), f"model {k} loss: {gl} vs {rl}"
+        p0 = OM.init_params(w.archs[k], w.init_seed, k)
+        for (nm, _, _), a, b, z in zip(OM.tensor_specs(w.archs[k]), gp, rp, p0):
+            a, b, z = a.astype(np.float64), b.astype(np.float64), z.astype(np.float64)
+            if nm.endswith("bqkv"):
+                d3 = a.size // 3
+                assert np.abs(a[d3:2 * d3]).max() <= 1.01 * w.hparams[k]["lr"] * steps, f"model {k} {nm}: key bias"
+                keep = np.r_[0:d3, 2 * d3:3 * d3]
+                a, b, z = a[keep], b[keep], z[keep]
+            nb = np.linalg.norm(b)
+            assert abs(np.linalg.norm(a) - nb) <= rel * max(nb, 1e-3), f"model {k} {nm}: norm"
+            mv, mr = np.linalg.norm(a - z), np.linalg.norm(b - z)
+            assert abs(mv - mr) <= 5e-2 * mr + 1e-7, f"model {k} {nm}: movement {mv} vs {mr}"
+
+
 def _same(got, ref, what, models=None):
     for k in (models if models is not None else ref):
         assert np.array_equal(got[k][0], ref[k][0]), f"loss of model {k} differs ({what})"
@@ -37,6 +60,7 @@ def test_task_parallel_policy_reproduces_the_shard_parallel_bits(H, i):
         got, st = H.train_workload(w, data, H.SCHED_TASK_PARALLEL, n_streams=n_streams)
         assert st[0]["grouped_tasks"] == 0 and st[0]["launches"] > rs[0]["launches"]
         _same(got, ref, f"task-parallel, {n_streams} streams")
+    _oracle_parity_bf16(w, got, data, w.steps, list(range(w.K)))      # and the task-parallel result is the oracle's
     if i == 3:  # with spilled state and recomputed activations as well
         nb = [sum((r * c + 63) // 64 * 64 for r, c in sh) for sh in _shapes(H, w)]
         budget = sum(nb) * 2 + 256 * 1024 + int(2.5 * (max(nb) // 2 * 16 + 64 * 1024))
@@ -80,6 +104,10 @@ def test_dropping_models_leaves_the_others_unchanged(H):
     two = _epochs(H, w, data, 2)
     _same(part, one, "model 1 stopped after one epoch", models=[1])
     _same(part, two, "model 3 stopped after two epochs", models=[3])
+    # against the oracle: every model trained alone, unsharded, for as many steps as it stayed in the schedule
+    # (the batches cycle: epoch e uses the same w.steps batches again)
+    for k, n_ep in ((0, 3), (1, 1), (2, 3), (3, 2)):
+        _oracle_parity_bf16(w, part, data, n_ep * w.steps, [k])
 
 
 def test_successive_halving_keeps_the_best_configuration(H):
@@ -126,6 +154,7 @@ def test_automatic_cuts_train_to_the_same_bits(H):
     finally:
         H.hydra_destroy(ctx)
     _same(got, ref, "automatic cuts")
+    _oracle_parity_bf16(w, got, data, w.steps, [0, 1])                # the oracle knows no cuts at all
 
 
 def test_paper_shaped_feed_forward_net_sharded_equals_unsharded_and_matches_oracle(H):

@@ -7,6 +7,7 @@ import pytest
 
 from hydra_workloads import make_data, scaled_workload, workload
 from oracle import model as OM
+from oracle import optim as OO
 from oracle import train as OT
 
 pytestmark = pytest.mark.gpu
@@ -161,3 +162,82 @@ def test_config3_full_size_one_step_sampled_against_oracle(H):
     for kk in range(w.K):
         assert abs(got[kk][0][0] - np.log(32000)) < 0.4
         assert all(np.all(np.isfinite(p)) for p in got[kk][1])
+
+
+def _first_step_against_oracle(H, w, k, batch):
+    """Full-width models on `batch` sequences per step, all K models in the benchmark's launch configuration.
+    Step 1: every gradient tensor of model k against the oracle's (relative L2 and cosine), the loss, and the
+    parameters after the update (norms, and how far each tensor moved); step 2, on a new batch: the loss."""
+    w.batch, w.steps, w.n_batches = batch, 2, 2
+    data = make_data(w)
+    one = lambda i: {n: (None if v is None else v[i:i + 1]) for n, v in data.items()}
+    arch, hp, names = w.archs[k], w.hparams[k], _names(w.archs[k])
+    # GPU, gradients kept: first-step gradients
+    ctx = H.hydra_create(n_streams=4, keep_grads=True)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for kk in range(w.K):
+            H.hydra_shard(ctx, kk, w.boundaries[kk])
+        H.hydra_set_data(ctx, one(0)["inputs"], one(0)["target_pos"], one(0)["targets"])
+        H.hydra_train_epoch(ctx)
+        grads = H.hydra_read_grads(ctx, k)
+    finally:
+        H.hydra_destroy(ctx)
+    # GPU, the default placement (updates inside the gradient kernels): two steps, parameters read after the first
+    ctx = H.hydra_create(n_streams=4)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for kk in range(w.K):
+            H.hydra_shard(ctx, kk, w.boundaries[kk])
+        H.hydra_set_data(ctx, one(0)["inputs"], one(0)["target_pos"], one(0)["targets"])
+        st = H.hydra_train_epoch(ctx)
+        assert st["grouped_tasks"] > 0
+        p1 = H.hydra_read_params(ctx, k)
+        H.hydra_set_data(ctx, one(1)["inputs"], one(1)["target_pos"], one(1)["targets"])
+        H.hydra_train_epoch(ctx)
+        losses = H.hydra_read_loss(ctx, k)
+        others = [H.hydra_read_loss(ctx, kk) for kk in range(w.K)]
+    finally:
+        H.hydra_destroy(ctx)
+    assert len(losses) == 2 and all(np.all(np.isfinite(l)) for l in others)
+    # oracle: one forward + backward + update, then a forward on the second batch
+    p0 = OM.init_params(arch, w.init_seed, k)
+    l1, gref = OM.loss_and_grads(arch, p0, OT.batch_at(data, 1))
+    bad = []
+    for nm, a, b in zip(names, grads, gref):
+        a, b = a.astype(np.float64).reshape(-1), b.reshape(-1)
+        if nm.endswith("bqkv"):      # the key third has an exactly zero gradient (softmax shift invariance); compare q and v
+            d3 = a.size // 3
+            assert np.abs(b[d3:2 * d3]).max() < 1e-12
+            a, b = np.r_[a[:d3], a[2 * d3:]], np.r_[b[:d3], b[2 * d3:]]
+        rel = np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30)
+        cos = float(a @ b) / max(np.linalg.norm(a) * np.linalg.norm(b), 1e-30)
+        if rel > 3e-2 or cos < 0.999:
+            bad.append(f"{nm}: rel {rel:.3e} cos {cos:.5f}")
+    assert not bad, "; ".join(bad)
+    ref = [p.copy() for p in p0]
+    state = OO.new_state(ref)
+    for j, g in enumerate(gref):
+        OO.update_tensor(hp, 1, ref[j], g, state["m"][j], state["v"][j])
+    x, b2 = None, OT.batch_at(data, 2)
+    for u in range(OM.n_units(arch)):
+        x, _ = OM.unit_fwd(arch, ref, u, x, b2)
+    lr1 = hp["lr"] * (min(1.0, 1.0 / hp["warmup_steps"]) if hp["warmup_steps"] > 0 else 1.0)
+    _check_bf16((losses.astype(np.float64), p1), (np.array([l1, float(x)]), ref), names,
+                [p.astype(np.float64) for p in p0], max_step=lr1)
+
+
+def test_config2_full_width_first_step_gradients_and_update_against_oracle(H):
+    """Workload 2's encoders at full width (12 blocks, d=768, 12 heads, FFN 3072, S=512, vocabulary 30522, K=4, 3 shards)
+    on 8 sequences per step instead of 32, which is what the fp64 oracle finishes in a test: 4096 tokens, so the
+    weight gradients of the 768-wide matrices still run as split sums (4 ranges), attention has 8 key tiles per block
+    and the head is 608 target rows x 30522 classes."""
+    _first_step_against_oracle(H, workload(2), k=1, batch=8)
+
+
+def test_config3_full_width_first_step_gradients_and_update_against_oracle(H):
+    """Workload 3's encoders at full width (d=1024, 16 heads, FFN 4096, S=512, vocabulary 32000, K=16 models of depth
+    12/18/24 in shards of 6 blocks, warm-up grid) on 4 sequences per step instead of 16; the sampled model is the first
+    one of depth 12."""
+    w = workload(3)
+    _first_step_against_oracle(H, w, k=w.extra["depths"].index(12), batch=4)

@@ -269,3 +269,67 @@ def test_initial_loss_is_near_log_classes_for_transformers():
     res = T.train_all(w.archs, w.hparams, data, 1, w.init_seed)
     for k in res:
         assert res[k][0][0] == pytest.approx(math.log(w.archs[k]["n_out"]), rel=0.03)
+
+
+def _splitmix_python(state, n):
+    """n-th output of SplitMix64 from `state` with Python integers (Steele, Lea, Flood 2014)."""
+    mask = (1 << 64) - 1
+    z = (state + (n + 1) * 0x9E3779B97F4A7C15) & mask
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+    return z ^ (z >> 31)
+
+
+def test_transformer_initialisation_bound_moments_and_stream():
+    """Matrices and embeddings of a Transformer start uniform on [-a, a) with a = fp32(0.02*sqrt(3)), i.e. standard
+    deviation 0.02: the bound, the first two moments, the zero / one tensors and, value by value, the counter
+    stream keyed by (seed, model, tensor) recomputed here with Python integers and exact rational arithmetic."""
+    from fractions import Fraction
+    arch = C.transformer_arch(C.KIND_ENCODER, 2, 64, 1, 256, 5000, 16, 0, C.DTYPE_BF16)
+    seed, model = 42, 3
+    params = M.init_params(arch, seed, model)
+    specs = M.tensor_specs(arch)
+    a = np.float32(0.02 * math.sqrt(3.0))
+    assert abs(float(a) - 0.0346410162) < 1e-9
+    for j, ((name, shape, kind), p) in enumerate(zip(specs, params)):
+        assert p.dtype == np.float32 and p.shape == tuple(shape)
+        if kind == "zero":
+            assert not p.any(), name
+        elif kind == "one":
+            assert np.all(p == 1.0), name
+        else:
+            assert kind == "n02" and np.abs(p).max() <= a, name
+            if p.size >= 1 << 14:   # sampling error of the moments of n uniform draws
+                n = p.size
+                assert abs(float(p.mean())) < 5 * 0.02 / math.sqrt(n), name
+                assert float(p.std()) == pytest.approx(0.02, rel=5 * math.sqrt(0.8 / n) / 2 + 1e-4), name
+                assert np.abs(p).max() > float(a) * (1 - 20.0 / n), name
+            # the first values of the stream, exactly
+            key = _splitmix_python(_splitmix_python(seed, 0) ^ ((model << 20) | j), 0)
+            for i in range(3):
+                u = Fraction(_splitmix_python(key, i) >> 40, 1 << 24)
+                exact = u * 2 * Fraction(float(a)) - Fraction(float(a))
+                assert p.reshape(-1)[i] == np.float32(float(exact)), (name, i)   # one rounding of the exact value
+    # the largest embedding has 5000*64 = 320000 entries: the head matrix differs from it (another stream)
+    assert not np.array_equal(params[0], params[-2])
+
+
+def test_batches_cycle_through_the_data_set():
+    """Step t (1-based) consumes batch (t-1) mod n_batches: a second pass over the data set reuses the batches in order."""
+    arch = C.mlp_arch(1, 4, 6, 3, C.ACT_GELU, C.DTYPE_F32)
+    r = np.random.default_rng(3)
+    nb = 3
+    data = dict(inputs=r.normal(size=(nb, 5, 4)).astype(np.float32), target_pos=None,
+                targets=r.integers(0, 3, size=(nb, 5)).astype(np.int32))
+    for t, want in zip(range(1, 9), [0, 1, 2, 0, 1, 2, 0, 1]):
+        b = T.batch_at(data, t)
+        assert np.array_equal(b["inputs"], data["inputs"][want]) and np.array_equal(b["targets"], data["targets"][want])
+        assert b["target_pos"] is None
+    # training 7 steps on 3 batches = training 7 steps on the 7 batches laid out in that order
+    order = [0, 1, 2, 0, 1, 2, 0]
+    flat = dict(inputs=data["inputs"][order], target_pos=None, targets=data["targets"][order])
+    hp = C.hparams(C.OPT_ADAM, 1e-2, warmup_steps=3)
+    l1, p1, _ = T.train_model(arch, hp, data, 7, 11, 0)
+    l2, p2, _ = T.train_model(arch, hp, flat, 7, 11, 0)
+    assert np.array_equal(l1, l2) and all(np.array_equal(x, y) for x, y in zip(p1, p2))
+    assert len(set(np.round(l1, 12))) == 7                    # and the steps are not all the same batch
