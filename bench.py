@@ -119,7 +119,7 @@ def measure(torch, H, w, label, steps, warmup, workload_index=None, profile=True
             H.hydra_profile_read(ctx, reset=True)
             H.hydra_profile_busy(ctx, reset=True)
             dt_prof, _ = run(steps, H.SCHED_SHARD_PARALLEL, True)
-            prof = H.hydra_profile_read(ctx, reset=True)
+            prof = {k: v for k, v in H.hydra_profile_read(ctx, reset=True).items() if not k.startswith("copy_")}
             busy = H.hydra_profile_busy(ctx, reset=True)
         dtype = "bf16" if w.archs[0]["dtype"] == 1 else "f32"
         peak = PEAK_TFLOPS[dtype]

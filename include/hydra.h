@@ -218,7 +218,9 @@ enum { HYDRA_K_GEMM_FWD = 0, HYDRA_K_GEMM_DGRAD = 1, HYDRA_K_GEMM_WGRAD = 2, HYD
        HYDRA_K_SOFTMAX_CE = 4, HYDRA_K_COLSUM = 5, HYDRA_K_LAYERNORM = 6, HYDRA_K_ATTENTION = 7,
        HYDRA_K_EMBED = 8, HYDRA_K_ELEMENTWISE = 9,
        HYDRA_K_WGRAD_UPDATE = 10, /* weight-gradient GEMM with the parameter update in its epilogue */
-       HYDRA_K_COUNT = 11 };
+       HYDRA_K_COPY_H2D = 11,     /* spilled state copied in from pinned host memory (not a kernel: bytes only) */
+       HYDRA_K_COPY_D2H = 12,     /* ... and copied back out after the update                                   */
+       HYDRA_K_COUNT = 13 };
 typedef struct {
   uint64_t launches;
   double total_ms;   /* sum of event-pair times                                                     */
@@ -232,6 +234,11 @@ hydra_status hydra_profile_read(hydra_ctx* ctx, int kernel_class, int reset, hyd
  * streams overlap, so this is at most the wall time, unlike the sum of the durations), span_ms = first start to last
  * end, summed over the epochs.  Accumulates until read with reset = 1. */
 hydra_status hydra_profile_busy(hydra_ctx* ctx, int reset, double* busy_ms, double* span_ms);
+/* Spill copies of the profiled epochs against the kernels (paper, Approach: work of other shards hides the wait for
+ * one shard's data): copy_ms = length of the union of the copy intervals of both directions, overlapped_ms = the part
+ * of it during which at least one kernel was running.  Both 0 when nothing is spilled.  Accumulates until read with
+ * reset = 1. */
+hydra_status hydra_profile_copy_overlap(hydra_ctx* ctx, int reset, double* copy_ms, double* overlapped_ms);
 
 /* Library-owned string, valid until the next call on ctx (ctx may be NULL: last create error). */
 const char* hydra_last_error(const hydra_ctx* ctx);

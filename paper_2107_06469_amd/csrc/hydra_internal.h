@@ -198,7 +198,8 @@ struct hydra_ctx {
   struct ProfSum { uint64_t launches = 0; double ms = 0, flops = 0, bytes = 0; };
   ProfSum prof_sum[HYDRA_K_COUNT];
   hipEvent_t prof_origin = nullptr;   // recorded when a profiled epoch starts, after the streams have drained
-  double prof_busy_ms = 0, prof_span_ms = 0;  // union of the launches' [start, end] intervals / first start to last end
+  double prof_busy_ms = 0, prof_span_ms = 0;
+  double prof_copy_ms = 0, prof_copy_overlapped_ms = 0;  // union of the spill copies' intervals / its part under kernels  // union of the launches' [start, end] intervals / first start to last end
 
   hydra_status fail(hydra_status st, const char* fmt, ...) {
     char buf[512];

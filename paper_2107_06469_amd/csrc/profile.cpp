@@ -37,15 +37,33 @@ hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double f
   return hipSuccess;
 }
 
+// merges intervals into a sorted list of disjoint ones
+static std::vector<std::pair<double, double>> union_of(std::vector<std::pair<double, double>> iv) {
+  std::vector<std::pair<double, double>> u;
+  std::sort(iv.begin(), iv.end());
+  for (const auto& x : iv) {
+    if (!u.empty() && x.first <= u.back().second) u.back().second = std::max(u.back().second, x.second);
+    else u.push_back(x);
+  }
+  return u;
+}
+
+static double length_of(const std::vector<std::pair<double, double>>& u) {
+  double t = 0;
+  for (const auto& x : u) t += x.second - x.first;
+  return t;
+}
+
 hydra_status prof_collect(hydra_ctx* c) {
-  std::vector<std::pair<double, double>> iv;  // [start, end] of every launch, ms since the epoch's origin
-  iv.reserve(c->prof_recs.size());
+  // [start, end] of every launch and of every spill copy, ms since the epoch's origin
+  std::vector<std::pair<double, double>> kern, copy;
   for (const auto& r : c->prof_recs) {
     float ms = 0.f, at = 0.f;
     HYDRA_HIP(c, hipEventElapsedTime(&ms, r.a, r.b));
     if (c->prof_origin) {
       HYDRA_HIP(c, hipEventElapsedTime(&at, c->prof_origin, r.a));
-      iv.push_back({(double)at, (double)at + ms});
+      const bool is_copy = r.cls == HYDRA_K_COPY_H2D || r.cls == HYDRA_K_COPY_D2H;
+      (is_copy ? copy : kern).push_back({(double)at, (double)at + ms});
     }
     auto& s = c->prof_sum[r.cls];
     ++s.launches;
@@ -55,22 +73,24 @@ hydra_status prof_collect(hydra_ctx* c) {
   }
   // time during which at least one kernel was running: launches on different streams overlap, so the sum of their
   // durations can exceed the wall time; the union of the intervals cannot
-  if (!iv.empty()) {
-    std::sort(iv.begin(), iv.end());
-    double busy = 0, lo = iv[0].first, hi = iv[0].second, first = iv[0].first, last = iv[0].second;
-    for (size_t i = 1; i < iv.size(); ++i) {
-      if (iv[i].first > hi) {
-        busy += hi - lo;
-        lo = iv[i].first;
-        hi = iv[i].second;
-      } else {
-        hi = std::max(hi, iv[i].second);
-      }
-      last = std::max(last, iv[i].second);
+  const auto ku = union_of(kern), cu = union_of(copy);
+  if (!ku.empty()) {
+    double last = 0;
+    for (const auto& x : ku) last = std::max(last, x.second);
+    c->prof_busy_ms += length_of(ku);
+    c->prof_span_ms += last - ku[0].first;
+  }
+  if (!cu.empty()) {
+    double both = 0;  // two sorted lists of disjoint intervals: length of their intersection
+    size_t i = 0, j = 0;
+    while (i < ku.size() && j < cu.size()) {
+      const double lo = std::max(ku[i].first, cu[j].first), hi = std::min(ku[i].second, cu[j].second);
+      if (hi > lo) both += hi - lo;
+      if (ku[i].second < cu[j].second) ++i;
+      else ++j;
     }
-    busy += hi - lo;
-    c->prof_busy_ms += busy;
-    c->prof_span_ms += last - first;
+    c->prof_copy_ms += length_of(cu);
+    c->prof_copy_overlapped_ms += both;
   }
   c->prof_recs.clear();
   c->prof_used = 0;
@@ -93,6 +113,15 @@ hydra_status hydra_profile_busy(hydra_ctx* c, int reset, double* busy_ms, double
   *busy_ms = c->prof_busy_ms;
   *span_ms = c->prof_span_ms;
   if (reset) c->prof_busy_ms = c->prof_span_ms = 0;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_profile_copy_overlap(hydra_ctx* c, int reset, double* copy_ms, double* overlapped_ms) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  if (!copy_ms || !overlapped_ms) return c->fail(HYDRA_ERR_INVALID_ARG, "NULL output");
+  *copy_ms = c->prof_copy_ms;
+  *overlapped_ms = c->prof_copy_overlapped_ms;
+  if (reset) c->prof_copy_ms = c->prof_copy_overlapped_ms = 0;
   return HYDRA_OK;
 }
 

@@ -190,9 +190,12 @@ hydra_status spill_acquire(hydra_ctx* c, int k, int s, hipStream_t compute, bool
   // the shard's own state must have reached host memory: its copy-out of the previous step runs on another stream
   // and nothing else orders it before this copy-in (the slot's event belongs to whichever shard held the slot last)
   if (sh.stored_ev) HYDRA_HIP(c, hipStreamWaitEvent(in, sh.stored_ev, 0));
+  hipEvent_t pa = nullptr;
+  if (c->profiling) HYDRA_HIP(c, prof_begin(c, in, &pa));
   HYDRA_HIP(c, copy_in_pieces(m.host_p, sh.off, sh.n, sh.p, in));
   HYDRA_HIP(c, copy_in_pieces(m.host_m, sh.off, sh.n, sh.m, in));
   HYDRA_HIP(c, copy_in_pieces(m.host_v, sh.off, sh.n, sh.v, in));
+  if (c->profiling) HYDRA_HIP(c, prof_end(c, in, pa, HYDRA_K_COPY_H2D, 0.0, 3.0 * bytes));
   if (!sh.loaded_ev) HYDRA_HIP(c, hipEventCreateWithFlags(&sh.loaded_ev, hipEventDisableTiming));
   HYDRA_HIP(c, hipEventRecord(sh.loaded_ev, in));
   return HYDRA_OK;
@@ -229,9 +232,12 @@ hydra_status spill_after_update(hydra_ctx* c, int k, int s, hipStream_t compute,
     HYDRA_HIP(c, hipEventRecord(sh.updated_ev, compute));
     HYDRA_HIP(c, hipStreamWaitEvent(out, sh.updated_ev, 0));
   }
+  hipEvent_t pa = nullptr;
+  if (c->profiling) HYDRA_HIP(c, prof_begin(c, out, &pa));
   HYDRA_HIP(c, copy_out_pieces(m.host_p, sh.off, sh.n, sh.p, out));
   HYDRA_HIP(c, copy_out_pieces(m.host_m, sh.off, sh.n, sh.m, out));
   HYDRA_HIP(c, copy_out_pieces(m.host_v, sh.off, sh.n, sh.v, out));
+  if (c->profiling) HYDRA_HIP(c, prof_end(c, out, pa, HYDRA_K_COPY_D2H, 0.0, 3.0 * bytes));
   HYDRA_HIP(c, hipEventRecord(sl.free_ev, out));
   if (!sh.stored_ev) HYDRA_HIP(c, hipEventCreateWithFlags(&sh.stored_ev, hipEventDisableTiming));
   HYDRA_HIP(c, hipEventRecord(sh.stored_ev, out));

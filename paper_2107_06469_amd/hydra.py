@@ -66,7 +66,7 @@ class hydra_kernel_profile(C.Structure):
 
 
 KERNEL_CLASSES = ["gemm_fwd", "gemm_dgrad", "gemm_wgrad", "optim", "softmax_ce", "colsum", "layernorm", "attention",
-                  "embed", "elementwise", "wgrad_update"]
+                  "embed", "elementwise", "wgrad_update", "copy_h2d", "copy_d2h"]
 
 _lib = None
 
@@ -97,6 +97,7 @@ def lib() -> C.CDLL:
         L.hydra_profile_enable.argtypes = [vp, C.c_int]
         L.hydra_profile_read.argtypes = [vp, C.c_int, C.c_int, C.POINTER(hydra_kernel_profile)]
         L.hydra_profile_busy.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.hydra_profile_copy_overlap.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.hydra_last_error.argtypes = [vp]
         L.hydra_last_error.restype = C.c_char_p
         _lib = L
@@ -316,6 +317,13 @@ def hydra_profile_busy(ctx: Context, reset: bool = True) -> Dict[str, float]:
     b, sp = C.c_double(0), C.c_double(0)
     _check(ctx.handle, lib().hydra_profile_busy(ctx.handle, 1 if reset else 0, C.byref(b), C.byref(sp)))
     return dict(busy_ms=b.value, span_ms=sp.value)
+
+
+def hydra_profile_copy_overlap(ctx: Context, reset: bool = True) -> Dict[str, float]:
+    """copy_ms: time with at least one spill copy in flight; overlapped_ms: the part of it under running kernels."""
+    a, b = C.c_double(0), C.c_double(0)
+    _check(ctx.handle, lib().hydra_profile_copy_overlap(ctx.handle, 1 if reset else 0, C.byref(a), C.byref(b)))
+    return dict(copy_ms=a.value, overlapped_ms=b.value)
 
 
 def train_workload(w, data, policy: int = SCHED_SHARD_PARALLEL, n_streams: int = 4, epochs: int = 1, tasks=None,

@@ -51,6 +51,7 @@ def run(w, data, n_models: int, policy: int, device_budget: int, activation_budg
         H.hydra_profile_enable(ctx, True)
         st = H.hydra_train_epoch(ctx, policy)
         prof = H.hydra_profile_read(ctx)
+        busy, ovl = H.hydra_profile_busy(ctx), H.hydra_profile_copy_overlap(ctx)
         losses = [H.hydra_read_loss(ctx, k) for k in range(n_models)]
         n_t = len(H.hydra_tensor_shapes(ctx, 0))
         probe = [2, 4, n_t - 6, n_t - 3]  # Wqkv and Wo of block 0, W2 of the last block, the final LayerNorm's bias
@@ -65,6 +66,9 @@ def run(w, data, n_models: int, policy: int, device_budget: int, activation_budg
               "host_link_GBps_each_way": st["h2d_bytes"] / 1e9 / sec,
               "peak_dev_GiB": st["peak_dev_bytes"] / 2 ** 30, "peak_host_GiB": st["peak_host_bytes"] / 2 ** 30,
               "launches_per_step": st["launches"] / w.steps, "losses": [l.tolist() for l in losses],
+              "gpu_busy_fraction": busy["busy_ms"] / st["wall_ms"],
+              "copy_busy_fraction": ovl["copy_ms"] / st["wall_ms"],
+              "copy_time_under_kernels": ovl["overlapped_ms"] / ovl["copy_ms"] if ovl["copy_ms"] > 0 else None,
               "kernel_ms_per_step": {k: round(v["total_ms"] / w.steps, 1) for k, v in prof.items()}}
     return losses, tensors, report
 
