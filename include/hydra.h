@@ -102,7 +102,23 @@ typedef struct {
   int max_group;               /* largest number of same-shaped shard tasks of different models that share one
                                   grouped launch under the shard-parallel and explicit schedules: 0 = as many
                                   as are ready (at most 16), 1..16 = that many; the ready tasks beyond a group
-                                  go to the next compute stream.  Results do not depend on it           */
+                                  go to the next compute stream.  Results do not depend on it.  Automatic:
+                                  the ready tasks of one shape are split into as many groups as there are
+                                  compute streams while every group still holds at least 384 tiles of 256 x 256
+                                  outputs of the shard's smallest matrix product (one and a half passes over the
+                                  256 compute units): below that a launch would leave units idle, which is what
+                                  grouping across models is for; above it, groups side by side on two streams let
+                                  one group's output stores overlap the other's products                  */
+  int auto_budget;             /* 1: the library chooses the two budgets above itself, from the memory the device
+                                  has (the scheduler the paper leaves as its next step is to automate sharding and
+                                  training; Evaluation, "Execution Plan").  State stays resident while parameters,
+                                  gradients and optimizer state of all models take at most 85 % of the capacity;
+                                  otherwise device_budget_bytes = 55 % of it (bf16 models trained with Adam).
+                                  Activations are kept while they fit 90 % of what is then left, otherwise
+                                  activation_budget_bytes = that amount and backward tasks recompute.  A budget
+                                  the caller gives (non-zero) is kept.  Results do not depend on any of this  */
+  size_t device_capacity_bytes;/* with auto_budget: the memory to plan for; 0 = the free device memory reported by
+                                  the runtime when the models are defined (a dry run needs a value)          */
 } hydra_options;
 
 typedef struct {

@@ -147,6 +147,23 @@ hydra_status hydra_define_models(hydra_ctx* c, int K, const hydra_arch* archs, i
       return st;
     }
   }
+  if (c->opt.auto_budget) {
+    // memory-aware default: keep state resident while it leaves room for activations, otherwise spill it
+    c->capacity = c->opt.device_capacity_bytes;
+    if (!c->capacity && !c->dry) {
+      size_t fr = 0, tot = 0;
+      HYDRA_HIP(c, hipMemGetInfo(&fr, &tot));
+      c->capacity = fr;
+    }
+    if (!c->capacity) {
+      c->models.clear();
+      return c->fail(HYDRA_ERR_INVALID_ARG, "auto_budget in a dry run needs device_capacity_bytes");
+    }
+    bool can_spill = true;
+    for (const Model& m : c->models) can_spill = can_spill && m.arch.dtype == HYDRA_DTYPE_BF16 && m.hp.opt == HYDRA_OPT_ADAM;
+    if (!c->opt.device_budget_bytes && can_spill && (double)resident_state_bytes(c) > 0.85 * (double)c->capacity)
+      c->opt.device_budget_bytes = (size_t)(0.55 * (double)c->capacity);
+  }
   c->spill = c->opt.device_budget_bytes > 0 && resident_state_bytes(c) > c->opt.device_budget_bytes;
   c->fuse = !c->spill && !c->opt.keep_grads;
   hydra_status st = c->spill ? spill_alloc_models(c) : alloc_models(c);

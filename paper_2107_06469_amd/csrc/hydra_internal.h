@@ -176,6 +176,7 @@ struct hydra_ctx {
   // allocations
   std::vector<void*> dev_allocs;
   size_t dev_bytes = 0, peak_dev_bytes = 0;
+  size_t capacity = 0;  // auto_budget: the device memory the budgets are planned for
   // spill mode (state does not fit device_budget_bytes)
   // weight updates run in the epilogue of the weight-gradient GEMM (resident state, gradients not kept)
   bool fuse = false;

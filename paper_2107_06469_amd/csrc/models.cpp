@@ -329,6 +329,12 @@ static hydra_status alloc_transformer_activations(hydra_ctx* c) {
     const TrDims q = dims_of(c, m.arch);
     keep_all += (size_t)m.arch.n_layers * block_bytes(q) + scratch_bytes(q);
   }
+  if (c->opt.auto_budget && !c->opt.activation_budget_bytes) {
+    // what the device has left once the state (or, when spilled, the state budget with its slots) is taken
+    const size_t held = c->spill ? std::max(c->dev_bytes, c->opt.device_budget_bytes) : c->dev_bytes;
+    const size_t left = c->capacity > held ? (size_t)(0.9 * (double)(c->capacity - held)) : 0;
+    if (keep_all > left) c->opt.activation_budget_bytes = std::max<size_t>(left, 1);
+  }
   c->recompute = c->opt.activation_budget_bytes > 0 && keep_all > c->opt.activation_budget_bytes;
   for (int k = 0; k < c->K; ++k) {
     Model& m = c->models[k];

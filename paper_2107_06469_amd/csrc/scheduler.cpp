@@ -29,6 +29,23 @@ static std::vector<Task> preds_of(const hydra_ctx* c, const Task& t) {
   return p;
 }
 
+// 256 x 256 output tiles of the smallest matrix product of a forward or backward task of shard s of model m
+// (rows = the step's tokens, columns = the hidden width): what one member adds to a grouped launch
+static long min_tiles_of(const hydra_ctx* c, const Model& m) {
+  const long rows = m.arch.kind == HYDRA_KIND_MLP ? c->B : (long)c->B * c->S;
+  return ((rows + 255) / 256) * ((m.arch.d_model + 255) / 256);
+}
+
+// Launch-group size for n ready same-shaped tasks (automatic mode): as many groups as there are compute streams,
+// as long as every group still brings at least 384 tiles (1.5 passes over 256 compute units) to its smallest launch.
+static int auto_group_size(const hydra_ctx* c, const Model& m, int n, int n_compute_streams, int maxg) {
+  const long per = min_tiles_of(c, m);
+  long groups = std::max<long>(1, (long)n * per / 384);
+  groups = std::min<long>(groups, std::max(1, n_compute_streams));
+  const int g = (int)((n + groups - 1) / groups);
+  return std::max(1, std::min(g, maxg));
+}
+
 static const char* ph_name(int ph) { return ph == 0 ? "F" : (ph == 1 ? "B" : "U"); }
 
 hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan) {
@@ -159,10 +176,14 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
     int next_c = 0;
     for (const auto& key : order) {
       const std::vector<Task>& ts = groups[key];
-      for (size_t i = 0; i < ts.size(); i += maxg) {
+      // update tasks stream their shard's state once: one launch for all of them; forward and backward groups are
+      // sized by the tile count of their products unless the caller fixed the size
+      const int gs = (c->opt.max_group > 0 || ts[0].ph == HYDRA_PHASE_U)
+                         ? maxg : auto_group_size(c, c->models[ts[0].k], (int)ts.size(), nc, maxg);
+      for (size_t i = 0; i < ts.size(); i += gs) {
         Bucket b;
         b.ph = ts[i].ph;
-        for (size_t j = i; j < std::min(ts.size(), i + (size_t)maxg); ++j) b.members.push_back({ts[j].k, ts[j].s});
+        for (size_t j = i; j < std::min(ts.size(), i + (size_t)gs); ++j) b.members.push_back({ts[j].k, ts[j].s});
         if (b.ph == HYDRA_PHASE_U && nu > 0) b.stream = nc + (next_u++ % nu);
         else b.stream = next_c++ % nc;
         plan.push_back(b);

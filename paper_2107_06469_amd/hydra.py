@@ -38,7 +38,8 @@ class hydra_options(C.Structure):
     _fields_ = [("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("user", C.c_void_p),
                 ("streams", C.POINTER(C.c_void_p)), ("n_streams", C.c_int),
                 ("device_budget_bytes", C.c_size_t), ("host_budget_bytes", C.c_size_t), ("dry_run", C.c_int), ("keep_grads", C.c_int),
-                ("activation_budget_bytes", C.c_size_t), ("max_group", C.c_int)]
+                ("activation_budget_bytes", C.c_size_t), ("max_group", C.c_int), ("auto_budget", C.c_int),
+                ("device_capacity_bytes", C.c_size_t)]
 
 
 class hydra_arch(C.Structure):
@@ -127,9 +128,12 @@ class Context:
 
 def hydra_create(n_streams: int = 4, dry_run: bool = False, use_torch: bool = True,
                  device_budget_bytes: int = 0, host_budget_bytes: int = 0, keep_grads: bool = False,
-                 activation_budget_bytes: int = 0, max_group: int = 0) -> Context:
+                 activation_budget_bytes: int = 0, max_group: int = 0, auto_budget: bool = False,
+                 device_capacity_bytes: int = 0) -> Context:
     """keep_grads: store every gradient and apply all updates in the update task (needed by hydra_read_grads).
-    use_torch: device memory comes from torch's allocator and streams are torch.cuda.Stream objects."""
+    use_torch: device memory comes from torch's allocator and streams are torch.cuda.Stream objects.
+    auto_budget: the library plans spilling and recomputation itself for device_capacity_bytes of device memory
+    (0: what is free now, counting the blocks torch's allocator holds but has not handed out)."""
     opts = hydra_options()
     opts.dry_run = 1 if dry_run else 0
     opts.device_budget_bytes = device_budget_bytes
@@ -137,6 +141,12 @@ def hydra_create(n_streams: int = 4, dry_run: bool = False, use_torch: bool = Tr
     opts.keep_grads = 1 if keep_grads else 0
     opts.activation_budget_bytes = activation_budget_bytes
     opts.max_group = max_group
+    opts.auto_budget = 1 if auto_budget else 0
+    opts.device_capacity_bytes = device_capacity_bytes
+    if auto_budget and not device_capacity_bytes and not dry_run and use_torch:
+        import torch
+        free, _total = torch.cuda.mem_get_info()
+        opts.device_capacity_bytes = int(free + torch.cuda.memory_reserved() - torch.cuda.memory_allocated())
     keep: Dict = {}
     if dry_run:
         opts.n_streams = n_streams
@@ -328,11 +338,12 @@ def hydra_profile_copy_overlap(ctx: Context, reset: bool = True) -> Dict[str, fl
 
 def train_workload(w, data, policy: int = SCHED_SHARD_PARALLEL, n_streams: int = 4, epochs: int = 1, tasks=None,
                    cuts=None, device_budget_bytes: int = 0, keep_grads: bool = False, activation_budget_bytes: int = 0,
-                   max_group: int = 0):
+                   max_group: int = 0, auto_budget: bool = False, device_capacity_bytes: int = 0):
     """Convenience used by tests and the benchmark: runs a hydra_workloads.Workload through the
     boundary and returns ({model: (losses, params)}, [stats per epoch])."""
     ctx = hydra_create(n_streams=n_streams, device_budget_bytes=device_budget_bytes, keep_grads=keep_grads,
-                       activation_budget_bytes=activation_budget_bytes, max_group=max_group)
+                       activation_budget_bytes=activation_budget_bytes, max_group=max_group, auto_budget=auto_budget,
+                       device_capacity_bytes=device_capacity_bytes)
     try:
         hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
         for k in range(w.K):

@@ -266,3 +266,26 @@ def test_profile_accounts_the_products_of_transformer_blocks(H, i):
         assert prof["attention"]["flops"] == pytest.approx(14.0 * att * steps, rel=1e-12)
     finally:
         H.hydra_destroy(ctx)
+
+
+def test_automatic_budgets_reproduce_the_resident_bits_and_the_oracle(H):
+    """auto_budget plans spilling and recomputation from the device capacity it is given: with room for the state but
+    not the activations it recomputes, with less than the state it spills as well; either way every bit equals the
+    run that keeps everything resident, which in turn matches the oracle."""
+    w = scaled_workload(4, K=3, depths=[4, 4, 4], steps=3, batch=8, seq=128)
+    data = make_data(w)
+    ref, rs = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL)
+    nb = [sum((r * c + 63) // 64 * 64 for r, c in sh) for sh in _shapes(H, w)]
+    state = sum(nb) * 18
+    acts = rs[0]["peak_dev_bytes"] - state
+    assert acts > state
+    got, st = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL, auto_budget=True, device_capacity_bytes=state + acts // 2)
+    assert st[0]["h2d_bytes"] == 0 and st[0]["launches"] > rs[0]["launches"] and st[0]["peak_dev_bytes"] < rs[0]["peak_dev_bytes"]
+    _same(got, ref, "automatic budgets: recomputed activations")
+    got, st = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL, auto_budget=True, device_capacity_bytes=int(state * 0.9))
+    assert st[0]["h2d_bytes"] > 0 and st[0]["peak_dev_bytes"] <= int(state * 0.9)
+    _same(got, ref, "automatic budgets: spilled state and recomputed activations")
+    got, st = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL, auto_budget=True)      # the real device: room for everything
+    assert st[0]["h2d_bytes"] == 0 and st[0]["launches"] == rs[0]["launches"]
+    _same(got, ref, "automatic budgets on the whole device")
+    _oracle_parity_bf16(w, ref, data, w.steps, [0, 1, 2])

@@ -302,3 +302,57 @@ def test_models_with_different_optimizers_never_share_a_launch_group():
         assert same["launches"] * 4 == seq["launches"] or same["launches"] < mixed["launches"]
     finally:
         H.hydra_destroy(ctx)
+
+
+def _plan_stats(w, d, **opts):
+    ctx = H.hydra_create(dry_run=True, **opts)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+        H.hydra_set_data(ctx, d["inputs"], d["target_pos"], d["targets"])
+        return H.hydra_train_epoch(ctx, H.SCHED_SHARD_PARALLEL)
+    finally:
+        H.hydra_destroy(ctx)
+
+
+def test_automatic_launch_groups_follow_the_tile_count_of_the_products():
+    """Automatic group size: ready same-shaped tasks are split over the compute streams only while every group
+    still brings 384 output tiles to its smallest product.  Workload 2 (16384 tokens x 768: 192 tiles per model)
+    with two compute streams runs forward and backward in two groups of two; with one stream, and workload 1
+    (512 tokens x 4096: 32 tiles per model) always, in one group of all models.  Update tasks stay in one group."""
+    w = workload(2)
+    w.steps = w.n_batches = 1
+    d = make_data(w)
+    auto4, full4, two4 = (_plan_stats(w, d, n_streams=4, max_group=g) for g in (0, 4, 2))
+    assert auto4["grouped_tasks"] == full4["grouped_tasks"] == 4 * 3 * 3
+    assert full4["launches"] < auto4["launches"] < two4["launches"]            # F and B in halves, U whole
+    assert _plan_stats(w, d, n_streams=1, max_group=0)["launches"] == _plan_stats(w, d, n_streams=1, max_group=4)["launches"]
+    w1 = workload(1)
+    w1.steps = w1.n_batches = 1
+    d1 = make_data(w1)
+    assert _plan_stats(w1, d1, n_streams=8, max_group=0)["launches"] == _plan_stats(w1, d1, n_streams=8, max_group=16)["launches"]
+
+
+def test_automatic_budgets_spill_and_recompute_only_when_the_device_is_too_small():
+    """auto_budget: with room for everything nothing is spilled or recomputed; with a capacity below the models' state
+    the state is spilled to the host; with a capacity between state and state + activations the backward tasks
+    recompute their shard's forward (more launches).  A dry run must be told the capacity."""
+    w = scaled_workload(4, K=3, depths=[4, 4, 4], steps=2, batch=8, seq=128)   # activations 1.6 x the state
+    d = make_data(w)
+    nb = _padded_blocks(w)
+    state = sum(nb) * 18                                      # fp32 master, gradient, two moments, bf16 copy
+    roomy = _plan_stats(w, d, n_streams=4, auto_budget=True, device_capacity_bytes=1 << 40)
+    plain = _plan_stats(w, d, n_streams=4)
+    assert roomy["h2d_bytes"] == 0 and roomy["launches"] == plain["launches"] and roomy["peak_dev_bytes"] == plain["peak_dev_bytes"]
+    acts = plain["peak_dev_bytes"] - state                    # activations, data and scratch of the resident plan
+    assert acts > 0
+    tight = _plan_stats(w, d, n_streams=4, auto_budget=True, device_capacity_bytes=state + acts // 2)
+    assert tight["h2d_bytes"] == 0 and tight["launches"] > plain["launches"]          # state resident, forward recomputed
+    assert tight["peak_dev_bytes"] < plain["peak_dev_bytes"]
+    small = _plan_stats(w, d, n_streams=4, auto_budget=True, device_capacity_bytes=int(state * 0.9))
+    assert small["h2d_bytes"] > 0 and small["peak_host_bytes"] >= sum(nb) * 12       # master and moments live on the host
+    assert small["peak_dev_bytes"] <= int(state * 0.9)
+    with pytest.raises(H.HydraError) as e:
+        _plan_stats(w, d, auto_budget=True)
+    assert e.value.status == 1
