@@ -6,6 +6,7 @@
 // unit L:      logits = x_L W_out^T + b_out, softmax cross-entropy
 // backward of unit l given dz_l:  dW_l = dz_l^T x_l;  db_l = column sums of dz_l (same launch);
 //                                 dz_{l-1} = (dz_l W_l) * act'(z_{l-1})         (l > 0)
+#include <algorithm>
 #include <cmath>
 
 #include "hydra_internal.h"
@@ -21,8 +22,69 @@ static const Tensor& b_of(const Model& m, int u) { return m.tensors[2 * u + 1]; 
 template <typename T>
 static T* at(T* base, const Shard& sh, const Tensor& t) { return base + (t.off - sh.off); }
 
+// Small fp32 models (at most 32 rows per step, layers at most 256 wide) run whole shard phases in one launch each
+// (mlp_fused.hip); the choice depends on the architecture and the batch alone, never on cuts, groups or policy.
+static bool fused_small(const hydra_ctx* c, const Model& m) {
+  const hydra_arch& a = m.arch;
+  return a.kind == HYDRA_KIND_MLP && a.dtype == HYDRA_DTYPE_F32 && !c->spill &&
+         mlp_fused_shape_ok(c->B, a.d_in, a.d_model, a.n_out, a.n_layers + 1);
+}
+
+static void fill_fused(hydra_ctx* c, const Bucket& b, int batch, int step, MlpFusedArgs& f) {
+  const Model& m0 = c->models[b.members[0].first];
+  const Shard& sh0 = m0.shards[b.members[0].second];
+  const hydra_arch& a = m0.arch;
+  f = MlpFusedArgs{};
+  f.G = (int)b.members.size();
+  f.B = c->B;
+  f.d_in = a.d_in;
+  f.d = a.d_model;
+  f.n_out = a.n_out;
+  f.L = a.n_layers;
+  f.u0 = sh0.u0;
+  f.u1 = sh0.u1;
+  f.act = a.act == HYDRA_ACT_RELU ? EPI_ACT_RELU : EPI_ACT_GELU;
+  f.opt = m0.hp.opt == HYDRA_OPT_ADAM ? 1 : 0;
+  f.keep_grads = c->fuse ? 0 : 1;
+  f.ld_in = c->ld_in;
+  f.ldd = rup8(a.d_model);
+  f.ldv = rup8(a.n_out);
+  for (int u = 0; u <= a.n_layers; ++u) {
+    f.w_off[u] = (unsigned)W_of(m0, u).off;
+    f.b_off[u] = (unsigned)b_of(m0, u).off;
+  }
+  f.inv_n = 1.0f / (float)c->B;
+  f.labels = c->targets + (size_t)batch * c->B;
+  for (int i = 0; i < f.G; ++i) {
+    const Model& m = c->models[b.members[i].first];
+    f.p[i] = m.p;
+    f.g[i] = m.g;
+    f.m[i] = m.m;
+    f.v[i] = m.v;
+    f.tab[i] = m.mlp.tab;
+    f.x[i] = static_cast<const float*>(c->x_staged) + (size_t)batch * c->B * c->ld_in;
+    f.loss[i] = m.loss_dev + step;
+    f.hp[i] = step_hparams(m, step);
+  }
+}
+
+// algorithmic flops of the products of units [u_lo, u_hi) for one model: 2 * rows * in * out each
+static double unit_flops(const hydra_ctx* c, const hydra_arch& a, int u_lo, int u_hi) {
+  double f = 0;
+  for (int u = u_lo; u < u_hi; ++u)
+    f += 2.0 * c->B * (u == 0 ? a.d_in : a.d_model) * (u < a.n_layers ? a.d_model : a.n_out);
+  return f;
+}
+
 static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   const Model& m0 = c->models[b.members[0].first];
+  if (fused_small(c, m0)) {
+    const Shard& sh = m0.shards[b.members[0].second];
+    MlpFusedArgs f;
+    fill_fused(c, b, batch, step, f);
+    HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, s, unit_flops(c, m0.arch, sh.u0, sh.u1) * f.G, 0.0, launch_mlp_fwd_fused(f, s));
+    return HYDRA_OK;
+  }
   const Shard& sh0 = m0.shards[b.members[0].second];
   const hydra_arch& a = m0.arch;
   const bool bf = a.dtype == HYDRA_DTYPE_BF16;
@@ -82,6 +144,23 @@ static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int st
 static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   const Model& m0 = c->models[b.members[0].first];
   const Shard& sh0 = m0.shards[b.members[0].second];
+  if (fused_small(c, m0)) {
+    const hydra_arch& a0 = m0.arch;
+    MlpFusedArgs f;
+    fill_fused(c, b, batch, step, f);
+    // input gradients through units u1-1 ... max(u0, 1), before any weight of the shard changes
+    const int u_lo = std::max(sh0.u0, 1);
+    if (sh0.u1 - 1 >= u_lo)
+      HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, unit_flops(c, a0, u_lo, sh0.u1) * f.G, 0.0, launch_mlp_dgrad_chain(f, s));
+    double bytes = 0;
+    for (int u = sh0.u0; u < sh0.u1; ++u) {
+      const double in = u == 0 ? a0.d_in : a0.d_model, out = u < a0.n_layers ? a0.d_model : a0.n_out;
+      bytes += fused_update_bytes(f.opt, false) * in * out + 4.0 * c->B * (in + out);
+    }
+    HYDRA_LAUNCH(c, c->fuse ? HYDRA_K_WGRAD_UPDATE : HYDRA_K_GEMM_WGRAD, s, unit_flops(c, a0, sh0.u0, sh0.u1) * f.G,
+                 c->fuse ? bytes * f.G : 0.0, launch_mlp_wgrad_update(f, s));
+    return HYDRA_OK;
+  }
   const hydra_arch& a = m0.arch;
   const bool bf = a.dtype == HYDRA_DTYPE_BF16;
   const size_t es = bf ? 2 : 4;
@@ -205,6 +284,7 @@ hydra_status run_update(hydra_ctx* c, const Bucket& b, int step, hipStream_t s) 
   size_t n = o.n;
   if (c->fuse) {
     const Shard& sh0 = c->models[b.members[0].first].shards[b.members[0].second];
+    if (fused_small(c, c->models[b.members[0].first])) return HYDRA_OK;  // weights and biases were updated by the backward task
     if (!sh0.n_tail_chunks) return HYDRA_OK;  // every tensor of the shard was updated by its gradient GEMM
     o.chunks = sh0.tail_chunks;
     o.n_chunks = sh0.n_tail_chunks;

@@ -55,6 +55,7 @@ struct MlpActs {                // per model, allocated by set_data
   float* logits = nullptr;      // [B, ldv] fp32
   void* dlogits = nullptr;      // [B, ldv] operand dtype
   float* rowloss = nullptr;     // [B]
+  MlpTab* tab = nullptr;        // device copy of the pointers above for the kernels that run whole shard phases
 };
 
 // Transformer activations of one model (bf16), allocated by set_data.  Tk = B*S tokens, NT = B*P targets.

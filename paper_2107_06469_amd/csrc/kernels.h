@@ -145,6 +145,41 @@ struct GemmUpdate {
 };
 hipError_t launch_gemm_update(const GemmArgs& a, const GemmUpdate& u, hipStream_t s);
 
+// ---- whole shard phases of small fp32 MLPs in one launch (mlp_fused.hip) --------------------------------------
+// For models with at most 32 rows per step and layers at most 256 wide: the forward pass of a shard's units [u0, u1)
+// is one launch (with the softmax cross-entropy when the shard ends the model), the backward pass two (the chain of
+// input gradients, then every weight gradient of the shard together with the update of its weights and biases, or
+// with keep_grads the stored gradients instead).  Unit u < L is Linear + activation, unit L the output Linear + loss.
+constexpr int MLP_FUSED_MAX_UNITS = 16;
+struct MlpTab {                      // device-resident table of one model's activation buffers (fp32)
+  float* z[MLP_FUSED_MAX_UNITS];     // [B, ldd] pre-activations of the hidden units
+  float* h[MLP_FUSED_MAX_UNITS];     // [B, ldd] activations
+  float* dz[MLP_FUSED_MAX_UNITS];    // [B, ldd] gradients w.r.t. the pre-activations
+  float* logits;                     // [B, ldv]
+  float* dlogits;                    // [B, ldv]
+  float* rowloss;                    // [B]
+};
+struct MlpFusedArgs {
+  int G, B, d_in, d, n_out, L, u0, u1, act, opt, keep_grads;
+  int ld_in, ldd, ldv;                          // row pitches of the batch, of z/h/dz, of logits/dlogits
+  unsigned w_off[MLP_FUSED_MAX_UNITS];          // element offsets of W_u [out, in] and b_u in a model's parameter block
+  unsigned b_off[MLP_FUSED_MAX_UNITS];
+  float inv_n;                                  // 1 / B
+  const int32_t* labels;                        // [B], shared by the group
+  float* p[MAXG];                               // parameter blocks (and gradient / moment blocks laid out alike)
+  float* g[MAXG];
+  float* m[MAXG];
+  float* v[MAXG];
+  const MlpTab* tab[MAXG];                      // device pointers
+  const float* x[MAXG];                         // [B, ld_in] rows of the step's batch
+  float* loss[MAXG];                            // one float each: the step's loss
+  OptimHp hp[MAXG];
+};
+bool mlp_fused_shape_ok(int B, int d_in, int d, int n_out, int n_units);
+hipError_t launch_mlp_fwd_fused(const MlpFusedArgs& a, hipStream_t s);
+hipError_t launch_mlp_dgrad_chain(const MlpFusedArgs& a, hipStream_t s);   // no launch when the shard has no unit > 0
+hipError_t launch_mlp_wgrad_update(const MlpFusedArgs& a, hipStream_t s);
+
 // ---- LayerNorm (layernorm.hip) --------------------------------------------------------------------------
 // y = (x-mean)*rstd*gamma + beta over rows of width d (d % 8 == 0, d <= 4096); mean/rstd fp32 per row.
 struct LnArgs {

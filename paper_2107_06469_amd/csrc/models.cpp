@@ -429,6 +429,21 @@ hydra_status alloc_activations(hydra_ctx* c) {
       ALLOC_OR_FAIL(c, t.logits, float*, (size_t)c->B * ldv * 4);
       ALLOC_OR_FAIL(c, t.dlogits, void*, (size_t)c->B * ldv * es);
       ALLOC_OR_FAIL(c, t.rowloss, float*, (size_t)c->B * 4);
+      if (a.dtype == HYDRA_DTYPE_F32 && mlp_fused_shape_ok(c->B, a.d_in, a.d_model, a.n_out, a.n_layers + 1)) {
+        ALLOC_OR_FAIL(c, t.tab, MlpTab*, sizeof(MlpTab));
+        if (!c->dry) {
+          MlpTab h{};
+          for (int l = 0; l < a.n_layers; ++l) {
+            h.z[l] = static_cast<float*>(t.z[l]);
+            h.h[l] = static_cast<float*>(t.h[l]);
+            h.dz[l] = static_cast<float*>(t.dz[l]);
+          }
+          h.logits = t.logits;
+          h.dlogits = static_cast<float*>(t.dlogits);
+          h.rowloss = t.rowloss;
+          HYDRA_HIP(c, hipMemcpy(t.tab, &h, sizeof(MlpTab), hipMemcpyHostToDevice));
+        }
+      }
     }
   }
   if (c->models[0].arch.kind != HYDRA_KIND_MLP) {

@@ -149,7 +149,19 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
   // wavefronts of ready tasks; inside a wavefront tasks are bucketed by (phase, signature)
   int nc = ns >= 2 ? std::max(1, ns / 2) : 1;  // streams [0,nc): F and B; [nc,ns): U
   if (c->recompute) nc = std::min(nc, c->ws_streams);  // every compute stream needs its own activation workspaces
-  const int nu = ns - nc;
+  int nu = ns - nc;
+  if (c->opt.max_group == 0) {
+    // launch-bound models (all of them together fill less than a quarter of the compute units with 256 x 256 tiles):
+    // their kernels take microseconds, less than a dependency that crosses streams costs, so everything stays on
+    // one stream and the launches simply queue
+    long all_tiles = 0;
+    for (int k = 0; k < K; ++k)
+      if (c->models[k].active) all_tiles += min_tiles_of(c, c->models[k]);
+    if (all_tiles < 64) {
+      nc = 1;
+      nu = 0;
+    }
+  }
   int next_u = 0;
   std::set<Task> issued;
   while (issued.size() < total) {

@@ -270,3 +270,46 @@ def test_config1_full_size_sampled_against_oracle(H):
         rl, rp, _ = OT.train_model(w.archs[k], w.hparams[k], data, 2, w.init_seed, k)
         p0 = [p.astype(np.float64) for p in OM.init_params(w.archs[k], w.init_seed, k)]
         _assert_bf16_parity(got[k], (rl, rp), _names(w.archs[k]), p0)
+
+
+@pytest.mark.parametrize("opt", [C.OPT_SGD, C.OPT_ADAM])
+def test_small_fp32_models_run_whole_shard_phases_in_one_launch_and_match_oracle(H, opt):
+    """fp32 models with at most 32 rows per step and layers at most 256 wide take the kernels that run a whole shard
+    phase per launch: one launch per forward task, two per backward task, none per update task.  Ragged sizes
+    (20 rows, 72 -> 136 wide, 25 classes), GeLU, SGD and Adam, three shards; against the oracle at the fp32 tolerance,
+    and bit-identical across policies, cuts, group sizes and the two update placements."""
+    K = 3
+    arch = C.mlp_arch(4, 72, 136, 25, C.ACT_GELU, C.DTYPE_F32)
+    lrs = [0.05, 0.02, 0.01] if opt == C.OPT_SGD else [1e-3, 3e-3, 1e-4]
+    w = C.Workload("mlp_small_f32", 0, [dict(arch) for _ in range(K)], [C.hparams(opt, lr) for lr in lrs], [[1, 3]] * K,
+                   20, 0, 0, 6, 6, 4321)
+    data = make_data(w)
+    ref = OT.train_all(w.archs, w.hparams, data, w.steps, w.init_seed)
+    got, st = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL)
+    assert st[0]["launches"] == w.steps * (3 + 2 + 3)        # F: 3 shards; B: chain + gradients, no chain for the first
+    for k in range(K):
+        kw = _adam_outliers(w, k) if opt == C.OPT_ADAM else {}
+        _assert_fp32_parity(got[k], ref[k], _names(w.archs[k]), **kw)
+    variants = [dict(policy=H.SCHED_SEQUENTIAL), dict(policy=H.SCHED_TASK_PARALLEL, n_streams=3),
+                dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[]] * K), dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[2], [1, 2, 3, 4], [4]]),
+                dict(policy=H.SCHED_SHARD_PARALLEL, max_group=2), dict(policy=H.SCHED_SHARD_PARALLEL, keep_grads=True)]
+    for v in variants:
+        other, _ = H.train_workload(w, data, **v)
+        for k in range(K):
+            assert np.array_equal(other[k][0], got[k][0]), f"loss differs under {v}"
+            for a, b in zip(other[k][1], got[k][1]):
+                assert np.array_equal(a, b), f"parameters differ under {v}"
+    # first-step gradients as stored by the gradient kernel, against the oracle's
+    ctx = H.hydra_create(n_streams=2, keep_grads=True)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        H.hydra_shard(ctx, -1, [1, 3])
+        one = {n: (None if v is None else v[:1]) for n, v in data.items()}
+        H.hydra_set_data(ctx, one["inputs"], None, one["targets"])
+        H.hydra_train_epoch(ctx)
+        for k in range(K):
+            _, gref = OM.loss_and_grads(w.archs[k], OM.init_params(w.archs[k], w.init_seed, k), OT.batch_at(data, 1))
+            for nm, a, b in zip(_names(w.archs[k]), H.hydra_read_grads(ctx, k), gref):
+                assert np.abs(a - b).max() <= 1e-5 * max(np.abs(b).max(), 1e-6) + 1e-9, (k, nm)
+    finally:
+        H.hydra_destroy(ctx)
