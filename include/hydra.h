@@ -219,6 +219,18 @@ hydra_status hydra_read_loss(hydra_ctx* ctx, int model, float* dst, size_t cap, 
 hydra_status hydra_read_grads(hydra_ctx* ctx, int model, int tensor, float* dst, size_t cap, size_t* n_written);
 hydra_status hydra_write_params(hydra_ctx* ctx, int model, int tensor, const float* src, size_t n);
 
+/* Checkpoint and resume.  A model's training state is its parameters (hydra_read_params / hydra_write_params), the
+ * optimizer's moments and the number of steps taken (which sets Adam's bias corrections and the warm-up).  read copies
+ * the first moments of all tensors in canonical order to m_dst and the second moments to v_dst (cap floats each;
+ * too small: HYDRA_ERR_BUFFER_TOO_SMALL with *n_written = the count per array; SGD models have no moments and report
+ * 0) and the step count to *steps.  write restores them (n floats each, the count read reports) into a context whose
+ * models were defined with the same architectures.  Training on from restored state gives the bits uninterrupted
+ * training gives (paper, Approach, "Desiderata", third item, extended over a restart). */
+hydra_status hydra_read_optimizer_state(hydra_ctx* ctx, int model, float* m_dst, float* v_dst, size_t cap, size_t* n_written,
+                                        int64_t* steps);
+hydra_status hydra_write_optimizer_state(hydra_ctx* ctx, int model, const float* m_src, const float* v_src, size_t n,
+                                         int64_t steps);
+
 /* Shape queries: number of tensors of a model; elements, rows and columns of one tensor;
  * number of shards of a model. */
 hydra_status hydra_tensor_count(hydra_ctx* ctx, int model, int* n_tensors);

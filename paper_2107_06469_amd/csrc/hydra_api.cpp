@@ -514,6 +514,73 @@ hydra_status hydra_write_params(hydra_ctx* c, int model, int tensor, const float
   HYDRA_CATCH(c)
 }
 
+hydra_status hydra_read_optimizer_state(hydra_ctx* c, int model, float* m_dst, float* v_dst, size_t cap, size_t* n_written,
+                                        int64_t* steps) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  if (!n_written || !steps) return c->fail(HYDRA_ERR_INVALID_ARG, "n_written or steps is NULL");
+  Model& m = c->models[model];
+  size_t need = 0;
+  if (m.hp.opt == HYDRA_OPT_ADAM)
+    for (const Tensor& t : m.tensors) need += t.n;
+  if (need && (cap < need || !m_dst || !v_dst)) {
+    *n_written = need;
+    return c->fail(HYDRA_ERR_BUFFER_TOO_SMALL, "need room for %zu floats per array, got %zu", need, cap);
+  }
+  if (c->dry) return c->fail(HYDRA_ERR_BAD_STATE, "a dry-run context holds no values");
+  for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  if (c->copy_out) HYDRA_HIP(c, hipStreamSynchronize(c->copy_out));
+  size_t o = 0;
+  if (need)
+    for (const Tensor& t : m.tensors) {
+      if (c->spill) {
+        m.host_m.pieces(t.off, t.n, [&](float* h, size_t at, size_t take) { memcpy(m_dst + o + at, h, take * 4); });
+        m.host_v.pieces(t.off, t.n, [&](float* h, size_t at, size_t take) { memcpy(v_dst + o + at, h, take * 4); });
+      } else {
+        HYDRA_HIP(c, hipMemcpy(m_dst + o, m.m + t.off, t.n * 4, hipMemcpyDeviceToHost));
+        HYDRA_HIP(c, hipMemcpy(v_dst + o, m.v + t.off, t.n * 4, hipMemcpyDeviceToHost));
+      }
+      o += t.n;
+    }
+  *n_written = need;
+  *steps = (int64_t)m.t;
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
+hydra_status hydra_write_optimizer_state(hydra_ctx* c, int model, const float* m_src, const float* v_src, size_t n,
+                                         int64_t steps) {
+  if (!c) return HYDRA_ERR_INVALID_ARG;
+  HYDRA_TRY
+  if (c->state < ST_DEFINED) return c->fail(HYDRA_ERR_BAD_STATE, "no models are defined");
+  if (model < 0 || model >= c->K) return c->fail(HYDRA_ERR_INVALID_ARG, "model %d does not exist", model);
+  if (steps < 0) return c->fail(HYDRA_ERR_INVALID_ARG, "steps must be >= 0");
+  Model& m = c->models[model];
+  size_t need = 0;
+  if (m.hp.opt == HYDRA_OPT_ADAM)
+    for (const Tensor& t : m.tensors) need += t.n;
+  if (n != need || (need && (!m_src || !v_src))) return c->fail(HYDRA_ERR_INVALID_ARG, "expected %zu floats per array, got %zu", need, n);
+  m.t = (long)steps;
+  if (c->dry || !need) return HYDRA_OK;
+  for (hipStream_t s : c->streams) HYDRA_HIP(c, hipStreamSynchronize(s));
+  if (c->copy_out) HYDRA_HIP(c, hipStreamSynchronize(c->copy_out));
+  size_t o = 0;
+  for (const Tensor& t : m.tensors) {
+    if (c->spill) {
+      m.host_m.pieces(t.off, t.n, [&](float* h, size_t at, size_t take) { memcpy(h, m_src + o + at, take * 4); });
+      m.host_v.pieces(t.off, t.n, [&](float* h, size_t at, size_t take) { memcpy(h, v_src + o + at, take * 4); });
+    } else {
+      HYDRA_HIP(c, hipMemcpy(m.m + t.off, m_src + o, t.n * 4, hipMemcpyHostToDevice));
+      HYDRA_HIP(c, hipMemcpy(m.v + t.off, v_src + o, t.n * 4, hipMemcpyHostToDevice));
+    }
+    o += t.n;
+  }
+  return HYDRA_OK;
+  HYDRA_CATCH(c)
+}
+
 hydra_status hydra_read_loss(hydra_ctx* c, int model, float* dst, size_t cap, size_t* n_written) {
   if (!c) return HYDRA_ERR_INVALID_ARG;
   HYDRA_TRY

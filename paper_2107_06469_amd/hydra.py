@@ -95,6 +95,8 @@ def lib() -> C.CDLL:
         L.hydra_shard_count.argtypes = [vp, C.c_int, C.POINTER(C.c_int)]
         L.hydra_auto_shard.argtypes = [vp, C.c_int, C.c_size_t, C.c_int, i32p, C.c_int, C.POINTER(C.c_int)]
         L.hydra_set_active.argtypes = [vp, C.c_int, C.c_int]
+        L.hydra_read_optimizer_state.argtypes = [vp, C.c_int, fp, fp, C.c_size_t, szp, C.POINTER(C.c_int64)]
+        L.hydra_write_optimizer_state.argtypes = [vp, C.c_int, fp, fp, C.c_size_t, C.c_int64]
         L.hydra_profile_enable.argtypes = [vp, C.c_int]
         L.hydra_profile_read.argtypes = [vp, C.c_int, C.c_int, C.POINTER(hydra_kernel_profile)]
         L.hydra_profile_busy.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -305,6 +307,27 @@ def hydra_write_params(ctx: Context, model: int, tensor: int, values):
         values = np.concatenate([np.asarray(v, dtype=np.float32).reshape(-1) for v in values])
     v = np.ascontiguousarray(values, dtype=np.float32).reshape(-1)
     _check(ctx.handle, lib().hydra_write_params(ctx.handle, model, tensor, v.ctypes.data_as(C.POINTER(C.c_float)), v.size))
+
+
+def hydra_read_optimizer_state(ctx: Context, model: int):
+    """(first moments, second moments, steps taken): flat fp32 arrays over all tensors in canonical order (empty for SGD)."""
+    n, steps = C.c_size_t(0), C.c_int64(0)
+    st = lib().hydra_read_optimizer_state(ctx.handle, model, None, None, 0, C.byref(n), C.byref(steps))
+    if st not in (0, 8):
+        _check(ctx.handle, st)
+    m, v = np.empty(n.value, dtype=np.float32), np.empty(n.value, dtype=np.float32)
+    fp = C.POINTER(C.c_float)
+    _check(ctx.handle, lib().hydra_read_optimizer_state(ctx.handle, model, m.ctypes.data_as(fp), v.ctypes.data_as(fp), n.value,
+                                                        C.byref(n), C.byref(steps)))
+    return m, v, int(steps.value)
+
+
+def hydra_write_optimizer_state(ctx: Context, model: int, m: np.ndarray, v: np.ndarray, steps: int):
+    m = np.ascontiguousarray(m, dtype=np.float32).reshape(-1)
+    v = np.ascontiguousarray(v, dtype=np.float32).reshape(-1)
+    fp = C.POINTER(C.c_float)
+    _check(ctx.handle, lib().hydra_write_optimizer_state(ctx.handle, model, m.ctypes.data_as(fp), v.ctypes.data_as(fp), m.size,
+                                                         steps))
 
 
 def hydra_profile_enable(ctx: Context, on: bool = True):

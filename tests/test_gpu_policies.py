@@ -289,3 +289,52 @@ def test_automatic_budgets_reproduce_the_resident_bits_and_the_oracle(H):
     assert st[0]["h2d_bytes"] == 0 and st[0]["launches"] == rs[0]["launches"]
     _same(got, ref, "automatic budgets on the whole device")
     _oracle_parity_bf16(w, ref, data, w.steps, [0, 1, 2])
+
+
+@pytest.mark.parametrize("case", ["mlp_bf16_adam", "mlp_f32_sgd_small", "encoder_warmup", "decoder_spilled"])
+def test_training_resumed_from_a_checkpoint_continues_bit_for_bit(H, case):
+    """Two epochs in one context against one epoch, then parameters, moments and step counts exported, imported into
+    a fresh context and a second epoch there: same losses and parameters, bit for bit (Adam's bias corrections and the
+    warm-up depend on the step count; spilled state lives in host memory)."""
+    budget = 0
+    if case == "mlp_bf16_adam":
+        w = scaled_workload(1, K=3, steps=3)
+    elif case == "mlp_f32_sgd_small":
+        w = C.workload(0)
+        w.steps = w.n_batches = 4
+    elif case == "encoder_warmup":
+        w = scaled_workload(3, K=3, steps=3, warmup=4)
+    else:
+        w = scaled_workload(4, K=2, depths=[4, 4], steps=3)
+        nb = [sum((r * c + 63) // 64 * 64 for r, c in sh) for sh in _shapes(H, w)]
+        budget = sum(nb) * 2 + 256 * 1024 + int(2.5 * (max(nb) // 2 * 16 + 64 * 1024))
+    data = make_data(w)
+
+    def fresh():
+        ctx = H.hydra_create(n_streams=4, device_budget_bytes=budget)
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+        H.hydra_set_data(ctx, data["inputs"], data["target_pos"], data["targets"])
+        return ctx
+    a = fresh()
+    try:
+        H.hydra_train_epoch(a)
+        saved = [(H.hydra_read_params(a, k), H.hydra_read_optimizer_state(a, k)) for k in range(w.K)]
+        H.hydra_train_epoch(a)
+        want = {k: (H.hydra_read_loss(a, k), H.hydra_read_params(a, k)) for k in range(w.K)}
+    finally:
+        H.hydra_destroy(a)
+    b = fresh()
+    try:
+        for k, (params, (m, v, steps)) in enumerate(saved):
+            assert steps == w.steps and (m.size == 0) == (w.hparams[k]["opt"] == C.OPT_SGD)
+            H.hydra_write_params(b, k, -1, params)
+            H.hydra_write_optimizer_state(b, k, m, v, steps)
+        H.hydra_train_epoch(b)
+        for k in range(w.K):
+            assert np.array_equal(H.hydra_read_loss(b, k), want[k][0][w.steps:]), f"{case}: loss of model {k}"
+            for x, y in zip(H.hydra_read_params(b, k), want[k][1]):
+                assert np.array_equal(x, y), f"{case}: parameters of model {k}"
+    finally:
+        H.hydra_destroy(b)

@@ -356,3 +356,33 @@ def test_automatic_budgets_spill_and_recompute_only_when_the_device_is_too_small
     with pytest.raises(H.HydraError) as e:
         _plan_stats(w, d, auto_budget=True)
     assert e.value.status == 1
+
+
+def test_optimizer_state_calls_check_their_arguments():
+    import ctypes as C
+    w = scaled_workload(1, K=2)                         # Adam
+    ctx = _dry(w)
+    try:
+        n, steps = C.c_size_t(0), C.c_int64(-1)
+        st = H.lib().hydra_read_optimizer_state(ctx.handle, 0, None, None, 0, C.byref(n), C.byref(steps))
+        assert st == 8 and n.value == sum(r * c for r, c in H.hydra_tensor_shapes(ctx, 0))
+        buf = np.zeros(n.value, dtype=np.float32)
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_write_optimizer_state(ctx, 0, buf[:-1], buf[:-1], 3)
+        assert e.value.status == 1
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_write_optimizer_state(ctx, 0, buf, buf, -1)
+        assert e.value.status == 1
+        with pytest.raises(H.HydraError):
+            H.hydra_write_optimizer_state(ctx, 5, buf, buf, 0)
+        H.hydra_write_optimizer_state(ctx, 0, buf, buf, 7)      # a dry run records the step count only
+    finally:
+        H.hydra_destroy(ctx)
+    w0 = workload(0)                                     # SGD: no moments
+    ctx = _dry(w0)
+    try:
+        n, steps = C.c_size_t(9), C.c_int64(-1)
+        st = H.lib().hydra_read_optimizer_state(ctx.handle, 0, None, None, 0, C.byref(n), C.byref(steps))
+        assert st == 2 and "dry-run" in H.lib().hydra_last_error(ctx.handle).decode()   # nothing to size, no values to give
+    finally:
+        H.hydra_destroy(ctx)
