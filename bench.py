@@ -34,7 +34,7 @@ def measured_traffic(kernel_class, workload):
     try:
         kv = dict(l.split(":", 1) for l in open(path) if ":" in l and not l.startswith("#"))
         h = hashlib.sha256()
-        for f in ("gemm.hip", "optim_math.h"):
+        for f in ("gemm.hip", "optim_math.h", "act_math.h"):
             h.update(open(os.path.join(ROOT, "paper_2107_06469_amd", "csrc", f), "rb").read())
         if kv["source_sha256"].strip() != h.hexdigest():
             return None
