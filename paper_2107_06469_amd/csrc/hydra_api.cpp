@@ -52,6 +52,7 @@ hydra_status hydra_create(const hydra_options* opts, hydra_ctx** out) {
       return HYDRA_ERR_DEVICE;
     }
     hipError_t e = kernels_init();
+    if (e == hipSuccess) e = mlp_fused_init();
     if (e != hipSuccess) {
       g_create_error = std::string("hydra_create: kernel set-up failed: ") + hipGetErrorString(e);
       delete c;

@@ -6,7 +6,9 @@
 // the model) is one launch with one workgroup per model; the backward pass is two: the chain of input gradients
 // through the shard's layers (one workgroup per model), then every weight gradient of the shard at once, each with the
 // parameter update in the same kernel (a workgroup per 32 output rows of a layer).  Activations stay in LDS between
-// layers; weights go from memory straight into MFMA operand registers, all requests of a layer in flight together.
+// layers.  In both chains a wave needs only its own 32 rows (forward) or columns (input gradient) of a weight matrix;
+// it streams them through a private piece of LDS in chunks of 32 k, requested 128 contiguous bytes per 8 lanes, two
+// chunks ahead of the one being multiplied, with the data movement placed between the dependent MFMAs.
 //
 // The products use v_mfma_f32_32x32x2_f32 with the same operand roles, the same k pairing inside an instruction
 // (k and k+4 of every group of 8) and the same ascending chain as the tiled fp32 GEMM kernel, and the epilogues apply
@@ -21,7 +23,6 @@ namespace {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int XS = 260;            // LDS row pitch in floats (256 + 4: rows spread over the banks)
-constexpr int MAXK8 = 32;          // groups of 8 k in the widest layer (256)
 
 // acc += W-operand chunk (4 consecutive k of one row n) x X-operand chunk (the same k of one row m): four instructions,
 // each summing k and k+4 (the two half-waves hold chunks 4 apart), in ascending order
@@ -55,27 +56,87 @@ __device__ __forceinline__ void stage_rows(float* xs, const float* src, int ld, 
 }
 
 // ---- forward: units [u0, u1) of one model per workgroup (8 waves; wave w owns output columns [32w, 32w+32)) ------
+// A wave multiplies by its own 32 rows of W only, so it stages them for itself: chunks of 32 k x 32 rows pass through
+// a piece of LDS that no other wave touches (8 lanes per row, 128 contiguous bytes each, so every line that travels is
+// used in full), two chunks are in flight in registers while a third is multiplied, and the requests run ahead across
+// layer ends (weights do not depend on activations).  Nothing inside a layer waits for another wave: the workgroup
+// meets only where a layer's outputs replace its inputs in LDS.
+constexpr int WP = 36;               // LDS pitch of a staged weight row: 32 k + 4 (16 rows read as float4 hit 16 bank groups)
+constexpr int WCH = 32 * WP;         // floats of one staged chunk of one wave
+constexpr size_t FWD_LDS = (32 * XS + 8 * 2 * WCH) * sizeof(float);
+
+// the same value in every lane, told to the compiler (descriptors of buffer loads must sit in scalar registers)
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const float* uniform(const float* p) {
+  const unsigned long long b = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+  return reinterpret_cast<const float*>(((unsigned long long)hi << 32) | lo);
+}
+
+// orders a wave's own LDS writes before its later LDS reads (the hardware keeps a wave's LDS operations in order; this
+// keeps the compiler from moving them)
+__device__ __forceinline__ void wave_lds_order() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+
 __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a) {
-  __shared__ float xs[32 * XS];
+  extern __shared__ float smem[];
+  float* xs = smem;                  // [32][XS] the layer's input rows
   __shared__ float rl[32];
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lrow = lane & 31, lgrp = lane >> 5;
   const MlpTab* tb = a.tab[g];
   const float* P = a.p[g];
-  const int n0 = wave * 32, n = n0 + lrow;
-  // this lane's chunks of row n of W_u: all K/8 requests of a layer in flight together
-  float4 wf[MAXK8];
-  auto load_w = [&](int u) {
-    const int K = u == 0 ? a.d_in : a.d, N = u < a.L ? a.d : a.n_out;
-    const float* W = P + a.w_off[u];
-#pragma unroll
-    for (int s = 0; s < MAXK8; ++s)
-      wf[s] = (8 * s < K && n < N) ? *reinterpret_cast<const float4*>(W + (size_t)n * K + 8 * s + 4 * lgrp) : zero4();
+  const int n0 = wave * 32;
+  float* wb = smem + 32 * XS + wave * 2 * WCH;  // [2][32][WP] this wave's weight chunks
+  const int ldrow = lane >> 3, ldseg = lane & 7;  // this lane's part of a chunk: rows n0 + ldrow + 8 i, k 4 ldseg .. + 3
+  // The next chunk to request: unit lu, chunk lc of it, and the unit's matrix (lW: lN x lK floats; past the shard's
+  // last unit an empty one).  Buffer loads with the whole address in the checked offset: rows at or past lN lie behind
+  // the end of the descriptor and read as zero, a chunk column at or past lK is sent out of range.
+  int lu = a.u0, lc = 0, lK = 0, lN = 0;
+  const float* lW = P;
+  auto unit_to_request = [&]() {  // after lu has changed
+    const bool live = lu < a.u1;
+    lK = uniform(lu == 0 ? a.d_in : a.d);
+    lN = uniform(!live ? 0 : (lu < a.L ? a.d : a.n_out));
+    lW = uniform(P + a.w_off[live ? lu : a.u0]);
   };
-  load_w(a.u0);  // in flight while the input rows are staged
+  unit_to_request();
+  auto advance = [&]() {
+    if (++lc * 32 >= (lK + 63) / 64 * 64) {  // every unit takes an even number of chunks (the last may be empty)
+      ++lu;
+      lc = 0;
+      unit_to_request();
+    }
+  };
+  auto issue = [&](float4 (&st)[4]) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lW), 0, lN * lK * 4, 0x00020000);
+    const int col = 32 * lc + 4 * ldseg;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned off = col < lK ? (unsigned)((n0 + ldrow + 8 * i) * lK + col) * 4u : 0xfffffff0u;
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+      st[i] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    }
+    advance();
+  };
+  auto commit = [&](const float4 (&st)[4], float* buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&buf[(ldrow + 8 * i) * WP + 4 * ldseg]) = st[i];
+    wave_lds_order();
+  };
+  float4 s0[4], s1[4];
+  issue(s0);  // chunk 0
+  issue(s1);  // chunk 1
   stage_rows(xs, a.u0 == 0 ? a.x[g] : tb->h[a.u0 - 1], a.u0 == 0 ? a.ld_in : a.ldd, a.B, a.u0 == 0 ? a.d_in : a.d, tid, 512);
-  __syncthreads();
+  commit(s0, wb);
+  issue(s0);  // chunk 2
+  __syncthreads();  // the input rows are in place
   for (int u = a.u0; u < a.u1; ++u) {
+    // here: buffer 0 holds the unit's chunk 0, s1 its chunk 1, s0 the chunk after that
     const int K = u == 0 ? a.d_in : a.d, N = u < a.L ? a.d : a.n_out;
     const float* bias = P + a.b_off[u];
     const bool active = n0 < N;  // uniform over the wave
@@ -91,11 +152,68 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
           const int nn = n0 + 8 * q + 4 * lgrp + e;
           bv[q][e] = nn < N ? bias[nn] : 0.f;
         }
-#pragma unroll
-      for (int s = 0; s < MAXK8; ++s)
-        if (8 * s < K) mma4(acc, wf[s], *reinterpret_cast<const float4*>(&xs[lrow * XS + 8 * s + 4 * lgrp]));
     }
-    if (u + 1 < a.u1) load_w(u + 1);  // the next layer's weights travel while this layer's outputs are finished
+    // where the unit's outputs go: read from the table now, not between the stores at the unit's end (a pointer read
+    // there would wait for every store before it)
+    float* const zu = u < a.L ? tb->z[u] : tb->logits;
+    float* const hu = u < a.L ? tb->h[u] : nullptr;
+    float* const dlog = u == a.L ? tb->dlogits : nullptr;
+    float* const rowl = u == a.L ? tb->rowloss : nullptr;
+    // One chunk: multiply by the chunk in `cur` while the chunk held in `st` moves into `other` and the next chunk to
+    // request takes its place in `st`, a quarter after each quarter of the products.  A wave's dependent MFMAs leave
+    // its issue slot idle; the data movement goes into those gaps instead of standing in front of the products.
+    auto half = [&](float4 (&st)[4], float* other, const float* cur, int c) {
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lW), 0, lN * lK * 4, 0x00020000);
+      const int col = 32 * lc + 4 * ldseg;
+      const bool inside = col < lK;
+      const unsigned off0 = (unsigned)((n0 + ldrow) * lK + col) * 4u, step = (unsigned)(8 * lK) * 4u;
+      auto move = [&](int s) {  // a quarter of the chunk in st goes to LDS, a quarter of the next request takes its place
+        __builtin_amdgcn_sched_barrier(0);
+        *reinterpret_cast<float4*>(&other[(ldrow + 8 * s) * WP + 4 * ldseg]) = st[s];
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(inside ? off0 + step * s : 0xfffffff0u), 0, 0);
+        st[s] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      if (active) {
+        // all of the chunk's operands are requested from LDS before the first product, so that only the first of
+        // them is waited for (steps at or past K read staged zeros or stale rows and are not multiplied)
+        float4 wq[4], xq[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          wq[s] = *reinterpret_cast<const float4*>(&cur[lrow * WP + 8 * s + 4 * lgrp]);
+          xq[s] = *reinterpret_cast<const float4*>(&xs[lrow * XS + 32 * c + 8 * s + 4 * lgrp]);
+        }
+        if (32 * c + 32 <= K) {  // a whole chunk: straight-line code
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            mma4(acc, wq[s], xq[s]);
+            move(s);
+          }
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            if (32 * c + 8 * s < K) mma4(acc, wq[s], xq[s]);
+            move(s);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) move(s);
+      }
+      advance();
+      wave_lds_order();
+    };
+    auto two_chunks = [&](int c) {
+      // the wave has multiplied by the other buffer's last chunk (its operands are in registers): it is free
+      half(s1, wb + WCH, wb, c);
+      half(s0, wb, wb + WCH, c + 1);
+    };
+    // The first pair stands outside the loop: the previous unit's stores may still be on their way when it starts,
+    // and a wait with loads and stores both outstanding is a wait for everything; inside the loop only loads are
+    // outstanding, so the wait for a chunk leaves the younger chunk's requests in flight.
+    two_chunks(0);
+    for (int c = 2; c * 32 < K; c += 2) two_chunks(c);
+    __syncthreads();  // every wave has read this layer's input from LDS
     // a lane holds, for row m = lrow, columns n0 + 8q + 4 lgrp + (0..3), q = 0..3
     float v[4][4];
     if (active) {
@@ -109,7 +227,6 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
         }
       }
     }
-    __syncthreads();  // every wave has read this layer's input from LDS
     if (active) {
       const int m = lrow;
 #pragma unroll
@@ -121,15 +238,15 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
 #pragma unroll
           for (int e = 0; e < 4; ++e) h[e] = act_fwd(v[q][e], a.act);
           if (m < a.B) {  // N = d is a multiple of 8: whole vectors
-            *reinterpret_cast<float4*>(tb->z[u] + (size_t)m * a.ldd + nq) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
-            *reinterpret_cast<float4*>(tb->h[u] + (size_t)m * a.ldd + nq) = make_float4(h[0], h[1], h[2], h[3]);
+            *reinterpret_cast<float4*>(zu + (size_t)m * a.ldd + nq) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
+            *reinterpret_cast<float4*>(hu + (size_t)m * a.ldd + nq) = make_float4(h[0], h[1], h[2], h[3]);
           }
           *reinterpret_cast<float4*>(&xs[m * XS + nq]) = make_float4(h[0], h[1], h[2], h[3]);
         } else {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             if (nq + e < N) {
-              if (m < a.B) tb->logits[(size_t)m * a.ldv + nq + e] = v[q][e];
+              if (m < a.B) zu[(size_t)m * a.ldv + nq + e] = v[q][e];
               xs[m * XS + nq + e] = v[q][e];
             }
         }
@@ -150,10 +267,10 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
           float sum = 0.f;
           for (int c = 0; c < C; ++c) sum += expf(z[c] - mx);
           const float lse = logf(sum) + mx, inv_sum = 1.f / sum;
-          float* dz = tb->dlogits + (size_t)m * a.ldv;
+          float* dz = dlog + (size_t)m * a.ldv;
           for (int c = 0; c < a.ldv; ++c) dz[c] = c < C ? (expf(z[c] - mx) * inv_sum - (c == y ? 1.f : 0.f)) * a.inv_n : 0.f;
           rowloss = lse - z[y];
-          tb->rowloss[m] = rowloss;
+          rowl[m] = rowloss;
         }
         rl[m] = rowloss;
       }
@@ -168,60 +285,128 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
 }
 
 // ---- backward, part 1: dz_{u-1} = (dz_u W_u) * act'(z_{u-1}) for u = u1-1 ... max(u0, 1), one model per workgroup ----
+// W_u is k-major for this product (its rows are the k of the sum); a wave stages its own 32 columns of a chunk of 32 k
+// (8 lanes per row, 128 contiguous bytes each) through the same private two-deep pipeline as in the forward kernel.
+constexpr int DCH = 32 * 32;         // floats of one staged chunk of one wave: 32 k x 32 columns
+constexpr size_t DGRAD_LDS = (32 * XS + 8 * 2 * DCH) * sizeof(float);
+
 __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs a) {
-  __shared__ float ds[32 * XS];
+  extern __shared__ float smem[];
+  float* ds = smem;                  // [32][XS] dz_u
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lrow = lane & 31, lgrp = lane >> 5;
   const MlpTab* tb = a.tab[g];
   const float* P = a.p[g];
   const int u_hi = a.u1 - 1, u_lo = a.u0 > 1 ? a.u0 : 1;
   if (u_hi < u_lo) return;
-  const int n0 = wave * 32, n = n0 + lrow;
-  const int Kin = a.d;                      // width of dz_{u-1} (u >= 1)
-  const bool active = n0 < Kin;
-  // W_u[k][n] for this lane's column n and the four rows k = 8s + 4 lgrp + (0..3) of every group s: buffer loads
-  // with the row offset as the uniform part of the address; rows at or past K and columns at or past Kin lie
-  // outside the descriptor and read as zero.  gate = z_{u-1} at the outputs this lane will hold.
-  float4 wf[MAXK8], gate[4];
-  auto load_w = [&](int u) {
-    const int K = u < a.L ? a.d : a.n_out;  // width of dz_u: the sum runs over it
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(P + a.w_off[u]), 0, K * Kin * 4, 0x00020000);
-    const int voff = n < Kin ? (4 * lgrp * Kin + n) * 4 : 0x7ffffff0;
-#pragma unroll
-    for (int s = 0; s < MAXK8; ++s) {
-      wf[s] = zero4();
-      if (8 * s < K) {
-        const int so = 8 * s * Kin * 4, row = Kin * 4;
-        wf[s].x = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, so, 0));
-        wf[s].y = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, so + row, 0));
-        wf[s].z = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, so + 2 * row, 0));
-        wf[s].w = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, voff, so + 3 * row, 0));
-      }
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int nq = n0 + 8 * q + 4 * lgrp;
-      gate[q] = (lrow < a.B && nq < Kin) ? *reinterpret_cast<const float4*>(tb->z[u - 1] + (size_t)lrow * a.ldd + nq) : zero4();
+  const int n0 = wave * 32;
+  float* wb = smem + 32 * XS + wave * 2 * DCH;  // [2][32][32] this wave's weight chunks
+  const int ldrow = lane >> 3, ldseg = lane & 7;  // this lane's part of a chunk: k ldrow + 8 i, columns n0 + 4 ldseg .. + 3
+  const int Kin = a.d;               // width of dz_{u-1} (u >= 1)
+  const bool active = n0 < Kin;      // uniform over the wave
+  // The next chunk to request: unit lu (descending), chunk lc of it, and the unit's matrix (lW: lK rows of Kin floats;
+  // below the shard's first unit an empty one).  Buffer loads with the whole address in the checked offset: the
+  // descriptor ends with row lK - 1, so rows at or past it read as zero; columns at or past Kin are sent out of range.
+  int lu = u_hi, lc = 0, lK = 0, lrows = 0;
+  const float* lW = P;
+  auto unit_to_request = [&]() {  // after lu has changed
+    const bool live = lu >= u_lo;
+    lK = uniform(lu < a.L ? a.d : a.n_out);  // rows of W_lu: the k of its sum
+    lrows = uniform(live ? lK : 0);
+    lW = uniform(P + a.w_off[live ? lu : u_hi]);
+  };
+  unit_to_request();
+  auto advance = [&]() {
+    if (++lc * 32 >= (lK + 63) / 64 * 64) {  // every unit takes an even number of chunks (the last may be empty)
+      --lu;
+      lc = 0;
+      unit_to_request();
     }
   };
-  if (active) load_w(u_hi);
+  const bool inside = n0 + 4 * ldseg < Kin;
+  auto issue = [&](float4 (&st)[4]) {
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lW), 0, lrows * Kin * 4, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned off = inside ? (unsigned)((32 * lc + ldrow + 8 * i) * Kin + n0 + 4 * ldseg) * 4u : 0xfffffff0u;
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
+      st[i] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    }
+    advance();
+  };
+  auto commit = [&](const float4 (&st)[4], float* buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&buf[(ldrow + 8 * i) * 32 + 4 * ldseg]) = st[i];
+    wave_lds_order();
+  };
+  float4 s0[4], s1[4];
+  issue(s0);  // chunk 0
+  issue(s1);  // chunk 1
   stage_rows(ds, u_hi < a.L ? tb->dz[u_hi] : tb->dlogits, u_hi < a.L ? a.ldd : a.ldv, a.B, u_hi < a.L ? a.d : a.n_out, tid, 512);
-  __syncthreads();
+  commit(s0, wb);
+  issue(s0);  // chunk 2
+  __syncthreads();  // dz of the shard's last unit is in place
   for (int u = u_hi; u >= u_lo; --u) {
+    // here: buffer 0 holds the unit's chunk 0, s1 its chunk 1, s0 the chunk after that
     const int K = u < a.L ? a.d : a.n_out;
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    float4 gz4[4];
-    if (active) {
+    // read the table now: between the stores at the unit's end a pointer read would wait for each of them
+    float* const dzo = tb->dz[u - 1];
+    const float* const zg = tb->z[u - 1];
+    float4 gate[4];  // z_{u-1} at the outputs this lane will hold
 #pragma unroll
-      for (int s = 0; s < MAXK8; ++s)
-        if (8 * s < K) mma4(acc, wf[s], *reinterpret_cast<const float4*>(&ds[lrow * XS + 8 * s + 4 * lgrp]));
-#pragma unroll
-      for (int q = 0; q < 4; ++q) gz4[q] = gate[q];
-      if (u - 1 >= u_lo) load_w(u - 1);  // the next unit's weights travel while this unit's outputs are finished
+    for (int q = 0; q < 4; ++q) {
+      const int nq = n0 + 8 * q + 4 * lgrp;
+      gate[q] = (active && lrow < a.B && nq < Kin) ? *reinterpret_cast<const float4*>(zg + (size_t)lrow * a.ldd + nq) : zero4();
     }
+    auto half = [&](float4 (&st)[4], float* other, const float* cur, int c) {
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lW), 0, lrows * Kin * 4, 0x00020000);
+      const unsigned off0 = (unsigned)((32 * lc + ldrow) * Kin + n0 + 4 * ldseg) * 4u, step = (unsigned)(8 * Kin) * 4u;
+      auto move = [&](int s) {  // a quarter of the chunk in st goes to LDS, a quarter of the next request takes its place
+        __builtin_amdgcn_sched_barrier(0);
+        *reinterpret_cast<float4*>(&other[(ldrow + 8 * s) * 32 + 4 * ldseg]) = st[s];
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(inside ? off0 + step * s : 0xfffffff0u), 0, 0);
+        st[s] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+        __builtin_amdgcn_sched_barrier(0);
+      };
+      if (active) {
+        // all of the chunk's operands are requested from LDS before the first product
+        const float* col = cur + lrow + 4 * lgrp * 32;
+        float4 wq[4], xq[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const float* r = col + 8 * s * 32;
+          wq[s] = make_float4(r[0], r[32], r[64], r[96]);
+          xq[s] = *reinterpret_cast<const float4*>(&ds[lrow * XS + 32 * c + 8 * s + 4 * lgrp]);
+        }
+        if (32 * c + 32 <= K) {  // a whole chunk: straight-line code
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            mma4(acc, wq[s], xq[s]);
+            move(s);
+          }
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            if (32 * c + 8 * s < K) mma4(acc, wq[s], xq[s]);
+            move(s);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) move(s);
+      }
+      advance();
+      wave_lds_order();
+    };
+    auto two_chunks = [&](int c) {
+      half(s1, wb + DCH, wb, c);
+      half(s0, wb, wb + DCH, c + 1);
+    };
+    two_chunks(0);  // outside the loop for the same reason as in the forward kernel
+    for (int c = 2; c * 32 < K; c += 2) two_chunks(c);
     __syncthreads();  // every wave has read dz_u from LDS
     if (active) {
       const int m = lrow;
@@ -229,12 +414,12 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
       for (int q = 0; q < 4; ++q) {
         const int nq = n0 + 8 * q + 4 * lgrp;
         if (nq >= Kin) continue;
-        const float gz[4] = {gz4[q].x, gz4[q].y, gz4[q].z, gz4[q].w};
+        const float gz[4] = {gate[q].x, gate[q].y, gate[q].z, gate[q].w};
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[4 * q + e] * act_grad(gz[e], a.act);
         const float4 o = make_float4(v[0], v[1], v[2], v[3]);
-        if (m < a.B) *reinterpret_cast<float4*>(tb->dz[u - 1] + (size_t)m * a.ldd + nq) = o;
+        if (m < a.B) *reinterpret_cast<float4*>(dzo + (size_t)m * a.ldd + nq) = o;
         *reinterpret_cast<float4*>(&ds[m * XS + nq]) = m < a.B ? o : zero4();
       }
     }
@@ -369,13 +554,21 @@ bool mlp_fused_shape_ok(int B, int d_in, int d, int n_out, int n_units) {
          n_out <= 256 && n_units <= MLP_FUSED_MAX_UNITS;
 }
 
+hipError_t mlp_fused_init() {
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_fwd_fused_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)FWD_LDS);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_dgrad_chain_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)DGRAD_LDS);
+}
+
 hipError_t launch_mlp_fwd_fused(const MlpFusedArgs& a, hipStream_t s) {
   hipError_t e = check(a);
   if (e != hipSuccess) return e;
   if (a.u1 == a.L + 1)
     for (int g = 0; g < a.G; ++g)
       if (!a.loss[g] || !a.labels) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(mlp_fwd_fused_kernel, dim3(a.G), dim3(512), 0, s, a);
+  hipLaunchKernelGGL(mlp_fwd_fused_kernel, dim3(a.G), dim3(512), FWD_LDS, s, a);
   return hipGetLastError();
 }
 
@@ -383,7 +576,7 @@ hipError_t launch_mlp_dgrad_chain(const MlpFusedArgs& a, hipStream_t s) {
   hipError_t e = check(a);
   if (e != hipSuccess) return e;
   if (a.u1 - 1 < (a.u0 > 1 ? a.u0 : 1)) return hipSuccess;  // no unit of the shard has an input gradient to produce
-  hipLaunchKernelGGL(mlp_dgrad_chain_kernel, dim3(a.G), dim3(512), 0, s, a);
+  hipLaunchKernelGGL(mlp_dgrad_chain_kernel, dim3(a.G), dim3(512), DGRAD_LDS, s, a);
   return hipGetLastError();
 }
 
