@@ -268,6 +268,15 @@ __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float (&v)[8]) {
     v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
   }
 }
+// 8 bf16 held in a 16-byte register group -> 8 floats
+__device__ __forceinline__ void unpack8(const uint4& a, float (&v)[8]) {
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
 template <typename T>
 __device__ __forceinline__ void store8(T* p, const float (&v)[8]);
 template <>
@@ -359,6 +368,72 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
   const bool plain_f32 = !UPD && a.out_f32 && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
   const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(bias) & 15) == 0;
+  // A wave whose 32 FM x 32 FN block lies inside the matrix (bf16 operands) takes a path without bounds checks: the
+  // bias is read once, and per 32-row band everything the band reads from memory (gate, multiplier, residual) is
+  // requested before the band's first store, so that a wait for a load is not also a wait for the stores in front of
+  // it.  Same operations in the same order per element as the general path below.
+  bool fast = false;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  void* const outp = a.out[g];
+  if constexpr (!UPD && sizeof(T) == 2) {
+    fast = !plain_f32 && mrow0 + FM * 32 <= a.M && ncol0 + FN * 32 <= a.N;
+    if (fast && bias) load8<float>(bias + ncol0 + (lane % LPR) * 8, bv);
+    if (fast) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
+                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        wave_lds_sync();
+        constexpr int NP = 32 / RPP;
+        const int c = (lane % LPR) * 8, r0 = lane / LPR, n = ncol0 + c;
+        uint4 gz[NP], mz[NP], rz[NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const size_t m = (size_t)(mrow0 + i * 32 + p * RPP + r0);
+          if (gate) gz[p] = *reinterpret_cast<const uint4*>(gate + m * a.ldg + n);
+          if (mul) mz[p] = *reinterpret_cast<const uint4*>(mul + m * a.ldo + n);
+          if (resid) rz[p] = *reinterpret_cast<const uint4*>(resid + m * a.ldr + n);
+        }
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const size_t m = (size_t)(mrow0 + i * 32 + p * RPP + r0);
+          float v[8], z[8];
+          load8<float>(&patch[(p * RPP + r0) * SP + c], v);
+          if (bias) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += bv[e];
+          }
+          if (pre) store8_stream<T>(pre + m * a.ldo + n, v);
+          if (gate) {
+            unpack8(gz[p], z);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= act_grad(z[e], act);
+          } else if (act != EPI_ACT_NONE) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = act_fwd(v[e], act);
+          }
+          if (mul) {
+            unpack8(mz[p], z);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] *= z[e];
+          }
+          if (resid) {
+            unpack8(rz[p], z);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += z[e];
+          }
+          if (a.out_f32) store8<float>(static_cast<float*>(outp) + out_off + m * a.ldo + n, v);
+          else store8_stream<T>(static_cast<T*>(outp) + m * a.ldo + n, v);
+        }
+        wave_lds_sync();
+      }
+      return;
+    }
+  }
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
 #pragma unroll

@@ -35,16 +35,33 @@ __device__ __forceinline__ void mma4(f32x16& acc, const float4& w, const float4&
 
 __device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 
+// A pointer read from the activation table in memory carries no address space, and through such a pointer the compiler
+// emits flat instructions, which count against the LDS counter as well and may complete out of order: every wait
+// after one is a wait for everything.  The table's pointers go to global memory; these types say so.
+typedef __attribute__((address_space(1))) float gfloat;
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) f32x4v gf32x4v;
+__device__ __forceinline__ gfloat* global_ptr(float* p) { return (gfloat*)p; }
+__device__ __forceinline__ const gfloat* global_ptr(const float* p) { return (const gfloat*)p; }
+__device__ __forceinline__ float4 gload4(const gfloat* p) {
+  const f32x4v v = *(const gf32x4v*)p;
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void gstore4(gfloat* p, float a, float b, float c, float d) {
+  const f32x4v v = {a, b, c, d};
+  *(gf32x4v*)p = v;
+}
+
 // rows [0, B) x columns [0, cols) of a row-major matrix into LDS rows of pitch XS; the rest of the 32 x cols8 block
 // (cols8 = cols rounded up to 8) is zero
-__device__ __forceinline__ void stage_rows(float* xs, const float* src, int ld, int B, int cols, int tid, int nt) {
+__device__ __forceinline__ void stage_rows(float* xs, const gfloat* src, int ld, int B, int cols, int tid, int nt) {
   const int c4n = (cols + 7) / 8 * 2;  // float4 groups per row
   for (int i = tid; i < 32 * c4n; i += nt) {
     const int m = i / c4n, c = (i % c4n) * 4;
     float4 v = zero4();
     if (m < B) {
-      const float* r = src + (size_t)m * ld + c;
-      if (c + 4 <= cols) v = *reinterpret_cast<const float4*>(r);
+      const gfloat* r = src + (size_t)m * ld + c;
+      if (c + 4 <= cols) v = gload4(r);
       else {
         if (c < cols) v.x = r[0];
         if (c + 1 < cols) v.y = r[1];
@@ -88,7 +105,7 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
   __shared__ float rl[32];
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lrow = lane & 31, lgrp = lane >> 5;
-  const MlpTab* tb = a.tab[g];
+  const __attribute__((address_space(1))) MlpTab* tb = (const __attribute__((address_space(1))) MlpTab*)a.tab[g];
   const float* P = a.p[g];
   const int n0 = wave * 32;
   float* wb = smem + 32 * XS + wave * 2 * WCH;  // [2][32][WP] this wave's weight chunks
@@ -131,7 +148,8 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
   float4 s0[4], s1[4];
   issue(s0);  // chunk 0
   issue(s1);  // chunk 1
-  stage_rows(xs, a.u0 == 0 ? a.x[g] : tb->h[a.u0 - 1], a.u0 == 0 ? a.ld_in : a.ldd, a.B, a.u0 == 0 ? a.d_in : a.d, tid, 512);
+  stage_rows(xs, global_ptr(a.u0 == 0 ? a.x[g] : tb->h[a.u0 - 1]), a.u0 == 0 ? a.ld_in : a.ldd, a.B, a.u0 == 0 ? a.d_in : a.d, tid,
+             512);
   commit(s0, wb);
   issue(s0);  // chunk 2
   __syncthreads();  // the input rows are in place
@@ -155,10 +173,10 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
     }
     // where the unit's outputs go: read from the table now, not between the stores at the unit's end (a pointer read
     // there would wait for every store before it)
-    float* const zu = u < a.L ? tb->z[u] : tb->logits;
-    float* const hu = u < a.L ? tb->h[u] : nullptr;
-    float* const dlog = u == a.L ? tb->dlogits : nullptr;
-    float* const rowl = u == a.L ? tb->rowloss : nullptr;
+    gfloat* const zu = global_ptr(u < a.L ? tb->z[u] : tb->logits);
+    gfloat* const hu = global_ptr(u < a.L ? tb->h[u] : nullptr);
+    gfloat* const dlog = global_ptr(u == a.L ? tb->dlogits : nullptr);
+    gfloat* const rowl = global_ptr(u == a.L ? tb->rowloss : nullptr);
     // One chunk: multiply by the chunk in `cur` while the chunk held in `st` moves into `other` and the next chunk to
     // request takes its place in `st`, a quarter after each quarter of the products.  A wave's dependent MFMAs leave
     // its issue slot idle; the data movement goes into those gaps instead of standing in front of the products.
@@ -238,8 +256,8 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
 #pragma unroll
           for (int e = 0; e < 4; ++e) h[e] = act_fwd(v[q][e], a.act);
           if (m < a.B) {  // N = d is a multiple of 8: whole vectors
-            *reinterpret_cast<float4*>(zu + (size_t)m * a.ldd + nq) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
-            *reinterpret_cast<float4*>(hu + (size_t)m * a.ldd + nq) = make_float4(h[0], h[1], h[2], h[3]);
+            gstore4(zu + (size_t)m * a.ldd + nq, v[q][0], v[q][1], v[q][2], v[q][3]);
+            gstore4(hu + (size_t)m * a.ldd + nq, h[0], h[1], h[2], h[3]);
           }
           *reinterpret_cast<float4*>(&xs[m * XS + nq]) = make_float4(h[0], h[1], h[2], h[3]);
         } else {
@@ -267,7 +285,7 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
           float sum = 0.f;
           for (int c = 0; c < C; ++c) sum += expf(z[c] - mx);
           const float lse = logf(sum) + mx, inv_sum = 1.f / sum;
-          float* dz = dlog + (size_t)m * a.ldv;
+          gfloat* dz = dlog + (size_t)m * a.ldv;
           for (int c = 0; c < a.ldv; ++c) dz[c] = c < C ? (expf(z[c] - mx) * inv_sum - (c == y ? 1.f : 0.f)) * a.inv_n : 0.f;
           rowloss = lse - z[y];
           rowl[m] = rowloss;
@@ -295,7 +313,7 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
   float* ds = smem;                  // [32][XS] dz_u
   const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lrow = lane & 31, lgrp = lane >> 5;
-  const MlpTab* tb = a.tab[g];
+  const __attribute__((address_space(1))) MlpTab* tb = (const __attribute__((address_space(1))) MlpTab*)a.tab[g];
   const float* P = a.p[g];
   const int u_hi = a.u1 - 1, u_lo = a.u0 > 1 ? a.u0 : 1;
   if (u_hi < u_lo) return;
@@ -342,7 +360,8 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
   float4 s0[4], s1[4];
   issue(s0);  // chunk 0
   issue(s1);  // chunk 1
-  stage_rows(ds, u_hi < a.L ? tb->dz[u_hi] : tb->dlogits, u_hi < a.L ? a.ldd : a.ldv, a.B, u_hi < a.L ? a.d : a.n_out, tid, 512);
+  stage_rows(ds, global_ptr(u_hi < a.L ? tb->dz[u_hi] : tb->dlogits), u_hi < a.L ? a.ldd : a.ldv, a.B, u_hi < a.L ? a.d : a.n_out,
+             tid, 512);
   commit(s0, wb);
   issue(s0);  // chunk 2
   __syncthreads();  // dz of the shard's last unit is in place
@@ -353,13 +372,13 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     // read the table now: between the stores at the unit's end a pointer read would wait for each of them
-    float* const dzo = tb->dz[u - 1];
-    const float* const zg = tb->z[u - 1];
+    gfloat* const dzo = global_ptr(tb->dz[u - 1]);
+    const gfloat* const zg = global_ptr(tb->z[u - 1]);
     float4 gate[4];  // z_{u-1} at the outputs this lane will hold
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int nq = n0 + 8 * q + 4 * lgrp;
-      gate[q] = (active && lrow < a.B && nq < Kin) ? *reinterpret_cast<const float4*>(zg + (size_t)lrow * a.ldd + nq) : zero4();
+      gate[q] = (active && lrow < a.B && nq < Kin) ? gload4(zg + (size_t)lrow * a.ldd + nq) : zero4();
     }
     auto half = [&](float4 (&st)[4], float* other, const float* cur, int c) {
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lW), 0, lrows * Kin * 4, 0x00020000);
@@ -419,7 +438,7 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[4 * q + e] * act_grad(gz[e], a.act);
         const float4 o = make_float4(v[0], v[1], v[2], v[3]);
-        if (m < a.B) *reinterpret_cast<float4*>(dzo + (size_t)m * a.ldd + nq) = o;
+        if (m < a.B) gstore4(dzo + (size_t)m * a.ldd + nq, v[0], v[1], v[2], v[3]);
         *reinterpret_cast<float4*>(&ds[m * XS + nq]) = m < a.B ? o : zero4();
       }
     }
@@ -435,10 +454,10 @@ __global__ __launch_bounds__(256) void mlp_wgrad_update_kernel(const MlpFusedArg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lgrp = lane >> 5;
   const int N = u < a.L ? a.d : a.n_out, Kin = u == 0 ? a.d_in : a.d;
   if (strip * 32 >= N) return;
-  const MlpTab* tb = a.tab[g];
-  const float* dz = u < a.L ? tb->dz[u] : tb->dlogits;
+  const __attribute__((address_space(1))) MlpTab* tb = (const __attribute__((address_space(1))) MlpTab*)a.tab[g];
+  const gfloat* dz = global_ptr(u < a.L ? tb->dz[u] : tb->dlogits);
   const int lddz = u < a.L ? a.ldd : a.ldv;
-  const float* xin = u == 0 ? a.x[g] : tb->h[u - 1];
+  const gfloat* xin = global_ptr(u == 0 ? a.x[g] : tb->h[u - 1]);
   const int ldx = u == 0 ? a.ld_in : a.ldd;
   const int n = strip * 32 + lrow;
   const OptimHp hp = a.hp[g];
