@@ -346,12 +346,98 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Epilogue of a wave whose 32 FM x 32 FN block lies inside the matrix, bf16 operands, no update: no bounds checks, the
+// bias is read once, and per 32-row band everything the band reads from memory (gate, multiplier, residual) is
+// requested before the band's first store, so that a wait for a load is not also a wait for the stores in front of
+// it.  MODE >= 0 fixes which operands exist (EPI_* bits) and ACT the activation at compile time: straight-line code,
+// where the version that tests them at run time (MODE = -1) spends much of its time in taken branches.  Per element
+// the same operations in the same order as the general path of tile_epilogue.
+enum { EPI_BIAS = 1, EPI_PRE = 2, EPI_GATE = 4, EPI_RESID = 8, EPI_ACTF = 16 };
+template <typename T, int FM, int FN, int MODE, int ACT>
+__device__ __forceinline__ void fast_bands(f32x16 (&acc)[FM][FN], float* patch, const GemmArgs& a, int g, int mrow0,
+                                           int ncol0, int lane, size_t out_off) {
+  constexpr bool CT = MODE >= 0;
+  constexpr int SP = FN * 32 + 4, LPR = FN * 4, RPP = 64 / LPR, NP = 32 / RPP;
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  const float* bias = a.bias[g];
+  T* pre = static_cast<T*>(a.pre[g]);
+  const T* gate = static_cast<const T*>(a.gate[g]);
+  const T* resid = static_cast<const T*>(a.resid[g]);
+  const T* mul = static_cast<const T*>(a.mul[g]);
+  void* const outp = a.out[g];
+  const bool has_bias = CT ? (MODE & EPI_BIAS) != 0 : bias != nullptr;
+  const bool has_pre = CT ? (MODE & EPI_PRE) != 0 : pre != nullptr;
+  const bool has_gate = CT ? (MODE & EPI_GATE) != 0 : gate != nullptr;
+  const bool has_resid = CT ? (MODE & EPI_RESID) != 0 : resid != nullptr;
+  const bool has_mul = CT ? false : mul != nullptr;
+  const bool out_f32 = CT ? false : a.out_f32 != 0;
+  const int act = CT ? ACT : a.act;
+  const bool has_actf = CT ? (MODE & EPI_ACTF) != 0 : (!has_gate && act != EPI_ACT_NONE);
+  const int c = (lane % LPR) * 8, r0 = lane / LPR, n = ncol0 + c;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (has_bias) load8<float>(bias + n, bv);
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    wave_lds_sync();
+    uint4 gz[NP], mz[NP], rz[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const size_t m = (size_t)(mrow0 + i * 32 + p * RPP + r0);
+      if (has_gate) gz[p] = *reinterpret_cast<const uint4*>(gate + m * a.ldg + n);
+      if (has_mul) mz[p] = *reinterpret_cast<const uint4*>(mul + m * a.ldo + n);
+      if (has_resid) rz[p] = *reinterpret_cast<const uint4*>(resid + m * a.ldr + n);
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+      const size_t m = (size_t)(mrow0 + i * 32 + p * RPP + r0);
+      float v[8], z[8];
+      load8<float>(&patch[(p * RPP + r0) * SP + c], v);
+      if (has_bias) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += bv[e];
+      }
+      if (has_pre) store8_stream<T>(pre + m * a.ldo + n, v);
+      if (has_gate) {
+        unpack8(gz[p], z);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= act_grad(z[e], act);
+      } else if (has_actf) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = act_fwd(v[e], act);
+      }
+      if (has_mul) {
+        unpack8(mz[p], z);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= z[e];
+      }
+      if (has_resid) {
+        unpack8(rz[p], z);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += z[e];
+      }
+      if (out_f32) store8<float>(static_cast<float*>(outp) + out_off + m * a.ldo + n, v);
+      else store8_stream<T>(static_cast<T*>(outp) + m * a.ldo + n, v);
+    }
+    wave_lds_sync();
+  }
+}
+
 // Epilogue of one wave: its FM x FN accumulators (rows mrow0.., columns ncol0.. of problem g) pass through the
 // wave's own LDS patch (32 x (FN*32+4) floats), one 32-row band at a time, and are read back row-wise so that a
 // lane owns 8 consecutive n of one m: global accesses are 16/32-byte vectors and a row band is written as FN*32
 // contiguous elements.  Only the wave itself touches its patch, so the waves of a workgroup run their epilogues
 // independently.
-template <typename T, int FM, int FN, bool UPD>
+// SPEC: which versions of the fast path a kernel carries (each costs compile time and code size): -1 none, 0 the one
+// that tests the operands at run time, 1 also the straight-line ones of forward products (bias; bias + residual;
+// bias + activation + stored pre-activation), 2 also those of input gradients (nothing; residual; gate; gate +
+// residual).
+template <typename T, int FM, int FN, bool UPD, int SPEC = -1>
 __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patch, const GemmArgs& a,
                                               const typename UpdSel<UPD>::type& upd, int g, int mrow0, int ncol0, int lane,
                                               size_t out_off = 0) {
@@ -368,69 +454,45 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
   const bool plain_f32 = !UPD && a.out_f32 && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
   const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(bias) & 15) == 0;
-  // A wave whose 32 FM x 32 FN block lies inside the matrix (bf16 operands) takes a path without bounds checks: the
-  // bias is read once, and per 32-row band everything the band reads from memory (gate, multiplier, residual) is
-  // requested before the band's first store, so that a wait for a load is not also a wait for the stores in front of
-  // it.  Same operations in the same order per element as the general path below.
-  bool fast = false;
-  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  void* const outp = a.out[g];
-  if constexpr (!UPD && sizeof(T) == 2) {
-    fast = !plain_f32 && mrow0 + FM * 32 <= a.M && ncol0 + FN * 32 <= a.N;
-    if (fast && bias) load8<float>(bias + ncol0 + (lane % LPR) * 8, bv);
-    if (fast) {
-#pragma unroll
-      for (int i = 0; i < FM; ++i) {
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
-                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-        wave_lds_sync();
-        constexpr int NP = 32 / RPP;
-        const int c = (lane % LPR) * 8, r0 = lane / LPR, n = ncol0 + c;
-        uint4 gz[NP], mz[NP], rz[NP];
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-          const size_t m = (size_t)(mrow0 + i * 32 + p * RPP + r0);
-          if (gate) gz[p] = *reinterpret_cast<const uint4*>(gate + m * a.ldg + n);
-          if (mul) mz[p] = *reinterpret_cast<const uint4*>(mul + m * a.ldo + n);
-          if (resid) rz[p] = *reinterpret_cast<const uint4*>(resid + m * a.ldr + n);
+  // A wave whose 32 FM x 32 FN block lies inside the matrix (bf16 operands) takes the path without bounds checks
+  // (fast_bands above); the combinations of epilogue operands that the trainers use have straight-line versions.
+  if constexpr (!UPD && sizeof(T) == 2 && SPEC >= 0) {
+    if (!plain_f32 && mrow0 + FM * 32 <= a.M && ncol0 + FN * 32 <= a.N) {
+      const int mode = (bias ? EPI_BIAS : 0) | (pre ? EPI_PRE : 0) | (gate ? EPI_GATE : 0) | (resid ? EPI_RESID : 0) |
+                       (!gate && act != EPI_ACT_NONE ? EPI_ACTF : 0);
+      bool done = false;
+      if constexpr (SPEC > 0) {
+        if (!mul && !a.out_f32 && (mode & (EPI_GATE | EPI_ACTF) ? (act == EPI_ACT_GELU || act == EPI_ACT_RELU) : true)) {
+          done = true;
+#define HYDRA_EPI_CASE(M)                                                                                              \
+  case M:                                                                                                              \
+    if ((M) & (EPI_GATE | EPI_ACTF)) {                                                                                 \
+      if (act == EPI_ACT_GELU) fast_bands<T, FM, FN, M, EPI_ACT_GELU>(acc, patch, a, g, mrow0, ncol0, lane, out_off);   \
+      else fast_bands<T, FM, FN, M, EPI_ACT_RELU>(acc, patch, a, g, mrow0, ncol0, lane, out_off);                      \
+    } else {                                                                                                           \
+      fast_bands<T, FM, FN, M, EPI_ACT_NONE>(acc, patch, a, g, mrow0, ncol0, lane, out_off);                           \
+    }                                                                                                                  \
+    break;
+          if constexpr (SPEC == 1) {
+            switch (mode) {
+              HYDRA_EPI_CASE(EPI_BIAS)
+              HYDRA_EPI_CASE(EPI_BIAS | EPI_RESID)
+              HYDRA_EPI_CASE(EPI_BIAS | EPI_PRE | EPI_ACTF)
+              default: done = false;
+            }
+          } else {
+            switch (mode) {
+              HYDRA_EPI_CASE(0)
+              HYDRA_EPI_CASE(EPI_RESID)
+              HYDRA_EPI_CASE(EPI_GATE)
+              HYDRA_EPI_CASE(EPI_GATE | EPI_RESID)
+              default: done = false;
+            }
+          }
+#undef HYDRA_EPI_CASE
         }
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-          const size_t m = (size_t)(mrow0 + i * 32 + p * RPP + r0);
-          float v[8], z[8];
-          load8<float>(&patch[(p * RPP + r0) * SP + c], v);
-          if (bias) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] += bv[e];
-          }
-          if (pre) store8_stream<T>(pre + m * a.ldo + n, v);
-          if (gate) {
-            unpack8(gz[p], z);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] *= act_grad(z[e], act);
-          } else if (act != EPI_ACT_NONE) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = act_fwd(v[e], act);
-          }
-          if (mul) {
-            unpack8(mz[p], z);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] *= z[e];
-          }
-          if (resid) {
-            unpack8(rz[p], z);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] += z[e];
-          }
-          if (a.out_f32) store8<float>(static_cast<float*>(outp) + out_off + m * a.ldo + n, v);
-          else store8_stream<T>(static_cast<T*>(outp) + m * a.ldo + n, v);
-        }
-        wave_lds_sync();
       }
+      if (!done) fast_bands<T, FM, FN, -1, 0>(acc, patch, a, g, mrow0, ncol0, lane, out_off);
       return;
     }
   }
@@ -1003,8 +1065,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
   constexpr int SP = FN * 32 + 4;
   static_assert((size_t)NW * 32 * SP * 4 <= (size_t)NS * STAGE, "epilogue patch exceeds LDS");
   float* patch = reinterpret_cast<float*>(lds) + wave * (32 * SP);
-  tile_epilogue<T, FM, FN, UPD>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane,
-                                SPLITK ? (size_t)sp * a.M * a.ldo : 0);
+  constexpr int SPEC = (UPD || SPLITK) ? -1 : (FM != 4 || FN != 2 || !X_KMAJ) ? 0 : (W_KMAJ ? 1 : 2);
+  tile_epilogue<T, FM, FN, UPD, SPEC>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane,
+                                      SPLITK ? (size_t)sp * a.M * a.ldo : 0);
 }
 
 // Second launch of a split weight gradient: element (m, n) of problem g = the S partial sums added in ascending
