@@ -38,18 +38,20 @@ def _report(label, seconds, flops=0.0, nbytes=0.0):
         rate, peak, unit = flops / seconds / 1e12, MFMA_PEAK / 1e12, "TFLOP/s"
     else:
         rate, peak, unit = nbytes / seconds / 1e9, HBM_PEAK / 1e9, "GB/s"
-    print(f"{label:86s} {seconds * 1e6:9.1f} us {rate:9.0f} {unit:8s} {rate / peak:6.3f} of peak", flush=True)
+    print(f"{label:112s} {seconds * 1e6:9.1f} us {rate:9.0f} {unit:8s} {rate / peak:6.3f} of peak", flush=True)
 
 
 def _gemms(want):
     import torch
     from . import ops
     bf = torch.bfloat16
-    # (label, models in one launch, tokens, out features, in features)
-    shapes = [("workload 1 layer", 8, 512, 4096, 4096), ("workload 2 QKV", 4, 16384, 2304, 768),
-              ("workload 2 FFN in", 4, 16384, 3072, 768), ("workload 2 FFN out", 4, 16384, 768, 3072),
-              ("workload 3 FFN in", 16, 8192, 4096, 1024), ("workload 4 FFN in", 2, 16384, 11008, 4096)]
-    for name, G, M, N, K in shapes:
+    # (label, models in one launch, tokens, out features, in features, forward epilogue, input-gradient epilogue) with
+    # the epilogues the trainers give these layers: "act" = bias, GeLU and the stored pre-activation; "resid" = bias and
+    # the residual stream added; "gate" = the product times GeLU'(stored pre-activation of the layer before)
+    shapes = [("workload 1 layer", 8, 512, 4096, 4096, "act", "gate"), ("workload 2 QKV", 4, 16384, 2304, 768, "bias", "plain"),
+              ("workload 2 FFN in", 4, 16384, 3072, 768, "act", "plain"), ("workload 2 FFN out", 4, 16384, 768, 3072, "resid", "gate"),
+              ("workload 3 FFN in", 16, 8192, 4096, 1024, "act", "plain"), ("workload 4 FFN in", 2, 16384, 11008, 4096, "act", "plain")]
+    for name, G, M, N, K, fwd_epi, bwd_epi in shapes:
         if not want(f"gemm {name}"):
             continue
         X = [torch.randn(M, K, device="cuda").to(bf) for _ in range(G)]
@@ -64,10 +66,22 @@ def _gemms(want):
             ws = [torch.zeros(ops.hydra_op_gemm_split_ws_bytes(N, K, M, K), dtype=torch.uint8, device="cuda") for _ in range(G)]
         fl = 2.0 * M * N * K * G
         tag = f"gemm {name}: {G} x [{M} tokens, {K} -> {N}]"
-        _report(tag + " forward (+bias)", _time(lambda: ops.hydra_op_gemm(
-            ops.BF16, M, N, K, X, W, O, x_kmajor=True, w_kmajor=True, ldx=K, ldw=K, ldo=N, bias=bias)), flops=fl)
-        _report(tag + " input gradient", _time(lambda: ops.hydra_op_gemm(
-            ops.BF16, M, K, N, DY, W, DX, x_kmajor=True, w_kmajor=False, ldx=N, ldw=K, ldo=K)), flops=fl)
+        fkw, flabel = dict(bias=bias), " forward (+bias)"
+        if fwd_epi == "act":
+            PRE = [torch.zeros(M, N, dtype=bf, device="cuda") for _ in range(G)]
+            fkw, flabel = dict(bias=bias, pre=PRE, act=ops.EPI_GELU), " forward (+bias, GeLU, pre-activation stored)"
+        elif fwd_epi == "resid":
+            RES = [torch.randn(M, N, device="cuda").to(bf) for _ in range(G)]
+            fkw, flabel = dict(bias=bias, resid=RES, ldr=N), " forward (+bias, +residual)"
+        bkw, blabel = dict(), " input gradient"
+        if bwd_epi == "gate":
+            GATE = [torch.randn(M, K, device="cuda").to(bf) for _ in range(G)]
+            bkw, blabel = dict(gate=GATE, ldg=K, act=ops.EPI_GELU), " input gradient (x GeLU' of the stored pre-activation)"
+        _report(tag + flabel, _time(lambda: ops.hydra_op_gemm(
+            ops.BF16, M, N, K, X, W, O, x_kmajor=True, w_kmajor=True, ldx=K, ldw=K, ldo=N, **fkw)), flops=fl)
+        _report(tag + blabel, _time(lambda: ops.hydra_op_gemm(
+            ops.BF16, M, K, N, DY, W, DX, x_kmajor=True, w_kmajor=False, ldx=N, ldw=K, ldo=K, **bkw)), flops=fl)
+        del fkw, bkw
         _report(tag + " weight gradient (fp32 out" + (", split over k)" if ws else ")"), _time(lambda: ops.hydra_op_gemm(
             ops.BF16, N, K, M, DY, X, GW, x_kmajor=False, w_kmajor=False, ldx=N, ldw=K, ldo=K, out_f32=True, ws=ws)), flops=fl)
         del X, W, O, DY, DX, GW, ws
