@@ -346,6 +346,95 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Epilogue of a wave of a weight-gradient product with the parameter update in it.  The optimizer state of a pass (8
+// rows of a 32-row band) depends on addresses only, so the loads of LA passes are issued together, ahead of the values
+// they will be combined with: more bytes in flight per wave while the accumulators still travel through the patch.
+// A lane takes 4 consecutive columns in two rows (RPP/2 apart) rather than 8 in one, so that each 16-byte load or
+// store instruction of the wave covers whole contiguous row segments (FN*128 bytes per row).  The state is read once
+// and written once per launch: loads and fp32 stores carry the non-temporal hint, so that the lines do not displace
+// the operand panels that other workgroups' k-loops still re-read from L2.  OPT (the optimizer) and INSIDE (the
+// wave's block lies inside the matrix: no bounds tests) are fixed at compile time and every pointer is read from the
+// argument block once, so that the passes are straight-line code.
+template <int FM, int FN, int OPT, bool INSIDE>
+__device__ __forceinline__ void update_bands(f32x16 (&acc)[FM][FN], float* patch, const GemmArgs& a, const GemmUpdate& upd,
+                                             int g, int mrow0, int ncol0, int lane) {
+  constexpr int SP = FN * 32 + 4, LPR = FN * 4, RPP = 64 / LPR, NP = 32 / RPP;
+  constexpr int LA = FM * FN <= 4 ? NP : 2;  // passes in flight (registers permitting)
+  constexpr int LPR4 = FN * 8, RPH = 64 / LPR4;  // lanes per row with 4 columns each; rows per instruction
+  static_assert(NP % LA == 0 && RPH * 2 == RPP, "passes per band");
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  const bool adam = OPT < 0 ? upd.opt == 1 : OPT == 1;  // OPT = -1: decided at run time (one copy of the code)
+  const OptimHp h = upd.hp[g];
+  float* const P = upd.p[g];
+  float* const Mo = upd.m[g];
+  float* const Vo = upd.v[g];
+  bf16_t* const W16 = upd.w16[g];
+  float* const G = static_cast<float*>(a.out[g]);
+  const int M = a.M, N = a.N;
+  const size_t ldo = (size_t)a.ldo;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    wave_lds_sync();
+#pragma unroll
+    for (int p0 = 0; p0 < NP; p0 += LA) {
+      f32x4 pe[LA][2], me[LA][2], ve[LA][2];
+      size_t idx[LA][2];
+      bool ok[LA][2];
+#pragma unroll
+      for (int q = 0; q < LA; ++q)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          const int r = (p0 + q) * RPP + hf * RPH + lane / LPR4, n = ncol0 + (lane % LPR4) * 4;
+          const int m = mrow0 + i * 32 + r;
+          ok[q][hf] = INSIDE || (m < M && n < N);  // N is a multiple of 8 here (checked by the launcher): full vectors only
+          idx[q][hf] = (size_t)m * ldo + n;
+          if (ok[q][hf]) {
+            pe[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(P + idx[q][hf]));
+            if (adam) {
+              me[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Mo + idx[q][hf]));
+              ve[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Vo + idx[q][hf]));
+            }
+          }
+        }
+#pragma unroll
+      for (int q = 0; q < LA; ++q)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+          if (!ok[q][hf]) continue;
+          const int r = (p0 + q) * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
+          const float4 gv = *reinterpret_cast<const float4*>(&patch[r * SP + c]);
+          const float v[4] = {gv.x, gv.y, gv.z, gv.w};
+          float pp[4] = {pe[q][hf].x, pe[q][hf].y, pe[q][hf].z, pe[q][hf].w};
+          float mm[4] = {0.f, 0.f, 0.f, 0.f}, vv[4] = {0.f, 0.f, 0.f, 0.f};
+          const size_t ix = idx[q][hf];
+          if (adam) {
+            mm[0] = me[q][hf].x; mm[1] = me[q][hf].y; mm[2] = me[q][hf].z; mm[3] = me[q][hf].w;
+            vv[0] = ve[q][hf].x; vv[1] = ve[q][hf].y; vv[2] = ve[q][hf].z; vv[3] = ve[q][hf].w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) optim_step<1>(pp[e], mm[e], vv[e], v[e], h);
+            const f32x4 mo = {mm[0], mm[1], mm[2], mm[3]}, vo = {vv[0], vv[1], vv[2], vv[3]};
+            __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(Mo + ix));
+            __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(Vo + ix));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) optim_step<0>(pp[e], mm[e], vv[e], v[e], h);
+          }
+          const f32x4 po = {pp[0], pp[1], pp[2], pp[3]};
+          __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(P + ix));
+          if (W16) *reinterpret_cast<uint2*>(W16 + ix) = make_uint2(pack_bf16x2(pp[0], pp[1]), pack_bf16x2(pp[2], pp[3]));
+          if (G) *reinterpret_cast<float4*>(G + ix) = gv;
+        }
+    }
+    wave_lds_sync();
+  }
+}
+
 // Epilogue of a wave whose 32 FM x 32 FN block lies inside the matrix, bf16 operands, no update: no bounds checks, the
 // bias is read once, and per 32-row band everything the band reads from memory (gate, multiplier, residual) is
 // requested before the band's first store, so that a wait for a load is not also a wait for the stores in front of
@@ -454,6 +543,21 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
   const bool plain_f32 = !UPD && a.out_f32 && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
   const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(bias) & 15) == 0;
+  if constexpr (UPD) {
+    if constexpr (SPEC >= 0) {
+      const bool inside = mrow0 + FM * 32 <= a.M && ncol0 + FN * 32 <= a.N;
+      if (upd.opt == 1) {
+        if (inside) update_bands<FM, FN, 1, true>(acc, patch, a, upd, g, mrow0, ncol0, lane);
+        else update_bands<FM, FN, 1, false>(acc, patch, a, upd, g, mrow0, ncol0, lane);
+      } else {
+        if (inside) update_bands<FM, FN, 0, true>(acc, patch, a, upd, g, mrow0, ncol0, lane);
+        else update_bands<FM, FN, 0, false>(acc, patch, a, upd, g, mrow0, ncol0, lane);
+      }
+    } else {  // the register-staged kernel's 256x256 tile has no registers to spare for more than one copy
+      update_bands<FM, FN, -1, false>(acc, patch, a, upd, g, mrow0, ncol0, lane);
+    }
+    return;
+  }
   // A wave whose 32 FM x 32 FN block lies inside the matrix (bf16 operands) takes the path without bounds checks
   // (fast_bands above); the combinations of epilogue operands that the trainers use have straight-line versions.
   if constexpr (!UPD && sizeof(T) == 2 && SPEC >= 0) {
@@ -504,75 +608,6 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
       for (int q = 0; q < 4; ++q)
         *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
             make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-    if constexpr (UPD) {
-      // The optimizer state of a pass (8 rows of the band) depends on addresses only, so the loads of LA passes are
-      // issued together, ahead of the values they will be combined with: more bytes in flight per wave while the
-      // accumulators still travel through the patch.
-      // A lane takes 4 consecutive columns in two rows (RPP/2 apart) rather than 8 in one, so that each 16-byte
-      // load or store instruction of the wave covers whole contiguous row segments (FN*128 bytes per row).
-      // The state is read once and written once per launch: loads and fp32 stores carry the non-temporal hint, so that
-      // the lines do not displace the operand panels that other workgroups' k-loops still re-read from L2.
-      constexpr int NP = 32 / RPP;
-      constexpr int LA = FM * FN <= 4 ? NP : 2;  // passes in flight (registers permitting)
-      constexpr int LPR4 = FN * 8, RPH = 64 / LPR4;  // lanes per row with 4 columns each; rows per instruction
-      static_assert(NP % LA == 0 && RPH * 2 == RPP, "passes per band");
-      const OptimHp h = upd.hp[g];
-      wave_lds_sync();
-#pragma unroll
-      for (int p0 = 0; p0 < NP; p0 += LA) {
-        f32x4 pe[LA][2], me[LA][2], ve[LA][2];
-        size_t idx[LA][2];
-        bool ok[LA][2];
-#pragma unroll
-        for (int q = 0; q < LA; ++q)
-#pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            const int r = (p0 + q) * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
-            const int m = mrow0 + i * 32 + r, n = ncol0 + c;
-            ok[q][hf] = m < a.M && n < a.N;  // N is a multiple of 8 here (checked by the launcher): full vectors only
-            idx[q][hf] = (size_t)m * a.ldo + n;
-            if (ok[q][hf]) {
-              pe[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(upd.p[g] + idx[q][hf]));
-              if (upd.opt == 1) {
-                me[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(upd.m[g] + idx[q][hf]));
-                ve[q][hf] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(upd.v[g] + idx[q][hf]));
-              }
-            }
-          }
-#pragma unroll
-        for (int q = 0; q < LA; ++q)
-#pragma unroll
-          for (int hf = 0; hf < 2; ++hf) {
-            if (!ok[q][hf]) continue;
-            const int r = (p0 + q) * RPP + hf * RPH + lane / LPR4, c = (lane % LPR4) * 4;
-            const float4 gv = *reinterpret_cast<const float4*>(&patch[r * SP + c]);
-            const float v[4] = {gv.x, gv.y, gv.z, gv.w};
-            float pp[4] = {pe[q][hf].x, pe[q][hf].y, pe[q][hf].z, pe[q][hf].w};
-            float mm[4] = {0.f, 0.f, 0.f, 0.f}, vv[4] = {0.f, 0.f, 0.f, 0.f};
-            const size_t ix = idx[q][hf];
-            if (upd.opt == 1) {
-              mm[0] = me[q][hf].x; mm[1] = me[q][hf].y; mm[2] = me[q][hf].z; mm[3] = me[q][hf].w;
-              vv[0] = ve[q][hf].x; vv[1] = ve[q][hf].y; vv[2] = ve[q][hf].z; vv[3] = ve[q][hf].w;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) optim_step<1>(pp[e], mm[e], vv[e], v[e], h);
-              const f32x4 mo = {mm[0], mm[1], mm[2], mm[3]}, vo = {vv[0], vv[1], vv[2], vv[3]};
-              __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(upd.m[g] + ix));
-              __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(upd.v[g] + ix));
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) optim_step<0>(pp[e], mm[e], vv[e], v[e], h);
-            }
-            const f32x4 po = {pp[0], pp[1], pp[2], pp[3]};
-            __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(upd.p[g] + ix));
-            if (upd.w16[g])
-              *reinterpret_cast<uint2*>(upd.w16[g] + ix) =
-                  make_uint2(pack_bf16x2(pp[0], pp[1]), pack_bf16x2(pp[2], pp[3]));
-            if (a.out[g]) *reinterpret_cast<float4*>(static_cast<float*>(a.out[g]) + ix) = gv;
-          }
-      }
-      wave_lds_sync();
-      continue;
-    }
     wave_lds_sync();
     if (plain_f32) {
       // fp32 sums stored as they are (a gradient, or a partial sum of a split one): 4 consecutive columns per lane in
@@ -1065,7 +1100,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const GemmArgs a,
   constexpr int SP = FN * 32 + 4;
   static_assert((size_t)NW * 32 * SP * 4 <= (size_t)NS * STAGE, "epilogue patch exceeds LDS");
   float* patch = reinterpret_cast<float*>(lds) + wave * (32 * SP);
-  constexpr int SPEC = (UPD || SPLITK) ? -1 : (FM != 4 || FN != 2 || !X_KMAJ) ? 0 : (W_KMAJ ? 1 : 2);
+  constexpr int SPEC = SPLITK ? -1 : (UPD || FM != 4 || FN != 2 || !X_KMAJ) ? 0 : (W_KMAJ ? 1 : 2);
   tile_epilogue<T, FM, FN, UPD, SPEC>(acc, patch, a, upd, g, m0 + wm * FM * 32, n0 + wn * FN * 32, lane,
                                       SPLITK ? (size_t)sp * a.M * a.ldo : 0);
 }
