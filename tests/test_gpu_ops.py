@@ -225,6 +225,63 @@ def test_gemm_result_is_independent_of_tile_and_group(torch, ops, layout):
             assert np.array_equal(ref, mine), f"{layout}: tile {tile}, group of {len(group)}"
 
 
+@pytest.mark.parametrize("combo", ["bias", "bias_resid", "bias_gelu_pre", "bias_relu_pre", "none", "resid", "gate_gelu",
+                                   "gate_relu_resid", "fwd_plain", "fwd_resid_only"])
+def test_gemm_epilogue_variants_on_big_tiles_agree_with_the_general_path(torch, ops, combo):
+    """256x256 tiles of the direct-to-LDS kernel (tile 1) run waves whose block lies inside the matrix through an
+    epilogue without bounds checks, compiled as straight-line code for the operand combinations the trainers use (the
+    last two combinations take its version that tests the operands at run time); the
+    register-staged 256x256 tile (tile 4) runs every wave through the general epilogue.  Both must give the same bits
+    for every element, also in the ragged last tiles (M = 600: rows 512.. of the third tile row; N = 520), and match the
+    oracle's Linear with the same epilogue."""
+    r = np.random.default_rng(100 + len(combo) + sum(map(ord, combo)))
+    fwd = combo.startswith(("bias", "fwd"))   # forward layout (W k-contiguous) or input-gradient layout
+    M, N, K, G = 600, 520, 264, 2
+    act = 2 if "gelu" in combo else (1 if "relu" in combo else 0)
+    Xs, Ws, want, extra = [], [], [], dict(bias=[], pre=[], gate=[], resid=[])
+    for g in range(G):
+        xd, xv = _dev(torch, r.normal(size=(M, K)), 1)
+        w = r.normal(size=(N, K)) / math.sqrt(K)
+        wd, wv = _dev(torch, w if fwd else w.T.copy(), 1)
+        Xs.append(xd), Ws.append(wd)
+        z = xv @ (wv.T if fwd else wv)
+        if "bias" in combo:
+            b = r.normal(size=N).astype(np.float32)
+            extra["bias"].append(torch.from_numpy(b).cuda())
+            z = z + b.astype(np.float64)
+        v = z
+        if "pre" in combo:
+            extra["pre"].append(torch.zeros((M, _ld(N)), dtype=torch.bfloat16, device="cuda"))
+        if "gate" in combo:
+            gd, gv = _dev(torch, r.normal(size=(M, N)) + 0.3, 1)
+            extra["gate"].append(gd)
+            v = v * (OL.gelu_grad(gv) if act == 2 else OL.relu_grad(gv))
+        elif act:
+            v = OL.gelu(v) if act == 2 else OL.relu(v)
+        if "resid" in combo:
+            rd, rv = _dev(torch, r.normal(size=(M, N)), 1)
+            extra["resid"].append(rd)
+            v = v + rv
+        want.append(v)
+    kw = {k: v for k, v in extra.items() if v}
+    got = {}
+    for tile in (1, 4):
+        outs = [torch.zeros((M, _ld(N)), dtype=torch.bfloat16, device="cuda") for _ in range(G)]
+        if "pre" in kw:
+            kw["pre"] = [torch.zeros((M, _ld(N)), dtype=torch.bfloat16, device="cuda") for _ in range(G)]
+        ops.hydra_op_gemm(1, M, N, K, Xs, Ws, outs, x_kmajor=1, w_kmajor=int(fwd), ldx=Xs[0].shape[1], ldw=Ws[0].shape[1],
+                          ldo=_ld(N), ldg=_ld(N), ldr=_ld(N), act=act, tile=tile, **kw)
+        torch.cuda.synchronize()
+        got[tile] = ([o[:, :N].float().cpu().numpy() for o in outs],
+                     [p_[:, :N].float().cpu().numpy() for p_ in kw.get("pre", [])])
+    for g in range(G):
+        assert np.array_equal(got[1][0][g], got[4][0][g]), f"{combo}: outputs differ between the two epilogue paths"
+        for a_, b_ in zip(got[1][1], got[4][1]):
+            assert np.array_equal(a_, b_), f"{combo}: stored pre-activations differ between the two epilogue paths"
+        scale = np.abs(want[g]).max()
+        assert np.abs(got[1][0][g] - want[g]).max() <= 2 ** -7 * scale + 1e-3, combo   # bf16 output rounding + bf16 operands
+
+
 def test_gemm_rejects_bad_arguments(torch, ops):
     from paper_2107_06469_amd.hydra import HydraError
     x = torch.zeros((8, 16), dtype=torch.bfloat16, device="cuda")
