@@ -435,6 +435,36 @@ __device__ __forceinline__ void update_bands(f32x16 (&acc)[FM][FN], float* patch
   }
 }
 
+// Epilogue of a wave that stores its fp32 sums as they are (a gradient, or a partial sum of a split one) and whose
+// block lies inside the matrix: 4 consecutive columns per lane in two rows, so that each 16-byte store instruction of
+// the wave covers contiguous row segments; no tests per element.
+template <int FM, int FN>
+__device__ __forceinline__ void plain_f32_bands(f32x16 (&acc)[FM][FN], float* patch, float* out, size_t ldo, int mrow0,
+                                                int ncol0, int lane) {
+  constexpr int SP = FN * 32 + 4, LPR = FN * 4, RPP = 64 / LPR, LPR4 = FN * 8, RPH = 64 / LPR4;
+  const int lrow = lane & 31, lgrp = lane >> 5;
+  const int c = (lane % LPR4) * 4, rl = lane / LPR4;
+  float* const o = out + (size_t)(mrow0 + rl) * ldo + ncol0 + c;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4*>(&patch[lrow * SP + j * 32 + 8 * q + 4 * lgrp]) =
+            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    wave_lds_sync();
+#pragma unroll
+    for (int p = 0; p < 32 / RPP; ++p)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int r = p * RPP + hf * RPH;
+        *reinterpret_cast<float4*>(o + (size_t)(i * 32 + r) * ldo) = *reinterpret_cast<const float4*>(&patch[(r + rl) * SP + c]);
+      }
+    wave_lds_sync();
+  }
+}
+
 // Epilogue of a wave whose 32 FM x 32 FN block lies inside the matrix, bf16 operands, no update: no bounds checks, the
 // bias is read once, and per 32-row band everything the band reads from memory (gate, multiplier, residual) is
 // requested before the band's first store, so that a wait for a load is not also a wait for the stores in front of
@@ -543,6 +573,12 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[FM][FN], float* patc
   const bool plain_f32 = !UPD && a.out_f32 && !pre && !gate && !resid && !mul && act == EPI_ACT_NONE;
   const bool vec4_ok = a.ldo % 4 == 0 && (reinterpret_cast<uintptr_t>(a.out[g]) & 15) == 0 && out_off % 4 == 0 &&
                       (reinterpret_cast<uintptr_t>(bias) & 15) == 0;
+  if constexpr (!UPD) {
+    if (plain_f32 && !bias && vec4_ok && mrow0 + FM * 32 <= a.M && ncol0 + FN * 32 <= a.N) {
+      plain_f32_bands<FM, FN>(acc, patch, static_cast<float*>(a.out[g]) + out_off, (size_t)a.ldo, mrow0, ncol0, lane);
+      return;
+    }
+  }
   if constexpr (UPD) {
     if constexpr (SPEC >= 0) {
       const bool inside = mrow0 + FM * 32 <= a.M && ncol0 + FN * 32 <= a.N;
