@@ -1157,54 +1157,62 @@ struct SplitFinishArgs {
 // A thread takes 4 consecutive columns, so that every 16-byte access of a wave covers contiguous memory; the S
 // partial sums are all requested before the first is used and added in ascending order of s.
 constexpr int SPLIT_MAX = 8;
+// MODE: 0 = store the sums, 1 = SGD, 2 = Adam (then `out` also receives the sums when it is given).  A wave takes 64
+// consecutive 16-byte pieces of a row, a workgroup four rows at a time: no index division, and the problem's pointers
+// are read from the argument block once.
+template <int MODE>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(const SplitFinishArgs a) {
   const int g = blockIdx.y;
   const size_t plane = (size_t)a.M * a.ldo;
   const int n4 = a.N / 4;  // N is a multiple of 8
-  const size_t total = (size_t)a.M * n4;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-    const int m = (int)(i / n4), n = (int)(i % n4) * 4;
-    const size_t idx = (size_t)m * a.ldo + n;
-    f32x4 part[SPLIT_MAX];
+  const int S = a.S;
+  const float* const WS = a.ws[g];
+  float* const P = a.p[g];
+  float* const Mo = a.m[g];
+  float* const Vo = a.v[g];
+  bf16_t* const W16 = a.w16[g];
+  float* const OUT = a.out[g];
+  const OptimHp h = a.hp[g];
+  const int lx = threadIdx.x & 63, ly = threadIdx.x >> 6;
+  for (int m = blockIdx.x * 4 + ly; m < a.M; m += gridDim.x * 4) {
+    for (int c = lx; c < n4; c += 64) {
+      const size_t idx = (size_t)m * a.ldo + 4 * c;
+      f32x4 part[SPLIT_MAX];
 #pragma unroll
-    for (int s = 0; s < SPLIT_MAX; ++s)
-      if (s < a.S) part[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.ws[g] + (size_t)s * plane + idx));
-    f32x4 pv, mv, vv;
-    if (a.upd) {
-      pv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.p[g] + idx));
-      if (a.opt == 1) {
-        mv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.m[g] + idx));
-        vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.v[g] + idx));
+      for (int s = 0; s < SPLIT_MAX; ++s)
+        if (s < S) part[s] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(WS + (size_t)s * plane + idx));
+      f32x4 pv, mv, vv;
+      if (MODE >= 1) pv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(P + idx));
+      if (MODE == 2) {
+        mv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Mo + idx));
+        vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Vo + idx));
       }
+      float v[4] = {part[0].x, part[0].y, part[0].z, part[0].w};
+#pragma unroll
+      for (int s = 1; s < SPLIT_MAX; ++s)
+        if (s < S) {
+          v[0] += part[s].x; v[1] += part[s].y; v[2] += part[s].z; v[3] += part[s].w;
+        }
+      if (MODE >= 1) {
+        float pe[4] = {pv.x, pv.y, pv.z, pv.w}, me[4] = {0.f, 0.f, 0.f, 0.f}, ve[4] = {0.f, 0.f, 0.f, 0.f};
+        if (MODE == 2) {
+          me[0] = mv.x; me[1] = mv.y; me[2] = mv.z; me[3] = mv.w;
+          ve[0] = vv.x; ve[1] = vv.y; ve[2] = vv.z; ve[3] = vv.w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
+          const f32x4 mo = {me[0], me[1], me[2], me[3]}, vo = {ve[0], ve[1], ve[2], ve[3]};
+          __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(Mo + idx));
+          __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(Vo + idx));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
+        }
+        const f32x4 po = {pe[0], pe[1], pe[2], pe[3]};
+        __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(P + idx));
+        if (W16) *reinterpret_cast<uint2*>(W16 + idx) = make_uint2(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]));
+      }
+      if (OUT) *reinterpret_cast<float4*>(OUT + idx) = make_float4(v[0], v[1], v[2], v[3]);
     }
-    float v[4] = {part[0].x, part[0].y, part[0].z, part[0].w};
-#pragma unroll
-    for (int s = 1; s < SPLIT_MAX; ++s)
-      if (s < a.S) {
-        v[0] += part[s].x; v[1] += part[s].y; v[2] += part[s].z; v[3] += part[s].w;
-      }
-    if (a.upd) {
-      const OptimHp h = a.hp[g];
-      float pe[4] = {pv.x, pv.y, pv.z, pv.w}, me[4] = {0.f, 0.f, 0.f, 0.f}, ve[4] = {0.f, 0.f, 0.f, 0.f};
-      if (a.opt == 1) {
-        me[0] = mv.x; me[1] = mv.y; me[2] = mv.z; me[3] = mv.w;
-        ve[0] = vv.x; ve[1] = vv.y; ve[2] = vv.z; ve[3] = vv.w;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) optim_step<1>(pe[e], me[e], ve[e], v[e], h);
-        const f32x4 mo = {me[0], me[1], me[2], me[3]}, vo = {ve[0], ve[1], ve[2], ve[3]};
-        __builtin_nontemporal_store(mo, reinterpret_cast<f32x4*>(a.m[g] + idx));
-        __builtin_nontemporal_store(vo, reinterpret_cast<f32x4*>(a.v[g] + idx));
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) optim_step<0>(pe[e], me[e], ve[e], v[e], h);
-      }
-      const f32x4 po = {pe[0], pe[1], pe[2], pe[3]};
-      __builtin_nontemporal_store(po, reinterpret_cast<f32x4*>(a.p[g] + idx));
-      if (a.w16[g])
-        *reinterpret_cast<uint2*>(a.w16[g] + idx) =
-            make_uint2(pack_bf16x2(pe[0], pe[1]), pack_bf16x2(pe[2], pe[3]));
-    }
-    if (a.out[g]) *reinterpret_cast<float4*>(a.out[g] + idx) = make_float4(v[0], v[1], v[2], v[3]);
   }
   if (a.rowsum[g] && blockIdx.x == 0) {
     const float* rs = a.ws[g] + (size_t)a.S * plane;
@@ -1396,9 +1404,11 @@ hipError_t run_split(const GemmArgs& a, const GemmUpdate* u, int S, hipStream_t 
   b.split_k = S;
   hipError_t e = DmaBig::run_split(b, s);
   if (e != hipSuccess) return e;
-  const size_t vecs = (size_t)a.M * (a.N / 8);
-  const unsigned bx = (unsigned)std::min<size_t>((vecs + 255) / 256, 4096);
-  hipLaunchKernelGGL(splitk_finish_kernel, dim3(bx, a.G), dim3(256), 0, s, f);
+  // a workgroup takes four rows at a time; enough workgroups to fill the device several times over
+  const unsigned bx = (unsigned)std::min<size_t>(((size_t)a.M + 3) / 4, 4096);
+  if (!u) hipLaunchKernelGGL(splitk_finish_kernel<0>, dim3(bx, a.G), dim3(256), 0, s, f);
+  else if (u->opt == 1) hipLaunchKernelGGL(splitk_finish_kernel<2>, dim3(bx, a.G), dim3(256), 0, s, f);
+  else hipLaunchKernelGGL(splitk_finish_kernel<1>, dim3(bx, a.G), dim3(256), 0, s, f);
   return hipGetLastError();
 }
 
