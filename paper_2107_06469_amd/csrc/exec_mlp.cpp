@@ -24,7 +24,7 @@ static T* at(T* base, const Shard& sh, const Tensor& t) { return base + (t.off -
 
 // Small fp32 models (at most 32 rows per step, layers at most 256 wide) run whole shard phases in one launch each
 // (mlp_fused.hip); the choice depends on the architecture and the batch alone, never on cuts, groups or policy.
-static bool fused_small(const hydra_ctx* c, const Model& m) {
+bool mlp_runs_fused(const hydra_ctx* c, const Model& m) {
   const hydra_arch& a = m.arch;
   return a.kind == HYDRA_KIND_MLP && a.dtype == HYDRA_DTYPE_F32 && !c->spill &&
          mlp_fused_shape_ok(c->B, a.d_in, a.d_model, a.n_out, a.n_layers + 1);
@@ -41,8 +41,11 @@ static void fill_fused(hydra_ctx* c, const Bucket& b, int batch, int step, MlpFu
   f.d = a.d_model;
   f.n_out = a.n_out;
   f.L = a.n_layers;
-  f.u0 = sh0.u0;
-  f.u1 = sh0.u1;
+  // the units of all the shards the group covers (a backward group lists its highest shard)
+  const Shard& sh_lo = m0.shards[b.ph == HYDRA_PHASE_B ? b.shard_at(0, b.span - 1) : b.members[0].second];
+  const Shard& sh_hi = m0.shards[b.ph == HYDRA_PHASE_B ? b.members[0].second : b.shard_at(0, b.span - 1)];
+  f.u0 = sh_lo.u0;
+  f.u1 = sh_hi.u1;
   f.act = a.act == HYDRA_ACT_RELU ? EPI_ACT_RELU : EPI_ACT_GELU;
   f.opt = m0.hp.opt == HYDRA_OPT_ADAM ? 1 : 0;
   f.keep_grads = c->fuse ? 0 : 1;
@@ -78,11 +81,10 @@ static double unit_flops(const hydra_ctx* c, const hydra_arch& a, int u_lo, int 
 
 static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   const Model& m0 = c->models[b.members[0].first];
-  if (fused_small(c, m0)) {
-    const Shard& sh = m0.shards[b.members[0].second];
+  if (mlp_runs_fused(c, m0)) {
     MlpFusedArgs f;
     fill_fused(c, b, batch, step, f);
-    HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, s, unit_flops(c, m0.arch, sh.u0, sh.u1) * f.G, 0.0, launch_mlp_fwd_fused(f, s));
+    HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, s, unit_flops(c, m0.arch, f.u0, f.u1) * f.G, 0.0, launch_mlp_fwd_fused(f, s));
     return HYDRA_OK;
   }
   const Shard& sh0 = m0.shards[b.members[0].second];
@@ -144,20 +146,20 @@ static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int st
 static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   const Model& m0 = c->models[b.members[0].first];
   const Shard& sh0 = m0.shards[b.members[0].second];
-  if (fused_small(c, m0)) {
+  if (mlp_runs_fused(c, m0)) {
     const hydra_arch& a0 = m0.arch;
     MlpFusedArgs f;
     fill_fused(c, b, batch, step, f);
     // input gradients through units u1-1 ... max(u0, 1), before any weight of the shard changes
-    const int u_lo = std::max(sh0.u0, 1);
-    if (sh0.u1 - 1 >= u_lo)
-      HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, unit_flops(c, a0, u_lo, sh0.u1) * f.G, 0.0, launch_mlp_dgrad_chain(f, s));
+    const int u_lo = std::max(f.u0, 1);
+    if (f.u1 - 1 >= u_lo)
+      HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, unit_flops(c, a0, u_lo, f.u1) * f.G, 0.0, launch_mlp_dgrad_chain(f, s));
     double bytes = 0;
-    for (int u = sh0.u0; u < sh0.u1; ++u) {
+    for (int u = f.u0; u < f.u1; ++u) {
       const double in = u == 0 ? a0.d_in : a0.d_model, out = u < a0.n_layers ? a0.d_model : a0.n_out;
       bytes += fused_update_bytes(f.opt, false) * in * out + 4.0 * c->B * (in + out);
     }
-    HYDRA_LAUNCH(c, c->fuse ? HYDRA_K_WGRAD_UPDATE : HYDRA_K_GEMM_WGRAD, s, unit_flops(c, a0, sh0.u0, sh0.u1) * f.G,
+    HYDRA_LAUNCH(c, c->fuse ? HYDRA_K_WGRAD_UPDATE : HYDRA_K_GEMM_WGRAD, s, unit_flops(c, a0, f.u0, f.u1) * f.G,
                  c->fuse ? bytes * f.G : 0.0, launch_mlp_wgrad_update(f, s));
     return HYDRA_OK;
   }
@@ -284,7 +286,7 @@ hydra_status run_update(hydra_ctx* c, const Bucket& b, int step, hipStream_t s) 
   size_t n = o.n;
   if (c->fuse) {
     const Shard& sh0 = c->models[b.members[0].first].shards[b.members[0].second];
-    if (fused_small(c, c->models[b.members[0].first])) return HYDRA_OK;  // weights and biases were updated by the backward task
+    if (mlp_runs_fused(c, c->models[b.members[0].first])) return HYDRA_OK;  // weights and biases were updated by the backward task
     if (!sh0.n_tail_chunks) return HYDRA_OK;  // every tensor of the shard was updated by its gradient GEMM
     o.chunks = sh0.tail_chunks;
     o.n_chunks = sh0.n_tail_chunks;

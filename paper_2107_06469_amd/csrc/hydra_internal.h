@@ -141,6 +141,11 @@ struct Bucket {
   int ph = 0;
   std::vector<std::pair<int, int>> members;  // (model, shard)
   int stream = 0;
+  // A launch group may cover `span` consecutive shard tasks of each member: shards second, second+1, ... for a forward
+  // group, second, second-1, ... for a backward group (the order the tasks run in).  Only where one launch can take
+  // several shards (the small-MLP kernels): the tasks' dependencies and completion are those of all of them together.
+  int span = 1;
+  int shard_at(size_t member, int j) const { return ph == 1 ? members[member].second - j : members[member].second + j; }
 };
 
 enum State { ST_CREATED = 0, ST_DEFINED = 1, ST_SHARDED = 2, ST_DATA = 3 };
@@ -246,6 +251,7 @@ hydra_status mlp_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch
 hydra_status tr_run(hydra_ctx* c, const Bucket& b, int batch, int step_in_epoch, hipStream_t s);
 hydra_status fill_optim(hydra_ctx* c, const Bucket& b, int step, OptimArgs& o);
 OptimHp step_hparams(const Model& m, int step_in_epoch);  // fp32 hyper-parameters of optimizer step m.t + step_in_epoch + 1
+bool mlp_runs_fused(const hydra_ctx* c, const Model& m);  // small fp32 MLP: whole shard phases in one launch each
 // runs the update task of a launch group: the whole block, or only what the fused epilogues leave
 hydra_status run_update(hydra_ctx* c, const Bucket& b, int step, hipStream_t s);
 inline hydra_status run_bucket(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {

@@ -46,6 +46,36 @@ static int auto_group_size(const hydra_ctx* c, const Model& m, int n, int n_comp
   return std::max(1, std::min(g, maxg));
 }
 
+// Small fp32 MLPs run a whole shard phase in one launch, and that launch can as well take the next shard's phase when
+// the plan runs it right behind, on the same stream, for the same models: forward of shards s, s+1, ... or backward of
+// shards s, s-1, ...  Such neighbours become one launch group that spans the shards (update groups of these models
+// launch nothing when the update runs in the gradient kernel, and are stepped over).  Same kernels over the same
+// units in the same order: the values do not change, only the number of launches.
+static void merge_shard_spans(const hydra_ctx* c, std::vector<Bucket>& plan) {
+  if (c->spill) return;
+  auto fused = [&](const Bucket& b) {
+    for (const auto& mem : b.members)
+      if (!mlp_runs_fused(c, c->models[mem.first])) return false;
+    return true;
+  };
+  for (size_t i = 0; i < plan.size(); ++i) {
+    Bucket& a = plan[i];
+    if (a.ph == HYDRA_PHASE_U || c->models[0].arch.kind != HYDRA_KIND_MLP || !fused(a)) continue;
+    for (;;) {
+      size_t j = i + 1;
+      while (j < plan.size() && plan[j].ph == HYDRA_PHASE_U && c->fuse && fused(plan[j])) ++j;
+      if (j >= plan.size()) break;
+      const Bucket& b = plan[j];
+      bool ok = b.ph == a.ph && b.stream == a.stream && b.span == 1 && b.members.size() == a.members.size();
+      for (size_t m = 0; ok && m < a.members.size(); ++m)
+        ok = b.members[m].first == a.members[m].first && b.members[m].second == a.shard_at(m, a.span);
+      if (!ok) break;
+      ++a.span;
+      plan.erase(plan.begin() + (long)j);
+    }
+  }
+}
+
 static const char* ph_name(int ph) { return ph == 0 ? "F" : (ph == 1 ? "B" : "U"); }
 
 hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Bucket>& plan) {
@@ -212,6 +242,7 @@ hydra_status build_plan(hydra_ctx* c, const hydra_schedule* sch, std::vector<Buc
     for (const Task& t : ready) issued.insert(t);
     for (const Task& t : also_issued) issued.insert(t);
   }
+  merge_shard_spans(c, plan);
   return HYDRA_OK;
 }
 
@@ -235,7 +266,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
   for (int step = 0; step < c->n_batches; ++step) {
     for (size_t i = 0; i < nb; ++i) {
       const Bucket& b = plan[i];
-      if (b.members.size() > 1) c->grouped_tasks += b.members.size();
+      if (b.members.size() > 1) c->grouped_tasks += b.members.size() * b.span;
       if (c->dry) {
         hydra_status st = HYDRA_OK;
         if (c->spill && b.ph == HYDRA_PHASE_B)
@@ -250,18 +281,19 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
       }
       hipStream_t s = c->streams[b.stream];
       std::vector<hipEvent_t> waited;
-      for (const auto& mem : b.members) {
-        Task t{mem.first, mem.second, b.ph};
-        std::vector<Task> deps = preds_of(c, t);
-        if (b.ph == HYDRA_PHASE_F) deps.push_back({t.k, t.s, HYDRA_PHASE_U});  // previous step's update
-        for (const Task& d : deps) {
-          auto it = last.find(d);
-          if (it == last.end() || it->second.stream == b.stream) continue;
-          if (std::find(waited.begin(), waited.end(), it->second.ev) != waited.end()) continue;
-          HYDRA_HIP(c, hipStreamWaitEvent(s, it->second.ev, 0));
-          waited.push_back(it->second.ev);
+      for (size_t mi = 0; mi < b.members.size(); ++mi)
+        for (int j = 0; j < b.span; ++j) {  // every shard task the group covers
+          Task t{b.members[mi].first, b.shard_at(mi, j), b.ph};
+          std::vector<Task> deps = preds_of(c, t);
+          if (b.ph == HYDRA_PHASE_F) deps.push_back({t.k, t.s, HYDRA_PHASE_U});  // previous step's update
+          for (const Task& d : deps) {
+            auto it = last.find(d);
+            if (it == last.end() || it->second.stream == b.stream) continue;
+            if (std::find(waited.begin(), waited.end(), it->second.ev) != waited.end()) continue;
+            HYDRA_HIP(c, hipStreamWaitEvent(s, it->second.ev, 0));
+            waited.push_back(it->second.ev);
+          }
         }
-      }
       hydra_status st = HYDRA_OK;
       if (c->spill && b.ph == HYDRA_PHASE_B)
         for (const auto& mem : b.members)
@@ -276,7 +308,8 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
           if ((st = spill_after_update(c, mem.first, mem.second, s, c->sync_spill)) != HYDRA_OK) return st;
       hipEvent_t ev = c->events[(step & 1) * nb + i];
       HYDRA_HIP(c, hipEventRecord(ev, s));
-      for (const auto& mem : b.members) last[{mem.first, mem.second, b.ph}] = {ev, b.stream};
+      for (size_t mi = 0; mi < b.members.size(); ++mi)
+        for (int j = 0; j < b.span; ++j) last[{b.members[mi].first, b.shard_at(mi, j), b.ph}] = {ev, b.stream};
     }
   }
   if (!c->dry) {

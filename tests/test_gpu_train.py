@@ -275,7 +275,8 @@ def test_config1_full_size_sampled_against_oracle(H):
 @pytest.mark.parametrize("opt", [C.OPT_SGD, C.OPT_ADAM])
 def test_small_fp32_models_run_whole_shard_phases_in_one_launch_and_match_oracle(H, opt):
     """fp32 models with at most 32 rows per step and layers at most 256 wide take the kernels that run a whole shard
-    phase per launch: one launch per forward task, two per backward task, none per update task.  Ragged sizes
+    phase per launch: one launch per forward task, two per backward task, none per update task; the shard-parallel plan
+    merges the forward tasks of consecutive shards into one launch and the backward tasks likewise.  Ragged sizes
     (20 rows, 72 -> 136 wide, 25 classes), GeLU, SGD and Adam, three shards; against the oracle at the fp32 tolerance,
     and bit-identical across policies, cuts, group sizes and the two update placements."""
     K = 3
@@ -286,7 +287,7 @@ def test_small_fp32_models_run_whole_shard_phases_in_one_launch_and_match_oracle
     data = make_data(w)
     ref = OT.train_all(w.archs, w.hparams, data, w.steps, w.init_seed)
     got, st = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL)
-    assert st[0]["launches"] == w.steps * (3 + 2 + 3)        # F: 3 shards; B: chain + gradients, no chain for the first
+    assert st[0]["launches"] == w.steps * (1 + 2)            # F: the 3 shards in one; B: one chain, one gradient launch
     for k in range(K):
         kw = _adam_outliers(w, k) if opt == C.OPT_ADAM else {}
         _assert_fp32_parity(got[k], ref[k], _names(w.archs[k]), **kw)
@@ -294,7 +295,9 @@ def test_small_fp32_models_run_whole_shard_phases_in_one_launch_and_match_oracle
                 dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[]] * K), dict(policy=H.SCHED_SHARD_PARALLEL, cuts=[[2], [1, 2, 3, 4], [4]]),
                 dict(policy=H.SCHED_SHARD_PARALLEL, max_group=2), dict(policy=H.SCHED_SHARD_PARALLEL, keep_grads=True)]
     for v in variants:
-        other, _ = H.train_workload(w, data, **v)
+        other, ost = H.train_workload(w, data, **v)
+        if v["policy"] == H.SCHED_SEQUENTIAL:                # unmerged: per shard F 1, B chain + gradients (no chain for the first)
+            assert ost[0]["launches"] == K * w.steps * (3 + 2 + 3)
         for k in range(K):
             assert np.array_equal(other[k][0], got[k][0]), f"loss differs under {v}"
             for a, b in zip(other[k][1], got[k][1]):
