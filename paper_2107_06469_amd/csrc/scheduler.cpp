@@ -47,9 +47,9 @@ static int auto_group_size(const hydra_ctx* c, const Model& m, int n, int n_comp
 }
 
 // Small fp32 MLPs run a whole shard phase in one launch, and that launch can as well take the next shard's phase when
-// the plan runs it right behind, on the same stream, for the same models: forward of shards s, s+1, ... or backward of
-// shards s, s-1, ...  Such neighbours become one launch group that spans the shards (update groups of these models
-// launch nothing when the update runs in the gradient kernel, and are stepped over).  Same kernels over the same
+// the plan runs it next for these models, on the same stream: forward of shards s, s+1, ... or backward of shards
+// s, s-1, ...  Such groups become one launch group that spans the shards (update groups of these models launch
+// nothing when the update runs in the gradient kernel, and are stepped over, as are groups of other models).  Same kernels over the same
 // units in the same order: the values do not change, only the number of launches.
 static void merge_shard_spans(const hydra_ctx* c, std::vector<Bucket>& plan) {
   if (c->spill) return;
@@ -62,8 +62,15 @@ static void merge_shard_spans(const hydra_ctx* c, std::vector<Bucket>& plan) {
     Bucket& a = plan[i];
     if (a.ph == HYDRA_PHASE_U || c->models[0].arch.kind != HYDRA_KIND_MLP || !fused(a)) continue;
     for (;;) {
+      // the next group of these models: groups of other models in between neither feed it nor need it first
+      auto shares_model = [&](const Bucket& x) {
+        for (const auto& xm : x.members)
+          for (const auto& am : a.members)
+            if (xm.first == am.first) return true;
+        return false;
+      };
       size_t j = i + 1;
-      while (j < plan.size() && plan[j].ph == HYDRA_PHASE_U && c->fuse && fused(plan[j])) ++j;
+      while (j < plan.size() && ((plan[j].ph == HYDRA_PHASE_U && c->fuse && fused(plan[j])) || !shares_model(plan[j]))) ++j;
       if (j >= plan.size()) break;
       const Bucket& b = plan[j];
       bool ok = b.ph == a.ph && b.stream == a.stream && b.span == 1 && b.members.size() == a.members.size();

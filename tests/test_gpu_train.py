@@ -298,6 +298,10 @@ def test_small_fp32_models_run_whole_shard_phases_in_one_launch_and_match_oracle
         other, ost = H.train_workload(w, data, **v)
         if v["policy"] == H.SCHED_SEQUENTIAL:                # unmerged: per shard F 1, B chain + gradients (no chain for the first)
             assert ost[0]["launches"] == K * w.steps * (3 + 2 + 3)
+        if v.get("cuts") == [[2], [1, 2, 3, 4], [4]]:        # three shapes of shards: every model alone, its shards merged
+            assert ost[0]["launches"] == w.steps * K * (1 + 2)
+        if v.get("max_group") == 2:                          # groups {0, 1} and {2}
+            assert ost[0]["launches"] == w.steps * 2 * (1 + 2)
         for k in range(K):
             assert np.array_equal(other[k][0], got[k][0]), f"loss differs under {v}"
             for a, b in zip(other[k][1], got[k][1]):
