@@ -199,6 +199,31 @@ def test_gemm_dgrad_epilogue_gate_and_residual(torch, ops, dtype, act):
         _check(outs[g][:, :N].double().cpu().numpy(), wants[g], bounds[g], dtype == 1, "dgrad epilogue")
 
 
+def test_gelu_and_its_derivative_over_the_whole_range(torch, ops):
+    """The kernels' GeLU (an exponential of a fitted polynomial) and GeLU' (rational erf) against the oracle's erf
+    forms on a dense grid of arguments from -10 to 10: fp32 products with an identity weight (and, for the
+    derivative, a product that is exactly 1), so that the epilogue's function is all that is measured."""
+    M, N = 520, 64
+    z = np.linspace(-10.0, 10.0, M * N).reshape(M, N)
+    zd, zv = _dev(torch, z, 0)
+    eye = torch.eye(N, dtype=torch.float32, device="cuda")
+    out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    ops.hydra_op_gemm(0, M, N, N, [zd], [eye], [out], x_kmajor=1, w_kmajor=1, ldx=N, ldw=N, ldo=N, act=2)
+    torch.cuda.synchronize()
+    want = OL.gelu(zv)
+    err = np.abs(out.double().cpu().numpy() - want)
+    assert (err <= 6e-7 + 2.0 ** -23 * np.abs(want)).all(), f"GeLU off by {err.max()} at z = {zv.flat[err.argmax()]}"
+    ones = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    ones[:, 0] = 1.0
+    w = torch.zeros((N, N), dtype=torch.float32, device="cuda")
+    w[0, :] = 1.0                                          # (ones @ w)[m, n] = 1
+    ops.hydra_op_gemm(0, M, N, N, [ones], [w], [out], x_kmajor=1, w_kmajor=0, ldx=N, ldw=N, ldo=N, gate=[zd], ldg=N, act=2)
+    torch.cuda.synchronize()
+    want = OL.gelu_grad(zv)
+    err = np.abs(out.double().cpu().numpy() - want)
+    assert (err <= 6e-7 + 2.0 ** -23 * np.abs(want)).all(), f"GeLU' off by {err.max()} at z = {zv.flat[err.argmax()]}"
+
+
 @pytest.mark.parametrize("layout", ["fwd", "dgrad", "wgrad"])
 def test_gemm_result_is_independent_of_tile_and_group(torch, ops, layout):
     """Bitwise: the same problem alone, inside a group, and with every tile shape gives the same bits (tile 1
