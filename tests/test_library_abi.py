@@ -334,6 +334,32 @@ def test_automatic_launch_groups_follow_the_tile_count_of_the_products():
     assert _plan_stats(w1, d1, n_streams=8, max_group=0)["launches"] == _plan_stats(w1, d1, n_streams=8, max_group=16)["launches"]
 
 
+def test_small_fp32_mlps_merge_the_launch_groups_of_consecutive_shards():
+    """Workload 0 (fp32 MLPs of width 256, 32 rows: the kernels that run a whole shard phase per launch): the
+    shard-parallel plan merges the forward groups of consecutive shards into one launch and the backward groups
+    likewise (input-gradient chain + weight gradients with the update): 3 launches per step for the 4 x 2 shards;
+    with gradients kept the update groups between the backward groups launch the optimizer and nothing is merged
+    across them; the sequential plan keeps one launch group per task."""
+    w = workload(0)
+    w.steps = w.n_batches = 2
+    d = make_data(w)
+    merged = _plan_stats(w, d, n_streams=4)
+    assert merged["launches"] == w.steps * 3 and merged["grouped_tasks"] == w.steps * w.K * 2 * 3
+    kept = _plan_stats(w, d, n_streams=4, keep_grads=True)
+    assert kept["launches"] > merged["launches"]
+    ctx = H.hydra_create(dry_run=True, n_streams=4)
+    try:
+        H.hydra_define_models(ctx, w.archs, w.hparams, w.init_seed)
+        for k in range(w.K):
+            H.hydra_shard(ctx, k, w.boundaries[k])
+        H.hydra_set_data(ctx, d["inputs"], d["target_pos"], d["targets"])
+        seq = H.hydra_train_epoch(ctx, H.SCHED_SEQUENTIAL)
+    finally:
+        H.hydra_destroy(ctx)
+    # per model: forward 1 + 1, backward of the last shard chain + gradients, of the first shard chain + gradients
+    assert seq["launches"] == w.steps * w.K * (2 + 2 + 2) and seq["grouped_tasks"] == 0
+
+
 def test_automatic_budgets_spill_and_recompute_only_when_the_device_is_too_small():
     """auto_budget: with room for everything nothing is spilled or recomputed; with a capacity below the models' state
     the state is spilled to the host; with a capacity between state and state + activations the backward tasks
