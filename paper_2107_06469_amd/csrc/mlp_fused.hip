@@ -2,18 +2,21 @@
 //
 // A model whose step is a few megaflops (32 rows, layers up to 256 wide) is bound by the chain of dependent launches,
 // not by arithmetic or memory: every Linear layer as a launch of its own costs a launch, a round trip to memory for its
-// operands and a kernel boundary.  Here the forward pass of a shard (all its layers, and the loss when the shard ends
-// the model) is one launch with one workgroup per model; the backward pass is two: the chain of input gradients
-// through the shard's layers (one workgroup per model), then every weight gradient of the shard at once, each with the
-// parameter update in the same kernel (a workgroup per 32 output rows of a layer).  Activations stay in LDS between
-// layers.  In both chains a wave needs only its own 32 rows (forward) or columns (input gradient) of a weight matrix;
-// it streams them through a private piece of LDS in chunks of 32 k, requested 128 contiguous bytes per 8 lanes, two
-// chunks ahead of the one being multiplied, with the data movement placed between the dependent MFMAs.
+// operands and a kernel boundary.  Here the forward pass of a shard (all its layers, and the rows' losses when the shard
+// ends the model) is one launch; the backward pass is two: the chain of input gradients through the shard's layers,
+// then every weight gradient of the shard at once, each with the parameter update in the same kernel (a workgroup per
+// 32 output rows of a layer; the one that has the model's last layer also adds up the step's loss).  In the two chains
+// a workgroup takes 16 rows of one model's batch through all the layers, activations staying in LDS between them:
+// rows are independent there, and the fp32 matrix pipes of one compute unit are what bounds a layer, so two
+// workgroups of 16 rows take half the time of one of 32.  A wave needs only its own 32 rows (forward) or columns (input
+// gradient) of a weight matrix; it streams them through a private piece of LDS in chunks of 32 k, requested 128
+// contiguous bytes per 8 lanes, two chunks ahead of the one being multiplied, with the data movement placed between
+// the dependent MFMAs.
 //
-// The products use v_mfma_f32_32x32x2_f32 with the same operand roles, the same k pairing inside an instruction
-// (k and k+4 of every group of 8) and the same ascending chain as the tiled fp32 GEMM kernel, and the epilogues apply
-// the same single-rounded operations, so a layer computes the same values here as there.  Results depend on nothing
-// but the model: not on the group, the cut points or the schedule.
+// The chains use v_mfma_f32_16x16x4_f32 (16 batch rows x 16 columns per tile), the weight gradients
+// v_mfma_f32_32x32x2_f32; every sum runs in a fixed order that depends on the layer's shape alone, and the epilogues
+// apply the same single-rounded operations as the tiled GEMM kernel's.  Results depend on nothing but the model: not
+// on the group, the cut points or the schedule.
 #include "act_math.h"
 #include "kernels.h"
 #include "optim_math.h"
@@ -22,15 +25,29 @@ namespace hydra {
 namespace {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4a;
 constexpr int XS = 260;            // LDS row pitch in floats (256 + 4: rows spread over the banks)
+constexpr int RB = 16;             // batch rows of a workgroup of the two chain kernels
 
-// acc += W-operand chunk (4 consecutive k of one row n) x X-operand chunk (the same k of one row m): four instructions,
-// each summing k and k+4 (the two half-waves hold chunks 4 apart), in ascending order
+// acc += W-operand chunk (4 consecutive k of one row n) x X-operand chunk (the same k of one row m) for the weight-gradient
+// kernel's 32 x 32 tiles: four instructions, each summing k and k+4 (the two half-waves hold chunks 4 apart)
 __device__ __forceinline__ void mma4(f32x16& acc, const float4& w, const float4& x) {
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, x.x, acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, x.y, acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, x.z, acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, x.w, acc, 0, 0, 0);
+}
+// The chain kernels' 16 x 16 tiles (v_mfma_f32_16x16x4_f32): lane l supplies row l%16 of either operand at
+// k = 4 (l/16) + e of a group of 16 k (a float4 holds e = 0..3), so instruction e sums k = e, 4+e, 8+e, 12+e, and
+// receives, for column (batch row) l%16, rows 4 (l/16) + 0..3 of the tile.  Two tiles (two blocks of 16 output
+// columns) alternate, so that a wave has two independent chains in the matrix pipe.
+__device__ __forceinline__ void mma16x2(f32x4a (&acc)[2], const float4& w0, const float4& w1, const float4& x, int e0) {
+  const float wa[4] = {w0.x, w0.y, w0.z, w0.w}, wb[4] = {w1.x, w1.y, w1.z, w1.w}, xv[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+  for (int e = e0; e < e0 + 2; ++e) {
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[e], xv[e], acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(wb[e], xv[e], acc[1], 0, 0, 0);
+  }
 }
 
 __device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
@@ -52,18 +69,18 @@ __device__ __forceinline__ void gstore4(gfloat* p, float a, float b, float c, fl
   *(gf32x4v*)p = v;
 }
 
-// rows [0, B) x columns [0, cols) of a row-major matrix into LDS rows of pitch XS; the rest of the 32 x cols8 block
-// (cols8 = cols rounded up to 8) is zero
-__device__ __forceinline__ void stage_rows(float* xs, const gfloat* src, int ld, int B, int cols, int tid, int nt) {
-  const int c4n = (cols + 7) / 8 * 2;  // float4 groups per row
-  for (int i = tid; i < 32 * c4n; i += nt) {
-    const int m = i / c4n, c = (i % c4n) * 4;
+// rows [0, rows) x columns [0, cols) of a row-major matrix into the RB LDS rows of pitch XS; everything else in the
+// RB x XS block is zero (the products run over k in groups of 16 and must not meet what an earlier kernel left in LDS)
+__device__ __forceinline__ void stage_rows(float* xs, const gfloat* src, int ld, int rows, int cols, int tid, int nt) {
+  constexpr int C4 = XS / 4;  // float4 groups per row
+  for (int i = tid; i < RB * C4; i += nt) {
+    const int m = i / C4, c = (i % C4) * 4;
     float4 v = zero4();
-    if (m < B) {
+    if (m < rows && c < cols) {
       const gfloat* r = src + (size_t)m * ld + c;
       if (c + 4 <= cols) v = gload4(r);
       else {
-        if (c < cols) v.x = r[0];
+        v.x = r[0];
         if (c + 1 < cols) v.y = r[1];
         if (c + 2 < cols) v.z = r[2];
       }
@@ -72,15 +89,18 @@ __device__ __forceinline__ void stage_rows(float* xs, const gfloat* src, int ld,
   }
 }
 
-// ---- forward: units [u0, u1) of one model per workgroup (8 waves; wave w owns output columns [32w, 32w+32)) ------
-// A wave multiplies by its own 32 rows of W only, so it stages them for itself: chunks of 32 k x 32 rows pass through
-// a piece of LDS that no other wave touches (8 lanes per row, 128 contiguous bytes each, so every line that travels is
-// used in full), two chunks are in flight in registers while a third is multiplied, and the requests run ahead across
-// layer ends (weights do not depend on activations).  Nothing inside a layer waits for another wave: the workgroup
-// meets only where a layer's outputs replace its inputs in LDS.
+// ---- forward: units [u0, u1) of 16 batch rows of one model per workgroup (8 waves; wave w owns output columns
+// [32w, 32w+32)) --------------------------------------------------------------------------------------------------
+// Rows of the batch do not meet before the loss, so a model's rows are split over workgroups (the fp32 matrix pipes of
+// one compute unit are what bounds a layer: 16 rows take half the time of 32).  A wave multiplies by its own 32 rows
+// of W only, so it stages them for itself: chunks of 32 k x 32 rows pass through a piece of LDS that no other wave
+// touches (8 lanes per row, 128 contiguous bytes each, so every line that travels is used in full), two chunks are in
+// flight in registers while a third is multiplied, and the requests run ahead across layer ends (weights do not depend
+// on activations).  Nothing inside a layer waits for another wave: the workgroup meets only where a layer's outputs
+// replace its inputs in LDS.
 constexpr int WP = 36;               // LDS pitch of a staged weight row: 32 k + 4 (16 rows read as float4 hit 16 bank groups)
 constexpr int WCH = 32 * WP;         // floats of one staged chunk of one wave
-constexpr size_t FWD_LDS = (32 * XS + 8 * 2 * WCH) * sizeof(float);
+constexpr size_t FWD_LDS = (RB * XS + 8 * 2 * WCH) * sizeof(float);
 
 // the same value in every lane, told to the compiler (descriptors of buffer loads must sit in scalar registers)
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -101,14 +121,15 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a) {
   extern __shared__ float smem[];
-  float* xs = smem;                  // [32][XS] the layer's input rows
-  __shared__ float rl[32];
-  const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lrow = lane & 31, lgrp = lane >> 5;
+  float* xs = smem;                  // [RB][XS] the layer's input rows
+  const int g = blockIdx.x % a.G, r0 = (blockIdx.x / a.G) * RB;  // model, first batch row
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lrow = lane & 15, lgrp = lane >> 4;
+  const int rows = a.B - r0 < RB ? a.B - r0 : RB;  // >= 1: the grid has ceil(B / RB) workgroups per model
   const __attribute__((address_space(1))) MlpTab* tb = (const __attribute__((address_space(1))) MlpTab*)a.tab[g];
   const float* P = a.p[g];
   const int n0 = wave * 32;
-  float* wb = smem + 32 * XS + wave * 2 * WCH;  // [2][32][WP] this wave's weight chunks
+  float* wb = smem + RB * XS + wave * 2 * WCH;  // [2][32][WP] this wave's weight chunks
   const int ldrow = lane >> 3, ldseg = lane & 7;  // this lane's part of a chunk: rows n0 + ldrow + 8 i, k 4 ldseg .. + 3
   // The next chunk to request: unit lu, chunk lc of it, and the unit's matrix (lW: lN x lK floats; past the shard's
   // last unit an empty one).  Buffer loads with the whole address in the checked offset: rows at or past lN lie behind
@@ -148,8 +169,8 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
   float4 s0[4], s1[4];
   issue(s0);  // chunk 0
   issue(s1);  // chunk 1
-  stage_rows(xs, global_ptr(a.u0 == 0 ? a.x[g] : tb->h[a.u0 - 1]), a.u0 == 0 ? a.ld_in : a.ldd, a.B, a.u0 == 0 ? a.d_in : a.d, tid,
-             512);
+  stage_rows(xs, global_ptr(a.u0 == 0 ? a.x[g] : tb->h[a.u0 - 1]) + (size_t)r0 * (a.u0 == 0 ? a.ld_in : a.ldd),
+             a.u0 == 0 ? a.ld_in : a.ldd, rows, a.u0 == 0 ? a.d_in : a.d, tid, 512);
   commit(s0, wb);
   issue(s0);  // chunk 2
   __syncthreads();  // the input rows are in place
@@ -158,16 +179,18 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
     const int K = u == 0 ? a.d_in : a.d, N = u < a.L ? a.d : a.n_out;
     const float* bias = P + a.b_off[u];
     const bool active = n0 < N;  // uniform over the wave
-    f32x16 acc;
+    f32x4a acc[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    float bv[4][4];
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[q][e] = 0.f;
+    float bv[2][4];
     if (active) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int q = 0; q < 2; ++q)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int nn = n0 + 8 * q + 4 * lgrp + e;
+          const int nn = n0 + 16 * q + 4 * lgrp + e;
           bv[q][e] = nn < N ? bias[nn] : 0.f;
         }
     }
@@ -194,25 +217,31 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
       };
       if (active) {
         // all of the chunk's operands are requested from LDS before the first product, so that only the first of
-        // them is waited for (steps at or past K read staged zeros or stale rows and are not multiplied)
-        float4 wq[4], xq[4];
+        // them is waited for (a group of 16 k that starts at or past K is not multiplied; inside a group, k at or past
+        // K meet staged zeros on both sides)
+        float4 wq[2][2], xq[2];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          wq[s] = *reinterpret_cast<const float4*>(&cur[lrow * WP + 8 * s + 4 * lgrp]);
-          xq[s] = *reinterpret_cast<const float4*>(&xs[lrow * XS + 32 * c + 8 * s + 4 * lgrp]);
+        for (int s = 0; s < 2; ++s) {
+#pragma unroll
+          for (int q = 0; q < 2; ++q) wq[q][s] = *reinterpret_cast<const float4*>(&cur[(16 * q + lrow) * WP + 16 * s + 4 * lgrp]);
+          xq[s] = *reinterpret_cast<const float4*>(&xs[lrow * XS + 32 * c + 16 * s + 4 * lgrp]);
         }
         if (32 * c + 32 <= K) {  // a whole chunk: straight-line code
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            mma4(acc, wq[s], xq[s]);
-            move(s);
-          }
+          for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              mma16x2(acc, wq[0][s], wq[1][s], xq[s], 2 * h);
+              move(2 * s + h);
+            }
         } else {
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            if (32 * c + 8 * s < K) mma4(acc, wq[s], xq[s]);
-            move(s);
-          }
+          for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              if (32 * c + 16 * s < K) mma16x2(acc, wq[0][s], wq[1][s], xq[s], 2 * h);
+              move(2 * s + h);
+            }
         }
       } else {
 #pragma unroll
@@ -232,93 +261,81 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
     two_chunks(0);
     for (int c = 2; c * 32 < K; c += 2) two_chunks(c);
     __syncthreads();  // every wave has read this layer's input from LDS
-    // a lane holds, for row m = lrow, columns n0 + 8q + 4 lgrp + (0..3), q = 0..3
-    float v[4][4];
+    // a lane holds, for batch row r0 + lrow, columns n0 + 16q + 4 lgrp + (0..3), q = 0, 1
     if (active) {
+      const int m = r0 + lrow;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nq = n0 + 8 * q + 4 * lgrp;
+      for (int q = 0; q < 2; ++q) {
+        const int nq = n0 + 16 * q + 4 * lgrp;
+        if (nq >= N) continue;
+        float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          v[q][e] = acc[4 * q + e];
-          if (nq + e < N) v[q][e] += bv[q][e];
+          v[e] = acc[q][e];
+          if (nq + e < N) v[e] += bv[q][e];
         }
-      }
-    }
-    if (active) {
-      const int m = lrow;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nq = n0 + 8 * q + 4 * lgrp;
-        if (nq >= N) continue;
         if (u < a.L) {
           float h[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) h[e] = act_fwd(v[q][e], a.act);
+          for (int e = 0; e < 4; ++e) h[e] = act_fwd(v[e], a.act);
           if (m < a.B) {  // N = d is a multiple of 8: whole vectors
-            gstore4(zu + (size_t)m * a.ldd + nq, v[q][0], v[q][1], v[q][2], v[q][3]);
+            gstore4(zu + (size_t)m * a.ldd + nq, v[0], v[1], v[2], v[3]);
             gstore4(hu + (size_t)m * a.ldd + nq, h[0], h[1], h[2], h[3]);
           }
-          *reinterpret_cast<float4*>(&xs[m * XS + nq]) = make_float4(h[0], h[1], h[2], h[3]);
+          *reinterpret_cast<float4*>(&xs[lrow * XS + nq]) = make_float4(h[0], h[1], h[2], h[3]);
         } else {
 #pragma unroll
           for (int e = 0; e < 4; ++e)
             if (nq + e < N) {
-              if (m < a.B) zu[(size_t)m * a.ldv + nq + e] = v[q][e];
-              xs[m * XS + nq + e] = v[q][e];
+              if (m < a.B) zu[(size_t)m * a.ldv + nq + e] = v[e];
+              xs[lrow * XS + nq + e] = v[e];
             }
         }
       }
     }
     __syncthreads();
     if (u == a.L) {
-      // softmax cross-entropy of the 32 rows: lane m of the first wave walks its row in ascending class order
+      // softmax cross-entropy of the workgroup's rows: lane m of the first wave walks its row in ascending class order
+      // (the step's loss is the sum of the rows' losses; the gradient kernel, which follows, adds them up)
       const int C = a.n_out;
-      if (wave == 0 && lane < 32) {
-        const int m = lane;
-        float rowloss = 0.f;
-        if (m < a.B) {
-          const float* z = &xs[m * XS];
-          const int y = a.labels[m];
-          float mx = -INFINITY;
-          for (int c = 0; c < C; ++c) mx = fmaxf(mx, z[c]);
-          float sum = 0.f;
-          for (int c = 0; c < C; ++c) sum += expf(z[c] - mx);
-          const float lse = logf(sum) + mx, inv_sum = 1.f / sum;
-          gfloat* dz = dlog + (size_t)m * a.ldv;
-          for (int c = 0; c < a.ldv; ++c) dz[c] = c < C ? (expf(z[c] - mx) * inv_sum - (c == y ? 1.f : 0.f)) * a.inv_n : 0.f;
-          rowloss = lse - z[y];
-          rowl[m] = rowloss;
-        }
-        rl[m] = rowloss;
-      }
-      __syncthreads();
-      if (tid == 0) {
-        float t = 0.f;
-        for (int m = 0; m < a.B; ++m) t += rl[m];  // ascending rows
-        *a.loss[g] = t * a.inv_n;
+      if (wave == 0 && lane < rows) {
+        const int m = r0 + lane;
+        const float* z = &xs[lane * XS];
+        const int y = a.labels[m];
+        float mx = -INFINITY;
+        for (int c = 0; c < C; ++c) mx = fmaxf(mx, z[c]);
+        float sum = 0.f;
+        for (int c = 0; c < C; ++c) sum += expf(z[c] - mx);
+        const float lse = logf(sum) + mx, inv_sum = 1.f / sum;
+        gfloat* dz = dlog + (size_t)m * a.ldv;
+        for (int c = 0; c < a.ldv; ++c) dz[c] = c < C ? (expf(z[c] - mx) * inv_sum - (c == y ? 1.f : 0.f)) * a.inv_n : 0.f;
+        rowl[m] = lse - z[y];
       }
     }
   }
 }
 
-// ---- backward, part 1: dz_{u-1} = (dz_u W_u) * act'(z_{u-1}) for u = u1-1 ... max(u0, 1), one model per workgroup ----
+// ---- backward, part 1: dz_{u-1} = (dz_u W_u) * act'(z_{u-1}) for u = u1-1 ... max(u0, 1), 16 batch rows of one model
+// per workgroup ---------------------------------------------------------------------------------------------------
 // W_u is k-major for this product (its rows are the k of the sum); a wave stages its own 32 columns of a chunk of 32 k
 // (8 lanes per row, 128 contiguous bytes each) through the same private two-deep pipeline as in the forward kernel.
-constexpr int DCH = 32 * 32;         // floats of one staged chunk of one wave: 32 k x 32 columns
-constexpr size_t DGRAD_LDS = (32 * XS + 8 * 2 * DCH) * sizeof(float);
+constexpr int DP = 36;               // LDS pitch of a staged k-row: 32 columns + 4 (the four quarter-waves read rows 4 apart)
+constexpr int DCH = 32 * DP;         // floats of one staged chunk of one wave: 32 k x 32 columns
+constexpr size_t DGRAD_LDS = (RB * XS + 8 * 2 * DCH) * sizeof(float);
 
 __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs a) {
   extern __shared__ float smem[];
-  float* ds = smem;                  // [32][XS] dz_u
-  const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lrow = lane & 31, lgrp = lane >> 5;
+  float* ds = smem;                  // [RB][XS] dz_u
+  const int g = blockIdx.x % a.G, r0 = (blockIdx.x / a.G) * RB;  // model, first batch row
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lrow = lane & 15, lgrp = lane >> 4;
+  const int rows = a.B - r0 < RB ? a.B - r0 : RB;
   const __attribute__((address_space(1))) MlpTab* tb = (const __attribute__((address_space(1))) MlpTab*)a.tab[g];
   const float* P = a.p[g];
   const int u_hi = a.u1 - 1, u_lo = a.u0 > 1 ? a.u0 : 1;
   if (u_hi < u_lo) return;
   const int n0 = wave * 32;
-  float* wb = smem + 32 * XS + wave * 2 * DCH;  // [2][32][32] this wave's weight chunks
+  float* wb = smem + RB * XS + wave * 2 * DCH;  // [2][32][DP] this wave's weight chunks
   const int ldrow = lane >> 3, ldseg = lane & 7;  // this lane's part of a chunk: k ldrow + 8 i, columns n0 + 4 ldseg .. + 3
   const int Kin = a.d;               // width of dz_{u-1} (u >= 1)
   const bool active = n0 < Kin;      // uniform over the wave
@@ -354,64 +371,72 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
   };
   auto commit = [&](const float4 (&st)[4], float* buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&buf[(ldrow + 8 * i) * 32 + 4 * ldseg]) = st[i];
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&buf[(ldrow + 8 * i) * DP + 4 * ldseg]) = st[i];
     wave_lds_order();
   };
   float4 s0[4], s1[4];
   issue(s0);  // chunk 0
   issue(s1);  // chunk 1
-  stage_rows(ds, global_ptr(u_hi < a.L ? tb->dz[u_hi] : tb->dlogits), u_hi < a.L ? a.ldd : a.ldv, a.B, u_hi < a.L ? a.d : a.n_out,
-             tid, 512);
+  stage_rows(ds, global_ptr(u_hi < a.L ? tb->dz[u_hi] : tb->dlogits) + (size_t)r0 * (u_hi < a.L ? a.ldd : a.ldv),
+             u_hi < a.L ? a.ldd : a.ldv, rows, u_hi < a.L ? a.d : a.n_out, tid, 512);
   commit(s0, wb);
   issue(s0);  // chunk 2
   __syncthreads();  // dz of the shard's last unit is in place
   for (int u = u_hi; u >= u_lo; --u) {
     // here: buffer 0 holds the unit's chunk 0, s1 its chunk 1, s0 the chunk after that
     const int K = u < a.L ? a.d : a.n_out;
-    f32x16 acc;
+    f32x4a acc[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[q][e] = 0.f;
     // read the table now: between the stores at the unit's end a pointer read would wait for each of them
     gfloat* const dzo = global_ptr(tb->dz[u - 1]);
     const gfloat* const zg = global_ptr(tb->z[u - 1]);
-    float4 gate[4];  // z_{u-1} at the outputs this lane will hold
+    const int m = r0 + lrow;
+    float4 gate[2];  // z_{u-1} at the outputs this lane will hold
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int nq = n0 + 8 * q + 4 * lgrp;
-      gate[q] = (active && lrow < a.B && nq < Kin) ? gload4(zg + (size_t)lrow * a.ldd + nq) : zero4();
+    for (int q = 0; q < 2; ++q) {
+      const int nq = n0 + 16 * q + 4 * lgrp;
+      gate[q] = (active && m < a.B && nq < Kin) ? gload4(zg + (size_t)m * a.ldd + nq) : zero4();
     }
     auto half = [&](float4 (&st)[4], float* other, const float* cur, int c) {
       const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lW), 0, lrows * Kin * 4, 0x00020000);
       const unsigned off0 = (unsigned)((32 * lc + ldrow) * Kin + n0 + 4 * ldseg) * 4u, step = (unsigned)(8 * Kin) * 4u;
       auto move = [&](int s) {  // a quarter of the chunk in st goes to LDS, a quarter of the next request takes its place
         __builtin_amdgcn_sched_barrier(0);
-        *reinterpret_cast<float4*>(&other[(ldrow + 8 * s) * 32 + 4 * ldseg]) = st[s];
+        *reinterpret_cast<float4*>(&other[(ldrow + 8 * s) * DP + 4 * ldseg]) = st[s];
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(inside ? off0 + step * s : 0xfffffff0u), 0, 0);
         st[s] = make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
         __builtin_amdgcn_sched_barrier(0);
       };
       if (active) {
-        // all of the chunk's operands are requested from LDS before the first product
-        const float* col = cur + lrow + 4 * lgrp * 32;
-        float4 wq[4], xq[4];
+        // all of the chunk's operands are requested from LDS before the first product: this lane's W values are
+        // k = 16 s + 4 lgrp + (0..3) of columns lrow and 16 + lrow of the wave's 32
+        float4 wq[2][2], xq[2];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const float* r = col + 8 * s * 32;
-          wq[s] = make_float4(r[0], r[32], r[64], r[96]);
-          xq[s] = *reinterpret_cast<const float4*>(&ds[lrow * XS + 32 * c + 8 * s + 4 * lgrp]);
+        for (int s = 0; s < 2; ++s) {
+          const float* r = cur + (16 * s + 4 * lgrp) * DP + lrow;
+#pragma unroll
+          for (int q = 0; q < 2; ++q) wq[q][s] = make_float4(r[16 * q], r[DP + 16 * q], r[2 * DP + 16 * q], r[3 * DP + 16 * q]);
+          xq[s] = *reinterpret_cast<const float4*>(&ds[lrow * XS + 32 * c + 16 * s + 4 * lgrp]);
         }
         if (32 * c + 32 <= K) {  // a whole chunk: straight-line code
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            mma4(acc, wq[s], xq[s]);
-            move(s);
-          }
+          for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              mma16x2(acc, wq[0][s], wq[1][s], xq[s], 2 * h);
+              move(2 * s + h);
+            }
         } else {
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            if (32 * c + 8 * s < K) mma4(acc, wq[s], xq[s]);
-            move(s);
-          }
+          for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              if (32 * c + 16 * s < K) mma16x2(acc, wq[0][s], wq[1][s], xq[s], 2 * h);
+              move(2 * s + h);
+            }
         }
       } else {
 #pragma unroll
@@ -428,18 +453,17 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
     for (int c = 2; c * 32 < K; c += 2) two_chunks(c);
     __syncthreads();  // every wave has read dz_u from LDS
     if (active) {
-      const int m = lrow;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nq = n0 + 8 * q + 4 * lgrp;
+      for (int q = 0; q < 2; ++q) {
+        const int nq = n0 + 16 * q + 4 * lgrp;
         if (nq >= Kin) continue;
         const float gz[4] = {gate[q].x, gate[q].y, gate[q].z, gate[q].w};
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[4 * q + e] * act_grad(gz[e], a.act);
+        for (int e = 0; e < 4; ++e) v[e] = acc[q][e] * act_grad(gz[e], a.act);
         const float4 o = make_float4(v[0], v[1], v[2], v[3]);
         if (m < a.B) gstore4(dzo + (size_t)m * a.ldd + nq, v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4*>(&ds[m * XS + nq]) = m < a.B ? o : zero4();
+        *reinterpret_cast<float4*>(&ds[lrow * XS + nq]) = m < a.B ? o : zero4();
       }
     }
     __syncthreads();
@@ -455,6 +479,13 @@ __global__ __launch_bounds__(256) void mlp_wgrad_update_kernel(const MlpFusedArg
   const int N = u < a.L ? a.d : a.n_out, Kin = u == 0 ? a.d_in : a.d;
   if (strip * 32 >= N) return;
   const __attribute__((address_space(1))) MlpTab* tb = (const __attribute__((address_space(1))) MlpTab*)a.tab[g];
+  if (u == a.L && strip == 0 && tid == 0) {
+    // the step's loss: the rows' losses, which the forward kernel's workgroups left, added in ascending order
+    const gfloat* rl = global_ptr(tb->rowloss);
+    float t = 0.f;
+    for (int m = 0; m < a.B; ++m) t += rl[m];
+    *a.loss[g] = t * a.inv_n;
+  }
   const gfloat* dz = global_ptr(u < a.L ? tb->dz[u] : tb->dlogits);
   const int lddz = u < a.L ? a.ldd : a.ldv;
   const gfloat* xin = global_ptr(u == 0 ? a.x[g] : tb->h[u - 1]);
@@ -584,10 +615,8 @@ hipError_t mlp_fused_init() {
 hipError_t launch_mlp_fwd_fused(const MlpFusedArgs& a, hipStream_t s) {
   hipError_t e = check(a);
   if (e != hipSuccess) return e;
-  if (a.u1 == a.L + 1)
-    for (int g = 0; g < a.G; ++g)
-      if (!a.loss[g] || !a.labels) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(mlp_fwd_fused_kernel, dim3(a.G), dim3(512), FWD_LDS, s, a);
+  if (a.u1 == a.L + 1 && !a.labels) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(mlp_fwd_fused_kernel, dim3(a.G * ((a.B + RB - 1) / RB)), dim3(512), FWD_LDS, s, a);
   return hipGetLastError();
 }
 
@@ -595,7 +624,7 @@ hipError_t launch_mlp_dgrad_chain(const MlpFusedArgs& a, hipStream_t s) {
   hipError_t e = check(a);
   if (e != hipSuccess) return e;
   if (a.u1 - 1 < (a.u0 > 1 ? a.u0 : 1)) return hipSuccess;  // no unit of the shard has an input gradient to produce
-  hipLaunchKernelGGL(mlp_dgrad_chain_kernel, dim3(a.G), dim3(512), DGRAD_LDS, s, a);
+  hipLaunchKernelGGL(mlp_dgrad_chain_kernel, dim3(a.G * ((a.B + RB - 1) / RB)), dim3(512), DGRAD_LDS, s, a);
   return hipGetLastError();
 }
 
@@ -604,6 +633,7 @@ hipError_t launch_mlp_wgrad_update(const MlpFusedArgs& a, hipStream_t s) {
   if (e != hipSuccess) return e;
   for (int g = 0; g < a.G; ++g) {
     if (a.keep_grads ? !a.g[g] : (a.opt == 1 && (!a.m[g] || !a.v[g]))) return hipErrorInvalidValue;
+    if (a.u1 == a.L + 1 && !a.loss[g]) return hipErrorInvalidValue;  // the launch with the last unit writes the step's loss
   }
   const int widest = a.d > a.n_out ? a.d : a.n_out;
   const dim3 grid((widest + 31) / 32, a.u1 - a.u0, a.G);
