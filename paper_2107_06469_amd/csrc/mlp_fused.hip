@@ -10,7 +10,7 @@
 // rows are independent there, and the fp32 matrix pipes of one compute unit are what bounds a layer, so two
 // workgroups of 16 rows take half the time of one of 32.  A wave needs only its own 32 rows (forward) or columns (input
 // gradient) of a weight matrix; it streams them through a private piece of LDS in chunks of 32 k, requested 128
-// contiguous bytes per 8 lanes, two chunks ahead of the one being multiplied, with the data movement placed between
+// contiguous bytes per 8 lanes, four chunks ahead of the one being multiplied, with the data movement placed between
 // the dependent MFMAs.
 //
 // The chains use v_mfma_f32_16x16x4_f32 (16 batch rows x 16 columns per tile), the weight gradients
@@ -94,8 +94,8 @@ __device__ __forceinline__ void stage_rows(float* xs, const gfloat* src, int ld,
 // Rows of the batch do not meet before the loss, so a model's rows are split over workgroups (the fp32 matrix pipes of
 // one compute unit are what bounds a layer: 16 rows take half the time of 32).  A wave multiplies by its own 32 rows
 // of W only, so it stages them for itself: chunks of 32 k x 32 rows pass through a piece of LDS that no other wave
-// touches (8 lanes per row, 128 contiguous bytes each, so every line that travels is used in full), two chunks are in
-// flight in registers while a third is multiplied, and the requests run ahead across layer ends (weights do not depend
+// touches (8 lanes per row, 128 contiguous bytes each, so every line that travels is used in full), four chunks are in
+// flight in registers while a fifth is multiplied, and the requests run ahead across layer ends (weights do not depend
 // on activations).  Nothing inside a layer waits for another wave: the workgroup meets only where a layer's outputs
 // replace its inputs in LDS.
 constexpr int WP = 36;               // LDS pitch of a staged weight row: 32 k + 4 (16 rows read as float4 hit 16 bank groups)
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
   };
   unit_to_request();
   auto advance = [&]() {
-    if (++lc * 32 >= (lK + 63) / 64 * 64) {  // every unit takes an even number of chunks (the last may be empty)
+    if (++lc * 32 >= (lK + 127) / 128 * 128) {  // every unit takes a multiple of four chunks (the last ones may be empty)
       ++lu;
       lc = 0;
       unit_to_request();
@@ -166,16 +166,18 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
     for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&buf[(ldrow + 8 * i) * WP + 4 * ldseg]) = st[i];
     wave_lds_order();
   };
-  float4 s0[4], s1[4];
+  float4 s0[4], s1[4], s2[4], s3[4];
   issue(s0);  // chunk 0
   issue(s1);  // chunk 1
+  issue(s2);  // chunk 2
+  issue(s3);  // chunk 3
   stage_rows(xs, global_ptr(a.u0 == 0 ? a.x[g] : tb->h[a.u0 - 1]) + (size_t)r0 * (a.u0 == 0 ? a.ld_in : a.ldd),
              a.u0 == 0 ? a.ld_in : a.ldd, rows, a.u0 == 0 ? a.d_in : a.d, tid, 512);
   commit(s0, wb);
-  issue(s0);  // chunk 2
+  issue(s0);  // chunk 4
   __syncthreads();  // the input rows are in place
   for (int u = a.u0; u < a.u1; ++u) {
-    // here: buffer 0 holds the unit's chunk 0, s1 its chunk 1, s0 the chunk after that
+    // here: buffer 0 holds the unit's chunk 0, s1, s2, s3 its chunks 1, 2, 3, s0 the chunk after those
     const int K = u == 0 ? a.d_in : a.d, N = u < a.L ? a.d : a.n_out;
     const float* bias = P + a.b_off[u];
     const bool active = n0 < N;  // uniform over the wave
@@ -250,16 +252,18 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
       advance();
       wave_lds_order();
     };
-    auto two_chunks = [&](int c) {
+    auto four_chunks = [&](int c) {
       // the wave has multiplied by the other buffer's last chunk (its operands are in registers): it is free
       half(s1, wb + WCH, wb, c);
-      half(s0, wb, wb + WCH, c + 1);
+      half(s2, wb, wb + WCH, c + 1);
+      half(s3, wb + WCH, wb, c + 2);
+      half(s0, wb, wb + WCH, c + 3);
     };
     // The first pair stands outside the loop: the previous unit's stores may still be on their way when it starts,
     // and a wait with loads and stores both outstanding is a wait for everything; inside the loop only loads are
     // outstanding, so the wait for a chunk leaves the younger chunk's requests in flight.
-    two_chunks(0);
-    for (int c = 2; c * 32 < K; c += 2) two_chunks(c);
+    four_chunks(0);
+    for (int c = 4; c * 32 < K; c += 4) four_chunks(c);
     __syncthreads();  // every wave has read this layer's input from LDS
     // a lane holds, for batch row r0 + lrow, columns n0 + 16q + 4 lgrp + (0..3), q = 0, 1
     if (active) {
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a
 // ---- backward, part 1: dz_{u-1} = (dz_u W_u) * act'(z_{u-1}) for u = u1-1 ... max(u0, 1), 16 batch rows of one model
 // per workgroup ---------------------------------------------------------------------------------------------------
 // W_u is k-major for this product (its rows are the k of the sum); a wave stages its own 32 columns of a chunk of 32 k
-// (8 lanes per row, 128 contiguous bytes each) through the same private two-deep pipeline as in the forward kernel.
+// (8 lanes per row, 128 contiguous bytes each) through the same private pipeline as in the forward kernel.
 constexpr int DP = 36;               // LDS pitch of a staged k-row: 32 columns + 4 (the four quarter-waves read rows 4 apart)
 constexpr int DCH = 32 * DP;         // floats of one staged chunk of one wave: 32 k x 32 columns
 constexpr size_t DGRAD_LDS = (RB * XS + 8 * 2 * DCH) * sizeof(float);
@@ -352,7 +356,7 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
   };
   unit_to_request();
   auto advance = [&]() {
-    if (++lc * 32 >= (lK + 63) / 64 * 64) {  // every unit takes an even number of chunks (the last may be empty)
+    if (++lc * 32 >= (lK + 127) / 128 * 128) {  // every unit takes a multiple of four chunks (the last ones may be empty)
       --lu;
       lc = 0;
       unit_to_request();
@@ -374,16 +378,18 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
     for (int i = 0; i < 4; ++i) *reinterpret_cast<float4*>(&buf[(ldrow + 8 * i) * DP + 4 * ldseg]) = st[i];
     wave_lds_order();
   };
-  float4 s0[4], s1[4];
+  float4 s0[4], s1[4], s2[4], s3[4];
   issue(s0);  // chunk 0
   issue(s1);  // chunk 1
+  issue(s2);  // chunk 2
+  issue(s3);  // chunk 3
   stage_rows(ds, global_ptr(u_hi < a.L ? tb->dz[u_hi] : tb->dlogits) + (size_t)r0 * (u_hi < a.L ? a.ldd : a.ldv),
              u_hi < a.L ? a.ldd : a.ldv, rows, u_hi < a.L ? a.d : a.n_out, tid, 512);
   commit(s0, wb);
-  issue(s0);  // chunk 2
+  issue(s0);  // chunk 4
   __syncthreads();  // dz of the shard's last unit is in place
   for (int u = u_hi; u >= u_lo; --u) {
-    // here: buffer 0 holds the unit's chunk 0, s1 its chunk 1, s0 the chunk after that
+    // here: buffer 0 holds the unit's chunk 0, s1, s2, s3 its chunks 1, 2, 3, s0 the chunk after those
     const int K = u < a.L ? a.d : a.n_out;
     f32x4a acc[2];
 #pragma unroll
@@ -445,12 +451,14 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
       advance();
       wave_lds_order();
     };
-    auto two_chunks = [&](int c) {
+    auto four_chunks = [&](int c) {
       half(s1, wb + DCH, wb, c);
-      half(s0, wb, wb + DCH, c + 1);
+      half(s2, wb, wb + DCH, c + 1);
+      half(s3, wb + DCH, wb, c + 2);
+      half(s0, wb, wb + DCH, c + 3);
     };
-    two_chunks(0);  // outside the loop for the same reason as in the forward kernel
-    for (int c = 2; c * 32 < K; c += 2) two_chunks(c);
+    four_chunks(0);  // outside the loop for the same reason as in the forward kernel
+    for (int c = 4; c * 32 < K; c += 4) four_chunks(c);
     __syncthreads();  // every wave has read dz_u from LDS
     if (active) {
 #pragma unroll
