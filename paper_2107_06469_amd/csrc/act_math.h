@@ -7,25 +7,12 @@
 
 namespace hydra {
 
-// Normal CDF and density for GeLU's derivative (and wherever both are needed).  erf by the rational approximation of
-// Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, below fp32 rounding of the surrounding arithmetic): a dozen VALU
-// operations, a reciprocal and an exponential per element instead of a library erf, which matters because the
-// epilogue applies it to every output.
-__device__ __forceinline__ void normal_cdf_pdf(float z, float& cdf, float& pdf) {
-  const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * x);
-  const float e = __expf(-x * x);  // = exp(-z^2/2)
-  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float erf_abs = 1.0f - poly * e;
-  cdf = 0.5f * (1.0f + (z < 0.f ? -erf_abs : erf_abs));
-  pdf = e * 0.39894228040143268f;
-}
 // GeLU(z) = z Phi(z) where only the value is needed (forward epilogues apply it to every output, and the workgroup's
 // MFMAs wait meanwhile): Phi(-a) = 2^(a Q(a) - 1) on a = min(|z|, 6) with Q of degree 6, fitted to the normal CDF for
 // the smallest maximal absolute error of Phi (4e-8; 8e-8 as evaluated in fp32), and z Phi(z) = max(z, 0) - a Phi(-a).
-// One exponential and no reciprocal: 16 VALU issue slots per element with the bias and the two conversions of the
-// epilogue around it, against 23 through normal_cdf_pdf; the error of z Phi(z) in fp32 is 3.8e-7 at most (the other
-// form: 4.7e-7).  Past |z| = 6 Phi(-6) = 1e-9 stands for the smaller true value.
+// One exponential and no reciprocal: 13 instructions per element with the bias and the two conversions of the
+// epilogue around it, against 17 with the rational erf below; the error of z Phi(z) in fp32 is 3.8e-7 at most (with
+// the rational erf: 4.7e-7).  Past |z| = 6 Phi(-6) = 1e-9 stands for the smaller true value.
 __device__ __forceinline__ float gelu_fwd(float z) {
   const float a = fminf(fabsf(z), 6.0f);
   float q = 8.60450347e-06f;
@@ -43,13 +30,27 @@ __device__ __forceinline__ float act_fwd(float v, int act) {
   if (act == EPI_ACT_GELU) return gelu_fwd(v);
   return v;
 }
+// GeLU'(z) = Phi(z) + z phi(z) for the gate epilogues (which apply it to every output).  erf by the rational
+// approximation of Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, below fp32 rounding of the surrounding arithmetic):
+// erfc(x) = t (a1 + t (a2 + ...)) exp(-x^2), t = 1 / (1 + p x).  With x = |z| / sqrt(2) the exponential is the
+// density's as well; the 1/sqrt(2) is folded into p and the 1/2 of the CDF into the a's, so that
+// Phi(-|z|) = e t (a1/2 + t (a2/2 + ...)), e = exp(-z^2/2): 16 instructions.
+__device__ __forceinline__ float gelu_grad(float z) {
+  const float a = fabsf(z);
+  const float t = __builtin_amdgcn_rcpf(__fmaf_rn(0.3275911f * 0.70710678118654752f, a, 1.0f));
+  const float e = __builtin_amdgcn_exp2f((z * z) * (-0.5f * 1.4426950408889634f));  // exp(-z^2/2)
+  float p = 0.5f * 1.061405429f;
+  p = __fmaf_rn(p, t, 0.5f * -1.453152027f);
+  p = __fmaf_rn(p, t, 0.5f * 1.421413741f);
+  p = __fmaf_rn(p, t, 0.5f * -0.284496736f);
+  p = __fmaf_rn(p, t, 0.5f * 0.254829592f);
+  const float h = (p * t) * e;                  // Phi(-|z|)
+  const float cdf = z > 0.f ? 1.0f - h : h;
+  return __fmaf_rn(z * e, 0.39894228040143268f, cdf);
+}
 __device__ __forceinline__ float act_grad(float z, int act) {
   if (act == EPI_ACT_RELU) return z > 0.f ? 1.f : 0.f;
-  if (act == EPI_ACT_GELU) {
-    float cdf, pdf;
-    normal_cdf_pdf(z, cdf, pdf);
-    return cdf + z * pdf;
-  }
+  if (act == EPI_ACT_GELU) return gelu_grad(z);
   return 1.f;
 }
 
