@@ -79,11 +79,32 @@ static double unit_flops(const hydra_ctx* c, const hydra_arch& a, int u_lo, int 
   return f;
 }
 
+// the second launch of a small MLP's backward tasks: every weight gradient of units [f.u0, f.u1) with the update
+static hydra_status mlp_fused_gradients(hydra_ctx* c, const Bucket& b, const MlpFusedArgs& f, hipStream_t s) {
+  const hydra_arch& a0 = c->models[b.members[0].first].arch;
+  double bytes = 0;
+  for (int u = f.u0; u < f.u1; ++u) {
+    const double in = u == 0 ? a0.d_in : a0.d_model, out = u < a0.n_layers ? a0.d_model : a0.n_out;
+    bytes += fused_update_bytes(f.opt, false) * in * out + 4.0 * c->B * (in + out);
+  }
+  HYDRA_LAUNCH(c, c->fuse ? HYDRA_K_WGRAD_UPDATE : HYDRA_K_GEMM_WGRAD, s, unit_flops(c, a0, f.u0, f.u1) * f.G,
+               c->fuse ? bytes * f.G : 0.0, launch_mlp_wgrad_update(f, s));
+  return HYDRA_OK;
+}
+
 static hydra_status mlp_forward(hydra_ctx* c, const Bucket& b, int batch, int step, hipStream_t s) {
   const Model& m0 = c->models[b.members[0].first];
   if (mlp_runs_fused(c, m0)) {
     MlpFusedArgs f;
     fill_fused(c, b, batch, step, f);
+    if (b.bspan > 0) {
+      // the group also covers the backward tasks: forward and the chain of input gradients in one launch, then the
+      // gradients with the update
+      const hydra_arch& a0 = m0.arch;
+      HYDRA_LAUNCH2(c, HYDRA_K_GEMM_FWD, HYDRA_K_GEMM_DGRAD, s, unit_flops(c, a0, f.u0, f.u1) * f.G,
+                    unit_flops(c, a0, 1, f.u1) * f.G, 0.0, launch_mlp_fwd_chain(f, s));
+      return mlp_fused_gradients(c, b, f, s);
+    }
     HYDRA_LAUNCH(c, HYDRA_K_GEMM_FWD, s, unit_flops(c, m0.arch, f.u0, f.u1) * f.G, 0.0, launch_mlp_fwd_fused(f, s));
     return HYDRA_OK;
   }
@@ -154,14 +175,7 @@ static hydra_status mlp_backward(hydra_ctx* c, const Bucket& b, int batch, int s
     const int u_lo = std::max(f.u0, 1);
     if (f.u1 - 1 >= u_lo)
       HYDRA_LAUNCH(c, HYDRA_K_GEMM_DGRAD, s, unit_flops(c, a0, u_lo, f.u1) * f.G, 0.0, launch_mlp_dgrad_chain(f, s));
-    double bytes = 0;
-    for (int u = f.u0; u < f.u1; ++u) {
-      const double in = u == 0 ? a0.d_in : a0.d_model, out = u < a0.n_layers ? a0.d_model : a0.n_out;
-      bytes += fused_update_bytes(f.opt, false) * in * out + 4.0 * c->B * (in + out);
-    }
-    HYDRA_LAUNCH(c, c->fuse ? HYDRA_K_WGRAD_UPDATE : HYDRA_K_GEMM_WGRAD, s, unit_flops(c, a0, f.u0, f.u1) * f.G,
-                 c->fuse ? bytes * f.G : 0.0, launch_mlp_wgrad_update(f, s));
-    return HYDRA_OK;
+    return mlp_fused_gradients(c, b, f, s);
   }
   const hydra_arch& a = m0.arch;
   const bool bf = a.dtype == HYDRA_DTYPE_BF16;

@@ -146,6 +146,19 @@ struct Bucket {
   // several shards (the small-MLP kernels): the tasks' dependencies and completion are those of all of them together.
   int span = 1;
   int shard_at(size_t member, int j) const { return ph == 1 ? members[member].second - j : members[member].second + j; }
+  // A forward group that spans all of its members' shards may also take the backward tasks that the plan runs right
+  // behind it (shards second + span - 1, second + span - 2, ...: `bspan` of them, all or none): the small-MLP kernels
+  // go from the loss straight into the chain of input gradients.
+  int bspan = 0;
+  int back_shard_at(size_t member, int j) const { return members[member].second + span - 1 - j; }
+  // every (model, shard, phase) task the group covers, in the order they run
+  template <typename F>
+  void for_each_task(F&& f) const {
+    for (size_t mi = 0; mi < members.size(); ++mi) {
+      for (int j = 0; j < span; ++j) f(members[mi].first, shard_at(mi, j), ph);
+      for (int j = 0; j < bspan; ++j) f(members[mi].first, back_shard_at(mi, j), 1);
+    }
+  }
 };
 
 enum State { ST_CREATED = 0, ST_DEFINED = 1, ST_SHARDED = 2, ST_DATA = 3 };
@@ -198,7 +211,8 @@ struct hydra_ctx {
   uint64_t launches = 0, grouped_tasks = 0, h2d_bytes = 0, d2h_bytes = 0;
   // optional per-launch timing (hydra_profile_enable): event pairs on the launching stream
   bool profiling = false;
-  struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; };
+  // cls2 >= 0: the launch also does flops2 of work of a second class; its time is split in proportion to the flops
+  struct ProfRec { int cls; hipEvent_t a, b; double flops, bytes; int cls2; double flops2; };
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
   size_t prof_used = 0;
@@ -271,19 +285,22 @@ inline double fused_update_bytes(int opt, bool bf16) { return (opt == 1 ? 24.0 :
 // profile.cpp: event pair around one launch when profiling is on
 hipError_t prof_epoch_begin(hydra_ctx* c);  // records the time origin of a profiled epoch on stream 0
 hipError_t prof_begin(hydra_ctx* c, hipStream_t s, hipEvent_t* a);
-hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double flops, double bytes);
+hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double flops, double bytes, int cls2 = -1,
+                    double flops2 = 0.0);
 hydra_status prof_collect(hydra_ctx* c);  // after the streams have drained
 
 // a kernel launch of class `cls` on stream `s` doing `flops` / moving `bytes` of algorithmic work:
 // counted always, executed unless the context is a dry run, timed when profiling is on
-#define HYDRA_LAUNCH(c, cls, s, flops, bytes, expr)                                                     \
+#define HYDRA_LAUNCH(c, cls, s, flops, bytes, expr) HYDRA_LAUNCH2(c, cls, -1, s, flops, 0.0, bytes, expr)
+// ... of two classes (one kernel that does, say, a forward and an input-gradient pass)
+#define HYDRA_LAUNCH2(c, cls, cls2, s, flops, flops2, bytes, expr)                                      \
   do {                                                                                                  \
     ++(c)->launches;                                                                                    \
     if (!(c)->dry) {                                                                                    \
       hipEvent_t pa_ = nullptr;                                                                         \
       hipError_t e_ = (c)->profiling ? prof_begin(c, s, &pa_) : hipSuccess;                             \
       if (e_ == hipSuccess) e_ = (expr);                                                                \
-      if (e_ == hipSuccess && (c)->profiling) e_ = prof_end(c, s, pa_, cls, flops, bytes);              \
+      if (e_ == hipSuccess && (c)->profiling) e_ = prof_end(c, s, pa_, cls, flops, bytes, cls2, flops2); \
       if (e_ != hipSuccess) return (c)->fail(HYDRA_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
     }                                                                                                   \
   } while (0)

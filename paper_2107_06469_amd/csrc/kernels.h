@@ -179,6 +179,7 @@ bool mlp_fused_shape_ok(int B, int d_in, int d, int n_out, int n_units);
 hipError_t mlp_fused_init();  // once per device before the first launch (raises the forward kernel's LDS limit)
 hipError_t launch_mlp_fwd_fused(const MlpFusedArgs& a, hipStream_t s);
 hipError_t launch_mlp_dgrad_chain(const MlpFusedArgs& a, hipStream_t s);   // no launch when the shard has no unit > 0
+hipError_t launch_mlp_fwd_chain(const MlpFusedArgs& a, hipStream_t s);     // both of the above in one launch; units [0, L+1) only
 hipError_t launch_mlp_wgrad_update(const MlpFusedArgs& a, hipStream_t s);
 
 // ---- LayerNorm (layernorm.hip) --------------------------------------------------------------------------

@@ -119,8 +119,7 @@ __device__ __forceinline__ void wave_lds_order() {
 }
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-__global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a) {
-  extern __shared__ float smem[];
+__device__ __forceinline__ void fwd_body(const MlpFusedArgs& a, float* smem) {
   float* xs = smem;                  // [RB][XS] the layer's input rows
   const int g = blockIdx.x % a.G, r0 = (blockIdx.x / a.G) * RB;  // model, first batch row
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -327,8 +326,7 @@ constexpr int DP = 36;               // LDS pitch of a staged k-row: 32 columns 
 constexpr int DCH = 32 * DP;         // floats of one staged chunk of one wave: 32 k x 32 columns
 constexpr size_t DGRAD_LDS = (RB * XS + 8 * 2 * DCH) * sizeof(float);
 
-__global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs a) {
-  extern __shared__ float smem[];
+__device__ __forceinline__ void chain_body(const MlpFusedArgs& a, float* smem) {
   float* ds = smem;                  // [RB][XS] dz_u
   const int g = blockIdx.x % a.G, r0 = (blockIdx.x / a.G) * RB;  // model, first batch row
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -478,6 +476,29 @@ __global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs
   }
 }
 
+static_assert(FWD_LDS == DGRAD_LDS, "the two chains share one LDS layout");
+
+__global__ __launch_bounds__(512) void mlp_fwd_fused_kernel(const MlpFusedArgs a) {
+  extern __shared__ float smem[];
+  fwd_body(a, smem);
+}
+__global__ __launch_bounds__(512) void mlp_dgrad_chain_kernel(const MlpFusedArgs a) {
+  extern __shared__ float smem[];
+  chain_body(a, smem);
+}
+// Forward through all of a model's units, then straight on into the chain of input gradients: a workgroup's 16 rows
+// need nothing from other workgroups in between (the rows' losses and the gradient of the logits are its own), so
+// the two phases of a step that the plan runs back to back are one launch.  What the forward phase wrote to memory
+// (pre-activations, the logits' gradient) is read back by other waves of the workgroup: a workgroup-wide fence and
+// barrier stand between the phases.
+__global__ __launch_bounds__(512) void mlp_fwd_chain_kernel(const MlpFusedArgs a) {
+  extern __shared__ float smem[];
+  fwd_body(a, smem);
+  __threadfence_block();
+  __syncthreads();
+  chain_body(a, smem);
+}
+
 // ---- backward, part 2: dW_u = dz_u^T x_u with the update of W_u and b_u, for every unit of the shard -----------------
 // grid (strip of 32 output rows, unit, model); wave w takes the 32-column tiles w, w+4 of the strip
 template <int OPT>
@@ -616,8 +637,11 @@ hipError_t mlp_fused_init() {
   const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_fwd_fused_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)FWD_LDS);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_dgrad_chain_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)DGRAD_LDS);
+  const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_dgrad_chain_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)DGRAD_LDS);
+  if (e2 != hipSuccess) return e2;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&mlp_fwd_chain_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)FWD_LDS);
 }
 
 hipError_t launch_mlp_fwd_fused(const MlpFusedArgs& a, hipStream_t s) {
@@ -625,6 +649,14 @@ hipError_t launch_mlp_fwd_fused(const MlpFusedArgs& a, hipStream_t s) {
   if (e != hipSuccess) return e;
   if (a.u1 == a.L + 1 && !a.labels) return hipErrorInvalidValue;
   hipLaunchKernelGGL(mlp_fwd_fused_kernel, dim3(a.G * ((a.B + RB - 1) / RB)), dim3(512), FWD_LDS, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_mlp_fwd_chain(const MlpFusedArgs& a, hipStream_t s) {
+  hipError_t e = check(a);
+  if (e != hipSuccess) return e;
+  if (a.u0 != 0 || a.u1 != a.L + 1 || !a.labels) return hipErrorInvalidValue;  // the whole model, forward and back
+  hipLaunchKernelGGL(mlp_fwd_chain_kernel, dim3(a.G * ((a.B + RB - 1) / RB)), dim3(512), FWD_LDS, s, a);
   return hipGetLastError();
 }
 

@@ -27,13 +27,13 @@ hipError_t prof_begin(hydra_ctx* c, hipStream_t s, hipEvent_t* a) {
   return r != hipSuccess ? r : hipEventRecord(*a, s);
 }
 
-hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double flops, double bytes) {
+hipError_t prof_end(hydra_ctx* c, hipStream_t s, hipEvent_t a, int cls, double flops, double bytes, int cls2, double flops2) {
   hipEvent_t b;
   hipError_t r = next_event(c, &b);
   if (r != hipSuccess) return r;
   r = hipEventRecord(b, s);
   if (r != hipSuccess) return r;
-  c->prof_recs.push_back({cls, a, b, flops, bytes});
+  c->prof_recs.push_back({cls, a, b, flops, bytes, cls2, flops2});
   return hipSuccess;
 }
 
@@ -65,11 +65,19 @@ hydra_status prof_collect(hydra_ctx* c) {
       const bool is_copy = r.cls == HYDRA_K_COPY_H2D || r.cls == HYDRA_K_COPY_D2H;
       (is_copy ? copy : kern).push_back({(double)at, (double)at + ms});
     }
+    // a launch of two classes counts in both, its time split in proportion to their flops
+    const double share2 = r.cls2 >= 0 && r.flops + r.flops2 > 0 ? r.flops2 / (r.flops + r.flops2) : 0.0;
     auto& s = c->prof_sum[r.cls];
     ++s.launches;
-    s.ms += ms;
+    s.ms += ms * (1.0 - share2);
     s.flops += r.flops;
     s.bytes += r.bytes;
+    if (r.cls2 >= 0) {
+      auto& s2 = c->prof_sum[r.cls2];
+      ++s2.launches;
+      s2.ms += ms * share2;
+      s2.flops += r.flops2;
+    }
   }
   // time during which at least one kernel was running: launches on different streams overlap, so the sum of their
   // durations can exceed the wall time; the union of the intervals cannot

@@ -81,6 +81,32 @@ static void merge_shard_spans(const hydra_ctx* c, std::vector<Bucket>& plan) {
       plan.erase(plan.begin() + (long)j);
     }
   }
+  // a forward group over all shards, and right behind it (for these models) the backward group over all shards: one
+  // group; the gradient kernel that follows the fused launch is the backward tasks' second half
+  for (size_t i = 0; i < plan.size(); ++i) {
+    Bucket& a = plan[i];
+    if (a.ph != HYDRA_PHASE_F || !fused(a)) continue;
+    bool whole = true;
+    for (const auto& mem : a.members)
+      whole = whole && mem.second == 0 && a.span == (int)c->models[mem.first].shards.size();
+    if (!whole) continue;
+    auto shares_model = [&](const Bucket& x) {
+      for (const auto& xm : x.members)
+        for (const auto& am : a.members)
+          if (xm.first == am.first) return true;
+      return false;
+    };
+    size_t j = i + 1;
+    while (j < plan.size() && !shares_model(plan[j])) ++j;
+    if (j >= plan.size()) continue;
+    const Bucket& b = plan[j];
+    bool ok = b.ph == HYDRA_PHASE_B && b.stream == a.stream && b.span == a.span && b.bspan == 0 && b.members.size() == a.members.size();
+    for (size_t m = 0; ok && m < a.members.size(); ++m)
+      ok = b.members[m].first == a.members[m].first && b.members[m].second == a.span - 1;
+    if (!ok) continue;
+    a.bspan = b.span;
+    plan.erase(plan.begin() + (long)j);
+  }
 }
 
 static const char* ph_name(int ph) { return ph == 0 ? "F" : (ph == 1 ? "B" : "U"); }
@@ -273,7 +299,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
   for (int step = 0; step < c->n_batches; ++step) {
     for (size_t i = 0; i < nb; ++i) {
       const Bucket& b = plan[i];
-      if (b.members.size() > 1) c->grouped_tasks += b.members.size() * b.span;
+      if (b.members.size() > 1) c->grouped_tasks += b.members.size() * (b.span + b.bspan);
       if (c->dry) {
         hydra_status st = HYDRA_OK;
         if (c->spill && b.ph == HYDRA_PHASE_B)
@@ -288,19 +314,20 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
       }
       hipStream_t s = c->streams[b.stream];
       std::vector<hipEvent_t> waited;
-      for (size_t mi = 0; mi < b.members.size(); ++mi)
-        for (int j = 0; j < b.span; ++j) {  // every shard task the group covers
-          Task t{b.members[mi].first, b.shard_at(mi, j), b.ph};
-          std::vector<Task> deps = preds_of(c, t);
-          if (b.ph == HYDRA_PHASE_F) deps.push_back({t.k, t.s, HYDRA_PHASE_U});  // previous step's update
-          for (const Task& d : deps) {
-            auto it = last.find(d);
-            if (it == last.end() || it->second.stream == b.stream) continue;
-            if (std::find(waited.begin(), waited.end(), it->second.ev) != waited.end()) continue;
-            HYDRA_HIP(c, hipStreamWaitEvent(s, it->second.ev, 0));
-            waited.push_back(it->second.ev);
-          }
+      hipError_t werr = hipSuccess;
+      b.for_each_task([&](int k, int sh, int ph) {  // every task the group covers
+        Task t{k, sh, ph};
+        std::vector<Task> deps = preds_of(c, t);
+        if (ph == HYDRA_PHASE_F) deps.push_back({t.k, t.s, HYDRA_PHASE_U});  // previous step's update
+        for (const Task& d : deps) {
+          auto it = last.find(d);
+          if (it == last.end() || it->second.stream == b.stream) continue;
+          if (std::find(waited.begin(), waited.end(), it->second.ev) != waited.end()) continue;
+          if (werr == hipSuccess) werr = hipStreamWaitEvent(s, it->second.ev, 0);
+          waited.push_back(it->second.ev);
         }
+      });
+      HYDRA_HIP(c, werr);
       hydra_status st = HYDRA_OK;
       if (c->spill && b.ph == HYDRA_PHASE_B)
         for (const auto& mem : b.members)
@@ -315,8 +342,7 @@ hydra_status run_epoch(hydra_ctx* c, const std::vector<Bucket>& plan, hydra_epoc
           if ((st = spill_after_update(c, mem.first, mem.second, s, c->sync_spill)) != HYDRA_OK) return st;
       hipEvent_t ev = c->events[(step & 1) * nb + i];
       HYDRA_HIP(c, hipEventRecord(ev, s));
-      for (size_t mi = 0; mi < b.members.size(); ++mi)
-        for (int j = 0; j < b.span; ++j) last[{b.members[mi].first, b.shard_at(mi, j), b.ph}] = {ev, b.stream};
+      b.for_each_task([&](int k, int sh, int ph) { last[{k, sh, ph}] = {ev, b.stream}; });
     }
   }
   if (!c->dry) {

@@ -336,15 +336,15 @@ def test_automatic_launch_groups_follow_the_tile_count_of_the_products():
 
 def test_small_fp32_mlps_merge_the_launch_groups_of_consecutive_shards():
     """Workload 0 (fp32 MLPs of width 256, 32 rows: the kernels that run a whole shard phase per launch): the
-    shard-parallel plan merges the forward groups of consecutive shards into one launch and the backward groups
-    likewise (input-gradient chain + weight gradients with the update): 3 launches per step for the 4 x 2 shards;
-    with gradients kept the update groups between the backward groups launch the optimizer and nothing is merged
-    across them; the sequential plan keeps one launch group per task."""
+    shard-parallel plan merges the forward groups of consecutive shards, the backward groups likewise, and then the
+    two into one group of two launches (forward + input-gradient chain, weight gradients with the update) for the
+    4 x 2 shards; with gradients kept the update groups between the backward groups launch the optimizer and nothing
+    is merged across them; the sequential plan keeps one launch group per task."""
     w = workload(0)
     w.steps = w.n_batches = 2
     d = make_data(w)
     merged = _plan_stats(w, d, n_streams=4)
-    assert merged["launches"] == w.steps * 3 and merged["grouped_tasks"] == w.steps * w.K * 2 * 3
+    assert merged["launches"] == w.steps * 2 and merged["grouped_tasks"] == w.steps * w.K * 2 * 3
     kept = _plan_stats(w, d, n_streams=4, keep_grads=True)
     assert kept["launches"] > merged["launches"]
     ctx = H.hydra_create(dry_run=True, n_streams=4)
