@@ -322,3 +322,25 @@ def test_small_fp32_models_run_whole_shard_phases_in_one_launch_and_match_oracle
                 assert np.abs(a - b).max() <= 1e-5 * max(np.abs(b).max(), 1e-6) + 1e-9, (k, nm)
     finally:
         H.hydra_destroy(ctx)
+
+
+@pytest.mark.parametrize("batch", [1, 9, 16, 17, 32])
+def test_small_fp32_models_at_every_split_of_the_batch_rows(H, batch):
+    """The small-MLP chain kernels give a workgroup 16 rows of a model's batch: one workgroup for up to 16 rows, two
+    beyond, the second with 1 to 16 of them.  ReLU, two hidden layers of 64, one model with a single shard and one
+    with three; against the oracle, and the shard-parallel plan (forward and input-gradient chain in one launch where
+    a model's tasks allow it) bit-identical to the sequential one (a launch per task)."""
+    arch = C.mlp_arch(2, 40, 64, 7, C.ACT_RELU, C.DTYPE_F32)
+    w = C.Workload("mlp_rows_f32", 0, [dict(arch), dict(arch)], [C.hparams(C.OPT_SGD, 0.05), C.hparams(C.OPT_ADAM, 2e-3)],
+                   [[], [1, 2]], batch, 0, 0, 4, 4, 99 + batch)
+    data = make_data(w)
+    ref = OT.train_all(w.archs, w.hparams, data, w.steps, w.init_seed)
+    got, st = H.train_workload(w, data, H.SCHED_SHARD_PARALLEL)
+    assert st[0]["launches"] == w.steps * 2 * 2               # two models of different shard shapes, two launches each
+    seq, _ = H.train_workload(w, data, H.SCHED_SEQUENTIAL)
+    for k in range(w.K):
+        kw = _adam_outliers(w, k) if k == 1 else {}
+        _assert_fp32_parity(got[k], ref[k], _names(w.archs[k]), **kw)
+        assert np.array_equal(seq[k][0], got[k][0])
+        for a, b in zip(seq[k][1], got[k][1]):
+            assert np.array_equal(a, b)
