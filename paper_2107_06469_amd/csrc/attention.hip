@@ -53,7 +53,7 @@ __device__ __forceinline__ f32x16 mfma(const uint4& a, const uint4& b, f32x16 c)
 }
 
 // ---- LDS tiles of 64 rows x DH columns ---------------------------------------------------------------
-// uint4 chunk (row, kc) sits at row*NCH + (kc ^ (row & (NCH-1))), NCH = DH/8.
+// uint4 chunk (row, kc) sits at row*NCH + (kc ^ swz(row)), NCH = DH/8.
 // A tile load is split in two so that it can be pipelined: fetch (global -> registers, rows past nrows as zero)
 // and put (registers -> LDS).
 // Work item of a workgroup.  The hardware deals consecutive workgroup ids to the 8 XCDs in turn; items are numbered so
@@ -69,6 +69,17 @@ __device__ __forceinline__ bool attn_item(int n_blk, int n_bh, int n_g, AttnItem
   it.bh = (id / n_blk) % n_bh;
   it.gi = id / (n_blk * n_bh);
   return true;
+}
+
+// XOR term of a row's chunk index, a bijection of the 16 rows that a 128-bit row read touches in one pass, chosen so
+// that the transposing reads (rows 0..7 or 8..15 x 4 neighbouring chunks x 2 halves) spread over all banks as well.
+// A row of DH = 128 fills the 64 banks once: the terms of 8 consecutive rows must move the group of 4 chunks to each of
+// the 4 groups twice, hence 4*(row%4) + (row/4)%4.  A row of DH = 64 fills half of the banks, rows of equal parity
+// share them: the 8 such rows among 16 get the 8 different terms 2*((row/2)%4) + (row/8)%2, the even ones for rows 0..7.
+template <int DH>
+__device__ __forceinline__ int swz(int row) {
+  if (DH == 128) return 4 * (row & 3) + ((row >> 2) & 3);
+  return 2 * ((row >> 1) & 3) + ((row >> 3) & 1);
 }
 
 template <int DH>
@@ -87,7 +98,7 @@ struct TileRegs {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int c = tid + 256 * i, row = c / NCH, kc = c % NCH;
-      tile[row * NCH + (kc ^ (row & (NCH - 1)))] = r[i];
+      tile[row * NCH + (kc ^ swz<DH>(row))] = r[i];
     }
   }
 };
@@ -105,8 +116,8 @@ __device__ __forceinline__ uint4 read_cols(const uint4* tile, int col0, int row0
   const int col = col0 + 16 * (grp & 1) + 4 * (j & 3), kc = col >> 3, half = (col >> 2) & 1;
   const int r0 = row0 + 4 * (grp >> 1) + (j >> 2), r1 = r0 + 8;
   const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tile);
-  const unsigned a0 = base + (unsigned)((r0 * NCH + (kc ^ (r0 & (NCH - 1)))) * 16 + half * 8);
-  const unsigned a1 = base + (unsigned)((r1 * NCH + (kc ^ (r1 & (NCH - 1)))) * 16 + half * 8);
+  const unsigned a0 = base + (unsigned)((r0 * NCH + (kc ^ swz<DH>(r0))) * 16 + half * 8);
+  const unsigned a1 = base + (unsigned)((r1 * NCH + (kc ^ swz<DH>(r1))) * 16 + half * 8);
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)a0);
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)a1);
   const uint2 l = __builtin_bit_cast(uint2, lo), h = __builtin_bit_cast(uint2, hi);
@@ -116,7 +127,7 @@ __device__ __forceinline__ uint4 read_cols(const uint4* tile, int col0, int row0
 template <int DH>
 __device__ __forceinline__ uint4 read_rows(const uint4* tile, int row, int kc) {
   constexpr int NCH = DH / 8;
-  return tile[row * NCH + (kc ^ (row & (NCH - 1)))];
+  return tile[row * NCH + (kc ^ swz<DH>(row))];
 }
 
 // The same two reads with the lane's part of the address computed once: for rows row0 + l%32 (row0 a multiple of
@@ -125,7 +136,7 @@ __device__ __forceinline__ uint4 read_rows(const uint4* tile, int row, int kc) {
 template <int DH>
 __device__ __forceinline__ const uint4* rows_base(const uint4* tile, int li, int kc) {
   constexpr int NCH = DH / 8;
-  return tile + li * NCH + (kc ^ (li & (NCH - 1)));
+  return tile + li * NCH + (kc ^ swz<DH>(li));
 }
 // byte addresses of read_cols' two reads (rows r0 and r0 + 8) for row0 = 0; row0 (a multiple of 16) adds
 // row0 * NCH * 16 to both
@@ -138,8 +149,8 @@ __device__ __forceinline__ ColsBase cols_base(const uint4* tile, int col0, int l
   const int r0 = 4 * (grp >> 1) + (j >> 2), r1 = r0 + 8;
   const unsigned base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)reinterpret_cast<const char*>(tile);
   ColsBase b;
-  b.a0 = base + (unsigned)((r0 * NCH + (kc ^ (r0 & (NCH - 1)))) * 16 + half * 8);
-  b.a1 = base + (unsigned)((r1 * NCH + (kc ^ (r1 & (NCH - 1)))) * 16 + half * 8);
+  b.a0 = base + (unsigned)((r0 * NCH + (kc ^ swz<DH>(r0))) * 16 + half * 8);
+  b.a1 = base + (unsigned)((r1 * NCH + (kc ^ swz<DH>(r1))) * 16 + half * 8);
   return b;
 }
 template <int DH>
