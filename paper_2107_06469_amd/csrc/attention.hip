@@ -71,15 +71,16 @@ __device__ __forceinline__ bool attn_item(int n_blk, int n_bh, int n_g, AttnItem
   return true;
 }
 
-// XOR term of a row's chunk index, a bijection of the 16 rows that a 128-bit row read touches in one pass, chosen so
-// that the transposing reads (rows 0..7 or 8..15 x 4 neighbouring chunks x 2 halves) spread over all banks as well.
-// A row of DH = 128 fills the 64 banks once: the terms of 8 consecutive rows must move the group of 4 chunks to each of
-// the 4 groups twice, hence 4*(row%4) + (row/4)%4.  A row of DH = 64 fills half of the banks, rows of equal parity
-// share them: the 8 such rows among 16 get the 8 different terms 2*((row/2)%4) + (row/8)%2, the even ones for rows 0..7.
+// XOR term of a row's chunk index.  Two access patterns must each spread over all 64 banks: a 128-bit row read
+// (16 consecutive rows at one chunk index per pass) and a transposing 64-bit read (per pass of 32 lanes: rows 4g..4g+3 x
+// 4 neighbouring chunks x both halves).  A row of DH = 128 fills the banks once: the 16 rows need 16 different terms,
+// and 4 consecutive rows must move the group of 4 chunks to the 4 different groups: 4*(row%4) + (row/4)%4.  A row of
+// DH = 64 fills half of the banks and rows of equal parity share them: the 8 such rows among 16 need 8 different terms,
+// and the 2 among 4 consecutive rows must move the group of 4 chunks to different groups: 4*((row/2)%2) + (row/4)%4.
 template <int DH>
 __device__ __forceinline__ int swz(int row) {
   if (DH == 128) return 4 * (row & 3) + ((row >> 2) & 3);
-  return 2 * ((row >> 1) & 3) + ((row >> 3) & 1);
+  return 4 * ((row >> 1) & 1) + ((row >> 2) & 3);
 }
 
 template <int DH>
