@@ -135,6 +135,13 @@ def test_attention_at_the_workloads_shapes(torch, ops, shape):
     _attention_case(torch, ops, B, S, H, DH, causal, seed=S + DH)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_over_128_key_tiles(torch, ops, causal):
+    """One head of 64 at S = 8192 (the longest sequence the kernel rates are quoted at): the running maximum and sum go
+    through 128 key tiles per query block, the backward kernels through 128 query tiles per key block."""
+    _attention_case(torch, ops, 1, 8192, 1, 64, causal, seed=8192 + int(causal))
+
+
 def test_attention_uniform_scores_closed_form(torch, ops):
     """q = k = 0 gives uniform probabilities: o is the running (causal) or global mean of v; lse = log(count)."""
     B, S, H, DH = 1, 96, 1, 64
